@@ -1,0 +1,248 @@
+"""ctypes access to the CPU oracle (oracle/cc_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, the smoke check and the benchmark's CPU-baseline leg.
+The GPU library never imports this package and this package never imports the GPU library.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from concurrent.futures import ThreadPoolExecutor
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "cc_oracle.c")
+_LIB = os.path.join(_HERE, "libcc_oracle.so")
+
+SUM, MAX, SUM_DIRECTED, MAX_DIRECTED = 0, 1, 2, 3
+OBJECTIVES = {"sum": SUM, "max": MAX, "sum_directed": SUM_DIRECTED, "max_directed": MAX_DIRECTED}
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc -O2 (plain C, no intrinsics)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-Wall", "-Wextra", "-fPIC", "-shared", _SRC, "-o", _LIB])
+    return _LIB
+
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        i32, i64, u64, u32 = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64, ctypes.c_uint32
+        p = ctypes.c_void_p
+        lib.cco_splitmix64_at.restype = u64
+        lib.cco_splitmix64_at.argtypes = [u64, u64]
+        lib.cco_init_tour.restype = None
+        lib.cco_init_tour.argtypes = [u64, u32, i32, p]
+        lib.cco_init_tours.restype = None
+        lib.cco_init_tours.argtypes = [u64, i32, i64, i64, p]
+        lib.cco_ring_cost.restype = i64
+        lib.cco_ring_cost.argtypes = [p, i32, p, i32]
+        lib.cco_rd_cost.restype = i64
+        lib.cco_rd_cost.argtypes = [p, i32, p]
+        lib.cco_ring_cost_batch.restype = ctypes.c_int
+        lib.cco_ring_cost_batch.argtypes = [p, i32, i32, p, i64, p]
+        lib.cco_rd_cost_batch.restype = ctypes.c_int
+        lib.cco_rd_cost_batch.argtypes = [p, i32, p, i64, p]
+        lib.cco_apply_move.restype = None
+        lib.cco_apply_move.argtypes = [p, i32, i32, i32, i32]
+        lib.cco_move_id.restype = i64
+        lib.cco_move_id.argtypes = [i32, i32, i32, i32, i32]
+        lib.cco_move_value_by_definition.restype = i64
+        lib.cco_move_value_by_definition.argtypes = [p, i32, i32, p, i32, i32, i32]
+        lib.cco_neighbourhood_size.restype = i64
+        lib.cco_neighbourhood_size.argtypes = [i32, i32]
+        lib.cco_all_move_values.restype = ctypes.c_int
+        lib.cco_all_move_values.argtypes = [p, i32, i32, p, p]
+        lib.cco_2opt_descend.restype = ctypes.c_int
+        lib.cco_2opt_descend.argtypes = [p, i32, i32, p, p, p, i32, p, i32]
+        lib.cco_2opt_restarts.restype = ctypes.c_int
+        lib.cco_2opt_restarts.argtypes = [p, i32, i32, u64, i64, i64, p, p, p, p]
+        lib.cco_2opt_search.restype = ctypes.c_int
+        lib.cco_2opt_search.argtypes = [p, i32, i32, i32, u64, p, p, p, p, p, p, p]
+        lib.cco_exhaustive_rings.restype = ctypes.c_int
+        lib.cco_exhaustive_rings.argtypes = [p, i32, i32, i32, p, p, p, p, p, i64]
+        _lib = lib
+    return _lib
+
+
+def _mat(c) -> np.ndarray:
+    c = np.ascontiguousarray(c, dtype=np.int32)
+    assert c.ndim == 2 and c.shape[0] == c.shape[1]
+    return c
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise RuntimeError({-1: "oracle: invalid argument", -2: "oracle: matrix not symmetric",
+                            -3: "oracle: out of memory"}.get(rc, f"oracle error {rc}"))
+
+
+def splitmix64_at(seed: int, n: int) -> int:
+    return int(_L().cco_splitmix64_at(seed & (2**64 - 1), n & (2**64 - 1)))
+
+
+def init_tours(seed: int, n: int, count: int, first: int = 0) -> np.ndarray:
+    out = np.empty((count, n), dtype=np.int32)
+    _L().cco_init_tours(seed, n, first, count, _ptr(out))
+    return out
+
+
+def ring_cost(c, perm, objective: int = SUM) -> int:
+    c = _mat(c)
+    perm = np.ascontiguousarray(perm, dtype=np.int32)
+    return int(_L().cco_ring_cost(_ptr(c), c.shape[0], _ptr(perm), objective))
+
+
+def rd_cost(c, perm) -> int:
+    c = _mat(c)
+    perm = np.ascontiguousarray(perm, dtype=np.int32)
+    return int(_L().cco_rd_cost(_ptr(c), c.shape[0], _ptr(perm)))
+
+
+def ring_cost_batch(c, perms, objective: int = SUM) -> np.ndarray:
+    c = _mat(c)
+    perms = np.ascontiguousarray(perms, dtype=np.int32).reshape(-1, c.shape[0])
+    out = np.empty(perms.shape[0], dtype=np.int64)
+    _check(_L().cco_ring_cost_batch(_ptr(c), c.shape[0], objective, _ptr(perms), perms.shape[0], _ptr(out)))
+    return out
+
+
+def rd_cost_batch(c, perms) -> np.ndarray:
+    c = _mat(c)
+    perms = np.ascontiguousarray(perms, dtype=np.int32).reshape(-1, c.shape[0])
+    out = np.empty(perms.shape[0], dtype=np.int64)
+    _check(_L().cco_rd_cost_batch(_ptr(c), c.shape[0], _ptr(perms), perms.shape[0], _ptr(out)))
+    return out
+
+
+def apply_move(t, i: int, j: int, o: int = 0) -> np.ndarray:
+    u = np.array(t, dtype=np.int32, copy=True)
+    _L().cco_apply_move(_ptr(u), u.shape[0], i, j, o)
+    return u
+
+
+def move_id(n: int, objective: int, i: int, j: int, o: int = 0) -> int:
+    return int(_L().cco_move_id(n, objective, i, j, o))
+
+
+def move_value_by_definition(c, objective: int, t, i: int, j: int, o: int = 0) -> int:
+    c = _mat(c)
+    t = np.ascontiguousarray(t, dtype=np.int32)
+    return int(_L().cco_move_value_by_definition(_ptr(c), c.shape[0], objective, _ptr(t), i, j, o))
+
+
+def neighbourhood_size(n: int, objective: int) -> int:
+    return int(_L().cco_neighbourhood_size(n, objective))
+
+
+def moves_in_id_order(n: int, objective: int):
+    """(i, j, o) of every move, in increasing id order."""
+    directed = bool(objective & 2)
+    out = []
+    for i in range(1, n - 1):
+        for j in range(i + 1, n):
+            if (i, j) == (1, n - 1):
+                continue
+            for o in range(2 if directed else 1):
+                out.append((i, j, o))
+    return out
+
+
+def all_move_values(c, objective: int, t) -> np.ndarray:
+    c = _mat(c)
+    t = np.ascontiguousarray(t, dtype=np.int32)
+    out = np.empty(neighbourhood_size(c.shape[0], objective), dtype=np.int64)
+    _check(_L().cco_all_move_values(_ptr(c), c.shape[0], objective, _ptr(t), _ptr(out)))
+    return out
+
+
+def descend(c, objective: int, t, use_definition: bool = False, trace_cap: int = 0):
+    """One 2-opt descent from tour t. Returns (final tour, cost, applied moves, trace of move ids)."""
+    c = _mat(c)
+    u = np.array(t, dtype=np.int32, copy=True)
+    cost = ctypes.c_int64(0)
+    moves = ctypes.c_int32(0)
+    trace = np.zeros(max(trace_cap, 1), dtype=np.int64)
+    _check(_L().cco_2opt_descend(_ptr(c), c.shape[0], objective, _ptr(u), ctypes.byref(cost), ctypes.byref(moves),
+                                 1 if use_definition else 0, _ptr(trace), trace_cap))
+    return u, int(cost.value), int(moves.value), trace[:min(trace_cap, moves.value)]
+
+
+def restarts(c, objective: int, seed: int, r0: int, r1: int, init: Optional[np.ndarray] = None):
+    """Restarts [r0, r1): returns (costs int64[r1-r0], tours int32[r1-r0, N], moves int32[r1-r0])."""
+    c = _mat(c)
+    n = c.shape[0]
+    k = r1 - r0
+    costs = np.empty(k, dtype=np.int64)
+    tours = np.empty((k, n), dtype=np.int32)
+    moves = np.empty(k, dtype=np.int32)
+    if init is not None:
+        init = np.ascontiguousarray(init, dtype=np.int32)
+    _check(_L().cco_2opt_restarts(_ptr(c), n, objective, seed, r0, r1, _ptr(init), _ptr(costs), _ptr(tours),
+                                  _ptr(moves)))
+    return costs, tours, moves
+
+
+def restarts_parallel(c, objective: int, seed: int, r0: int, r1: int, threads: int,
+                      init: Optional[np.ndarray] = None):
+    """The same single-threaded routine over disjoint restart ranges on `threads` host threads
+    (ctypes releases the GIL).  Results are identical to restarts()."""
+    threads = max(1, min(threads, r1 - r0))
+    edges = np.linspace(r0, r1, threads * 4 + 1).astype(np.int64)
+    spans = [(int(a), int(b)) for a, b in zip(edges[:-1], edges[1:]) if b > a]
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        parts = list(ex.map(lambda s: restarts(c, objective, seed, s[0], s[1], init), spans))
+    return (np.concatenate([p[0] for p in parts]), np.concatenate([p[1] for p in parts]),
+            np.concatenate([p[2] for p in parts]))
+
+
+def search(c, objective: int, n_restarts: int, seed: int, init: Optional[np.ndarray] = None):
+    """Whole multi-start search. Returns dict(best_perm, best_cost, best_restart, costs, tours, moves)."""
+    c = _mat(c)
+    n = c.shape[0]
+    best = np.empty(n, dtype=np.int32)
+    bc = ctypes.c_int64(0)
+    br = ctypes.c_int32(0)
+    costs = np.empty(n_restarts, dtype=np.int64)
+    tours = np.empty((n_restarts, n), dtype=np.int32)
+    moves = np.empty(n_restarts, dtype=np.int32)
+    if init is not None:
+        init = np.ascontiguousarray(init, dtype=np.int32)
+    _check(_L().cco_2opt_search(_ptr(c), n, objective, n_restarts, seed, _ptr(init), _ptr(best), ctypes.byref(bc),
+                                ctypes.byref(br), _ptr(costs), _ptr(tours), _ptr(moves)))
+    return dict(best_perm=best, best_cost=int(bc.value), best_restart=int(br.value), costs=costs, tours=tours,
+                moves=moves)
+
+
+def exhaustive_rings(c, objective: int = SUM, half_only: bool = True, keep_all: bool = False):
+    """All rings with t[0]=0 (N <= 12). Returns dict(count, best_cost, best_ring[, rings, costs])."""
+    c = _mat(c)
+    n = c.shape[0]
+    count = ctypes.c_int64(0)
+    bc = ctypes.c_int64(0)
+    best = np.empty(n, dtype=np.int32)
+    rings = costs = None
+    cap = 0
+    if keep_all:
+        import math
+        cap = math.factorial(n - 1) // (2 if (half_only and n > 2) else 1)
+        rings = np.empty((cap, n), dtype=np.int32)
+        costs = np.empty(cap, dtype=np.int64)
+    _check(_L().cco_exhaustive_rings(_ptr(c), n, objective, 1 if half_only else 0, ctypes.byref(count),
+                                     ctypes.byref(bc), _ptr(best), _ptr(rings), _ptr(costs), cap))
+    out = dict(count=int(count.value), best_cost=int(bc.value), best_ring=best)
+    if keep_all:
+        out["rings"], out["costs"] = rings, costs
+    return out

@@ -1,0 +1,397 @@
+/*
+ * CPU oracle for rank-order search on a measured point-to-point cost matrix.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, slow, single-threaded C written from the paper's statement of
+ * the problem (Section 4.1 cost models, Section 4.3 rank variables and neighbour search).  It shares
+ * no code with the GPU library and must never be called from a product path: only the test-suite,
+ * the smoke check and the benchmark's CPU-baseline leg load it.
+ *
+ * Notation (Section 4.1 / 4.3):
+ *   N        number of ranks
+ *   c        row-major N x N int32, c[a*N+b] = cost of node a talking to node b (flattened c'_{iN+j})
+ *   t / pi   permutation array, t[p] = original node placed at rank p (the r_p of Section 4.3)
+ *   prev(p)  (p - 1 + N) mod N   (ranks alias modulo N, Section 4.1)
+ *
+ * All arithmetic is exact 64-bit integer.
+ *
+ * Pins (see tests/test_oracle_*.py): closed forms for constant / additive / line-metric / cyclic
+ * shift / clean-hierarchy matrices, rotation and reversal invariances, hypercube automorphisms,
+ * brute force over all rings for N <= 10, every move's fast value against apply-and-recompute,
+ * local-optimum certification, published SplitMix64 output vectors.
+ * Parity unpinned: none of the functions below.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { CCO_SUM = 0, CCO_MAX = 1, CCO_SUM_DIRECTED = 2, CCO_MAX_DIRECTED = 3 };
+enum { CCO_OK = 0, CCO_ERR_ARG = -1, CCO_ERR_NOT_SYMMETRIC = -2, CCO_ERR_NOMEM = -3 };
+
+#define C_(a, b) ((int64_t)c[(int64_t)(a) * N + (b)])
+
+static int64_t max64(int64_t a, int64_t b) { return a > b ? a : b; }
+
+/* ------------------------------------------------------------------------------------------------
+ * Counter-based random numbers: SplitMix64 (Steele, Lea, Flood 2014; public-domain reference by
+ * Vigna).  The generator's state advances by the golden-gamma constant and the output is a
+ * two-round xor-shift-multiply finaliser of the state, so the n-th output (n = 1, 2, ...) of a
+ * generator started at state `seed` is mix(seed + n * gamma) and can be computed directly.
+ * ---------------------------------------------------------------------------------------------- */
+uint64_t cco_splitmix64_at(uint64_t seed, uint64_t n)
+{
+    uint64_t z = seed + n * 0x9E3779B97F4A7C15ULL;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+/* Initial tour of restart r: Fisher-Yates from the identity, k = N-1 down to 1, swap t[k] with
+ * t[jdx], jdx = floor(u * (k+1) / 2^32) where u = high 32 bits of output number ((r<<32)|k)+1.
+ * (The paper only says the initial order is random, Section 1; this fixes one reproducible draw.) */
+void cco_init_tour(uint64_t seed, uint32_t r, int32_t N, int32_t *t)
+{
+    for (int32_t p = 0; p < N; ++p) t[p] = p;
+    for (int32_t k = N - 1; k >= 1; --k) {
+        uint64_t ctr = (((uint64_t)r << 32) | (uint64_t)(uint32_t)k) + 1u;
+        uint64_t u = cco_splitmix64_at(seed, ctr) >> 32;
+        int32_t jdx = (int32_t)((u * (uint64_t)(k + 1)) >> 32);
+        int32_t tmp = t[k]; t[k] = t[jdx]; t[jdx] = tmp;
+    }
+}
+
+void cco_init_tours(uint64_t seed, int32_t N, int64_t first, int64_t count, int32_t *tours)
+{
+    for (int64_t r = 0; r < count; ++r) cco_init_tour(seed, (uint32_t)(first + r), N, tours + r * N);
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * Cost models (Section 4.1).
+ * ---------------------------------------------------------------------------------------------- */
+
+/* Ring: sum over ranks p of the hop c[pi(p)][pi(p-1)] (the equation's c_{i,i-1}); objective MAX
+ * takes the largest hop instead (bottleneck link on the critical path, Section 5.3 / Section 6). */
+int64_t cco_ring_cost(const int32_t *c, int32_t N, const int32_t *pi, int32_t objective)
+{
+    int64_t acc = 0;
+    for (int32_t p = 0; p < N; ++p) {
+        int32_t pp = (p - 1 + N) % N;
+        int64_t hop = C_(pi[p], pi[pp]);
+        if (objective & 1) acc = (p == 0) ? hop : max64(acc, hop);
+        else acc += hop;
+    }
+    return acc;
+}
+
+/* Halving-doubling / recursive doubling: one round per bit k of the rank id; a round costs the
+ * slowest of its exchanges, rank i talking to rank i xor 2^k; rounds add up. */
+int64_t cco_rd_cost(const int32_t *c, int32_t N, const int32_t *pi)
+{
+    int64_t total = 0;
+    for (int32_t bit = 1; bit < N; bit <<= 1) {
+        int64_t worst = 0;
+        for (int32_t i = 0; i < N; ++i) worst = max64(worst, C_(pi[i], pi[i ^ bit]));
+        total += worst;
+    }
+    return total;
+}
+
+int cco_ring_cost_batch(const int32_t *c, int32_t N, int32_t objective, const int32_t *perms, int64_t B,
+                        int64_t *out)
+{
+    if (!c || N < 2 || B < 0 || (B > 0 && (!perms || !out))) return CCO_ERR_ARG;
+    for (int64_t b = 0; b < B; ++b) out[b] = cco_ring_cost(c, N, perms + b * N, objective);
+    return CCO_OK;
+}
+
+int cco_rd_cost_batch(const int32_t *c, int32_t N, const int32_t *perms, int64_t B, int64_t *out)
+{
+    if (!c || N < 2 || (N & (N - 1)) || B < 0 || (B > 0 && (!perms || !out))) return CCO_ERR_ARG;
+    for (int64_t b = 0; b < B; ++b) out[b] = cco_rd_cost(c, N, perms + b * N);
+    return CCO_OK;
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * 2-opt neighbourhood (the "permute a sub-array" neighbour of Section 4.3, made deterministic).
+ * Rank 0 is an anchor.  Move (i, j, o): 1 <= i < j <= N-1, (i, j) != (1, N-1); reverse t[i..j];
+ * if o = 1 additionally reverse t[1..N-1] (same ring walked the other way round).
+ * Undirected objectives use o = 0 only.
+ * ---------------------------------------------------------------------------------------------- */
+static void reverse_span(int32_t *t, int32_t lo, int32_t hi)
+{
+    while (lo < hi) { int32_t tmp = t[lo]; t[lo] = t[hi]; t[hi] = tmp; ++lo; --hi; }
+}
+
+void cco_apply_move(int32_t *t, int32_t N, int32_t i, int32_t j, int32_t o)
+{
+    reverse_span(t, i, j);
+    if (o) reverse_span(t, 1, N - 1);
+}
+
+int64_t cco_move_id(int32_t N, int32_t objective, int32_t i, int32_t j, int32_t o)
+{
+    int64_t id = (int64_t)i * N + j;
+    return (objective & 2) ? id * 2 + o : id;
+}
+
+/* Definition tier: value of a move = objective of the tour obtained by applying it. */
+int64_t cco_move_value_by_definition(const int32_t *c, int32_t N, int32_t objective, const int32_t *t,
+                                     int32_t i, int32_t j, int32_t o)
+{
+    int32_t *u = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    memcpy(u, t, sizeof(int32_t) * (size_t)N);
+    cco_apply_move(u, N, i, j, o);
+    int64_t v = cco_ring_cost(c, N, u, objective);
+    free(u);
+    return v;
+}
+
+/* Delta tier: O(1) value per move from the hop arrays
+ *   f[p] = c[t[p]][t[prev p]]  (hop as walked now),  b[p] = c[t[prev p]][t[p]]  (same edge, other way)
+ * With q = (j+1) mod N, inside I = {i+1..j}, outside O = all ranks except I, i and q:
+ *   reversing t[i..j] replaces hops i and q by x0 = c[t[j]][t[i-1]], y0 = c[t[q]][t[i]], and walks
+ *   the inside edges the other way (b instead of f); orientation 1 flips every hop of that ring:
+ *   x1 = c[t[i-1]][t[j]], y1 = c[t[i]][t[q]], outside b, inside f.
+ * Scans all moves in increasing id and returns the lexicographic minimum of (value, id).
+ * Returns 0 if the neighbourhood is empty (N < 4). */
+typedef struct { int64_t value; int64_t id; int32_t i, j, o; } cco_best;
+
+static int scan_moves(const int32_t *c, int32_t N, int32_t objective, const int32_t *t, int64_t cur,
+                      int64_t *ws /* 6N int64 */, cco_best *best, int64_t *all_values /* optional */)
+{
+    const int directed = (objective & 2) != 0, is_max = (objective & 1) != 0;
+    int64_t *f = ws, *b = ws + N, *pf = ws + 2 * N, *pb = ws + 3 * N, *sf = ws + 4 * N, *sb = ws + 5 * N;
+    /* pf/pb: inclusive prefix (sum or max) over ranks 0..p; sf/sb: inclusive suffix over p..N-1 */
+    int found = 0;
+    int64_t nvals = 0;
+    if (N < 4) return 0;
+    for (int32_t p = 0; p < N; ++p) {
+        int32_t pp = (p - 1 + N) % N;
+        f[p] = C_(t[p], t[pp]);
+        b[p] = C_(t[pp], t[p]);
+    }
+    for (int32_t p = 0; p < N; ++p) {
+        if (is_max) { pf[p] = p ? max64(pf[p - 1], f[p]) : f[p]; pb[p] = p ? max64(pb[p - 1], b[p]) : b[p]; }
+        else        { pf[p] = (p ? pf[p - 1] : 0) + f[p];          pb[p] = (p ? pb[p - 1] : 0) + b[p]; }
+    }
+    for (int32_t p = N - 1; p >= 0; --p) {
+        if (is_max) { sf[p] = p < N - 1 ? max64(sf[p + 1], f[p]) : f[p]; sb[p] = p < N - 1 ? max64(sb[p + 1], b[p]) : b[p]; }
+        else        { sf[p] = (p < N - 1 ? sf[p + 1] : 0) + f[p];          sb[p] = (p < N - 1 ? sb[p + 1] : 0) + b[p]; }
+    }
+    for (int32_t i = 1; i <= N - 2; ++i) {
+        int64_t in_f = 0, in_b = 0;              /* sum or max of f / b over I, grown as j advances */
+        for (int32_t j = i + 1; j <= N - 1; ++j) {
+            int32_t q = (j + 1) % N;
+            if (is_max) { in_f = max64(in_f, f[j]); in_b = max64(in_b, b[j]); }
+            else        { in_f += f[j];              in_b += b[j]; }
+            if (i == 1 && j == N - 1) continue;
+            int64_t x0 = C_(t[j], t[i - 1]), y0 = C_(t[q], t[i]);
+            int64_t x1 = C_(t[i - 1], t[j]), y1 = C_(t[i], t[q]);
+            int64_t v0, v1 = 0;
+            if (!is_max) {
+                if (!directed) {
+                    v0 = cur + x0 + y0 - f[i] - f[q];
+                } else {
+                    int64_t out_f = pf[N - 1] - f[i] - f[q] - in_f;
+                    int64_t out_b = pb[N - 1] - b[i] - b[q] - in_b;
+                    v0 = x0 + y0 + out_f + in_b;
+                    v1 = x1 + y1 + out_b + in_f;
+                }
+            } else {
+                /* outside = ranks 0..i-1 and j+2..N-1 (empty when q = 0 wraps: then rank 0 is q itself
+                 * and the prefix must skip it) */
+                int64_t out_f = 0, out_b = 0;
+                if (q == 0) {
+                    /* ranks 1..i-1 */
+                    for (int32_t p = 1; p <= i - 1; ++p) { out_f = max64(out_f, f[p]); out_b = max64(out_b, b[p]); }
+                } else {
+                    out_f = pf[i - 1]; out_b = pb[i - 1];
+                    if (j + 2 <= N - 1) { out_f = max64(out_f, sf[j + 2]); out_b = max64(out_b, sb[j + 2]); }
+                }
+                v0 = max64(max64(x0, y0), max64(out_f, in_b));
+                v1 = max64(max64(x1, y1), max64(out_b, in_f));
+            }
+            for (int32_t o = 0; o <= directed; ++o) {
+                int64_t v = o ? v1 : v0;
+                int64_t id = cco_move_id(N, objective, i, j, o);
+                if (all_values) all_values[nvals] = v;
+                ++nvals;
+                if (!found || v < best->value || (v == best->value && id < best->id)) {
+                    best->value = v; best->id = id; best->i = i; best->j = j; best->o = o;
+                    found = 1;
+                }
+            }
+        }
+    }
+    return found;
+}
+
+/* Number of moves in the neighbourhood: N(N-3)/2 undirected, N(N-3) directed. */
+int64_t cco_neighbourhood_size(int32_t N, int32_t objective)
+{
+    if (N < 4) return 0;
+    int64_t m = (int64_t)N * (N - 3) / 2;
+    return (objective & 2) ? 2 * m : m;
+}
+
+/* Values of every move in increasing id order (delta tier), for checking against the definition. */
+int cco_all_move_values(const int32_t *c, int32_t N, int32_t objective, const int32_t *t, int64_t *values)
+{
+    int64_t *ws = (int64_t *)malloc(sizeof(int64_t) * 6 * (size_t)N);
+    if (!ws) return CCO_ERR_NOMEM;
+    cco_best best;
+    scan_moves(c, N, objective, t, cco_ring_cost(c, N, t, objective), ws, &best, values);
+    free(ws);
+    return CCO_OK;
+}
+
+static int is_symmetric(const int32_t *c, int32_t N)
+{
+    for (int32_t a = 0; a < N; ++a)
+        for (int32_t b2 = a + 1; b2 < N; ++b2)
+            if (c[(int64_t)a * N + b2] != c[(int64_t)b2 * N + a]) return 0;
+    return 1;
+}
+
+/* One best-improvement descent: score the whole neighbourhood, take the lexicographically smallest
+ * (value, id); apply it if it strictly lowers the cost, else stop.  `use_definition` scores every
+ * move by apply-and-recompute instead of the delta formulas (tests compare the two trajectories).
+ * trace (optional, capacity trace_cap): ids of the applied moves. */
+int cco_2opt_descend(const int32_t *c, int32_t N, int32_t objective, int32_t *t, int64_t *cost,
+                     int32_t *moves, int32_t use_definition, int64_t *trace, int32_t trace_cap)
+{
+    if (!c || !t || N < 2 || objective < 0 || objective > 3) return CCO_ERR_ARG;
+    int64_t *ws = (int64_t *)malloc(sizeof(int64_t) * 6 * (size_t)N);
+    if (!ws) return CCO_ERR_NOMEM;
+    const int directed = (objective & 2) != 0;
+    int64_t cur = cco_ring_cost(c, N, t, objective);
+    int32_t applied = 0;
+    for (;;) {
+        cco_best best;
+        int found;
+        if (!use_definition) {
+            found = scan_moves(c, N, objective, t, cur, ws, &best, NULL);
+        } else {
+            found = 0;
+            for (int32_t i = 1; i <= N - 2; ++i)
+                for (int32_t j = i + 1; j <= N - 1; ++j) {
+                    if (i == 1 && j == N - 1) continue;
+                    for (int32_t o = 0; o <= directed; ++o) {
+                        int64_t v = cco_move_value_by_definition(c, N, objective, t, i, j, o);
+                        int64_t id = cco_move_id(N, objective, i, j, o);
+                        if (!found || v < best.value || (v == best.value && id < best.id)) {
+                            best.value = v; best.id = id; best.i = i; best.j = j; best.o = o; found = 1;
+                        }
+                    }
+                }
+        }
+        if (!found || best.value >= cur) break;
+        cco_apply_move(t, N, best.i, best.j, best.o);
+        cur = best.value;
+        if (trace && applied < trace_cap) trace[applied] = best.id;
+        ++applied;
+    }
+    free(ws);
+    *cost = cur;
+    if (moves) *moves = applied;
+    return CCO_OK;
+}
+
+/* Restarts [r0, r1) of a multi-start search.  Per-restart outputs are indexed by r - r0.
+ * init_tours (optional, [restarts_total, N], indexed by r) overrides the seeded shuffle.
+ * Undirected objectives require a symmetric matrix. */
+int cco_2opt_restarts(const int32_t *c, int32_t N, int32_t objective, uint64_t seed, int64_t r0, int64_t r1,
+                      const int32_t *init_tours, int64_t *restart_costs, int32_t *restart_tours,
+                      int32_t *restart_moves)
+{
+    if (!c || N < 2 || objective < 0 || objective > 3 || r0 < 0 || r1 < r0) return CCO_ERR_ARG;
+    if (!(objective & 2) && !is_symmetric(c, N)) return CCO_ERR_NOT_SYMMETRIC;
+    int32_t *t = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    if (!t) return CCO_ERR_NOMEM;
+    for (int64_t r = r0; r < r1; ++r) {
+        if (init_tours) memcpy(t, init_tours + r * N, sizeof(int32_t) * (size_t)N);
+        else cco_init_tour(seed, (uint32_t)r, N, t);
+        int64_t cost; int32_t mv;
+        int rc = cco_2opt_descend(c, N, objective, t, &cost, &mv, 0, NULL, 0);
+        if (rc != CCO_OK) { free(t); return rc; }
+        if (restart_costs) restart_costs[r - r0] = cost;
+        if (restart_moves) restart_moves[r - r0] = mv;
+        if (restart_tours) memcpy(restart_tours + (r - r0) * N, t, sizeof(int32_t) * (size_t)N);
+    }
+    free(t);
+    return CCO_OK;
+}
+
+/* Whole search: all restarts, then the lexicographic minimum of (final cost, restart id). */
+int cco_2opt_search(const int32_t *c, int32_t N, int32_t objective, int32_t restarts, uint64_t seed,
+                    const int32_t *init_tours, int32_t *best_perm, int64_t *best_cost, int32_t *best_restart,
+                    int64_t *restart_costs, int32_t *restart_tours, int32_t *restart_moves)
+{
+    if (restarts < 1 || !best_perm || !best_cost) return CCO_ERR_ARG;
+    int64_t *costs = restart_costs ? restart_costs : (int64_t *)malloc(sizeof(int64_t) * (size_t)restarts);
+    int32_t *tours = restart_tours ? restart_tours : (int32_t *)malloc(sizeof(int32_t) * (size_t)restarts * N);
+    if (!costs || !tours) return CCO_ERR_NOMEM;
+    int rc = cco_2opt_restarts(c, N, objective, seed, 0, restarts, init_tours, costs, tours, restart_moves);
+    if (rc == CCO_OK) {
+        int32_t arg = 0;
+        for (int32_t r = 1; r < restarts; ++r) if (costs[r] < costs[arg]) arg = r;
+        *best_cost = costs[arg];
+        if (best_restart) *best_restart = arg;
+        memcpy(best_perm, tours + (int64_t)arg * N, sizeof(int32_t) * (size_t)N);
+    }
+    if (!restart_costs) free(costs);
+    if (!restart_tours) free(tours);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * Exhaustive reference for N <= 12: every ring with t[0] = 0, in lexicographic order of t[1..N-1];
+ * half_only = 1 keeps one of each mirror pair (t[1] < t[N-1]) for symmetric matrices.
+ * Reports the number of rings visited, the minimum cost and the first ring that attains it; if
+ * all_rings / all_costs are given (capacity cap) also every ring visited and its cost, in order.
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct {
+    const int32_t *c; int32_t N, objective, half_only;
+    int64_t count, best_cost; int32_t *best; int32_t *all_rings; int64_t *all_costs; int64_t cap;
+    int32_t t[16]; uint8_t used[16];
+} enum_state;
+
+static void enum_rec(enum_state *s, int32_t depth)
+{
+    const int32_t N = s->N;
+    if (depth == N) {
+        if (s->half_only && N > 2 && !(s->t[1] < s->t[N - 1])) return;
+        int64_t v = cco_ring_cost(s->c, N, s->t, s->objective);
+        if (s->count < s->cap) {
+            if (s->all_rings) memcpy(s->all_rings + s->count * N, s->t, sizeof(int32_t) * (size_t)N);
+            if (s->all_costs) s->all_costs[s->count] = v;
+        }
+        if (s->count == 0 || v < s->best_cost) {
+            s->best_cost = v;
+            if (s->best) memcpy(s->best, s->t, sizeof(int32_t) * (size_t)N);
+        }
+        ++s->count;
+        return;
+    }
+    for (int32_t v = 1; v < N; ++v) {
+        if (s->used[v]) continue;
+        s->used[v] = 1; s->t[depth] = v;
+        enum_rec(s, depth + 1);
+        s->used[v] = 0;
+    }
+}
+
+int cco_exhaustive_rings(const int32_t *c, int32_t N, int32_t objective, int32_t half_only, int64_t *count,
+                         int64_t *best_cost, int32_t *best_ring, int32_t *all_rings, int64_t *all_costs,
+                         int64_t cap)
+{
+    if (!c || N < 2 || N > 12) return CCO_ERR_ARG;
+    enum_state s;
+    memset(&s, 0, sizeof s);
+    s.c = c; s.N = N; s.objective = objective; s.half_only = half_only;
+    s.best = best_ring; s.all_rings = all_rings; s.all_costs = all_costs; s.cap = cap;
+    s.t[0] = 0; s.used[0] = 1;
+    enum_rec(&s, 1);
+    if (count) *count = s.count;
+    if (best_cost) *best_cost = s.best_cost;
+    return CCO_OK;
+}

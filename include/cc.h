@@ -1,0 +1,147 @@
+/*
+ * cc.h -- C ABI of the rank-order search library for MI355X (gfx950).
+ *
+ * Problem (paper Section 4): N nodes, a measured N x N point-to-point cost matrix c, a collective
+ * algorithm whose cost model is a function of the rank order; find a permutation of the node list
+ * that minimises the model.  This library evaluates the ring and halving-doubling cost models over
+ * batches of candidate orders and runs many independent 2-opt local searches over the ring.
+ *
+ * Conventions
+ *   - Every buffer pointer is a DEVICE pointer owned by the caller unless stated otherwise.  The
+ *     library never frees or keeps caller memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work on
+ *     it and return; results are valid once the caller has synchronised the stream.  Only
+ *     cc_validate_matrix synchronises by itself.
+ *   - cost_matrix: row-major int32 [N, N]; cost_matrix[a*N + b] = cost of node a talking to node b
+ *     (the flattened c'_{iN+j} of Section 4.3).  Entries must satisfy 0 <= c <= CC_COST_MAX.
+ *   - A rank order ("perm", "tour") is int32 [N]; perm[p] = original node placed at rank p (the r_p of
+ *     Section 4.3).  The reordered node list is new_list[p] = old_list[perm[p]].
+ *   - Return value: CC_OK (0) or a negative cc_status.  Argument errors are detected on the host
+ *     before anything is launched.  Data errors (entries out of range, indices out of range, an
+ *     asymmetric matrix given to an undirected objective) are not detected by the compute calls:
+ *     results are then unspecified, but all memory accesses stay inside the caller's buffers
+ *     (indices are clamped).  cc_validate_matrix checks the matrix contract.
+ *   - All arithmetic is exact integer; costs are returned as int64.
+ */
+#ifndef CC_H_
+#define CC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CC_MAX_N 1024
+#define CC_COST_MAX ((1 << 21) - 1)
+
+typedef enum {
+    CC_OK = 0,
+    CC_ERR_INVALID_ARG = -1,     /* null required pointer, negative count, bad objective, misaligned pointer */
+    CC_ERR_UNSUPPORTED_N = -2,   /* N < 2, N > CC_MAX_N, or (halving-doubling) N not a power of two */
+    CC_ERR_WORKSPACE = -3,       /* workspace missing or smaller than cc_2opt_workspace_bytes() */
+    CC_ERR_HIP = -4,             /* a HIP runtime call failed; see cc_last_hip_error() */
+    CC_ERR_NOT_SYMMETRIC = -5,   /* cc_validate_matrix: matrix is not symmetric */
+    CC_ERR_COST_RANGE = -6       /* cc_validate_matrix: an entry is outside [0, CC_COST_MAX] */
+} cc_status;
+
+/* Objectives over the ring (Section 4.1, ring model).  SUM is the paper's sum of hop costs; MAX is
+ * the largest hop (the bottleneck transfer on the critical path, Sections 5.3 and 6).  The DIRECTED
+ * variants make the local search score every move for both walking directions of the resulting
+ * ring, for matrices with c[a][b] != c[b][a]. */
+typedef enum {
+    CC_RING_SUM = 0,
+    CC_RING_MAX = 1,
+    CC_RING_SUM_DIRECTED = 2,
+    CC_RING_MAX_DIRECTED = 3
+} cc_objective;
+
+/*
+ * Ring cost model (Section 4.1, equation C_r): for each of the B orders,
+ *     out_costs[b] = sum over ranks p of c[perm_b[p]][perm_b[(p-1) mod N]]      (objective SUM)
+ *     out_costs[b] = max over ranks p of the same hops                          (objective MAX)
+ * The DIRECTED bit of `objective` is ignored (evaluation is always directional).
+ * perms: int32 [B, N] row-major; out_costs: int64 [B].  2 <= N <= CC_MAX_N.  B = 0 is a no-op.
+ */
+int cc_ring_cost_batch(const int32_t* cost_matrix, int32_t N, int32_t objective, const int32_t* perms,
+                       int64_t B, int64_t* out_costs, void* stream);
+
+/*
+ * Halving-doubling (recursive-doubling) cost model (Section 4.1, equation C_hd, with every round
+ * weighted equally as in the latency-only view of Section 4.2):
+ *     out_costs[b] = sum over k in [0, log2 N) of  max over ranks i of c[perm_b[i]][perm_b[i xor 2^k]]
+ * N must be a power of two (Section 4.1 assumes it), 2 <= N <= CC_MAX_N.
+ */
+int cc_rd_cost_batch(const int32_t* cost_matrix, int32_t N, const int32_t* perms, int64_t B,
+                     int64_t* out_costs, void* stream);
+
+/*
+ * Multi-start 2-opt search for a ring order (Section 4.3: stochastic neighbour search started from
+ * random orders, neighbours obtained by permuting a sub-array; here the deterministic
+ * best-improvement form).
+ *
+ *   Moves.  Rank 0 is an anchor.  Move (i, j, o), 1 <= i < j <= N-1, (i, j) != (1, N-1): reverse
+ *   perm[i..j]; if o = 1 also reverse perm[1..N-1] (the same ring walked the other way).  Undirected
+ *   objectives use o = 0 only.  Move id = i*N + j (undirected) or (i*N + j)*2 + o (directed).
+ *   The value of a move is the objective of the order it produces.
+ *   One restart.  Score every move; take the lexicographically smallest (value, id); if the value is
+ *   strictly below the current cost apply the move and repeat, otherwise stop.
+ *   Restarts.  Restart r starts from the Fisher-Yates shuffle of the identity driven by SplitMix64:
+ *   for k = N-1 down to 1, u = high 32 bits of output number ((r << 32) | k) + 1 of the generator
+ *   started at state `seed`, swap perm[k] with perm[(u * (k+1)) >> 32].
+ *   Result.  The lexicographically smallest (final cost, r); best_perm (int32 [N]) receives that
+ *   restart's final order as it stands, best_cost (int64 [1]) its cost.
+ *
+ * N < 4 has no moves: the result is restart 0's initial order.  Undirected objectives require a
+ * symmetric matrix.  This call allocates its workspace from the stream-ordered device allocator.
+ */
+int cc_2opt_search(const int32_t* cost_matrix, int32_t N, int32_t objective, int32_t restarts, uint64_t seed,
+                   int32_t* best_perm, int64_t* best_cost, void* stream);
+
+/*
+ * The same search with caller-provided workspace and optional extra outputs.
+ *   init_tours     int32 [restarts, N] or NULL.  NULL: generate from `seed` as above.
+ *   best_restart   int32 [1] or NULL: index of the winning restart.
+ *   restart_costs  int64 [restarts] or NULL: final cost of every restart.
+ *   restart_tours  int32 [restarts, N] or NULL: final order of every restart.
+ *   restart_moves  int32 [restarts] or NULL: number of moves each restart applied.
+ *   workspace      device memory, 256-byte aligned, at least cc_2opt_workspace_bytes(N, objective,
+ *                  restarts) bytes; contents on entry are irrelevant and on exit unspecified.
+ * best_perm and best_cost are required.
+ */
+int cc_2opt_search_ex(const int32_t* cost_matrix, int32_t N, int32_t objective, int32_t restarts,
+                      uint64_t seed, const int32_t* init_tours, int32_t* best_perm, int64_t* best_cost,
+                      int32_t* best_restart, int64_t* restart_costs, int32_t* restart_tours,
+                      int32_t* restart_moves, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace cc_2opt_search_ex needs (0 on invalid arguments). Host-only computation. */
+size_t cc_2opt_workspace_bytes(int32_t N, int32_t objective, int32_t restarts);
+
+/*
+ * Initial orders of restarts first .. first+count-1 for `seed` (the shuffle described above);
+ * tours: int32 [count, N].  Also the generator of the seeded random orders used to exercise the
+ * batch calls.
+ */
+int cc_init_tours(int32_t N, int64_t first, int64_t count, uint64_t seed, int32_t* tours, void* stream);
+
+/*
+ * Checks the matrix contract: every entry in [0, CC_COST_MAX], and, if require_symmetric != 0,
+ * c[a][b] == c[b][a].  Synchronises `stream` and returns CC_OK, CC_ERR_COST_RANGE or
+ * CC_ERR_NOT_SYMMETRIC.  Allocates and frees four bytes of device memory.
+ */
+int cc_validate_matrix(const int32_t* cost_matrix, int32_t N, int32_t require_symmetric, void* stream);
+
+/* Static, human-readable text for a cc_status value (host pointer, never freed). */
+const char* cc_status_string(int status);
+
+/* hipError_t of the most recent failing HIP call made by this library on the calling thread (0 = none). */
+int cc_last_hip_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int cc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CC_H_ */

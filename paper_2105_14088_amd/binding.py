@@ -1,0 +1,208 @@
+"""ctypes binding of libcc.so (C ABI in include/cc.h).  Argument marshalling only: every step of the
+computation runs in the library's HIP kernels.  torch supplies device memory and streams.
+
+There is no CPU fallback: if the shared library is missing or a tensor is not on the GPU the call
+raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcc.so")
+
+CC_RING_SUM, CC_RING_MAX, CC_RING_SUM_DIRECTED, CC_RING_MAX_DIRECTED = 0, 1, 2, 3
+OBJECTIVES = {"sum": 0, "max": 1, "sum_directed": 2, "max_directed": 3}
+CC_MAX_N = 1024
+CC_COST_MAX = (1 << 21) - 1
+
+# every symbol include/cc.h declares
+EXPORTS = ["cc_ring_cost_batch", "cc_rd_cost_batch", "cc_2opt_search", "cc_2opt_search_ex",
+           "cc_2opt_workspace_bytes", "cc_init_tours", "cc_validate_matrix", "cc_status_string",
+           "cc_last_hip_error", "cc_version"]
+
+
+class CCError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().cc_status_string(status).decode()
+        if status == -4:
+            msg += f" (hipError {lib().cc_last_hip_error()})"
+        super().__init__(f"{where}: {msg} [{status}]")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libcc.so built in-tree (python -m paper_2105_14088_amd.build); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} not built: run `python __graft_entry__.py build` "
+                                    "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        i32, i64, u64, p, sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_size_t
+        L.cc_ring_cost_batch.restype = ctypes.c_int
+        L.cc_ring_cost_batch.argtypes = [p, i32, i32, p, i64, p, p]
+        L.cc_rd_cost_batch.restype = ctypes.c_int
+        L.cc_rd_cost_batch.argtypes = [p, i32, p, i64, p, p]
+        L.cc_2opt_search.restype = ctypes.c_int
+        L.cc_2opt_search.argtypes = [p, i32, i32, i32, u64, p, p, p]
+        L.cc_2opt_search_ex.restype = ctypes.c_int
+        L.cc_2opt_search_ex.argtypes = [p, i32, i32, i32, u64, p, p, p, p, p, p, p, p, sz, p]
+        L.cc_2opt_workspace_bytes.restype = sz
+        L.cc_2opt_workspace_bytes.argtypes = [i32, i32, i32]
+        L.cc_init_tours.restype = ctypes.c_int
+        L.cc_init_tours.argtypes = [i32, i64, i64, u64, p, p]
+        L.cc_validate_matrix.restype = ctypes.c_int
+        L.cc_validate_matrix.argtypes = [p, i32, i32, p]
+        L.cc_status_string.restype = ctypes.c_char_p
+        L.cc_status_string.argtypes = [ctypes.c_int]
+        L.cc_last_hip_error.restype = ctypes.c_int
+        L.cc_last_hip_error.argtypes = []
+        L.cc_version.restype = ctypes.c_int
+        L.cc_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _dev(t: Optional[torch.Tensor], dtype, name: str):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a GPU tensor")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous {dtype} tensor")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _matrix(c: torch.Tensor) -> int:
+    if c.dim() != 2 or c.shape[0] != c.shape[1]:
+        raise ValueError("cost_matrix must be square")
+    return int(c.shape[0])
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise CCError(rc, where)
+
+
+def cc_ring_cost_batch(cost_matrix: torch.Tensor, perms: torch.Tensor, objective: int = CC_RING_SUM,
+                       out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    n = _matrix(cost_matrix)
+    if perms.dim() != 2 or perms.shape[1] != n:
+        raise ValueError("perms must be [B, N]")
+    b = int(perms.shape[0])
+    if out is None:
+        out = torch.empty(b, dtype=torch.int64, device=cost_matrix.device)
+    _check(lib().cc_ring_cost_batch(_dev(cost_matrix, torch.int32, "cost_matrix"), n, objective,
+                                    _dev(perms, torch.int32, "perms"), b, _dev(out, torch.int64, "out"),
+                                    _stream(stream)), "cc_ring_cost_batch")
+    return out
+
+
+def cc_rd_cost_batch(cost_matrix: torch.Tensor, perms: torch.Tensor, out: Optional[torch.Tensor] = None,
+                     stream=None) -> torch.Tensor:
+    n = _matrix(cost_matrix)
+    if perms.dim() != 2 or perms.shape[1] != n:
+        raise ValueError("perms must be [B, N]")
+    b = int(perms.shape[0])
+    if out is None:
+        out = torch.empty(b, dtype=torch.int64, device=cost_matrix.device)
+    _check(lib().cc_rd_cost_batch(_dev(cost_matrix, torch.int32, "cost_matrix"), n, _dev(perms, torch.int32, "perms"),
+                                  b, _dev(out, torch.int64, "out"), _stream(stream)), "cc_rd_cost_batch")
+    return out
+
+
+def cc_2opt_workspace_bytes(n: int, objective: int, restarts: int) -> int:
+    return int(lib().cc_2opt_workspace_bytes(n, objective, restarts))
+
+
+def cc_2opt_search(cost_matrix: torch.Tensor, objective: int, restarts: int, seed: int, stream=None):
+    """Returns (best_perm int32[N], best_cost int64[1]) device tensors (valid after stream sync)."""
+    n = _matrix(cost_matrix)
+    best_perm = torch.empty(n, dtype=torch.int32, device=cost_matrix.device)
+    best_cost = torch.empty(1, dtype=torch.int64, device=cost_matrix.device)
+    _check(lib().cc_2opt_search(_dev(cost_matrix, torch.int32, "cost_matrix"), n, objective, restarts,
+                                seed & (2**64 - 1), _dev(best_perm, torch.int32, "best_perm"),
+                                _dev(best_cost, torch.int64, "best_cost"), _stream(stream)), "cc_2opt_search")
+    return best_perm, best_cost
+
+
+class SearchBuffers:
+    """Device buffers for cc_2opt_search_ex, allocated once and reusable across calls."""
+
+    def __init__(self, n: int, objective: int, restarts: int, device, per_restart: bool = True):
+        self.n, self.objective, self.restarts = n, objective, restarts
+        self.best_perm = torch.empty(n, dtype=torch.int32, device=device)
+        self.best_cost = torch.empty(1, dtype=torch.int64, device=device)
+        self.best_restart = torch.empty(1, dtype=torch.int32, device=device)
+        self.restart_costs = torch.empty(restarts, dtype=torch.int64, device=device) if per_restart else None
+        self.restart_tours = torch.empty((restarts, n), dtype=torch.int32, device=device) if per_restart else None
+        self.restart_moves = torch.empty(restarts, dtype=torch.int32, device=device) if per_restart else None
+        nbytes = cc_2opt_workspace_bytes(n, objective, restarts)
+        if nbytes == 0:
+            raise ValueError("invalid (N, objective, restarts)")
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+        off = (-self.workspace.data_ptr()) % 256
+        self.ws_ptr = self.workspace.data_ptr() + off
+        self.ws_bytes = nbytes
+
+
+def cc_2opt_search_ex(cost_matrix: torch.Tensor, objective: int, restarts: int, seed: int,
+                      init_tours: Optional[torch.Tensor] = None, buffers: Optional[SearchBuffers] = None,
+                      stream=None) -> SearchBuffers:
+    n = _matrix(cost_matrix)
+    if buffers is None:
+        buffers = SearchBuffers(n, objective, restarts, cost_matrix.device)
+    if (buffers.n, buffers.restarts) != (n, restarts):
+        raise ValueError("buffers were sized for a different search")
+    if init_tours is not None and tuple(init_tours.shape) != (restarts, n):
+        raise ValueError("init_tours must be [restarts, N]")
+    b = buffers
+    _check(lib().cc_2opt_search_ex(_dev(cost_matrix, torch.int32, "cost_matrix"), n, objective, restarts,
+                                   seed & (2**64 - 1), _dev(init_tours, torch.int32, "init_tours"),
+                                   _dev(b.best_perm, torch.int32, "best_perm"),
+                                   _dev(b.best_cost, torch.int64, "best_cost"),
+                                   _dev(b.best_restart, torch.int32, "best_restart"),
+                                   _dev(b.restart_costs, torch.int64, "restart_costs"),
+                                   _dev(b.restart_tours, torch.int32, "restart_tours"),
+                                   _dev(b.restart_moves, torch.int32, "restart_moves"),
+                                   ctypes.c_void_p(b.ws_ptr), b.ws_bytes, _stream(stream)), "cc_2opt_search_ex")
+    return b
+
+
+def cc_init_tours(n: int, count: int, seed: int, first: int = 0, device="cuda", out: Optional[torch.Tensor] = None,
+                  stream=None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty((count, n), dtype=torch.int32, device=device)
+    _check(lib().cc_init_tours(n, first, count, seed & (2**64 - 1), _dev(out, torch.int32, "tours"), _stream(stream)),
+           "cc_init_tours")
+    return out
+
+
+def cc_validate_matrix(cost_matrix: torch.Tensor, require_symmetric: bool = True, stream=None) -> int:
+    """Returns the status code (0 ok, -5 not symmetric, -6 out of range); raises on other errors."""
+    n = _matrix(cost_matrix)
+    rc = lib().cc_validate_matrix(_dev(cost_matrix, torch.int32, "cost_matrix"), n, 1 if require_symmetric else 0,
+                                  _stream(stream))
+    if rc not in (0, -5, -6):
+        raise CCError(rc, "cc_validate_matrix")
+    return rc
+
+
+def cc_status_string(status: int) -> str:
+    return lib().cc_status_string(status).decode()
+
+
+def cc_version() -> int:
+    return int(lib().cc_version())

@@ -1,0 +1,263 @@
+// Multi-start best-improvement 2-opt over the ring (Section 4.3 neighbour search; move set, value
+// and tie-break rules as stated in cc.h).
+//
+// General kernel: one workgroup per restart, one thread per rank.  Tour, hop arrays and the prefix /
+// suffix tables live in LDS; thread j scores the moves (i, j) for i = j-1 down to 1 so that the
+// "inside the reversed span" aggregate grows by one hop per step; keys (value << 32 | move id) are
+// min-reduced over the workgroup, which makes the lowest-id tie-break independent of the order in
+// which moves are visited.  Handles every objective and every N <= 1024; the matrix is gathered
+// through L2.
+#include "cc_device.h"
+#include "cc_internal.h"
+
+namespace cc {
+using namespace ccd;
+
+namespace {
+
+constexpr unsigned long long kNoMove = ~0ull;
+
+template <bool IS_MAX>
+__device__ __forceinline__ int comb(int a, int b) { return IS_MAX ? max(a, b) : a + b; }
+
+// In-place inclusive scan over arr[0..N) (forward: arr[p] = op(arr[0..p]); backward: op(arr[p..N-1])).
+// Every thread of the workgroup must call it; blockDim.x >= N.
+template <bool IS_MAX, bool BACKWARD>
+__device__ void block_scan(int32_t* arr, int N) {
+    const int p = threadIdx.x;
+    for (int off = 1; off < N; off <<= 1) {
+        int v = 0, w = 0;
+        bool has = false;
+        if (p < N) {
+            v = arr[p];
+            const int src = BACKWARD ? p + off : p - off;
+            has = BACKWARD ? (src < N) : (src >= 0);
+            if (has) w = arr[src];
+        }
+        __syncthreads();
+        if (p < N && has) arr[p] = comb<IS_MAX>(v, w);
+        __syncthreads();
+    }
+}
+
+template <int OBJ>
+__global__ void twoopt_general_kernel(const int32_t* __restrict__ c, int N, int32_t* __restrict__ tours,
+                                      int64_t* __restrict__ costs, int32_t* __restrict__ moves) {
+    constexpr bool IS_MAX = (OBJ & 1) != 0;
+    constexpr bool DIRECTED = (OBJ & 2) != 0;
+    extern __shared__ int32_t sm[];
+    int32_t* t = sm;           // tour
+    int32_t* f = t + N;        // f[p] = c[t[p]][t[p-1]]
+    int32_t* b = f + N;        // b[p] = c[t[p-1]][t[p]]
+    int32_t* pf = b + N;       // SUM: inclusive prefix sum of f;  MAX: max f over ranks 1..p (0 at p = 0)
+    int32_t* pb = pf + N;      // same for b
+    int32_t* sf = pb + N;      // MAX: max f over ranks p..N-1
+    int32_t* sb = sf + N;      // same for b
+    __shared__ unsigned long long red[16];
+    __shared__ unsigned long long winner;
+    __shared__ int red_cost[16];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wv = tid >> 6, nwv = blockDim.x >> 6;
+    const int64_t r = blockIdx.x;
+    if (tid < N) t[tid] = clampi(tours[r * N + tid], 0, N - 1);
+    __syncthreads();
+
+    int cur = 0;
+    int applied = 0;
+    bool first = true;
+    for (;;) {
+        // ---- hop arrays and tables for the current tour
+        int myf = 0;
+        if (tid < N) {
+            const int a = t[tid], pr = t[tid ? tid - 1 : N - 1];
+            myf = c[a * N + pr];
+            f[tid] = myf;
+            if (DIRECTED) b[tid] = c[pr * N + a];
+            if (DIRECTED || IS_MAX) {
+                pf[tid] = (IS_MAX && tid == 0) ? 0 : myf;
+                if (IS_MAX) sf[tid] = myf;
+            }
+        }
+        __syncthreads();
+        if (DIRECTED && tid < N) {
+            pb[tid] = (IS_MAX && tid == 0) ? 0 : b[tid];
+            if (IS_MAX) sb[tid] = b[tid];
+        }
+        if (DIRECTED || IS_MAX) {
+            __syncthreads();
+            block_scan<IS_MAX, false>(pf, N);
+            if (DIRECTED) block_scan<IS_MAX, false>(pb, N);
+            if (IS_MAX) {
+                block_scan<true, true>(sf, N);
+                if (DIRECTED) block_scan<true, true>(sb, N);
+            }
+        }
+        if (first) {   // cost of the initial tour (afterwards the winning move's value is the cost)
+            int v = IS_MAX ? wave_max(myf) : wave_sum(myf);
+            if (lane == 0) red_cost[wv] = v;
+            __syncthreads();
+            v = 0;
+            for (int k = 0; k < nwv; ++k) v = comb<IS_MAX>(v, red_cost[k]);
+            cur = v;
+            first = false;
+        }
+
+        // ---- score column j = tid of the neighbourhood
+        unsigned long long best = kNoMove;
+        const int j = tid;
+        if (j >= 2 && j < N) {
+            const int q = (j + 1 == N) ? 0 : j + 1;
+            const int tj = t[j], tq = t[q];
+            const int fq = f[q];
+            const int bq = DIRECTED ? b[q] : 0;
+            const int tot_f = (!IS_MAX && DIRECTED) ? pf[N - 1] : 0;
+            const int tot_b = (!IS_MAX && DIRECTED) ? pb[N - 1] : 0;
+            const int pfj = (!IS_MAX && DIRECTED) ? pf[j] : 0;
+            const int pbj = (!IS_MAX && DIRECTED) ? pb[j] : 0;
+            // MAX: hops outside the span on the far side (ranks j+2..N-1) and rank 0 unless it is q
+            int far_f = 0, far_b = 0;
+            if (IS_MAX && q != 0) {
+                far_f = f[0];
+                if (j + 2 <= N - 1) far_f = max(far_f, sf[j + 2]);
+                if (DIRECTED) {
+                    far_b = b[0];
+                    if (j + 2 <= N - 1) far_b = max(far_b, sb[j + 2]);
+                }
+            }
+            int in_f = 0, in_b = 0;
+            for (int i = j - 1; i >= 1; --i) {
+                if (IS_MAX) {                       // inside = ranks i+1..j
+                    in_f = max(in_f, f[i + 1]);
+                    if (DIRECTED) in_b = max(in_b, b[i + 1]);
+                }
+                if (i == 1 && j == N - 1) continue;
+                const int ti = t[i], tim = t[i - 1];
+                const int x0 = c[tj * N + tim], y0 = c[tq * N + ti];
+                int v0, v1 = 0;
+                if (!IS_MAX && !DIRECTED) {
+                    v0 = cur + x0 + y0 - f[i] - fq;
+                } else if (!IS_MAX) {
+                    const int x1 = c[tim * N + tj], y1 = c[ti * N + tq];
+                    const int inf = pfj - pf[i], inb = pbj - pb[i];
+                    const int outf = tot_f - f[i] - fq - inf, outb = tot_b - b[i] - bq - inb;
+                    v0 = x0 + y0 + outf + inb;
+                    v1 = x1 + y1 + outb + inf;
+                } else if (!DIRECTED) {
+                    const int outf = max(far_f, pf[i - 1]);
+                    v0 = max(max(x0, y0), max(outf, in_f));
+                } else {
+                    const int x1 = c[tim * N + tj], y1 = c[ti * N + tq];
+                    const int outf = max(far_f, pf[i - 1]), outb = max(far_b, pb[i - 1]);
+                    v0 = max(max(x0, y0), max(outf, in_b));
+                    v1 = max(max(x1, y1), max(outb, in_f));
+                }
+                const unsigned id = (unsigned)(i * N + j);
+                if (DIRECTED) {
+                    const unsigned long long k0 = ((unsigned long long)(unsigned)v0 << 32) | (id * 2u);
+                    const unsigned long long k1 = ((unsigned long long)(unsigned)v1 << 32) | (id * 2u + 1u);
+                    best = min(best, min(k0, k1));
+                } else {
+                    best = min(best, ((unsigned long long)(unsigned)v0 << 32) | id);
+                }
+            }
+        }
+        best = wave_min_u64(best);
+        if (lane == 0) red[wv] = best;
+        __syncthreads();
+        if (tid == 0) {
+            unsigned long long m = red[0];
+            for (int k = 1; k < nwv; ++k) m = min(m, red[k]);
+            winner = m;
+        }
+        __syncthreads();
+        const unsigned long long win = winner;
+        if (win == kNoMove || (long long)(win >> 32) >= (long long)cur) break;
+
+        // ---- apply the winning move: new[p] = old[src(p)]
+        unsigned id = (unsigned)(win & 0xffffffffu);
+        const int o = DIRECTED ? (int)(id & 1u) : 0;
+        if (DIRECTED) id >>= 1;
+        const int mi = (int)(id / (unsigned)N), mj = (int)(id % (unsigned)N);
+        int val = 0;
+        if (tid < N) {
+            const int p0 = o ? (tid == 0 ? 0 : N - tid) : tid;
+            const int src = (p0 >= mi && p0 <= mj) ? mi + mj - p0 : p0;
+            val = t[src];
+        }
+        __syncthreads();
+        if (tid < N) t[tid] = val;
+        __syncthreads();
+        cur = (int)(win >> 32);
+        ++applied;
+    }
+    if (tid < N) tours[r * N + tid] = t[tid];
+    if (tid == 0) {
+        costs[r] = (int64_t)cur;
+        moves[r] = applied;
+    }
+}
+
+// Lexicographic minimum of (cost, restart) over all restarts; copies the winner's tour.
+__global__ __launch_bounds__(256) void best_restart_kernel(const int64_t* __restrict__ costs,
+                                                           const int32_t* __restrict__ tours, int N, int restarts,
+                                                           int32_t* __restrict__ best_perm,
+                                                           int64_t* __restrict__ best_cost,
+                                                           int32_t* __restrict__ best_restart) {
+    __shared__ long long sc[256];
+    __shared__ int sr[256];
+    const int tid = threadIdx.x;
+    long long bc = 0x7fffffffffffffffll;
+    int br = 0x7fffffff;
+    for (int r = tid; r < restarts; r += 256) {
+        const long long v = costs[r];
+        if (v < bc || (v == bc && r < br)) { bc = v; br = r; }
+    }
+    sc[tid] = bc;
+    sr[tid] = br;
+    __syncthreads();
+    for (int s = 128; s >= 1; s >>= 1) {
+        if (tid < s) {
+            const long long v = sc[tid + s];
+            const int r = sr[tid + s];
+            if (v < sc[tid] || (v == sc[tid] && r < sr[tid])) { sc[tid] = v; sr[tid] = r; }
+        }
+        __syncthreads();
+    }
+    const int win = sr[0];
+    for (int p = tid; p < N; p += 256) best_perm[p] = tours[(int64_t)win * N + p];
+    if (tid == 0) {
+        best_cost[0] = sc[0];
+        if (best_restart) best_restart[0] = win;
+    }
+}
+
+template <int OBJ>
+hipError_t launch_general(const int32_t* c, int N, int restarts, int32_t* tours, int64_t* costs, int32_t* moves,
+                          hipStream_t s) {
+    const int threads = ((N + 63) / 64) * 64;
+    const size_t lds = sizeof(int32_t) * 7 * (size_t)N;
+    hipLaunchKernelGGL((twoopt_general_kernel<OBJ>), dim3(restarts), dim3(threads), lds, s, c, N, tours, costs, moves);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, int32_t* tours, int64_t* costs,
+                       int32_t* moves, int32_t* flags, int32_t* best_perm, int64_t* best_cost,
+                       int32_t* best_restart, hipStream_t s) {
+    (void)flags;
+    hipError_t e;
+    switch (objective) {
+        case 0: e = launch_general<0>(c, N, restarts, tours, costs, moves, s); break;
+        case 1: e = launch_general<1>(c, N, restarts, tours, costs, moves, s); break;
+        case 2: e = launch_general<2>(c, N, restarts, tours, costs, moves, s); break;
+        default: e = launch_general<3>(c, N, restarts, tours, costs, moves, s); break;
+    }
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(best_restart_kernel, dim3(1), dim3(256), 0, s, costs, tours, N, restarts, best_perm, best_cost,
+                       best_restart);
+    return hipGetLastError();
+}
+
+}  // namespace cc

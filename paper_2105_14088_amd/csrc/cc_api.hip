@@ -1,0 +1,165 @@
+// C ABI of the rank-order search library: argument checks, workspace carving, launches.
+// Declarations and contracts: include/cc.h.
+#include <hip/hip_runtime.h>
+
+#include "../../include/cc.h"
+#include "cc_internal.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return CC_ERR_HIP;
+}
+
+#define CC_HIP(expr)                                  \
+    do {                                              \
+        hipError_t e_ = (expr);                       \
+        if (e_ != hipSuccess) return hip_fail(e_);    \
+    } while (0)
+
+bool is_pow2(int n) { return n > 0 && (n & (n - 1)) == 0; }
+
+size_t align256(size_t x) { return (x + 255u) & ~(size_t)255u; }
+
+// Workspace layout of cc_2opt_search_ex: [flags 256 B][costs int64 R][moves int32 R][tours int32 R*N]
+struct WsLayout {
+    size_t flags, costs, moves, tours, total;
+};
+
+WsLayout ws_layout(int N, int restarts) {
+    WsLayout w;
+    w.flags = 0;
+    w.costs = 256;
+    w.moves = w.costs + align256(sizeof(int64_t) * (size_t)restarts);
+    w.tours = w.moves + align256(sizeof(int32_t) * (size_t)restarts);
+    w.total = w.tours + align256(sizeof(int32_t) * (size_t)restarts * (size_t)N);
+    return w;
+}
+
+int check_matrix_args(const int32_t* c, int N) {
+    if (!c) return CC_ERR_INVALID_ARG;
+    if (N < 2 || N > CC_MAX_N) return CC_ERR_UNSUPPORTED_N;
+    return CC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cc_ring_cost_batch(const int32_t* cost_matrix, int32_t N, int32_t objective, const int32_t* perms, int64_t B,
+                       int64_t* out_costs, void* stream) {
+    if (int rc = check_matrix_args(cost_matrix, N)) return rc;
+    if (objective < 0 || objective > 3 || B < 0) return CC_ERR_INVALID_ARG;
+    if (B == 0) return CC_OK;
+    if (!perms || !out_costs) return CC_ERR_INVALID_ARG;
+    if (((uintptr_t)perms & 3u) || ((uintptr_t)out_costs & 7u) || ((uintptr_t)cost_matrix & 3u)) return CC_ERR_INVALID_ARG;
+    CC_HIP(cc::launch_ring_cost_batch(cost_matrix, N, (objective & 1) != 0, perms, B, out_costs, (hipStream_t)stream));
+    return CC_OK;
+}
+
+int cc_rd_cost_batch(const int32_t* cost_matrix, int32_t N, const int32_t* perms, int64_t B, int64_t* out_costs,
+                     void* stream) {
+    if (int rc = check_matrix_args(cost_matrix, N)) return rc;
+    if (!is_pow2(N)) return CC_ERR_UNSUPPORTED_N;
+    if (B < 0) return CC_ERR_INVALID_ARG;
+    if (B == 0) return CC_OK;
+    if (!perms || !out_costs) return CC_ERR_INVALID_ARG;
+    if (((uintptr_t)perms & 3u) || ((uintptr_t)out_costs & 7u) || ((uintptr_t)cost_matrix & 3u)) return CC_ERR_INVALID_ARG;
+    CC_HIP(cc::launch_rd_cost_batch(cost_matrix, N, perms, B, out_costs, (hipStream_t)stream));
+    return CC_OK;
+}
+
+size_t cc_2opt_workspace_bytes(int32_t N, int32_t objective, int32_t restarts) {
+    if (N < 2 || N > CC_MAX_N || objective < 0 || objective > 3 || restarts < 1) return 0;
+    return ws_layout(N, restarts).total;
+}
+
+int cc_2opt_search_ex(const int32_t* cost_matrix, int32_t N, int32_t objective, int32_t restarts, uint64_t seed,
+                      const int32_t* init_tours, int32_t* best_perm, int64_t* best_cost, int32_t* best_restart,
+                      int64_t* restart_costs, int32_t* restart_tours, int32_t* restart_moves, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+    if (int rc = check_matrix_args(cost_matrix, N)) return rc;
+    if (objective < 0 || objective > 3 || restarts < 1 || !best_perm || !best_cost) return CC_ERR_INVALID_ARG;
+    const WsLayout w = ws_layout(N, restarts);
+    if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255u)) return CC_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    char* base = (char*)workspace;
+    int32_t* flags = (int32_t*)(base + w.flags);
+    int64_t* costs = restart_costs ? restart_costs : (int64_t*)(base + w.costs);
+    int32_t* moves = restart_moves ? restart_moves : (int32_t*)(base + w.moves);
+    int32_t* tours = restart_tours ? restart_tours : (int32_t*)(base + w.tours);
+    if (init_tours) {
+        if (init_tours != tours)
+            CC_HIP(hipMemcpyAsync(tours, init_tours, sizeof(int32_t) * (size_t)restarts * (size_t)N,
+                                  hipMemcpyDeviceToDevice, s));
+    } else {
+        CC_HIP(cc::launch_init_tours(N, 0, restarts, seed, tours, s));
+    }
+    CC_HIP(cc::launch_2opt(cost_matrix, N, objective, restarts, tours, costs, moves, flags, best_perm, best_cost,
+                           best_restart, s));
+    return CC_OK;
+}
+
+int cc_2opt_search(const int32_t* cost_matrix, int32_t N, int32_t objective, int32_t restarts, uint64_t seed,
+                   int32_t* best_perm, int64_t* best_cost, void* stream) {
+    if (int rc = check_matrix_args(cost_matrix, N)) return rc;
+    if (objective < 0 || objective > 3 || restarts < 1 || !best_perm || !best_cost) return CC_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    const size_t bytes = cc_2opt_workspace_bytes(N, objective, restarts);
+    void* ws = nullptr;
+    CC_HIP(hipMallocAsync(&ws, bytes, s));
+    const int rc = cc_2opt_search_ex(cost_matrix, N, objective, restarts, seed, nullptr, best_perm, best_cost, nullptr,
+                                     nullptr, nullptr, nullptr, ws, bytes, stream);
+    const hipError_t e = hipFreeAsync(ws, s);   // stream-ordered: released after the search has run
+    if (rc != CC_OK) return rc;
+    if (e != hipSuccess) return hip_fail(e);
+    return CC_OK;
+}
+
+int cc_init_tours(int32_t N, int64_t first, int64_t count, uint64_t seed, int32_t* tours, void* stream) {
+    if (N < 2 || N > CC_MAX_N) return CC_ERR_UNSUPPORTED_N;
+    if (first < 0 || count < 0 || first + count > (int64_t)1 << 32) return CC_ERR_INVALID_ARG;
+    if (count == 0) return CC_OK;
+    if (!tours || ((uintptr_t)tours & 3u)) return CC_ERR_INVALID_ARG;
+    CC_HIP(cc::launch_init_tours(N, first, count, seed, tours, (hipStream_t)stream));
+    return CC_OK;
+}
+
+int cc_validate_matrix(const int32_t* cost_matrix, int32_t N, int32_t require_symmetric, void* stream) {
+    if (int rc = check_matrix_args(cost_matrix, N)) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    int32_t* flags = nullptr;
+    CC_HIP(hipMalloc((void**)&flags, sizeof(int32_t)));
+    int32_t host = 0;
+    hipError_t e = hipMemsetAsync(flags, 0, sizeof(int32_t), s);
+    if (e == hipSuccess) e = cc::launch_validate(cost_matrix, N, require_symmetric != 0, flags, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(&host, flags, sizeof(int32_t), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    (void)hipFree(flags);
+    if (e != hipSuccess) return hip_fail(e);
+    if (host & 1) return CC_ERR_COST_RANGE;
+    if (host & 2) return CC_ERR_NOT_SYMMETRIC;
+    return CC_OK;
+}
+
+const char* cc_status_string(int status) {
+    switch (status) {
+        case CC_OK: return "ok";
+        case CC_ERR_INVALID_ARG: return "invalid argument";
+        case CC_ERR_UNSUPPORTED_N: return "unsupported N";
+        case CC_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case CC_ERR_HIP: return "HIP runtime error";
+        case CC_ERR_NOT_SYMMETRIC: return "cost matrix is not symmetric";
+        case CC_ERR_COST_RANGE: return "cost matrix entry out of range";
+        default: return "unknown status";
+    }
+}
+
+int cc_last_hip_error(void) { return g_last_hip_error; }
+
+int cc_version(void) { return 100; }
+
+}  // extern "C"

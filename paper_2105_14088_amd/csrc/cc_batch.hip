@@ -1,0 +1,262 @@
+// Batched evaluation of the ring and halving-doubling cost models (Section 4.1) over candidate rank
+// orders, plus the seeded initial-order generator and the matrix contract check.
+//
+// Ring, N a power of two in [8, 128]: the cost matrix (<= 64 KiB int32) is staged in LDS once per
+// workgroup; the order stream is read from HBM as 16-byte vectors, N/4 lanes per order, several
+// vector loads in flight per wave; each lane gathers its four hops from LDS and the N/4 lanes of an
+// order are combined with a butterfly.  The stream is read exactly once, so the kernel is bound by
+// HBM bandwidth (4N bytes in + 8 bytes out per order).
+// Other N: one wave per order, hops gathered from the L2-resident matrix.
+#include "cc_device.h"
+#include "cc_internal.h"
+
+namespace cc {
+using namespace ccd;
+
+// ------------------------------------------------------------------------------------------ ring
+template <int N, bool IS_MAX>
+__global__ __launch_bounds__(256) void ring_batch_lds_kernel(const int32_t* __restrict__ c,
+                                                             const int4* __restrict__ perms4, int64_t B,
+                                                             int64_t* __restrict__ out) {
+    __shared__ int32_t m[N * N];
+    for (int e = threadIdx.x; e < N * N; e += 256) m[e] = c[e];
+    __syncthreads();
+
+    constexpr int LP = N / 4;     // lanes that share one order
+    constexpr int PPW = 64 / LP;  // orders covered by one 1 KiB wave-load
+    constexpr int U = 4;          // wave-loads in flight
+    constexpr int M = N - 1;
+    const int lane = lane_id();
+    const int sub = lane & (LP - 1);
+    const int prev_lane = (lane & ~(LP - 1)) | ((sub + LP - 1) & (LP - 1));
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    const int64_t nloads = (B + PPW - 1) / PPW;
+
+    for (int64_t base = wave * U; base < nloads; base += nwaves * U) {
+        int4 v[U];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t ld = base + u;
+            const int64_t b = ld * PPW + lane / LP;
+            ok[u] = ld < nloads && b < B;
+            v[u] = ok[u] ? perms4[ld * 64 + lane] : make_int4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int x = v[u].x & M, y = v[u].y & M, z = v[u].z & M, w = v[u].w & M;
+            const int pw = __shfl(w, prev_lane, kWave);   // last node of the previous lane (cyclic in the order)
+            const int h0 = m[x * N + pw], h1 = m[y * N + x], h2 = m[z * N + y], h3 = m[w * N + z];
+            int acc = IS_MAX ? max(max(h0, h1), max(h2, h3)) : h0 + h1 + h2 + h3;
+#pragma unroll
+            for (int s = LP / 2; s >= 1; s >>= 1) {
+                const int o = __shfl_xor(acc, s, kWave);
+                acc = IS_MAX ? max(acc, o) : acc + o;
+            }
+            if (ok[u] && sub == 0) out[(base + u) * PPW + lane / LP] = (int64_t)acc;
+        }
+    }
+}
+
+template <bool IS_MAX>
+__global__ __launch_bounds__(256) void ring_batch_generic_kernel(const int32_t* __restrict__ c, int N,
+                                                                 const int32_t* __restrict__ perms, int64_t B,
+                                                                 int64_t* __restrict__ out) {
+    const int lane = lane_id();
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t b = wave; b < B; b += nwaves) {
+        const int32_t* pi = perms + b * N;
+        long long acc = 0;
+        for (int p = lane; p < N; p += kWave) {
+            const int a = clampi(pi[p], 0, N - 1);
+            const int q = clampi(pi[p ? p - 1 : N - 1], 0, N - 1);
+            const long long hop = c[(int64_t)a * N + q];
+            acc = IS_MAX ? (hop > acc ? hop : acc) : acc + hop;
+        }
+#pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) {
+            const long long o = __shfl_xor(acc, s, kWave);
+            acc = IS_MAX ? (o > acc ? o : acc) : acc + o;
+        }
+        if (lane == 0) out[b] = acc;
+    }
+}
+
+static int batch_grid(int64_t work_items_per_block_pass, int64_t total) {
+    int64_t blocks = (total + work_items_per_block_pass - 1) / work_items_per_block_pass;
+    const int64_t cap = 256 * 8;  // 8 workgroups of 4 waves per compute unit
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    return (int)blocks;
+}
+
+template <int N>
+static hipError_t ring_lds(const int32_t* c, bool is_max, const int32_t* perms, int64_t B, int64_t* out,
+                           hipStream_t s) {
+    constexpr int PPW = 64 / (N / 4);
+    const int grid = batch_grid((int64_t)PPW * 4 * 4, B);
+    if (is_max)
+        hipLaunchKernelGGL((ring_batch_lds_kernel<N, true>), dim3(grid), dim3(256), 0, s, c, (const int4*)perms, B, out);
+    else
+        hipLaunchKernelGGL((ring_batch_lds_kernel<N, false>), dim3(grid), dim3(256), 0, s, c, (const int4*)perms, B, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_ring_cost_batch(const int32_t* c, int N, bool is_max, const int32_t* perms, int64_t B,
+                                  int64_t* out, hipStream_t s) {
+    if (B == 0) return hipSuccess;
+    const bool aligned = ((uintptr_t)perms & 15u) == 0;
+    if (aligned) {
+        switch (N) {
+            case 8: return ring_lds<8>(c, is_max, perms, B, out, s);
+            case 16: return ring_lds<16>(c, is_max, perms, B, out, s);
+            case 32: return ring_lds<32>(c, is_max, perms, B, out, s);
+            case 64: return ring_lds<64>(c, is_max, perms, B, out, s);
+            case 128: return ring_lds<128>(c, is_max, perms, B, out, s);
+            default: break;
+        }
+    }
+    const int grid = batch_grid(4, B);
+    if (is_max)
+        hipLaunchKernelGGL((ring_batch_generic_kernel<true>), dim3(grid), dim3(256), 0, s, c, N, perms, B, out);
+    else
+        hipLaunchKernelGGL((ring_batch_generic_kernel<false>), dim3(grid), dim3(256), 0, s, c, N, perms, B, out);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------- halving-doubling rounds
+// One wave per order.  The order is parked in the wave's LDS slice so that rank i can look up its
+// partner i xor 2^k; NM = ceil(N / 64) ranks per lane.  Matrix in LDS when it fits 16 KiB (N <= 64),
+// otherwise gathered through L2.
+template <int NM, bool LDS_MATRIX>
+__global__ __launch_bounds__(256) void rd_batch_kernel(const int32_t* __restrict__ c, int N,
+                                                       const int32_t* __restrict__ perms, int64_t B,
+                                                       int64_t* __restrict__ out) {
+    extern __shared__ int32_t sm[];
+    int32_t* order = sm + (threadIdx.x >> 6) * N;   // this wave's slice
+    const int32_t* mat = c;
+    if (LDS_MATRIX) {
+        int32_t* m = sm + 4 * N;
+        for (int e = threadIdx.x; e < N * N; e += 256) m[e] = c[e];
+        __syncthreads();
+        mat = m;
+    }
+    const int lane = lane_id();
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t b = wave; b < B; b += nwaves) {
+        const int32_t* pi = perms + b * N;
+        int a[NM];
+#pragma unroll
+        for (int k = 0; k < NM; ++k) {
+            const int p = lane + 64 * k;
+            a[k] = p < N ? clampi(pi[p], 0, N - 1) : 0;
+            if (p < N) order[p] = a[k];
+        }
+        __builtin_amdgcn_wave_barrier();
+        long long total = 0;
+        for (int bit = 1; bit < N; bit <<= 1) {
+            int worst = 0;
+#pragma unroll
+            for (int k = 0; k < NM; ++k) {
+                const int p = lane + 64 * k;
+                if (p < N) worst = max(worst, mat[a[k] * N + order[p ^ bit]]);
+            }
+            total += wave_max(worst);
+        }
+        __builtin_amdgcn_wave_barrier();   // all partner look-ups done before the slice is overwritten
+        if (lane == 0) out[b] = total;
+    }
+}
+
+template <int NM>
+static hipError_t rd_launch(const int32_t* c, int N, const int32_t* perms, int64_t B, int64_t* out, hipStream_t s) {
+    const int grid = batch_grid(4, B);
+    if (N <= 64) {
+        const size_t lds = sizeof(int32_t) * (size_t)(4 * N + N * N);
+        hipLaunchKernelGGL((rd_batch_kernel<NM, true>), dim3(grid), dim3(256), lds, s, c, N, perms, B, out);
+    } else {
+        const size_t lds = sizeof(int32_t) * (size_t)(4 * N);
+        hipLaunchKernelGGL((rd_batch_kernel<NM, false>), dim3(grid), dim3(256), lds, s, c, N, perms, B, out);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_rd_cost_batch(const int32_t* c, int N, const int32_t* perms, int64_t B, int64_t* out,
+                                hipStream_t s) {
+    if (B == 0) return hipSuccess;
+    if (N <= 64) return rd_launch<1>(c, N, perms, B, out, s);
+    if (N == 128) return rd_launch<2>(c, N, perms, B, out, s);
+    if (N == 256) return rd_launch<4>(c, N, perms, B, out, s);
+    if (N == 512) return rd_launch<8>(c, N, perms, B, out, s);
+    return rd_launch<16>(c, N, perms, B, out, s);
+}
+
+// --------------------------------------------------------------------------------- initial orders
+// One wave per order: lanes draw the N-1 swap partners in parallel, lane 0 replays the swaps in
+// order (they are inherently sequential), all lanes store the result coalesced.
+__global__ __launch_bounds__(256) void init_tours_kernel(int N, int64_t first, int64_t count, uint64_t seed,
+                                                         int32_t* __restrict__ tours) {
+    extern __shared__ int32_t sm[];
+    int32_t* t = sm + (threadIdx.x >> 6) * 2 * N;
+    int32_t* partner = t + N;
+    const int lane = lane_id();
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t w = wave; w < count; w += nwaves) {
+        const uint32_t r = (uint32_t)(first + w);
+        for (int k = lane; k < N; k += kWave) {
+            t[k] = k;
+            partner[k] = k ? shuffle_partner(seed, r, k) : 0;
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (lane == 0) {
+            for (int k = N - 1; k >= 1; --k) {
+                const int j = partner[k];
+                const int tk = t[k], tj = t[j];
+                t[k] = tj;
+                t[j] = tk;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        for (int k = lane; k < N; k += kWave) tours[w * N + k] = t[k];
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+hipError_t launch_init_tours(int N, int64_t first, int64_t count, uint64_t seed, int32_t* tours, hipStream_t s) {
+    if (count == 0) return hipSuccess;
+    const int grid = batch_grid(4, count);
+    hipLaunchKernelGGL(init_tours_kernel, dim3(grid), dim3(256), sizeof(int32_t) * 8 * (size_t)N, s, N, first, count,
+                       seed, tours);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------ matrix contract
+// flags[0] bit 0: an entry outside [0, 2^21 - 1]; bit 1: c[a][b] != c[b][a] somewhere.
+__global__ __launch_bounds__(256) void validate_kernel(const int32_t* __restrict__ c, int N, int require_symmetric,
+                                                       int32_t* __restrict__ flags) {
+    int bad = 0;
+    const int64_t total = (int64_t)N * N;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int v = c[e];
+        if (v < 0 || v > (1 << 21) - 1) bad |= 1;
+        if (require_symmetric) {
+            const int a = (int)(e / N), b = (int)(e % N);
+            if (c[(int64_t)b * N + a] != v) bad |= 2;
+        }
+    }
+    if (bad) atomicOr(flags, bad);
+}
+
+hipError_t launch_validate(const int32_t* c, int N, bool require_symmetric, int32_t* flags, hipStream_t s) {
+    const int64_t total = (int64_t)N * N;
+    int grid = (int)((total + 255) / 256);
+    if (grid > 1024) grid = 1024;
+    hipLaunchKernelGGL(validate_kernel, dim3(grid), dim3(256), 0, s, c, N, require_symmetric ? 1 : 0, flags);
+    return hipGetLastError();
+}
+
+}  // namespace cc

@@ -1,0 +1,22 @@
+// Host-side launch functions behind the C ABI (one per kernel family).  Each validates nothing:
+// the ABI layer has already checked shapes, pointers and limits.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cc {
+
+hipError_t launch_ring_cost_batch(const int32_t* c, int N, bool is_max, const int32_t* perms, int64_t B,
+                                  int64_t* out, hipStream_t s);
+hipError_t launch_rd_cost_batch(const int32_t* c, int N, const int32_t* perms, int64_t B, int64_t* out,
+                                hipStream_t s);
+hipError_t launch_init_tours(int N, int64_t first, int64_t count, uint64_t seed, int32_t* tours, hipStream_t s);
+hipError_t launch_validate(const int32_t* c, int N, bool require_symmetric, int32_t* flags, hipStream_t s);
+
+// 2-opt descent of `restarts` tours held in `tours` ([restarts, N], updated in place), then the
+// lexicographic minimum over (cost, restart).  `flags` is a small int32 device scratch area (>= 64 B).
+hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, int32_t* tours, int64_t* costs,
+                       int32_t* moves, int32_t* flags, int32_t* best_perm, int64_t* best_cost,
+                       int32_t* best_restart, hipStream_t s);
+
+}  // namespace cc

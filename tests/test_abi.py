@@ -1,0 +1,90 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header declares, and
+rejects bad arguments before touching the GPU.  No compute call is made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2105_14088_amd as cc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "cc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree():
+    assert _declared_symbols() == sorted(cc.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    L = cc.lib()
+    for name in _declared_symbols():
+        assert hasattr(L, name), name
+
+
+def test_version_and_status_strings():
+    assert cc.cc_version() >= 100
+    seen = set()
+    for s in range(0, -7, -1):
+        txt = cc.cc_status_string(s)
+        assert txt and txt != "unknown status" and txt not in seen
+        seen.add(txt)
+    assert cc.cc_status_string(-99) == "unknown status"
+
+
+def test_workspace_bytes_host_only():
+    assert cc.cc_2opt_workspace_bytes(64, 0, 1024) >= 1024 * 64 * 4 + 1024 * 12
+    assert cc.cc_2opt_workspace_bytes(64, 0, 1024) % 256 == 0
+    assert cc.cc_2opt_workspace_bytes(1, 0, 1) == 0
+    assert cc.cc_2opt_workspace_bytes(1025, 0, 1) == 0
+    assert cc.cc_2opt_workspace_bytes(64, 4, 1) == 0
+    assert cc.cc_2opt_workspace_bytes(64, 0, 0) == 0
+
+
+def test_argument_errors_are_returned_before_any_launch():
+    L = cc.lib()
+    fake = ctypes.c_void_p(0x1000)        # never dereferenced: every call below fails its host checks
+    null = ctypes.c_void_p(0)
+    INVALID, UNSUPPORTED, WORKSPACE = -1, -2, -3
+    assert L.cc_ring_cost_batch(null, 64, 0, fake, 1, fake, null) == INVALID
+    assert L.cc_ring_cost_batch(fake, 1, 0, fake, 1, fake, null) == UNSUPPORTED
+    assert L.cc_ring_cost_batch(fake, 1025, 0, fake, 1, fake, null) == UNSUPPORTED
+    assert L.cc_ring_cost_batch(fake, 64, 7, fake, 1, fake, null) == INVALID
+    assert L.cc_ring_cost_batch(fake, 64, 0, fake, -1, fake, null) == INVALID
+    assert L.cc_ring_cost_batch(fake, 64, 0, null, 1, fake, null) == INVALID
+    assert L.cc_ring_cost_batch(fake, 64, 0, fake, 1, null, null) == INVALID
+    assert L.cc_ring_cost_batch(fake, 64, 0, null, 0, null, null) == 0          # B = 0 is a no-op
+    assert L.cc_rd_cost_batch(fake, 48, fake, 1, fake, null) == UNSUPPORTED      # not a power of two
+    assert L.cc_rd_cost_batch(fake, 64, fake, -5, fake, null) == INVALID
+    assert L.cc_rd_cost_batch(fake, 64, null, 0, null, null) == 0
+    assert L.cc_2opt_search(null, 64, 0, 1, 1, fake, fake, null) == INVALID
+    assert L.cc_2opt_search(fake, 64, 0, 0, 1, fake, fake, null) == INVALID
+    assert L.cc_2opt_search(fake, 64, 9, 1, 1, fake, fake, null) == INVALID
+    assert L.cc_2opt_search(fake, 64, 0, 1, 1, null, fake, null) == INVALID
+    assert L.cc_2opt_search(fake, 2048, 0, 1, 1, fake, fake, null) == UNSUPPORTED
+    args = [fake, 64, 0, 4, 1, null, fake, fake, null, null, null, null]
+    assert L.cc_2opt_search_ex(*args, null, 0, null) == WORKSPACE
+    assert L.cc_2opt_search_ex(*args, fake, 16, null) == WORKSPACE               # too small
+    assert L.cc_2opt_search_ex(*args, ctypes.c_void_p(0x1004), 1 << 30, null) == WORKSPACE   # misaligned
+    assert L.cc_init_tours(1, 0, 1, 1, fake, null) == UNSUPPORTED
+    assert L.cc_init_tours(64, -1, 1, 1, fake, null) == INVALID
+    assert L.cc_init_tours(64, 0, 1, 1, null, null) == INVALID
+    assert L.cc_init_tours(64, 0, 0, 1, null, null) == 0
+    assert L.cc_validate_matrix(null, 64, 1, null) == INVALID
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    c = torch.zeros((8, 8), dtype=torch.int32)
+    p = torch.zeros((1, 8), dtype=torch.int32)
+    with pytest.raises(ValueError):
+        cc.cc_ring_cost_batch(c, p, 0, out=torch.zeros(1, dtype=torch.int64), stream=_FakeStream())
+
+
+class _FakeStream:
+    cuda_stream = 0

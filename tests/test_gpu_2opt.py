@@ -1,0 +1,151 @@
+"""GPU parity, 2-opt search: cc_2opt_search / cc_2opt_search_ex against the CPU oracle.  The search is
+deterministic, so exactly one result is right: per restart the final order, its cost and the number of
+applied moves; over restarts the winner.  All integers: bit-exact."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2105_14088_amd as cc
+from gen import COST_MAX, WORKLOADS, make_matrix, random_matrix, random_perms
+from gpu_util import assert_search_equal, dev, gpu_search, say
+
+pytestmark = pytest.mark.gpu
+THREADS = min(16, os.cpu_count() or 1)
+
+
+def _oracle_rows(c, obj, seed, rows, init=None):
+    costs, tours, moves = [], [], []
+    for r in rows:
+        a = oracle.restarts(c, obj, seed, int(r), int(r) + 1, init)
+        costs.append(a[0]); tours.append(a[1]); moves.append(a[2])
+    return dict(costs=np.concatenate(costs), tours=np.concatenate(tours), moves=np.concatenate(moves))
+
+
+@pytest.mark.parametrize("n", [2, 3, 4, 5, 8, 13, 31, 64, 65, 100])
+@pytest.mark.parametrize("obj", [0, 1, 2, 3])
+def test_small_searches_every_objective(n, obj):
+    say(f"2-opt N={n} obj={obj} R=40")
+    c = random_matrix(n, 900 + n + obj, symmetric=not (obj & 2), lo=1, hi=4000)
+    want = oracle.search(c, obj, 40, seed=77 + n)
+    got = gpu_search(c, obj, 40, seed=77 + n)
+    assert_search_equal(got, want)
+
+
+@pytest.mark.parametrize("obj", [0, 2])
+def test_large_costs_up_to_cost_max(obj):
+    """Entries up to 2^21 - 1 (beyond any 16-bit fast path)."""
+    say(f"2-opt N=64 obj={obj} costs up to COST_MAX")
+    c = random_matrix(64, 4242 + obj, symmetric=not (obj & 2), lo=1, hi=COST_MAX)
+    want = oracle.search(c, obj, 48, seed=5)
+    assert_search_equal(gpu_search(c, obj, 48, seed=5), want)
+
+
+def test_many_ties_lowest_id_wins():
+    """Few distinct cost values: most sweeps have tied best moves and restarts tie on final cost."""
+    for n, obj in ((16, 0), (64, 0), (64, 1), (32, 3), (64, 2)):
+        say(f"2-opt ties N={n} obj={obj}")
+        c = random_matrix(n, 31 + n + obj, symmetric=not (obj & 2), lo=1, hi=3)
+        want = oracle.search(c, obj, 64, seed=3)
+        assert_search_equal(gpu_search(c, obj, 64, seed=3), want)
+
+
+def test_explicit_initial_tours_and_single_restart():
+    say("2-opt with caller-provided initial tours; R=1")
+    c = make_matrix(2)
+    init = random_perms(64, 17, seed=99)
+    want = oracle.search(c, 0, 17, seed=0, init=init)
+    assert_search_equal(gpu_search(c, 0, 17, seed=123, init=init), want)
+    want1 = oracle.search(c, 0, 1, seed=8)
+    assert_search_equal(gpu_search(c, 0, 1, seed=8), want1)
+
+
+def test_simple_entry_point_matches_extended():
+    say("cc_2opt_search (allocating form)")
+    c = make_matrix(2)
+    want = oracle.search(c, 0, 32, seed=WORKLOADS[2].search_seed)
+    perm, cost = cc.cc_2opt_search(dev(c), 0, 32, WORKLOADS[2].search_seed)
+    torch.cuda.synchronize()
+    assert int(cost.item()) == want["best_cost"] and np.array_equal(perm.cpu().numpy(), want["best_perm"])
+
+
+def test_workload2_n64_sum_1024_restarts_full():
+    say("C2: N=64 sum, 1024 restarts (all restarts compared)")
+    c = make_matrix(2)
+    seed = WORKLOADS[2].search_seed
+    o = oracle.restarts_parallel(c, oracle.SUM, seed, 0, 1024, THREADS)
+    k = int(np.argmin(o[0]))
+    want = dict(costs=o[0], tours=o[1], moves=o[2], best_cost=int(o[0][k]), best_restart=k, best_perm=o[1][k])
+    assert_search_equal(gpu_search(c, 0, 1024, seed), want)
+
+
+def test_workload3_n64_max_directed_1024_restarts_full():
+    say("C3: N=64 max directed, 1024 restarts (all restarts compared)")
+    c = make_matrix(3)
+    seed = WORKLOADS[3].search_seed
+    o = oracle.restarts_parallel(c, oracle.MAX_DIRECTED, seed, 0, 1024, THREADS)
+    k = int(np.argmin(o[0]))
+    want = dict(costs=o[0], tours=o[1], moves=o[2], best_cost=int(o[0][k]), best_restart=k, best_perm=o[1][k])
+    assert_search_equal(gpu_search(c, 3, 1024, seed), want)
+
+
+def _certify(c, obj, tour, cost):
+    """Properties that hold at any size: a permutation anchored at rank 0's start node, its cost, and
+    no improving move (checked with the oracle's move values)."""
+    n = c.shape[0]
+    assert sorted(tour) == list(range(n))
+    assert oracle.ring_cost(c, tour, obj) == cost
+    assert oracle.all_move_values(c, obj, tour).min() >= cost
+
+
+def test_workload4_n256_sum_4096_restarts_sampled():
+    """Full size on the GPU; the oracle replays a sample of restarts one by one (about 0.15 s each) and
+    certifies local optimality of further ones; the winner must be consistent with every restart."""
+    say("C4: N=256 sum, 4096 restarts (48 restarts replayed by the oracle)")
+    c = make_matrix(4)
+    seed = WORKLOADS[4].search_seed
+    got = gpu_search(c, 0, 4096, seed)
+    rows = np.unique(np.concatenate([np.arange(0, 4096, 97), [4095, 4094, 1, 2]]))
+    pool_rows = [rows[k::THREADS] for k in range(THREADS)]
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(THREADS) as ex:
+        parts = list(ex.map(lambda rr: _oracle_rows(c, 0, seed, rr), [r for r in pool_rows if len(r)]))
+    order = np.concatenate([r for r in pool_rows if len(r)])
+    want = dict(costs=np.concatenate([p["costs"] for p in parts]), tours=np.concatenate([p["tours"] for p in parts]),
+                moves=np.concatenate([p["moves"] for p in parts]))
+    assert_search_equal(got, want, rows=order)
+    k = int(np.argmin(got["costs"]))
+    assert got["best_restart"] == k and got["best_cost"] == got["costs"][k]
+    assert np.array_equal(got["best_perm"], got["tours"][k])
+    for r in (k, 7, 4000):
+        _certify(c, 0, got["tours"][r], int(got["costs"][r]))
+    init = oracle.init_tours(seed, 256, 4096)
+    assert (got["tours"][:, 0] == init[:, 0]).all()          # the anchor never moves
+
+
+def test_workload5_n1024_sum_256_restarts_sampled():
+    say("C5: N=1024 sum, 256 restarts (3 restarts replayed by the oracle)")
+    c = make_matrix(5)
+    seed = WORKLOADS[5].search_seed
+    got = gpu_search(c, 0, 256, seed)
+    rows = np.array([0, 131, 255])
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(3) as ex:
+        parts = list(ex.map(lambda r: _oracle_rows(c, 0, seed, [r]), rows))
+    want = dict(costs=np.concatenate([p["costs"] for p in parts]), tours=np.concatenate([p["tours"] for p in parts]),
+                moves=np.concatenate([p["moves"] for p in parts]))
+    assert_search_equal(got, want, rows=rows)
+    k = int(np.argmin(got["costs"]))
+    assert got["best_restart"] == k and np.array_equal(got["best_perm"], got["tours"][k])
+    _certify(c, 0, got["tours"][k], int(got["costs"][k]))
+    _certify(c, 0, got["tours"][17], int(got["costs"][17]))
+
+
+def test_determinism_same_call_twice():
+    say("2-opt determinism: two identical calls")
+    c = make_matrix(3)
+    a = gpu_search(c, 3, 256, 42)
+    b = gpu_search(c, 3, 256, 42)
+    assert_search_equal(a, b)

@@ -1,0 +1,146 @@
+"""GPU parity, batch cost models: the HIP kernels behind cc_ring_cost_batch / cc_rd_cost_batch /
+cc_init_tours / cc_validate_matrix against the CPU oracle, element by element (integers: bit-exact)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2105_14088_amd as cc
+from gen import COST_MAX, WORKLOADS, make_matrix, random_matrix, random_perms
+from gpu_util import dev, gpu_rd, gpu_ring, say
+
+pytestmark = pytest.mark.gpu
+
+
+def test_workload1_all_2520_rings_and_4096_seeded_orders():
+    say("C1: N=8, 2520 rings + 4096 seeded orders, ring sum")
+    c = make_matrix(1)
+    ex = oracle.exhaustive_rings(c, oracle.SUM, half_only=True, keep_all=True)
+    got = gpu_ring(c, ex["rings"], cc.CC_RING_SUM)
+    assert np.array_equal(got, ex["costs"])
+    k = int(np.argmin(got))                      # first minimum = first minimiser in enumeration order
+    assert got[k] == ex["best_cost"] and np.array_equal(ex["rings"][k], ex["best_ring"])
+    seed = WORKLOADS[1].search_seed
+    tours = cc.cc_init_tours(8, 4096, seed)
+    torch.cuda.synchronize()
+    tours = tours.cpu().numpy()
+    assert np.array_equal(tours, oracle.init_tours(seed, 8, 4096))
+    assert np.array_equal(gpu_ring(c, tours, cc.CC_RING_SUM), oracle.ring_cost_batch(c, tours, oracle.SUM))
+    assert np.array_equal(gpu_ring(c, tours, cc.CC_RING_MAX), oracle.ring_cost_batch(c, tours, oracle.MAX))
+
+
+@pytest.mark.parametrize("n", [2, 3, 5, 8, 13, 16, 32, 64, 100, 128, 256, 1000, 1024])
+@pytest.mark.parametrize("obj", [0, 1])
+def test_ring_batch_sizes_and_ragged_tails(n, obj):
+    # batch sizes that leave partial wave-loads, partial unrolled groups and a single order
+    c = random_matrix(n, 300 + n, symmetric=False, lo=0, hi=COST_MAX if n in (13, 64) else 6000)
+    for b in (1, 3, 67, 1029):
+        say(f"ring batch N={n} obj={obj} B={b}")
+        perms = random_perms(n, b, seed=n + b)
+        assert np.array_equal(gpu_ring(c, perms, obj), oracle.ring_cost_batch(c, perms, obj))
+
+
+def test_ring_batch_empty_and_unaligned():
+    c = random_matrix(64, 1, symmetric=True)
+    say("ring batch B=0")
+    out = cc.cc_ring_cost_batch(dev(c), torch.empty((0, 64), dtype=torch.int32, device="cuda"), 0)
+    torch.cuda.synchronize()
+    assert out.numel() == 0
+    say("ring batch, order stream not 16-byte aligned")
+    perms = random_perms(64, 33, seed=2)
+    flat = torch.empty(33 * 64 + 1, dtype=torch.int32, device="cuda")
+    view = flat[1:].view(33, 64)
+    view.copy_(dev(perms))
+    out = cc.cc_ring_cost_batch(dev(c), view, 0)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), oracle.ring_cost_batch(c, perms, 0))
+
+
+@pytest.mark.parametrize("wid,obj", [(2, 0), (3, 1)])
+def test_headline_batch_2pow20_orders_n64(wid, obj):
+    """The batch-evaluation headline case at full size: 2^20 seeded orders at N=64; the oracle recomputes
+    a 4096-order sample (spread over the batch, including both ends) and the batch minimum."""
+    say(f"M64: N=64 matrix {wid} obj={obj} B=2^20")
+    c = make_matrix(wid)
+    B = 1 << 20
+    tours = cc.cc_init_tours(64, B, WORKLOADS[wid].search_seed)
+    out = cc.cc_ring_cost_batch(dev(c), tours, obj)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    th = tours.cpu().numpy()
+    rows = np.unique(np.concatenate([np.arange(0, B, 257), np.arange(B - 64, B), np.arange(0, 64)]))
+    assert np.array_equal(got[rows], oracle.ring_cost_batch(c, th[rows], obj))
+    assert np.array_equal(th[rows], np.concatenate([oracle.init_tours(WORKLOADS[wid].search_seed, 64, 1, first=int(r))
+                                                    for r in rows]))
+    k = int(np.argmin(got))
+    assert got[k] == oracle.ring_cost(c, th[k], obj)
+    # every order is a permutation, so costs are bounded by N * max(c) and at least N * min off-diagonal
+    off = c[~np.eye(64, dtype=bool)]
+    if obj == 0:
+        assert got.min() >= 64 * int(off.min()) and got.max() <= 64 * int(off.max())
+
+
+@pytest.mark.parametrize("n", [2, 4, 8, 16, 32, 64, 128, 256, 512, 1024])
+def test_rd_batch(n):
+    c = random_matrix(n, 500 + n, symmetric=False, lo=0, hi=COST_MAX if n == 64 else 9000)
+    for b in (1, 5, 259):
+        say(f"rd batch N={n} B={b}")
+        perms = random_perms(n, b, seed=n * 3 + b)
+        assert np.array_equal(gpu_rd(c, perms), oracle.rd_cost_batch(c, perms))
+
+
+def test_workload5_rd_65536_orders_n1024():
+    """Full size: 65536 seeded orders at N=1024; the oracle recomputes a 512-order sample."""
+    say("C5: rd batch N=1024 B=65536")
+    c = make_matrix(5)
+    seed = WORKLOADS[5].search_seed
+    B = 65536
+    tours = cc.cc_init_tours(1024, B, seed)
+    out = cc.cc_rd_cost_batch(dev(c), tours)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    rows = np.unique(np.concatenate([np.arange(0, B, 131), np.arange(B - 8, B)]))
+    th = tours[torch.from_numpy(rows).cuda()].cpu().numpy()
+    assert np.array_equal(th, np.concatenate([oracle.init_tours(seed, 1024, 1, first=int(r)) for r in rows]))
+    assert np.array_equal(got[rows], oracle.rd_cost_batch(c, th))
+    assert (got > 0).all()
+
+
+@pytest.mark.parametrize("n", [2, 3, 8, 13, 64, 65, 256, 1024])
+def test_init_tours_match_oracle(n):
+    say(f"init tours N={n}")
+    for first, count in ((0, 1), (0, 300), (4093, 10), ((1 << 32) - 5, 5)):
+        t = cc.cc_init_tours(n, count, 0xC0FFEE02, first=first)
+        torch.cuda.synchronize()
+        assert np.array_equal(t.cpu().numpy(), oracle.init_tours(0xC0FFEE02, n, count, first=first))
+
+
+def test_out_of_range_indices_stay_memory_safe():
+    """Orders with indices outside [0, N) give unspecified costs but must not fault."""
+    for n in (13, 64, 256):
+        say(f"ring/rd batch with out-of-range indices N={n}")
+        c = random_matrix(n, n, symmetric=True)
+        perms = random_perms(n, 64, seed=n).astype(np.int32)
+        perms[::3, 1] = 1 << 30
+        perms[1::3, 2] = -7
+        gpu_ring(c, perms, 0)
+        if n & (n - 1) == 0:
+            gpu_rd(c, perms)
+        good = np.ones(64, dtype=bool)
+        good[::3] = False
+        good[1::3] = False
+        assert np.array_equal(gpu_ring(c, perms, 0)[good], oracle.ring_cost_batch(c, perms[good], 0))
+
+
+def test_validate_matrix():
+    say("validate matrix")
+    c = make_matrix(2)
+    assert cc.cc_validate_matrix(dev(c), True) == 0
+    a = make_matrix(3)
+    assert cc.cc_validate_matrix(dev(a), True) == -5
+    assert cc.cc_validate_matrix(dev(a), False) == 0
+    bad = c.copy()
+    bad[3, 5] = COST_MAX + 1
+    assert cc.cc_validate_matrix(dev(bad), False) == -6
+    bad[3, 5] = -1
+    assert cc.cc_validate_matrix(dev(bad), False) == -6

@@ -60,6 +60,9 @@ __global__ void twoopt_general_kernel(const int32_t* __restrict__ c, int N, int3
     const int tid = threadIdx.x;
     const int lane = tid & 63, wv = tid >> 6, nwv = blockDim.x >> 6;
     const int64_t r = blockIdx.x;
+    // entries are clamped to the contract range: all int32 arithmetic below is then exact, every applied
+    // move lowers the true cost, and the descent terminates whatever the buffer holds
+    auto C = [&](int a, int b2) { return clampi(c[a * N + b2], 0, (1 << 21) - 1); };
     if (tid < N) t[tid] = clampi(tours[r * N + tid], 0, N - 1);
     __syncthreads();
 
@@ -71,9 +74,9 @@ __global__ void twoopt_general_kernel(const int32_t* __restrict__ c, int N, int3
         int myf = 0;
         if (tid < N) {
             const int a = t[tid], pr = t[tid ? tid - 1 : N - 1];
-            myf = c[a * N + pr];
+            myf = C(a, pr);
             f[tid] = myf;
-            if (DIRECTED) b[tid] = c[pr * N + a];
+            if (DIRECTED) b[tid] = C(pr, a);
             if (DIRECTED || IS_MAX) {
                 pf[tid] = (IS_MAX && tid == 0) ? 0 : myf;
                 if (IS_MAX) sf[tid] = myf;
@@ -133,12 +136,12 @@ __global__ void twoopt_general_kernel(const int32_t* __restrict__ c, int N, int3
                 }
                 if (i == 1 && j == N - 1) continue;
                 const int ti = t[i], tim = t[i - 1];
-                const int x0 = c[tj * N + tim], y0 = c[tq * N + ti];
+                const int x0 = C(tj, tim), y0 = C(tq, ti);
                 int v0, v1 = 0;
                 if (!IS_MAX && !DIRECTED) {
                     v0 = cur + x0 + y0 - f[i] - fq;
                 } else if (!IS_MAX) {
-                    const int x1 = c[tim * N + tj], y1 = c[ti * N + tq];
+                    const int x1 = C(tim, tj), y1 = C(ti, tq);
                     const int inf = pfj - pf[i], inb = pbj - pb[i];
                     const int outf = tot_f - f[i] - fq - inf, outb = tot_b - b[i] - bq - inb;
                     v0 = x0 + y0 + outf + inb;
@@ -147,7 +150,7 @@ __global__ void twoopt_general_kernel(const int32_t* __restrict__ c, int N, int3
                     const int outf = max(far_f, pf[i - 1]);
                     v0 = max(max(x0, y0), max(outf, in_f));
                 } else {
-                    const int x1 = c[tim * N + tj], y1 = c[ti * N + tq];
+                    const int x1 = C(tim, tj), y1 = C(ti, tq);
                     const int outf = max(far_f, pf[i - 1]), outb = max(far_b, pb[i - 1]);
                     v0 = max(max(x0, y0), max(outf, in_b));
                     v1 = max(max(x1, y1), max(outb, in_f));
@@ -241,18 +244,31 @@ hipError_t launch_general(const int32_t* c, int N, int restarts, int32_t* tours,
     return hipGetLastError();
 }
 
+hipError_t launch_general_objective(const int32_t* c, int N, int objective, int restarts, int32_t* tours,
+                                    int64_t* costs, int32_t* moves, hipStream_t s) {
+    switch (objective) {
+        case 0: return launch_general<0>(c, N, restarts, tours, costs, moves, s);
+        case 1: return launch_general<1>(c, N, restarts, tours, costs, moves, s);
+        case 2: return launch_general<2>(c, N, restarts, tours, costs, moves, s);
+        default: return launch_general<3>(c, N, restarts, tours, costs, moves, s);
+    }
+}
+
 }  // namespace
 
-hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, int32_t* tours, int64_t* costs,
-                       int32_t* moves, int32_t* flags, int32_t* best_perm, int64_t* best_cost,
-                       int32_t* best_restart, hipStream_t s) {
+hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, uint64_t seed, bool tours_hold_init,
+                       int32_t* tours, int64_t* costs, int32_t* moves, int32_t* flags, int32_t* best_perm,
+                       int64_t* best_cost, int32_t* best_restart, hipStream_t s) {
     (void)flags;
     hipError_t e;
-    switch (objective) {
-        case 0: e = launch_general<0>(c, N, restarts, tours, costs, moves, s); break;
-        case 1: e = launch_general<1>(c, N, restarts, tours, costs, moves, s); break;
-        case 2: e = launch_general<2>(c, N, restarts, tours, costs, moves, s); break;
-        default: e = launch_general<3>(c, N, restarts, tours, costs, moves, s); break;
+    if (N == 64 && objective == 0) {
+        e = launch_2opt_sum_n64(c, restarts, seed, !tours_hold_init, tours, costs, moves, s);
+    } else {
+        if (!tours_hold_init) {
+            e = launch_init_tours(N, 0, restarts, seed, tours, s);
+            if (e != hipSuccess) return e;
+        }
+        e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, s);
     }
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(best_restart_kernel, dim3(1), dim3(256), 0, s, costs, tours, N, restarts, best_perm, best_cost,

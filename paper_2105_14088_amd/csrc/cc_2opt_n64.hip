@@ -1,0 +1,205 @@
+// 2-opt descent for N = 64, ring-sum objective on a symmetric matrix: one wavefront per restart, the
+// tour in one VGPR (lane p holds t[p]), the cost matrix staged once per workgroup in LDS.
+//
+// Neighbourhood as cyclic diagonals.  A 2-opt move exchanges two non-adjacent ring edges.  Number the
+// edges by their upper rank: edge p joins ranks p-1 and p (edge 0 joins 63 and 0).  Exchanging edges a
+// and b replaces them by (t[a-1], t[b-1]) and (t[a], t[b]), so with G(p, q) = c[t[p]][t[q]]
+//     delta(a, b) = G(a-1, b-1) + G(a, b) - f[a] - f[b],      f[p] = c[t[p]][t[p-1]].
+// Both new hops sit on the same cyclic diagonal d = b - a of G, in adjacent lanes.  Lane a therefore
+// needs ONE gather per move, D_d[a] = G(a, a+d), and takes G(a-1, a-1+d) from lane a-1 with a DPP
+// wave rotate.  Diagonals d = 2 .. 32 cover every unordered pair of non-adjacent edges (d = 32 twice),
+// i.e. all N(N-3)/2 = 1952 moves in 31 fully occupied wave steps; no lane is ever masked.
+// In move terms: edges {a, b}, lo = min, hi = max, is the reversal of ranks lo .. hi-1, or, when
+// lo = 0 (the edge into the anchor), of ranks hi .. 63; these are exactly the moves (i, j) of cc.h.
+//
+// Keys.  Per lane the running minimum is kept over   key = (delta' << 14) | rank(b) << 8 | 4*t[b]
+// where delta' = G + G - f[b] (the lane's own -f[a] is added after the sweep), rank(b) = (b-1) mod 64
+// orders the partners of one lane exactly as their move ids are ordered, and the low byte is the
+// column byte-offset of node t[b], which makes the gather address a single v_and_or.  The value
+// packed[b] = (-f[b] << 14) | rank(b) << 8 | 4*t[b] travels round the wave by one lane per diagonal
+// (DPP wave rotate), and the matrix is stored pre-shifted (c << 14), so a key costs two adds.
+// This needs |delta| < 2^17, i.e. max(c) < 2^16; larger matrices (up to 2^21 - 1) take the same
+// sweep with 64-bit keys.  After the sweep each lane turns its best partner into the move id
+// i*64 + j, and (delta << 12 | id) is min-reduced over the wave with DPP row operations: the result
+// is the lexicographic minimum of (value, id) over the whole neighbourhood, whatever the visit order.
+#include <type_traits>
+
+#include "cc_device.h"
+#include "cc_internal.h"
+
+namespace cc {
+using namespace ccd;
+
+namespace {
+
+constexpr int kN = 64;
+constexpr int kSh = 14;           // key = delta << 14 | rank << 8 | column byte offset
+constexpr int kIdBits = 12;       // move id i*64 + j
+constexpr int kCostMax = (1 << 21) - 1;
+
+// DPP controls (gfx9 encoding)
+constexpr int kDppQuadSwap1 = 0xB1;     // quad_perm:[1,0,3,2]
+constexpr int kDppQuadSwap2 = 0x4E;     // quad_perm:[2,3,0,1]
+constexpr int kDppWaveRol1 = 0x134;     // lane p <- lane p+1 (cyclic over 64 lanes)
+constexpr int kDppWaveRor1 = 0x13C;     // lane p <- lane p-1 (cyclic over 64 lanes)
+constexpr int kDppRowMirror = 0x140;
+constexpr int kDppRowHalfMirror = 0x141;
+constexpr int kDppRowBcast15 = 0x142;
+constexpr int kDppRowBcast31 = 0x143;
+
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ int dpp(int old, int v) {
+    return __builtin_amdgcn_update_dpp(old, v, CTRL, ROW_MASK, 0xf, false);
+}
+// full-wave rotates read a valid lane everywhere, so the "old" operand is irrelevant (bound_ctrl set)
+__device__ __forceinline__ int from_next_lane(int v) {
+    return __builtin_amdgcn_update_dpp(v, v, kDppWaveRol1, 0xf, 0xf, true);
+}
+__device__ __forceinline__ int from_prev_lane(int v) {
+    return __builtin_amdgcn_update_dpp(v, v, kDppWaveRor1, 0xf, 0xf, true);
+}
+__device__ __forceinline__ long long from_next_lane(long long v) {
+    const int lo = from_next_lane((int)(unsigned)(unsigned long long)v);
+    const int hi = from_next_lane((int)((unsigned long long)v >> 32));
+    return (long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo);
+}
+
+// Minimum over the wave, returned as a wave-uniform value.
+__device__ __forceinline__ int wave_min_uniform(int v) {
+    v = min(v, dpp<kDppQuadSwap1>(v, v));
+    v = min(v, dpp<kDppQuadSwap2>(v, v));
+    v = min(v, dpp<kDppRowHalfMirror>(v, v));
+    v = min(v, dpp<kDppRowMirror>(v, v));             // every lane of a row holds the row minimum
+    v = min(v, dpp<kDppRowBcast15, 0xa>(v, v));       // rows 1 and 3 absorb rows 0 and 2
+    v = min(v, dpp<kDppRowBcast31, 0xc>(v, v));       // rows 2 and 3 absorb row 1's result
+    return __builtin_amdgcn_readlane(v, 63);
+}
+__device__ __forceinline__ long long wave_min_uniform(long long v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+        const long long o = __shfl_xor(v, m, kWave);
+        v = o < v ? o : v;
+    }
+    return v;
+}
+
+// Seeded Fisher-Yates shuffle with the tour held one rank per lane: lanes draw their swap partner in
+// parallel, the swaps themselves are replayed in order with scalar lane reads.
+__device__ __forceinline__ int init_tour_in_wave(uint64_t seed, uint32_t r, int lane) {
+    const int partner = lane ? shuffle_partner(seed, r, lane) : 0;
+    int t = lane;
+#pragma unroll 1
+    for (int k = kN - 1; k >= 1; --k) {
+        const int j = __builtin_amdgcn_readlane(partner, k);
+        const int tk = __builtin_amdgcn_readlane(t, k);
+        const int tj = __builtin_amdgcn_readlane(t, j);
+        t = lane == k ? tj : t;
+        t = lane == j ? tk : t;
+    }
+    return t;
+}
+
+// One descent.  m: LDS matrix, entries c << 14 (narrow) or c (wide).  Returns the final tour in t.
+template <bool WIDE>
+__device__ __forceinline__ void descend(const int32_t* m, int lane, int& t, long long& cost, int& applied_out) {
+    using K = typename std::conditional<WIDE, long long, int>::type;
+    using UK = typename std::conditional<WIDE, unsigned long long, unsigned>::type;
+    const int rank_bits = ((lane + kN - 1) & (kN - 1)) << 8;
+    const char* mbytes = (const char*)m;
+    long long cur = 0;
+    int applied = 0;
+    bool first = true;
+    for (;;) {
+        // hop into rank `lane`, and the value that represents this rank as a partner b
+        const int tprev = from_prev_lane(t);
+        const int fm = m[t * kN + tprev];
+        const K negf = WIDE ? (K)(0 - ((UK)(unsigned)fm << kSh)) : (K)(0 - (UK)fm);
+        K pk = (K)((UK)negf + (UK)(rank_bits + 4 * t));
+        if (first) {
+            cur = wave_sum64((long long)(WIDE ? fm : (fm >> kSh)));
+            first = false;
+        }
+        const int rowofs = t * (kN * 4);
+        pk = from_next_lane(from_next_lane(pk));        // packed[a + 2]
+        K best = WIDE ? (K)0x7fffffffffffffffll : (K)0x7fffffff;
+#pragma unroll
+        for (int d = 2; d <= kN / 2; ++d) {
+            const int off = ((int)pk & 0xff) | rowofs;
+            const int D = *(const int32_t*)(mbytes + off);      // G(a, a+d)
+            const int E = from_prev_lane(D);                    // G(a-1, a-1+d)
+            const K key = WIDE ? (K)(((UK)(unsigned)(E + D) << kSh) + (UK)pk)
+                               : (K)((UK)E + (UK)D + (UK)pk);
+            best = key < best ? key : best;
+            if (d < kN / 2) pk = from_next_lane(pk);
+        }
+        best = (K)((UK)best + (UK)negf);
+        // partner -> move id (lowest id among this lane's best partners is already selected by rank)
+        const int low = (int)best & ((1 << kSh) - 1);
+        const K delta = best >> kSh;
+        const int b = ((low >> 8) + 1) & (kN - 1);
+        const int lo = min(lane, b), hi = max(lane, b);
+        const int mi_l = lo ? lo : hi, mj_l = lo ? hi - 1 : kN - 1;
+        const K key2 = (K)(((UK)delta << kIdBits) | (UK)(mi_l * kN + mj_l));
+        const K win = wave_min_uniform(key2);
+        const K dwin = win >> kIdBits;
+        if (dwin >= 0) break;
+        const int id = (int)win & ((1 << kIdBits) - 1);
+        const int mi = id >> 6, mj = id & (kN - 1);
+        const int src = (lane >= mi && lane <= mj) ? mi + mj - lane : lane;
+        t = __shfl(t, src, kWave);
+        cur += (long long)dwin;
+        ++applied;
+    }
+    cost = cur;
+    applied_out = applied;
+}
+
+__global__ __launch_bounds__(256) void twoopt_sum_n64_kernel(const int32_t* __restrict__ c, int restarts,
+                                                             uint64_t seed, int generate,
+                                                             int32_t* __restrict__ tours,
+                                                             int64_t* __restrict__ costs,
+                                                             int32_t* __restrict__ moves) {
+    __shared__ __attribute__((aligned(256))) int32_t m[kN * kN];
+    __shared__ int wave_max_entry[4];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+
+    // pass 1: largest entry (entries are clamped to the contract range so all arithmetic stays exact)
+    int mx = 0;
+    for (int e = tid; e < kN * kN; e += 256) mx = max(mx, clampi(c[e], 0, kCostMax));
+    mx = wave_max(mx);
+    if (lane == 0) wave_max_entry[wv] = mx;
+    __syncthreads();
+    mx = max(max(wave_max_entry[0], wave_max_entry[1]), max(wave_max_entry[2], wave_max_entry[3]));
+    const bool wide = mx >= (1 << 16);
+    // pass 2: stage, pre-shifted for 32-bit keys
+    for (int e = tid; e < kN * kN; e += 256) {
+        const int v = clampi(c[e], 0, kCostMax);
+        m[e] = wide ? v : (v << kSh);
+    }
+    __syncthreads();
+
+    const int64_t r = (int64_t)blockIdx.x * 4 + wv;
+    if (r >= restarts) return;
+    int t = generate ? init_tour_in_wave(seed, (uint32_t)r, lane) : clampi(tours[r * kN + lane], 0, kN - 1);
+    long long cost;
+    int applied;
+    if (wide) descend<true>(m, lane, t, cost, applied);
+    else descend<false>(m, lane, t, cost, applied);
+    tours[r * kN + lane] = t;
+    if (lane == 0) {
+        costs[r] = cost;
+        moves[r] = applied;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_2opt_sum_n64(const int32_t* c, int restarts, uint64_t seed, bool generate, int32_t* tours,
+                               int64_t* costs, int32_t* moves, hipStream_t s) {
+    const int grid = (restarts + 3) / 4;
+    hipLaunchKernelGGL(twoopt_sum_n64_kernel, dim3(grid), dim3(256), 0, s, c, restarts, seed, generate ? 1 : 0, tours,
+                       costs, moves);
+    return hipGetLastError();
+}
+
+}  // namespace cc

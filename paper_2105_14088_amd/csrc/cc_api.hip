@@ -91,15 +91,11 @@ int cc_2opt_search_ex(const int32_t* cost_matrix, int32_t N, int32_t objective, 
     int64_t* costs = restart_costs ? restart_costs : (int64_t*)(base + w.costs);
     int32_t* moves = restart_moves ? restart_moves : (int32_t*)(base + w.moves);
     int32_t* tours = restart_tours ? restart_tours : (int32_t*)(base + w.tours);
-    if (init_tours) {
-        if (init_tours != tours)
-            CC_HIP(hipMemcpyAsync(tours, init_tours, sizeof(int32_t) * (size_t)restarts * (size_t)N,
-                                  hipMemcpyDeviceToDevice, s));
-    } else {
-        CC_HIP(cc::launch_init_tours(N, 0, restarts, seed, tours, s));
-    }
-    CC_HIP(cc::launch_2opt(cost_matrix, N, objective, restarts, tours, costs, moves, flags, best_perm, best_cost,
-                           best_restart, s));
+    if (init_tours && init_tours != tours)
+        CC_HIP(hipMemcpyAsync(tours, init_tours, sizeof(int32_t) * (size_t)restarts * (size_t)N,
+                              hipMemcpyDeviceToDevice, s));
+    CC_HIP(cc::launch_2opt(cost_matrix, N, objective, restarts, seed, init_tours != nullptr, tours, costs, moves, flags,
+                           best_perm, best_cost, best_restart, s));
     return CC_OK;
 }
 

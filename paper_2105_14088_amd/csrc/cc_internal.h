@@ -13,10 +13,16 @@ hipError_t launch_rd_cost_batch(const int32_t* c, int N, const int32_t* perms, i
 hipError_t launch_init_tours(int N, int64_t first, int64_t count, uint64_t seed, int32_t* tours, hipStream_t s);
 hipError_t launch_validate(const int32_t* c, int N, bool require_symmetric, int32_t* flags, hipStream_t s);
 
-// 2-opt descent of `restarts` tours held in `tours` ([restarts, N], updated in place), then the
-// lexicographic minimum over (cost, restart).  `flags` is a small int32 device scratch area (>= 64 B).
-hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, int32_t* tours, int64_t* costs,
-                       int32_t* moves, int32_t* flags, int32_t* best_perm, int64_t* best_cost,
-                       int32_t* best_restart, hipStream_t s);
+// 2-opt descent of `restarts` tours, then the lexicographic minimum over (cost, restart).
+// `tours` ([restarts, N]) receives the final tours; if `tours_hold_init` it holds the initial tours on
+// entry, otherwise restart r starts from the seeded shuffle (seed, r).  `flags` is a small int32
+// device scratch area (>= 64 B).
+hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, uint64_t seed, bool tours_hold_init,
+                       int32_t* tours, int64_t* costs, int32_t* moves, int32_t* flags, int32_t* best_perm,
+                       int64_t* best_cost, int32_t* best_restart, hipStream_t s);
+
+// N = 64, ring-sum objective: one wavefront per restart (cc_2opt_n64.hip).
+hipError_t launch_2opt_sum_n64(const int32_t* c, int restarts, uint64_t seed, bool generate, int32_t* tours,
+                               int64_t* costs, int32_t* moves, hipStream_t s);
 
 }  // namespace cc

@@ -83,20 +83,21 @@ __device__ __forceinline__ long long wave_min_uniform(long long v) {
     return v;
 }
 
-// Seeded Fisher-Yates shuffle with the tour held one rank per lane: lanes draw their swap partner in
-// parallel, the swaps themselves are replayed in order with scalar lane reads.
+// Seeded Fisher-Yates shuffle without a serial chain across lanes.  Lane v follows node v: at step k
+// (k = 63 .. 1) ranks k and j_k swap, so a node sitting at rank k moves to j_k and a node sitting at
+// j_k moves to k, where it stays (later steps only touch ranks below k).  Swap partners are drawn in
+// parallel, one per lane, and broadcast step by step; a forward lane permute finally turns
+// "node -> rank" into "rank -> node".
 __device__ __forceinline__ int init_tour_in_wave(uint64_t seed, uint32_t r, int lane) {
     const int partner = lane ? shuffle_partner(seed, r, lane) : 0;
-    int t = lane;
-#pragma unroll 1
+    int pos = lane;
+#pragma unroll
     for (int k = kN - 1; k >= 1; --k) {
         const int j = __builtin_amdgcn_readlane(partner, k);
-        const int tk = __builtin_amdgcn_readlane(t, k);
-        const int tj = __builtin_amdgcn_readlane(t, j);
-        t = lane == k ? tj : t;
-        t = lane == j ? tk : t;
+        const int moved = (pos == k) ? j : pos;
+        pos = (pos == j) ? k : moved;
     }
-    return t;
+    return __builtin_amdgcn_ds_permute(pos << 2, lane);
 }
 
 // One descent.  m: LDS matrix, entries c << 14 (narrow) or c (wide).  Returns the final tour in t.
@@ -121,16 +122,24 @@ __device__ __forceinline__ void descend(const int32_t* m, int lane, int& t, long
         }
         const int rowofs = t * (kN * 4);
         pk = from_next_lane(from_next_lane(pk));        // packed[a + 2]
+        // phase 1: every diagonal's partner value and gather address, all 31 gathers in flight
+        K pkd[kN / 2 + 1];
+        int D[kN / 2 + 1];
+#pragma unroll
+        for (int d = 2; d <= kN / 2; ++d) {
+            pkd[d] = pk;
+            const int off = ((int)pk & 0xff) | rowofs;
+            D[d] = *(const int32_t*)(mbytes + off);             // G(a, a+d)
+            if (d < kN / 2) pk = from_next_lane(pk);
+        }
+        // phase 2: combine with the neighbour lane's gather, keep the minimum
         K best = WIDE ? (K)0x7fffffffffffffffll : (K)0x7fffffff;
 #pragma unroll
         for (int d = 2; d <= kN / 2; ++d) {
-            const int off = ((int)pk & 0xff) | rowofs;
-            const int D = *(const int32_t*)(mbytes + off);      // G(a, a+d)
-            const int E = from_prev_lane(D);                    // G(a-1, a-1+d)
-            const K key = WIDE ? (K)(((UK)(unsigned)(E + D) << kSh) + (UK)pk)
-                               : (K)((UK)E + (UK)D + (UK)pk);
+            const int E = from_prev_lane(D[d]);                 // G(a-1, a-1+d)
+            const K key = WIDE ? (K)(((UK)(unsigned)(E + D[d]) << kSh) + (UK)pkd[d])
+                               : (K)((UK)E + (UK)D[d] + (UK)pkd[d]);
             best = key < best ? key : best;
-            if (d < kN / 2) pk = from_next_lane(pk);
         }
         best = (K)((UK)best + (UK)negf);
         // partner -> move id (lowest id among this lane's best partners is already selected by rank)
@@ -154,7 +163,7 @@ __device__ __forceinline__ void descend(const int32_t* m, int lane, int& t, long
     applied_out = applied;
 }
 
-__global__ __launch_bounds__(256) void twoopt_sum_n64_kernel(const int32_t* __restrict__ c, int restarts,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) void twoopt_sum_n64_kernel(const int32_t* __restrict__ c, int restarts,
                                                              uint64_t seed, int generate,
                                                              int32_t* __restrict__ tours,
                                                              int64_t* __restrict__ costs,
@@ -163,24 +172,31 @@ __global__ __launch_bounds__(256) void twoopt_sum_n64_kernel(const int32_t* __re
     __shared__ int wave_max_entry[4];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
 
-    // pass 1: largest entry (entries are clamped to the contract range so all arithmetic stays exact)
+    // the matrix loads are issued first and stay in flight while the wave builds its initial tour
+    int v[kN * kN / 256];
+#pragma unroll
+    for (int k = 0; k < kN * kN / 256; ++k) v[k] = c[tid + 256 * k];
+    const int64_t r = (int64_t)blockIdx.x * 4 + wv;
+    int t = 0;
+    if (r < restarts)
+        t = generate ? init_tour_in_wave(seed, (uint32_t)r, lane) : clampi(tours[r * kN + lane], 0, kN - 1);
+    // entries are clamped to the contract range so that all arithmetic stays exact
     int mx = 0;
-    for (int e = tid; e < kN * kN; e += 256) mx = max(mx, clampi(c[e], 0, kCostMax));
+#pragma unroll
+    for (int k = 0; k < kN * kN / 256; ++k) {
+        v[k] = clampi(v[k], 0, kCostMax);
+        mx = max(mx, v[k]);
+    }
     mx = wave_max(mx);
     if (lane == 0) wave_max_entry[wv] = mx;
     __syncthreads();
     mx = max(max(wave_max_entry[0], wave_max_entry[1]), max(wave_max_entry[2], wave_max_entry[3]));
     const bool wide = mx >= (1 << 16);
-    // pass 2: stage, pre-shifted for 32-bit keys
-    for (int e = tid; e < kN * kN; e += 256) {
-        const int v = clampi(c[e], 0, kCostMax);
-        m[e] = wide ? v : (v << kSh);
-    }
+    // stage, pre-shifted when 32-bit keys suffice
+#pragma unroll
+    for (int k = 0; k < kN * kN / 256; ++k) m[tid + 256 * k] = wide ? v[k] : (v[k] << kSh);
     __syncthreads();
-
-    const int64_t r = (int64_t)blockIdx.x * 4 + wv;
     if (r >= restarts) return;
-    int t = generate ? init_tour_in_wave(seed, (uint32_t)r, lane) : clampi(tours[r * kN + lane], 0, kN - 1);
     long long cost;
     int applied;
     if (wide) descend<true>(m, lane, t, cost, applied);

@@ -64,14 +64,25 @@ __device__ __forceinline__ long long from_next_lane(long long v) {
     return (long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo);
 }
 
-// Minimum over the wave, returned as a wave-uniform value.
+// Minimum over the wave, returned as a wave-uniform value.  Six DPP steps: pairs, quads, half rows,
+// rows, then the last lane of each row is folded into the next row(s); lane 63 ends with the total.
+// Each step reads the register the previous step wrote, which needs two wait states before a DPP read.
 __device__ __forceinline__ int wave_min_uniform(int v) {
-    v = min(v, dpp<kDppQuadSwap1>(v, v));
-    v = min(v, dpp<kDppQuadSwap2>(v, v));
-    v = min(v, dpp<kDppRowHalfMirror>(v, v));
-    v = min(v, dpp<kDppRowMirror>(v, v));             // every lane of a row holds the row minimum
-    v = min(v, dpp<kDppRowBcast15, 0xa>(v, v));       // rows 1 and 3 absorb rows 0 and 2
-    v = min(v, dpp<kDppRowBcast31, 0xc>(v, v));       // rows 2 and 3 absorb row 1's result
+    asm volatile(
+        "s_nop 1\n\t"
+        "v_min_i32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_min_i32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_min_i32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_min_i32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_min_i32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_min_i32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+        "s_nop 1"
+        : "+v"(v));
     return __builtin_amdgcn_readlane(v, 63);
 }
 __device__ __forceinline__ long long wave_min_uniform(long long v) {
@@ -122,7 +133,7 @@ __device__ __forceinline__ void descend(const int32_t* m, int lane, int& t, long
         }
         const int rowofs = t * (kN * 4);
         pk = from_next_lane(from_next_lane(pk));        // packed[a + 2]
-        // phase 1: every diagonal's partner value and gather address, all 31 gathers in flight
+        // phase 1: every diagonal's partner value and gather address; gathers go out as early as possible
         K pkd[kN / 2 + 1];
         int D[kN / 2 + 1];
 #pragma unroll

@@ -1,0 +1,122 @@
+#!/usr/bin/env python3
+"""Times every workload of the rank-order search on one MI355X and prints one JSON line per workload.
+
+Workloads 1-5 are the parity-test configurations (matrix shapes and work amounts in gen/workloads.py);
+"M64" is the batch-evaluation headline case (ring sum and max on 2^20 seeded orders at N=64).  Times are
+HIP-event times around the library call on the launch stream, median of `--reps` after one warm-up.
+`bench.py` remains the single-line benchmark of the N=64 workload; this script gives the per-workload
+table of the design doc.  Pass --oracle to time the CPU oracle beside each search (a bounded sample of
+restarts on one core).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def timed(fn, reps):
+    import torch
+    fn()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1))
+    ts.sort()
+    return ts[len(ts) // 2]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--reps", type=int, default=5)
+    ap.add_argument("--oracle", action="store_true")
+    ap.add_argument("--only", type=str, default="")
+    args = ap.parse_args()
+
+    import numpy as np
+    import torch
+
+    import paper_2105_14088_amd as cc
+    from gen import WORKLOADS, make_matrix
+
+    torch.cuda.set_device(0)
+    only = set(args.only.split(",")) if args.only else None
+
+    def emit(d):
+        print(json.dumps(d), flush=True)
+
+    def search_case(wid):
+        w = WORKLOADS[wid]
+        obj = cc.OBJECTIVES[w.objective]
+        c_host = make_matrix(wid)
+        c = torch.from_numpy(c_host).cuda()
+        bufs = cc.SearchBuffers(w.n, obj, w.restarts, c.device)
+        ms = timed(lambda: cc.cc_2opt_search_ex(c, obj, w.restarts, w.search_seed, buffers=bufs), args.reps)
+        moves = bufs.restart_moves.cpu().numpy().astype(np.int64)
+        nbhd = w.n * (w.n - 3) // 2 * (2 if obj & 2 else 1)
+        evals = int(((moves + 1) * nbhd).sum())
+        d = {"workload": w.name, "call": "cc_2opt_search_ex", "N": w.n, "objective": w.objective,
+             "restarts": w.restarts, "ms": ms, "move_evals": evals, "move_evals_per_s": evals / (ms * 1e-3),
+             "applied_moves_mean": float(moves.mean()), "applied_moves_max": int(moves.max()),
+             "best_cost": int(bufs.best_cost.item())}
+        if args.oracle:
+            import oracle
+            sample = min(w.restarts, {64: 256, 256: 16, 1024: 1}[w.n])
+            t0 = time.perf_counter()
+            oc, ot, om = oracle.restarts(c_host, obj, w.search_seed, 0, sample)
+            dt = time.perf_counter() - t0
+            ok = bool(np.array_equal(om, moves[:sample]) and np.array_equal(ot, bufs.restart_tours.cpu().numpy()[:sample]))
+            d.update({"oracle_1core_move_evals_per_s": float(((om.astype(np.int64) + 1) * nbhd).sum() / dt),
+                      "oracle_sample_restarts": sample, "oracle_sample_s": dt, "bit_exact_on_sample": ok})
+        emit(d)
+
+    def batch_case(name, wid, kind, objective, batch):
+        w = WORKLOADS[wid]
+        c_host = make_matrix(wid)
+        c = torch.from_numpy(c_host).cuda()
+        orders = cc.cc_init_tours(w.n, batch, w.search_seed)
+        out = torch.empty(batch, dtype=torch.int64, device="cuda")
+        if kind == "ring":
+            fn = lambda: cc.cc_ring_cost_batch(c, orders, objective, out=out)  # noqa: E731
+        else:
+            fn = lambda: cc.cc_rd_cost_batch(c, orders, out=out)  # noqa: E731
+        ms = timed(fn, args.reps)
+        d = {"workload": name, "call": f"cc_{kind}_cost_batch", "N": w.n, "objective": objective, "batch": batch,
+             "ms": ms, "perm_evals_per_s": batch / (ms * 1e-3), "hbm_GBps": batch * (4 * w.n + 8) / (ms * 1e-3) / 1e9}
+        if args.oracle:
+            import oracle
+            sample = min(batch, 1 << 14 if w.n <= 64 else 256)
+            sub = orders[:sample].cpu().numpy()
+            t0 = time.perf_counter()
+            want = oracle.ring_cost_batch(c_host, sub, objective) if kind == "ring" else oracle.rd_cost_batch(c_host, sub)
+            dt = time.perf_counter() - t0
+            d.update({"oracle_1core_perm_evals_per_s": sample / dt,
+                      "bit_exact_on_sample": bool(np.array_equal(want, out[:sample].cpu().numpy()))})
+        emit(d)
+
+    cases = [
+        ("C1", lambda: batch_case("C1_n8_ring_sum_4096", 1, "ring", 0, 4096)),
+        ("C2", lambda: search_case(2)),
+        ("C3", lambda: search_case(3)),
+        ("C4", lambda: search_case(4)),
+        ("C5rd", lambda: batch_case("C5_n1024_rd_65536", 5, "rd", 0, 65536)),
+        ("C5", lambda: search_case(5)),
+        ("M64sum", lambda: batch_case("M64_ring_sum_2^20", 2, "ring", 0, 1 << 20)),
+        ("M64max", lambda: batch_case("M64_ring_max_2^20", 3, "ring", 1, 1 << 20)),
+    ]
+    for key, fn in cases:
+        if only is None or key in only:
+            fn()
+
+
+if __name__ == "__main__":
+    main()

@@ -42,7 +42,10 @@ __device__ void block_scan(int32_t* arr, int N) {
 
 template <int OBJ>
 __global__ void twoopt_general_kernel(const int32_t* __restrict__ c, int N, int32_t* __restrict__ tours,
-                                      int64_t* __restrict__ costs, int32_t* __restrict__ moves) {
+                                      int64_t* __restrict__ costs, int32_t* __restrict__ moves,
+                                      const int32_t* __restrict__ skip_if_small) {
+    // when a 16-bit fast path is launched beside this kernel, flags[0] = max(c) decides which of the two runs
+    if (skip_if_small && skip_if_small[0] < (1 << 16)) return;
     constexpr bool IS_MAX = (OBJ & 1) != 0;
     constexpr bool DIRECTED = (OBJ & 2) != 0;
     extern __shared__ int32_t sm[];
@@ -237,20 +240,21 @@ __global__ __launch_bounds__(256) void best_restart_kernel(const int64_t* __rest
 
 template <int OBJ>
 hipError_t launch_general(const int32_t* c, int N, int restarts, int32_t* tours, int64_t* costs, int32_t* moves,
-                          hipStream_t s) {
+                          const int32_t* skip_if_small, hipStream_t s) {
     const int threads = ((N + 63) / 64) * 64;
     const size_t lds = sizeof(int32_t) * 7 * (size_t)N;
-    hipLaunchKernelGGL((twoopt_general_kernel<OBJ>), dim3(restarts), dim3(threads), lds, s, c, N, tours, costs, moves);
+    hipLaunchKernelGGL((twoopt_general_kernel<OBJ>), dim3(restarts), dim3(threads), lds, s, c, N, tours, costs, moves,
+                       skip_if_small);
     return hipGetLastError();
 }
 
 hipError_t launch_general_objective(const int32_t* c, int N, int objective, int restarts, int32_t* tours,
-                                    int64_t* costs, int32_t* moves, hipStream_t s) {
+                                    int64_t* costs, int32_t* moves, const int32_t* skip_if_small, hipStream_t s) {
     switch (objective) {
-        case 0: return launch_general<0>(c, N, restarts, tours, costs, moves, s);
-        case 1: return launch_general<1>(c, N, restarts, tours, costs, moves, s);
-        case 2: return launch_general<2>(c, N, restarts, tours, costs, moves, s);
-        default: return launch_general<3>(c, N, restarts, tours, costs, moves, s);
+        case 0: return launch_general<0>(c, N, restarts, tours, costs, moves, skip_if_small, s);
+        case 1: return launch_general<1>(c, N, restarts, tours, costs, moves, skip_if_small, s);
+        case 2: return launch_general<2>(c, N, restarts, tours, costs, moves, skip_if_small, s);
+        default: return launch_general<3>(c, N, restarts, tours, costs, moves, skip_if_small, s);
     }
 }
 
@@ -259,7 +263,6 @@ hipError_t launch_general_objective(const int32_t* c, int N, int objective, int 
 hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, uint64_t seed, bool tours_hold_init,
                        int32_t* tours, int64_t* costs, int32_t* moves, int32_t* flags, int32_t* best_perm,
                        int64_t* best_cost, int32_t* best_restart, hipStream_t s) {
-    (void)flags;
     hipError_t e;
     if (N == 64 && objective == 0) {
         e = launch_2opt_sum_n64(c, restarts, seed, !tours_hold_init, tours, costs, moves, s);
@@ -268,7 +271,17 @@ hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, uin
             e = launch_init_tours(N, 0, restarts, seed, tours, s);
             if (e != hipSuccess) return e;
         }
-        e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, s);
+        if (objective == 0 && (N == 128 || N == 256)) {
+            // 16-bit LDS matrix path when max(c) < 2^16, else the general kernel: both are enqueued and the
+            // matrix maximum, computed on the device, decides which one does the work (no host round trip)
+            e = launch_matrix_max(c, N, flags, s);
+            if (e != hipSuccess) return e;
+            e = launch_2opt_sum_multi(c, N, restarts, tours, costs, moves, flags, s);
+            if (e != hipSuccess) return e;
+            e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, s);
+        } else {
+            e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, nullptr, s);
+        }
     }
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(best_restart_kernel, dim3(1), dim3(256), 0, s, costs, tours, N, restarts, best_perm, best_cost,

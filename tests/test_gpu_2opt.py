@@ -43,6 +43,24 @@ def test_large_costs_up_to_cost_max(obj):
     assert_search_equal(gpu_search(c, obj, 48, seed=5), want)
 
 
+@pytest.mark.parametrize("n,restarts", [(128, 24), (256, 20)])
+def test_n128_n256_sum_fast_path_and_its_fallback(n, restarts):
+    """Several ranks per lane with a 16-bit LDS matrix when max(c) < 2^16; entries at or above 2^16 must
+    take the general kernel (same results either way); and a matrix full of ties."""
+    for hi, tag in ((6000, "16-bit path"), (65535, "16-bit path, largest entry 65535"), (65536, "fallback at 2^16"),
+                    (COST_MAX, "fallback, COST_MAX"), (3, "ties")):
+        say(f"2-opt N={n} sum, entries up to {hi} ({tag})")
+        c = random_matrix(n, 7000 + n + hi % 97, symmetric=True, lo=1, hi=hi)
+        c[3, 5] = c[5, 3] = hi
+        want = oracle.search(c, 0, restarts, seed=11 + n)
+        assert_search_equal(gpu_search(c, 0, restarts, seed=11 + n), want)
+    say(f"2-opt N={n} sum, caller-provided initial tours, restarts not a multiple of 16")
+    c = random_matrix(n, 1234 + n, symmetric=True, lo=1, hi=9000)
+    init = random_perms(n, 19, seed=n)
+    want = oracle.search(c, 0, 19, seed=0, init=init)
+    assert_search_equal(gpu_search(c, 0, 19, seed=5, init=init), want)
+
+
 def test_many_ties_lowest_id_wins():
     """Few distinct cost values: most sweeps have tied best moves and restarts tie on final cost."""
     for n, obj in ((16, 0), (64, 0), (64, 1), (32, 3), (64, 2)):

@@ -266,6 +266,8 @@ hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, uin
     hipError_t e;
     if (N == 64 && objective == 0) {
         e = launch_2opt_sum_n64(c, restarts, seed, !tours_hold_init, tours, costs, moves, s);
+    } else if (N == 64 && (objective & 1)) {
+        e = launch_2opt_max_n64(c, restarts, seed, !tours_hold_init, tours, costs, moves, s);
     } else {
         if (!tours_hold_init) {
             e = launch_init_tours(N, 0, restarts, seed, tours, s);

@@ -26,90 +26,17 @@
 
 #include "cc_device.h"
 #include "cc_internal.h"
+#include "cc_wave64.h"
 
 namespace cc {
 using namespace ccd;
 
 namespace {
 
-constexpr int kN = 64;
+using namespace w64;
 constexpr int kSh = 14;           // key = delta << 14 | rank << 8 | column byte offset
 constexpr int kIdBits = 12;       // move id i*64 + j
 constexpr int kCostMax = (1 << 21) - 1;
-
-// DPP controls (gfx9 encoding)
-constexpr int kDppQuadSwap1 = 0xB1;     // quad_perm:[1,0,3,2]
-constexpr int kDppQuadSwap2 = 0x4E;     // quad_perm:[2,3,0,1]
-constexpr int kDppWaveRol1 = 0x134;     // lane p <- lane p+1 (cyclic over 64 lanes)
-constexpr int kDppWaveRor1 = 0x13C;     // lane p <- lane p-1 (cyclic over 64 lanes)
-constexpr int kDppRowMirror = 0x140;
-constexpr int kDppRowHalfMirror = 0x141;
-constexpr int kDppRowBcast15 = 0x142;
-constexpr int kDppRowBcast31 = 0x143;
-
-template <int CTRL, int ROW_MASK = 0xf>
-__device__ __forceinline__ int dpp(int old, int v) {
-    return __builtin_amdgcn_update_dpp(old, v, CTRL, ROW_MASK, 0xf, false);
-}
-// full-wave rotates read a valid lane everywhere, so the "old" operand is irrelevant (bound_ctrl set)
-__device__ __forceinline__ int from_next_lane(int v) {
-    return __builtin_amdgcn_update_dpp(v, v, kDppWaveRol1, 0xf, 0xf, true);
-}
-__device__ __forceinline__ int from_prev_lane(int v) {
-    return __builtin_amdgcn_update_dpp(v, v, kDppWaveRor1, 0xf, 0xf, true);
-}
-__device__ __forceinline__ long long from_next_lane(long long v) {
-    const int lo = from_next_lane((int)(unsigned)(unsigned long long)v);
-    const int hi = from_next_lane((int)((unsigned long long)v >> 32));
-    return (long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo);
-}
-
-// Minimum over the wave, returned as a wave-uniform value.  Six DPP steps: pairs, quads, half rows,
-// rows, then the last lane of each row is folded into the next row(s); lane 63 ends with the total.
-// Each step reads the register the previous step wrote, which needs two wait states before a DPP read.
-__device__ __forceinline__ int wave_min_uniform(int v) {
-    asm volatile(
-        "s_nop 1\n\t"
-        "v_min_i32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
-        "s_nop 1\n\t"
-        "v_min_i32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
-        "s_nop 1\n\t"
-        "v_min_i32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
-        "s_nop 1\n\t"
-        "v_min_i32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
-        "s_nop 1\n\t"
-        "v_min_i32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
-        "s_nop 1\n\t"
-        "v_min_i32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
-        "s_nop 1"
-        : "+v"(v));
-    return __builtin_amdgcn_readlane(v, 63);
-}
-__device__ __forceinline__ long long wave_min_uniform(long long v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) {
-        const long long o = __shfl_xor(v, m, kWave);
-        v = o < v ? o : v;
-    }
-    return v;
-}
-
-// Seeded Fisher-Yates shuffle without a serial chain across lanes.  Lane v follows node v: at step k
-// (k = 63 .. 1) ranks k and j_k swap, so a node sitting at rank k moves to j_k and a node sitting at
-// j_k moves to k, where it stays (later steps only touch ranks below k).  Swap partners are drawn in
-// parallel, one per lane, and broadcast step by step; a forward lane permute finally turns
-// "node -> rank" into "rank -> node".
-__device__ __forceinline__ int init_tour_in_wave(uint64_t seed, uint32_t r, int lane) {
-    const int partner = lane ? shuffle_partner(seed, r, lane) : 0;
-    int pos = lane;
-#pragma unroll
-    for (int k = kN - 1; k >= 1; --k) {
-        const int j = __builtin_amdgcn_readlane(partner, k);
-        const int moved = (pos == k) ? j : pos;
-        pos = (pos == j) ? k : moved;
-    }
-    return __builtin_amdgcn_ds_permute(pos << 2, lane);
-}
 
 // One descent.  m: LDS matrix, entries c << 14 (narrow) or c (wide).  Returns the final tour in t.
 template <bool WIDE>

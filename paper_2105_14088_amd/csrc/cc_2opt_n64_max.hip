@@ -1,0 +1,157 @@
+// 2-opt descent for N = 64 under the bottleneck (max-hop) objective, directed: one wavefront per
+// restart, one ring rank per lane, the cost matrix staged once per workgroup in LDS.  Also serves the
+// undirected max objective (on a symmetric matrix both walking directions of a move cost the same and
+// the lower id, orientation 0, wins, which is exactly the undirected trajectory).
+//
+// Cyclic-diagonal sweep as in cc_2opt_n64.hip.  Exchanging ring edges a and b = a + d (edge p joins
+// ranks p-1 and p) cuts the ring into S1 = ranks a..b-1 and S2 = ranks b..a-1 and rejoins them with one
+// of the pieces reversed.  As a directed ring the result can be walked two ways:
+//   A: S2 as it is, S1 backwards:  new hops c[t[b-1]][t[a-1]], c[t[b]][t[a]];  S2's inner hops f, S1's b
+//   B: the opposite direction:     new hops c[t[a-1]][t[b-1]], c[t[a]][t[b]];  S2's inner hops b, S1's f
+// (f[p] = c[t[p]][t[p-1]] is hop p as walked now, b[p] = c[t[p-1]][t[p]] the same edge the other way).
+// With G(p,q) = c[t[p]][t[q]] and GT(p,q) = c[t[q]][t[p]], lane a gathers G(a,b) and GT(a,b) and takes
+// G(a-1,b-1), GT(a-1,b-1) from lane a-1 by a DPP rotate; value = max of the two new hops and of the
+// largest inner hop of each piece:
+//   S1's inner edges a+1..b-1 grow by one edge per diagonal: a running max, fed by the rotating hop words;
+//   S2's inner edges b+1..a-1 are a cyclic window of 31..61 edges: max of two windows of 32 (16 at d = 32)
+//   from a doubling table M_k[p] = max f[p .. p+2^k-1] built once per sweep with lane permutes.
+// In move terms (cc.h): if a < b (or b = 0) the move is (i, j) = (a, b-1) and A / B are orientations 0 / 1;
+// otherwise it is (b, a-1) (or (b, 63) when a = 0) and A / B are orientations 1 / 0.  Per lane two running
+// minima are kept, over key = value << 6 | rank(b), rank(b) = (b-1) mod 64, one for A and one for B; after
+// the sweep both are turned into (value, move id) and min-reduced lexicographically over the wave.
+#include "cc_device.h"
+#include "cc_internal.h"
+#include "cc_wave64.h"
+
+namespace cc {
+using namespace ccd;
+
+namespace {
+
+using namespace w64;
+
+constexpr int kCostMax = (1 << 21) - 1;
+constexpr int kNone = 0x7fffffff;
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2)))
+void twoopt_max_n64_kernel(const int32_t* __restrict__ c, int restarts, uint64_t seed, int generate,
+                           int32_t* __restrict__ tours, int64_t* __restrict__ costs,
+                           int32_t* __restrict__ moves) {
+    __shared__ __attribute__((aligned(256))) int32_t m[kN * kN];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+
+    // the matrix loads are issued first and stay in flight while the wave builds its initial tour
+    int v[kN * kN / 256];
+#pragma unroll
+    for (int k = 0; k < kN * kN / 256; ++k) v[k] = c[tid + 256 * k];
+    const int64_t r = (int64_t)blockIdx.x * 4 + wv;
+    int t = 0;
+    if (r < restarts)
+        t = generate ? init_tour_in_wave(seed, (uint32_t)r, lane) : clampi(tours[r * kN + lane], 0, kN - 1);
+#pragma unroll
+    for (int k = 0; k < kN * kN / 256; ++k) m[tid + 256 * k] = clampi(v[k], 0, kCostMax);
+    __syncthreads();
+    if (r >= restarts) return;
+
+    const char* mbytes = (const char*)m;
+    const int rank_a = (lane + kN - 1) & (kN - 1);
+    // byte indices for lane permutes "take the value of lane p + k"
+    const int from2 = ((lane + 2) & 63) << 2, from4 = ((lane + 4) & 63) << 2, from8 = ((lane + 8) & 63) << 2;
+    const int from16 = ((lane + 16) & 63) << 2, from32 = ((lane + 32) & 63) << 2;
+    const int from33 = ((lane + 33) & 63) << 2, from48 = ((lane + 48) & 63) << 2;
+    auto take = [](int index, int value) { return __builtin_amdgcn_ds_bpermute(index, value); };
+
+    int cur = 0, applied = 0;
+    bool first = true;
+    for (;;) {
+        const int tprev = from_prev_lane(t);
+        const int rowofs = t << 8, col = t << 2;
+        const int f = *(const int32_t*)(mbytes + (rowofs | (tprev << 2)));
+        const int bw = *(const int32_t*)(mbytes + ((tprev << 8) | col));
+        if (first) {
+            cur = wave_max(f);
+            first = false;
+        }
+        // doubling tables: m5?[p] = max over hops p .. p+31, m4?[p] = max over hops p .. p+15
+        int m4f, m5f, m4b, m5b;
+        {
+            int x = max(f, from_next_lane(f)), y = max(bw, from_next_lane(bw));
+            x = max(x, take(from2, x));
+            y = max(y, take(from2, y));
+            x = max(x, take(from4, x));
+            y = max(y, take(from4, y));
+            m4f = max(x, take(from8, x));
+            m4b = max(y, take(from8, y));
+            m5f = max(m4f, take(from16, m4f));
+            m5b = max(m4b, take(from16, m4b));
+        }
+        const int far_f = take(from32, m5f), far_b = take(from32, m5b);              // hops a+32 .. a+63
+        const int far32_f = max(take(from33, m4f), take(from48, m4f));               // hops a+33 .. a+63
+        const int far32_b = max(take(from33, m4b), take(from48, m4b));
+        // words that travel round the wave, here in their state for partner a+1
+        int w = from_next_lane((rank_a << 26) | (t << 8) | (t << 2));
+        int fb = from_next_lane(f), bwb = from_next_lane(bw);
+        int r5f = from_next_lane(from_next_lane(m5f)), r5b = from_next_lane(from_next_lane(m5b));
+        int s1f = 0, s1b = 0, bestA = kNone, bestB = kNone;
+#pragma unroll
+        for (int d = 2; d <= kN / 2; ++d) {
+            s1f = max(s1f, fb);          // edge b-1 (the previous diagonal's partner) joins S1's inner edges
+            s1b = max(s1b, bwb);
+            w = from_next_lane(w);
+            if (d < kN / 2) {
+                fb = from_next_lane(fb);
+                bwb = from_next_lane(bwb);
+                r5f = from_next_lane(r5f);   // max over hops b+1 .. b+32
+                r5b = from_next_lane(r5b);
+            }
+            const int G = *(const int32_t*)(mbytes + ((w & 0xfc) | rowofs));        // c[t[a]][t[b]]
+            const int GT = *(const int32_t*)(mbytes + ((w & 0x3f00) | col));        // c[t[b]][t[a]]
+            const int EG = from_prev_lane(G), EGT = from_prev_lane(GT);
+            const int s2f = d < kN / 2 ? max(r5f, far_f) : far32_f;
+            const int s2b = d < kN / 2 ? max(r5b, far_b) : far32_b;
+            const int valA = max(max(EGT, GT), max(s2f, s1b));
+            const int valB = max(max(EG, G), max(s2b, s1f));
+            bestA = min(bestA, (int)__builtin_amdgcn_alignbit((unsigned)valA, (unsigned)w, 26));
+            bestB = min(bestB, (int)__builtin_amdgcn_alignbit((unsigned)valB, (unsigned)w, 26));
+        }
+        // (value, move id) of the lane's two candidates; keep the lexicographically smaller
+        int val = kNone, id = kNone;
+#pragma unroll
+        for (int which = 0; which < 2; ++which) {
+            const int key = which ? bestB : bestA;
+            const int kv = key >> 6, rk = key & 63;
+            const int b = (rk + 1) & 63;
+            const int lo = min(lane, b), hi = max(lane, b);
+            const int ij = lo ? lo * kN + hi - 1 : hi * kN + kN - 1;
+            const int flip = rk < rank_a ? 1 : 0;       // the reversed piece is S2, not S1
+            const int kid = ij * 2 + (which ^ flip);
+            if (kv < val || (kv == val && kid < id)) { val = kv; id = kid; }
+        }
+        const int vwin = wave_min_uniform(val);
+        if (vwin >= cur) break;
+        const int idwin = wave_min_uniform(val == vwin ? id : kNone);
+        const int o = idwin & 1, ij = idwin >> 1, mi = ij >> 6, mj = ij & 63;
+        const int p0 = o ? (lane ? kN - lane : 0) : lane;
+        const int src = (p0 >= mi && p0 <= mj) ? mi + mj - p0 : p0;
+        t = __shfl(t, src, kWave);
+        cur = vwin;
+        ++applied;
+    }
+    tours[r * kN + lane] = t;
+    if (lane == 0) {
+        costs[r] = (int64_t)cur;
+        moves[r] = applied;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_2opt_max_n64(const int32_t* c, int restarts, uint64_t seed, bool generate, int32_t* tours,
+                               int64_t* costs, int32_t* moves, hipStream_t s) {
+    const int grid = (restarts + 3) / 4;
+    hipLaunchKernelGGL(twoopt_max_n64_kernel, dim3(grid), dim3(256), 0, s, c, restarts, seed, generate ? 1 : 0, tours,
+                       costs, moves);
+    return hipGetLastError();
+}
+
+}  // namespace cc

@@ -261,8 +261,8 @@ hipError_t launch_general_objective(const int32_t* c, int N, int objective, int 
 }  // namespace
 
 hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, uint64_t seed, bool tours_hold_init,
-                       int32_t* tours, int64_t* costs, int32_t* moves, int32_t* flags, int32_t* best_perm,
-                       int64_t* best_cost, int32_t* best_restart, hipStream_t s) {
+                       int32_t* tours, int64_t* costs, int32_t* moves, int32_t* flags, uint16_t* mat16,
+                       int32_t* best_perm, int64_t* best_cost, int32_t* best_restart, hipStream_t s) {
     hipError_t e;
     if (N == 64 && objective == 0) {
         e = launch_2opt_sum_n64(c, restarts, seed, !tours_hold_init, tours, costs, moves, s);
@@ -279,6 +279,12 @@ hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, uin
             e = launch_matrix_max(c, N, flags, s);
             if (e != hipSuccess) return e;
             e = launch_2opt_sum_multi(c, N, restarts, tours, costs, moves, flags, s);
+            if (e != hipSuccess) return e;
+            e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, s);
+        } else if (objective == 0 && N == 1024) {
+            e = launch_matrix_max(c, N, flags, s);
+            if (e != hipSuccess) return e;
+            e = launch_2opt_sum_n1024(c, mat16, restarts, tours, costs, moves, flags, s);
             if (e != hipSuccess) return e;
             e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, s);
         } else {

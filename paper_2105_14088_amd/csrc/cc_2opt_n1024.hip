@@ -1,0 +1,251 @@
+// 2-opt descent for N = 1024, ring-sum objective on a symmetric matrix: one 16-wave workgroup per
+// restart.  The matrix (2 MiB as 16-bit entries) cannot live in LDS, so the sweep is organised by
+// matrix ROW: every move needs G(a-1, b-1) + G(a, b) with G(p, q) = c[t[p]][t[q]], i.e. one entry of
+// row t[a] and one of row t[a-1].  A wave owns 64 consecutive ranks a; for each it streams row t[a]
+// (2 KiB, coalesced, L2-resident) into its private LDS buffer and gathers that row at the columns of
+// the partners b = a + d.  Lanes own DIAGONALS: lane l, slot k scores d = 2 + 8l + k (d = 2 .. 513
+// covers every pair of non-adjacent ring edges; 513 repeats 511), so
+//   - the row-(a-1) term of a move is the same lane's gather of the previous row: no cross-lane traffic;
+//   - the partner words of a lane are a window of 8 consecutive ranks that slides by one rank per row;
+//     it is re-read from LDS (two aligned 16-byte loads per array) every 8 rows.
+// Keys.  key = (G + G - f[a] - f[b]) << 11 | rank.  A slot sees the moves of one diagonal for all rows
+// of the wave; their ids are ordered by the smaller rank of the pair: rank = 2a for a < b (the pair is
+// the move (a, b-1), or (a, N-1) when b wraps to 0) and 2b+1 for b < a (the move (b, a-1)), which is
+// min(2a, 2b+1).  The partner word carries 2b+1 (2047 for b = 0), the row contributes 2a (2047 for row
+// 0, whose pairs (0, b) are the moves (b, N-1) and sort after everything else in their slot).
+// After the sweep every slot's key is turned into (delta, move id); lanes, waves and then the
+// workgroup take the lexicographic minimum, so the result is independent of the visiting order.
+// Needs max(c) < 2^16 (16-bit copy of the matrix in the workspace); otherwise the general kernel runs.
+#include "cc_device.h"
+#include "cc_internal.h"
+
+namespace cc {
+using namespace ccd;
+
+namespace {
+
+constexpr int N = 1024;
+constexpr int kWaves = 16;
+constexpr int kSlots = 8;
+constexpr int kRankBits = 11;
+constexpr int kRankMask = (1 << kRankBits) - 1;
+constexpr int kPad = 8;                      // the partner arrays are indexed from -8
+constexpr int kWin = kPad + N + 64 * kSlots; // entry x holds rank (x + 2) mod N, x in [-8, 1536)
+constexpr int kRowBytes = N * 2;
+
+struct Layout {
+    static constexpr size_t t = 0;                                   // int32 [N]   tour
+    static constexpr size_t f = t + sizeof(int32_t) * N;             // int32 [N]   hop into each rank
+    static constexpr size_t tw = f + sizeof(int32_t) * N;            // int32 [kWin] column byte offset of the partner
+    static constexpr size_t kw = tw + sizeof(int32_t) * kWin;        // int32 [kWin] -f[b] << 11 | 2b+1
+    static constexpr size_t red = kw + sizeof(int32_t) * kWin;       // int32 [2 * kWaves + 2]
+    static constexpr size_t rows = (red + sizeof(int32_t) * 64 + 255) & ~(size_t)255;   // uint16 [kWaves][2][N]
+    static constexpr size_t total = rows + (size_t)kWaves * 2 * kRowBytes;
+};
+
+// 16-bit copy of the matrix (entries clamped); skipped when the maximum does not fit
+__global__ __launch_bounds__(256) void matrix_to_u16_kernel(const int32_t* __restrict__ c, int n2,
+                                                            uint16_t* __restrict__ c16,
+                                                            const int32_t* __restrict__ flags) {
+    if (flags[0] >= (1 << 16)) return;
+    for (int e = blockIdx.x * 256 + threadIdx.x; e < n2 / 2; e += gridDim.x * 256) {
+        const int lo = clampi(c[2 * e], 0, 0xffff), hi = clampi(c[2 * e + 1], 0, 0xffff);
+        ((uint32_t*)c16)[e] = (uint32_t)lo | ((uint32_t)hi << 16);
+    }
+}
+
+__global__ __launch_bounds__(64 * kWaves) void twoopt_sum_n1024_kernel(const uint16_t* __restrict__ c16, int restarts,
+                                                                       int32_t* __restrict__ tours,
+                                                                       int64_t* __restrict__ costs,
+                                                                       int32_t* __restrict__ moves,
+                                                                       const int32_t* __restrict__ flags) {
+    extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
+    if (flags[0] >= (1 << 16)) return;
+    int32_t* T = (int32_t*)(smem + Layout::t);
+    int32_t* F = (int32_t*)(smem + Layout::f);
+    int32_t* TW = (int32_t*)(smem + Layout::tw) + kPad;
+    int32_t* KW = (int32_t*)(smem + Layout::kw) + kPad;
+    int32_t* red = (int32_t*)(smem + Layout::red);
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int64_t r = blockIdx.x;
+    const int wbase = (int)(Layout::rows + (size_t)wv * 2 * kRowBytes);   // byte offset of this wave's row buffer 0
+
+    T[tid] = clampi(tours[r * N + tid], 0, N - 1);
+    __syncthreads();
+
+    long long cur = 0;
+    int applied = 0;
+    bool first = true;
+    for (;;) {
+        // ---- hops and the partner arrays for the current tour
+        {
+            const int tp = T[tid], tq = T[(tid + N - 1) & (N - 1)];
+            const int f = c16[tp * N + tq];
+            F[tid] = f;
+            const int kp = (int)(0u - ((unsigned)f << kRankBits)) + (tid ? 2 * tid + 1 : kRankMask);
+            const int x = tid - 2;
+            TW[x] = 2 * tp;
+            KW[x] = kp;
+            if (x + N < N + 64 * kSlots) {
+                TW[x + N] = 2 * tp;
+                KW[x + N] = kp;
+            }
+            if (first) {
+                const int s = wave_sum(f);
+                if (lane == 0) red[wv] = s;
+                __syncthreads();
+                long long tot = 0;
+                for (int k = 0; k < kWaves; ++k) tot += red[k];
+                cur = tot;
+                first = false;
+            }
+        }
+        __syncthreads();
+
+        // ---- this wave's 64 rows
+        const int a0 = wv * 64;
+        const int row_node = T[a0 + lane];                              // lane q: node whose row is streamed for rank a0+q
+        const int row_negf = -F[a0 + lane];
+        const int row_rank = (a0 + lane) ? 2 * (a0 + lane) : kRankMask;
+        const int gb = a0 + kSlots * lane;                              // window of row a0 starts at entry gb
+        int cwt[kSlots], cwk[kSlots], nwt[kSlots], nwk[kSlots], dprev[kSlots], best[kSlots];
+        {
+            const int4 a = *(const int4*)(TW + gb), b = *(const int4*)(TW + gb + 4);
+            const int4 c4 = *(const int4*)(KW + gb), d4 = *(const int4*)(KW + gb + 4);
+            cwt[0] = a.x + wbase; cwt[1] = a.y + wbase; cwt[2] = a.z + wbase; cwt[3] = a.w + wbase;
+            cwt[4] = b.x + wbase; cwt[5] = b.y + wbase; cwt[6] = b.z + wbase; cwt[7] = b.w + wbase;
+            cwk[0] = c4.x; cwk[1] = c4.y; cwk[2] = c4.z; cwk[3] = c4.w;
+            cwk[4] = d4.x; cwk[5] = d4.y; cwk[6] = d4.z; cwk[7] = d4.w;
+        }
+#pragma unroll
+        for (int k = 0; k < kSlots; ++k) best[k] = 0x7fffffff;
+
+        auto load_row = [&](int node, uint4& v0, uint4& v1) {
+            const uint4* src = (const uint4*)(c16 + (size_t)node * N);
+            v0 = src[lane];
+            v1 = src[64 + lane];
+        };
+        auto store_row = [&](int parity, const uint4& v0, const uint4& v1) {
+            uint4* dst = (uint4*)(smem + wbase + parity * kRowBytes);
+            dst[lane] = v0;
+            dst[64 + lane] = v1;
+        };
+        uint4 v0, v1;
+        // row a0-1 only provides the "previous row" gathers of row a0; it goes through buffer 1
+        {
+            const int node = T[(a0 + N - 1) & (N - 1)];
+            load_row(node, v0, v1);
+            store_row(1, v0, v1);
+            const int extra = TW[gb - 1] + wbase;
+            dprev[0] = *(const uint16_t*)(smem + extra + kRowBytes);
+#pragma unroll
+            for (int k = 1; k < kSlots; ++k) dprev[k] = *(const uint16_t*)(smem + cwt[k - 1] + kRowBytes);
+        }
+        load_row(__builtin_amdgcn_readlane(row_node, 0), v0, v1);
+#pragma unroll 1
+        for (int g = 0; g < 8; ++g) {
+            {
+                const int nb = gb + kSlots * (g + 1);
+                const int4 a = *(const int4*)(TW + nb), b = *(const int4*)(TW + nb + 4);
+                const int4 c4 = *(const int4*)(KW + nb), d4 = *(const int4*)(KW + nb + 4);
+                nwt[0] = a.x + wbase; nwt[1] = a.y + wbase; nwt[2] = a.z + wbase; nwt[3] = a.w + wbase;
+                nwt[4] = b.x + wbase; nwt[5] = b.y + wbase; nwt[6] = b.z + wbase; nwt[7] = b.w + wbase;
+                nwk[0] = c4.x; nwk[1] = c4.y; nwk[2] = c4.z; nwk[3] = c4.w;
+                nwk[4] = d4.x; nwk[5] = d4.y; nwk[6] = d4.z; nwk[7] = d4.w;
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int q = 8 * g + j;                 // row a0 + q, buffer j & 1
+                store_row(j & 1, v0, v1);
+                if (q + 1 < 64) load_row(__builtin_amdgcn_readlane(row_node, q + 1), v0, v1);
+                const int negfa = __builtin_amdgcn_readlane(row_negf, q);
+                const int rank2a = __builtin_amdgcn_readlane(row_rank, q);
+#pragma unroll
+                for (int k = 0; k < kSlots; ++k) {
+                    const int idx = j + k;
+                    const int twv = idx < kSlots ? cwt[idx] : nwt[idx - kSlots];
+                    const int kwv = idx < kSlots ? cwk[idx] : nwk[idx - kSlots];
+                    const int D = *(const uint16_t*)(smem + twv + (j & 1) * kRowBytes);
+                    const int sum = dprev[k] + D + negfa;
+                    const int keyfull = (int)(((unsigned)sum << kRankBits) + (unsigned)kwv);
+                    const int keyalt = (keyfull & ~kRankMask) | rank2a;
+                    best[k] = min(best[k], min(keyfull, keyalt));
+                    dprev[k] = D;
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < kSlots; ++k) {
+                cwt[k] = nwt[k];
+                cwk[k] = nwk[k];
+            }
+        }
+
+        // ---- slot keys -> (delta, move id); minimum over slots, lanes, waves
+        int bd = 0x7fffffff, bid = 0x7fffffff;
+#pragma unroll
+        for (int k = 0; k < kSlots; ++k) {
+            const int d = 2 + kSlots * lane + k;
+            const int delta = best[k] >> kRankBits, rank = best[k] & kRankMask;
+            int id;
+            if (!(rank & 1)) {
+                const int a = rank >> 1;                       // pair (a, a+d): move (a, a+d-1)
+                id = a * N + a + d - 1;
+            } else {
+                const int b = rank >> 1;
+                if (b == d) id = d * N + N - 1;                // row 0: pair (0, d): move (d, N-1)
+                else id = b * N + (b + N - d) - 1;             // pair (b+N-d, b): move (b, a-1)
+            }
+            if (delta < bd || (delta == bd && id < bid)) { bd = delta; bid = id; }
+        }
+        {
+            int dmin = bd;
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) dmin = min(dmin, __shfl_xor(dmin, m, kWave));
+            int imin = bd == dmin ? bid : 0x7fffffff;
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) imin = min(imin, __shfl_xor(imin, m, kWave));
+            if (lane == 0) { red[2 * wv] = dmin; red[2 * wv + 1] = imin; }
+        }
+        __syncthreads();
+        int gd = red[0], gid = red[1];
+        for (int k = 1; k < kWaves; ++k) {
+            const int d2 = red[2 * k], i2 = red[2 * k + 1];
+            if (d2 < gd || (d2 == gd && i2 < gid)) { gd = d2; gid = i2; }
+        }
+        if (gd >= 0) break;
+        // ---- reverse ranks mi..mj
+        const int mi = gid >> 10, mj = gid & (N - 1);
+        const int src = (tid >= mi && tid <= mj) ? mi + mj - tid : tid;
+        const int val = T[src];
+        __syncthreads();
+        T[tid] = val;
+        __syncthreads();
+        cur += gd;
+        ++applied;
+    }
+    tours[r * N + tid] = T[tid];
+    if (tid == 0) {
+        costs[r] = cur;
+        moves[r] = applied;
+    }
+}
+
+}  // namespace
+
+size_t twoopt_n1024_matrix_copy_bytes() { return (size_t)N * N * 2; }
+
+// `tours` must hold the initial tours, flags[0] the matrix maximum, c16 room for N*N 16-bit entries.
+hipError_t launch_2opt_sum_n1024(const int32_t* c, uint16_t* c16, int restarts, int32_t* tours, int64_t* costs,
+                                 int32_t* moves, const int32_t* flags, hipStream_t s) {
+    hipLaunchKernelGGL(matrix_to_u16_kernel, dim3(512), dim3(256), 0, s, c, N * N, c16, flags);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void*)twoopt_sum_n1024_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)Layout::total);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(twoopt_sum_n1024_kernel, dim3(restarts), dim3(64 * kWaves), Layout::total, s, c16, restarts,
+                       tours, costs, moves, flags);
+    return hipGetLastError();
+}
+
+}  // namespace cc

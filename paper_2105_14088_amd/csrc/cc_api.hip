@@ -24,9 +24,10 @@ bool is_pow2(int n) { return n > 0 && (n & (n - 1)) == 0; }
 
 size_t align256(size_t x) { return (x + 255u) & ~(size_t)255u; }
 
-// Workspace layout of cc_2opt_search_ex: [flags 256 B][costs int64 R][moves int32 R][tours int32 R*N]
+// Workspace layout of cc_2opt_search_ex:
+// [flags 256 B][costs int64 R][moves int32 R][tours int32 R*N][16-bit matrix copy, N > 256 only]
 struct WsLayout {
-    size_t flags, costs, moves, tours, total;
+    size_t flags, costs, moves, tours, mat16, total;
 };
 
 WsLayout ws_layout(int N, int restarts) {
@@ -35,7 +36,8 @@ WsLayout ws_layout(int N, int restarts) {
     w.costs = 256;
     w.moves = w.costs + align256(sizeof(int64_t) * (size_t)restarts);
     w.tours = w.moves + align256(sizeof(int32_t) * (size_t)restarts);
-    w.total = w.tours + align256(sizeof(int32_t) * (size_t)restarts * (size_t)N);
+    w.mat16 = w.tours + align256(sizeof(int32_t) * (size_t)restarts * (size_t)N);
+    w.total = w.mat16 + (N > 256 ? align256(sizeof(uint16_t) * (size_t)N * (size_t)N) : 0);
     return w;
 }
 
@@ -95,7 +97,7 @@ int cc_2opt_search_ex(const int32_t* cost_matrix, int32_t N, int32_t objective, 
         CC_HIP(hipMemcpyAsync(tours, init_tours, sizeof(int32_t) * (size_t)restarts * (size_t)N,
                               hipMemcpyDeviceToDevice, s));
     CC_HIP(cc::launch_2opt(cost_matrix, N, objective, restarts, seed, init_tours != nullptr, tours, costs, moves, flags,
-                           best_perm, best_cost, best_restart, s));
+                           (uint16_t*)(base + w.mat16), best_perm, best_cost, best_restart, s));
     return CC_OK;
 }
 

@@ -16,10 +16,10 @@ hipError_t launch_validate(const int32_t* c, int N, bool require_symmetric, int3
 // 2-opt descent of `restarts` tours, then the lexicographic minimum over (cost, restart).
 // `tours` ([restarts, N]) receives the final tours; if `tours_hold_init` it holds the initial tours on
 // entry, otherwise restart r starts from the seeded shuffle (seed, r).  `flags` is a small int32
-// device scratch area (>= 64 B).
+// device scratch area (>= 64 B); `mat16` has room for N*N 16-bit entries when N > 256.
 hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, uint64_t seed, bool tours_hold_init,
-                       int32_t* tours, int64_t* costs, int32_t* moves, int32_t* flags, int32_t* best_perm,
-                       int64_t* best_cost, int32_t* best_restart, hipStream_t s);
+                       int32_t* tours, int64_t* costs, int32_t* moves, int32_t* flags, uint16_t* mat16,
+                       int32_t* best_perm, int64_t* best_cost, int32_t* best_restart, hipStream_t s);
 
 // N = 64, ring-sum objective: one wavefront per restart (cc_2opt_n64.hip).
 hipError_t launch_2opt_sum_n64(const int32_t* c, int restarts, uint64_t seed, bool generate, int32_t* tours,
@@ -34,6 +34,11 @@ hipError_t launch_2opt_max_n64(const int32_t* c, int restarts, uint64_t seed, bo
 // flags[0] >= 2^16.  `tours` must hold the initial tours.
 hipError_t launch_matrix_max(const int32_t* c, int N, int32_t* flags, hipStream_t s);
 hipError_t launch_2opt_sum_multi(const int32_t* c, int N, int restarts, int32_t* tours, int64_t* costs,
+                                 int32_t* moves, const int32_t* flags, hipStream_t s);
+
+// N = 1024, ring-sum objective, max(c) < 2^16: one 16-wave workgroup per restart, matrix rows streamed
+// through LDS (cc_2opt_n1024.hip).  Same flags convention as above.
+hipError_t launch_2opt_sum_n1024(const int32_t* c, uint16_t* c16, int restarts, int32_t* tours, int64_t* costs,
                                  int32_t* moves, const int32_t* flags, hipStream_t s);
 
 }  // namespace cc

@@ -61,6 +61,21 @@ def test_n128_n256_sum_fast_path_and_its_fallback(n, restarts):
     assert_search_equal(gpu_search(c, 0, 19, seed=5, init=init), want)
 
 
+def test_n1024_sum_row_streaming_path_and_its_fallback():
+    """N = 1024: rows streamed through LDS when max(c) < 2^16, general kernel otherwise; ties."""
+    from concurrent.futures import ThreadPoolExecutor
+    for hi, tag, restarts in ((3, "ties", 3), (65535, "16-bit path, largest entry 65535", 2), (65536, "fallback", 2)):
+        say(f"2-opt N=1024 sum, entries up to {hi} ({tag})")
+        c = random_matrix(1024, 8100 + hi % 89, symmetric=True, lo=1, hi=hi)
+        c[3, 5] = c[5, 3] = hi
+        with ThreadPoolExecutor(restarts) as ex:
+            parts = list(ex.map(lambda r: oracle.restarts(c, 0, 21, r, r + 1), range(restarts)))
+        got = gpu_search(c, 0, restarts, seed=21)
+        assert np.array_equal(got["costs"], np.concatenate([p[0] for p in parts]))
+        assert np.array_equal(got["tours"], np.concatenate([p[1] for p in parts]))
+        assert np.array_equal(got["moves"], np.concatenate([p[2] for p in parts]))
+
+
 def test_many_ties_lowest_id_wins():
     """Few distinct cost values: most sweeps have tied best moves and restarts tie on final cost."""
     for n, obj in ((16, 0), (64, 0), (64, 1), (32, 3), (64, 2)):

@@ -2,8 +2,9 @@
 // restart.  The matrix (2 MiB as 16-bit entries) cannot live in LDS, so the sweep is organised by
 // matrix ROW: every move needs G(a-1, b-1) + G(a, b) with G(p, q) = c[t[p]][t[q]], i.e. one entry of
 // row t[a] and one of row t[a-1].  A wave owns 64 consecutive ranks a; for each it streams row t[a]
-// (2 KiB, coalesced, L2-resident) into its private LDS buffer and gathers that row at the columns of
-// the partners b = a + d.  Lanes own DIAGONALS: lane l, slot k scores d = 2 + 8l + k (d = 2 .. 513
+// (2 KiB, coalesced, L2-resident) straight into one of its four private LDS buffers
+// (global_load_lds_dwordx4, three rows ahead, no staging registers) and gathers that row at the columns
+// of the partners b = a + d.  Lanes own DIAGONALS: lane l, slot k scores d = 2 + 8l + k (d = 2 .. 513
 // covers every pair of non-adjacent ring edges; 513 repeats 511), so
 //   - the row-(a-1) term of a move is the same lane's gather of the previous row: no cross-lane traffic;
 //   - the partner words of a lane are a window of 8 consecutive ranks that slides by one rank per row;
@@ -32,6 +33,7 @@ constexpr int kRankMask = (1 << kRankBits) - 1;
 constexpr int kPad = 8;                      // the partner arrays are indexed from -8
 constexpr int kWin = kPad + N + 64 * kSlots; // entry x holds rank (x + 2) mod N, x in [-8, 1536)
 constexpr int kRowBytes = N * 2;
+constexpr int kBufs = 4;                     // row buffers per wave: the current row and three in flight
 
 struct Layout {
     static constexpr size_t t = 0;                                   // int32 [N]   tour
@@ -39,8 +41,8 @@ struct Layout {
     static constexpr size_t tw = f + sizeof(int32_t) * N;            // int32 [kWin] column byte offset of the partner
     static constexpr size_t kw = tw + sizeof(int32_t) * kWin;        // int32 [kWin] -f[b] << 11 | 2b+1
     static constexpr size_t red = kw + sizeof(int32_t) * kWin;       // int32 [2 * kWaves + 2]
-    static constexpr size_t rows = (red + sizeof(int32_t) * 64 + 255) & ~(size_t)255;   // uint16 [kWaves][2][N]
-    static constexpr size_t total = rows + (size_t)kWaves * 2 * kRowBytes;
+    static constexpr size_t rows = (red + sizeof(int32_t) * 64 + 255) & ~(size_t)255;   // uint16 [kWaves][kBufs][N]
+    static constexpr size_t total = rows + (size_t)kWaves * kBufs * kRowBytes;
 };
 
 // 16-bit copy of the matrix (entries clamped); skipped when the maximum does not fit
@@ -68,7 +70,10 @@ __global__ __launch_bounds__(64 * kWaves) void twoopt_sum_n1024_kernel(const uin
     int32_t* red = (int32_t*)(smem + Layout::red);
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int64_t r = blockIdx.x;
-    const int wbase = (int)(Layout::rows + (size_t)wv * 2 * kRowBytes);   // byte offset of this wave's row buffer 0
+    const int wbase = (int)(Layout::rows + (size_t)wv * kBufs * kRowBytes);   // byte offset of this wave's row buffer 0
+    const unsigned lds_rows = (unsigned)__builtin_amdgcn_readfirstlane(
+        (int)(size_t)(__attribute__((address_space(3))) unsigned char*)(smem + wbase));   // wave-uniform, in an SGPR
+    const int lane16 = lane * 16;
 
     T[tid] = clampi(tours[r * N + tid], 0, N - 1);
     __syncthreads();
@@ -76,7 +81,27 @@ __global__ __launch_bounds__(64 * kWaves) void twoopt_sum_n1024_kernel(const uin
     long long cur = 0;
     int applied = 0;
     bool first = true;
+    const int a0 = wv * 64;
+    // Row `node` of the 16-bit matrix -> this wave's buffer `buf`, global memory to LDS without passing through
+    // registers: lane l moves bytes [16l, 16l+16) and [1024+16l, 1024+16l+16) of the row; M0 holds the LDS address
+    // of the buffer and the instruction offset applies to both addresses.  Completion is tracked by vmcnt.
+    auto row_dma = [&](int node, int buf) {
+        const void* rowptr = (const void*)(c16 + (size_t)node * N);
+        const unsigned dst = lds_rows + (unsigned)buf * kRowBytes;
+        asm volatile(
+            "s_mov_b32 m0, %2\n\t"
+            "s_nop 0\n\t"
+            "global_load_lds_dwordx4 %0, %1\n\t"
+            "global_load_lds_dwordx4 %0, %1 offset:1024"
+            :: "v"(lane16), "s"(rowptr), "s"(dst) : "memory");
+    };
     for (;;) {
+        // the wave's first rows (ranks a0-1, a0, a0+1, a0+2) are requested before anything else so that their L2
+        // latency overlaps the hop gathers below; every LDS read of the previous sweep has long completed
+        row_dma(__builtin_amdgcn_readfirstlane(T[(a0 + N - 1) & (N - 1)]), 3);
+        row_dma(__builtin_amdgcn_readfirstlane(T[a0]), 0);
+        row_dma(__builtin_amdgcn_readfirstlane(T[a0 + 1]), 1);
+        row_dma(__builtin_amdgcn_readfirstlane(T[a0 + 2]), 2);
         // ---- hops and the partner arrays for the current tour
         {
             const int tp = T[tid], tq = T[(tid + N - 1) & (N - 1)];
@@ -103,7 +128,6 @@ __global__ __launch_bounds__(64 * kWaves) void twoopt_sum_n1024_kernel(const uin
         __syncthreads();
 
         // ---- this wave's 64 rows
-        const int a0 = wv * 64;
         const int row_node = T[a0 + lane];                              // lane q: node whose row is streamed for rank a0+q
         const int row_negf = -F[a0 + lane];
         const int row_rank = (a0 + lane) ? 2 * (a0 + lane) : kRankMask;
@@ -120,44 +144,39 @@ __global__ __launch_bounds__(64 * kWaves) void twoopt_sum_n1024_kernel(const uin
 #pragma unroll
         for (int k = 0; k < kSlots; ++k) best[k] = 0x7fffffff;
 
-        auto load_row = [&](int node, uint4& v0, uint4& v1) {
-            const uint4* src = (const uint4*)(c16 + (size_t)node * N);
-            v0 = src[lane];
-            v1 = src[64 + lane];
-        };
-        auto store_row = [&](int parity, const uint4& v0, const uint4& v1) {
-            uint4* dst = (uint4*)(smem + wbase + parity * kRowBytes);
-            dst[lane] = v0;
-            dst[64 + lane] = v1;
-        };
-        uint4 v0, v1;
-        // row a0-1 only provides the "previous row" gathers of row a0; it goes through buffer 1
+        // row a0-1 only provides the "previous row" gathers of row a0; it sits in buffer 3
         {
-            const int node = T[(a0 + N - 1) & (N - 1)];
-            load_row(node, v0, v1);
-            store_row(1, v0, v1);
             const int extra = TW[gb - 1] + wbase;
-            dprev[0] = *(const uint16_t*)(smem + extra + kRowBytes);
+            asm volatile("s_waitcnt vmcnt(6)" ::: "memory");      // rows a0, a0+1, a0+2 may still be in flight
+            dprev[0] = *(const uint16_t*)(smem + extra + 3 * kRowBytes);
 #pragma unroll
-            for (int k = 1; k < kSlots; ++k) dprev[k] = *(const uint16_t*)(smem + cwt[k - 1] + kRowBytes);
+            for (int k = 1; k < kSlots; ++k) dprev[k] = *(const uint16_t*)(smem + cwt[k - 1] + 3 * kRowBytes);
         }
-        load_row(__builtin_amdgcn_readlane(row_node, 0), v0, v1);
 #pragma unroll 1
         for (int g = 0; g < 8; ++g) {
-            {
-                const int nb = gb + kSlots * (g + 1);
-                const int4 a = *(const int4*)(TW + nb), b = *(const int4*)(TW + nb + 4);
-                const int4 c4 = *(const int4*)(KW + nb), d4 = *(const int4*)(KW + nb + 4);
-                nwt[0] = a.x + wbase; nwt[1] = a.y + wbase; nwt[2] = a.z + wbase; nwt[3] = a.w + wbase;
-                nwt[4] = b.x + wbase; nwt[5] = b.y + wbase; nwt[6] = b.z + wbase; nwt[7] = b.w + wbase;
-                nwk[0] = c4.x; nwk[1] = c4.y; nwk[2] = c4.z; nwk[3] = c4.w;
-                nwk[4] = d4.x; nwk[5] = d4.y; nwk[6] = d4.z; nwk[7] = d4.w;
-            }
+            const int nb = gb + kSlots * (g + 1);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const int q = 8 * g + j;                 // row a0 + q, buffer j & 1
-                store_row(j & 1, v0, v1);
-                if (q + 1 < 64) load_row(__builtin_amdgcn_readlane(row_node, q + 1), v0, v1);
+                const int q = 8 * g + j;                 // row a0 + q, buffer q & 3 = j & 3
+                // the next window is fetched in two halves, each just before its first use
+                if (j == 0) {
+                    const int4 a = *(const int4*)(TW + nb), c4 = *(const int4*)(KW + nb);
+                    nwt[0] = a.x + wbase; nwt[1] = a.y + wbase; nwt[2] = a.z + wbase; nwt[3] = a.w + wbase;
+                    nwk[0] = c4.x; nwk[1] = c4.y; nwk[2] = c4.z; nwk[3] = c4.w;
+                }
+                if (j == 4) {
+                    const int4 b = *(const int4*)(TW + nb + 4), d4 = *(const int4*)(KW + nb + 4);
+                    nwt[4] = b.x + wbase; nwt[5] = b.y + wbase; nwt[6] = b.z + wbase; nwt[7] = b.w + wbase;
+                    nwk[4] = d4.x; nwk[5] = d4.y; nwk[6] = d4.z; nwk[7] = d4.w;
+                }
+                // buffer (q+3) & 3 was last read by row q-1: its gathers have returned once lgkmcnt is 0
+                const bool tail = (g == 7) && (j >= 5);          // rows 61..63: nothing left to request
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                if (!tail) row_dma(__builtin_amdgcn_readlane(row_node, q + 3), (j + 3) & 3);
+                if (!tail) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+                else if (j == 5) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+                else if (j == 6) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 const int negfa = __builtin_amdgcn_readlane(row_negf, q);
                 const int rank2a = __builtin_amdgcn_readlane(row_rank, q);
 #pragma unroll
@@ -165,13 +184,14 @@ __global__ __launch_bounds__(64 * kWaves) void twoopt_sum_n1024_kernel(const uin
                     const int idx = j + k;
                     const int twv = idx < kSlots ? cwt[idx] : nwt[idx - kSlots];
                     const int kwv = idx < kSlots ? cwk[idx] : nwk[idx - kSlots];
-                    const int D = *(const uint16_t*)(smem + twv + (j & 1) * kRowBytes);
+                    const int D = *(const uint16_t*)(smem + twv + (j & 3) * kRowBytes);
                     const int sum = dprev[k] + D + negfa;
                     const int keyfull = (int)(((unsigned)sum << kRankBits) + (unsigned)kwv);
                     const int keyalt = (keyfull & ~kRankMask) | rank2a;
                     best[k] = min(best[k], min(keyfull, keyalt));
                     dprev[k] = D;
                 }
+                __builtin_amdgcn_sched_barrier(0);   // keep one row's gathers in flight, not eight rows' (registers)
             }
 #pragma unroll
             for (int k = 0; k < kSlots; ++k) {

@@ -39,6 +39,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy before the steps (a dispatch of known HBM "
+                         "traffic that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py runs on one GPU only: restarts and orders are independent, nothing is exchanged "
@@ -82,6 +85,12 @@ def main():
         if ev:
             ev[4].record()
 
+    if args.pmc_calibration:
+        cal_src = torch.zeros(64 << 20, dtype=torch.int32, device="cuda")
+        cal_dst = torch.empty_like(cal_src)
+        cal_dst.copy_(cal_src)
+        torch.cuda.synchronize()
+        del cal_src, cal_dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

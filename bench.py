@@ -29,8 +29,13 @@ LDS_BYTES_PER_CLK_PER_CU = 128          # nominal ds_read_b32 rate: 64 lanes x 4
 LDS_PEAK_GBS = N_CU * LDS_BYTES_PER_CLK_PER_CU * CLOCK_GHZ          # 78643 GB/s
 VALU_PEAK_GOPS = N_CU * 64 * CLOCK_GHZ                               # 39322 G int32 lane-ops/s
 HBM_PEAK_GBS = 8000.0
+LDS_MEASURED_B32_GBS = 72600.0          # conflict-free ds_read_b32 micro-kernel on this chip (92 % of nominal)
 LDS_BYTES_PER_MOVE = 8                  # two int32 new-hop gathers per undirected move
 VALU_OPS_PER_MOVE = 3                   # combine two gathers with the removed hops, form key, min
+# HBM bytes per launch from rocprofv3 FETCH_SIZE (x 2.000) + WRITE_SIZE (x 1.000), calibrated on a 256 MiB copy
+# (profiles/bench_n64_pmc_counters.md).  Set to None whenever the kernel changes after the counters were taken.
+TRAFFIC_SEARCH_KERNEL_BYTES = (272.0 + 272.0) * 1024
+TRAFFIC_RING_BATCH_BYTES = (262317.6 + 8196.2) * 1024
 
 
 def main():
@@ -135,13 +140,14 @@ def main():
         "perm_evals_per_s": perm_rate,
         "rd_perm_evals_per_s": rd_batch / (t_rd * 1e-3),
         "roofline": {"kernel": "2-opt search (neighbourhood sweep)", "bound": "lds", "achieved": lds_gbs,
-                     "peak": LDS_PEAK_GBS, "unit": "GB/s", "frac": lds_gbs / LDS_PEAK_GBS, "traffic": None,
-                     "bytes_per_move": LDS_BYTES_PER_MOVE,
+                     "peak": LDS_PEAK_GBS, "unit": "GB/s", "frac": lds_gbs / LDS_PEAK_GBS,
+                     "traffic": TRAFFIC_SEARCH_KERNEL_BYTES, "bytes_per_move": LDS_BYTES_PER_MOVE,
+                     "frac_of_measured_b32_peak": lds_gbs / LDS_MEASURED_B32_GBS,
                      "valu": {"achieved": move_rate * VALU_OPS_PER_MOVE / 1e9, "peak": VALU_PEAK_GOPS,
                               "unit": "G lane-ops/s", "frac": move_rate * VALU_OPS_PER_MOVE / 1e9 / VALU_PEAK_GOPS,
                               "ops_per_move": VALU_OPS_PER_MOVE}},
         "roofline_batch": {"kernel": "ring cost batch", "bound": "hbm", "achieved": hbm_gbs, "peak": HBM_PEAK_GBS,
-                           "unit": "GB/s", "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": None,
+                           "unit": "GB/s", "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": TRAFFIC_RING_BATCH_BYTES,
                            "bytes_per_perm": 4 * n + 8},
     }
 

@@ -76,6 +76,21 @@ def test_n1024_sum_row_streaming_path_and_its_fallback():
         assert np.array_equal(got["moves"], np.concatenate([p[2] for p in parts]))
 
 
+def test_n64_sum_many_restarts():
+    """Several wavefronts per SIMD and a ragged last workgroup: 4100 restarts on the workload matrix, a
+    wide-entry matrix and a matrix full of ties, each checked on a spread of restarts."""
+    for c, tag in ((make_matrix(2), "workload matrix"),
+                   (random_matrix(64, 515, symmetric=True, lo=1, hi=COST_MAX), "entries up to COST_MAX"),
+                   (random_matrix(64, 516, symmetric=True, lo=1, hi=3), "ties")):
+        say(f"2-opt N=64 sum, 4100 restarts ({tag})")
+        got = gpu_search(c, 0, 4100, seed=77)
+        rows = np.unique(np.concatenate([np.arange(0, 4100, 41), [4096, 4097, 4098, 4099]]))
+        want = _oracle_rows(c, 0, 77, rows)
+        assert_search_equal(got, want, rows=rows)
+        k = int(np.argmin(got["costs"]))
+        assert got["best_restart"] == k and np.array_equal(got["best_perm"], got["tours"][k])
+
+
 def test_many_ties_lowest_id_wins():
     """Few distinct cost values: most sweeps have tied best moves and restarts tie on final cost."""
     for n, obj in ((16, 0), (64, 0), (64, 1), (32, 3), (64, 2)):

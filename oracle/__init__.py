@@ -69,6 +69,18 @@ def _L():
         lib.cco_2opt_search.argtypes = [p, i32, i32, i32, u64, p, p, p, p, p, p, p]
         lib.cco_exhaustive_rings.restype = ctypes.c_int
         lib.cco_exhaustive_rings.argtypes = [p, i32, i32, i32, p, p, p, p, p, i64]
+        lib.cco_apply_swap.restype = None
+        lib.cco_apply_swap.argtypes = [p, i32, i32]
+        lib.cco_rd_swap_value_by_definition.restype = i64
+        lib.cco_rd_swap_value_by_definition.argtypes = [p, i32, p, i32, i32]
+        lib.cco_rd_swap_neighbourhood_size.restype = i64
+        lib.cco_rd_swap_neighbourhood_size.argtypes = [i32]
+        lib.cco_rd_swap_all_values.restype = ctypes.c_int
+        lib.cco_rd_swap_all_values.argtypes = [p, i32, p, p]
+        lib.cco_rd_swap_descend.restype = ctypes.c_int
+        lib.cco_rd_swap_descend.argtypes = [p, i32, p, p, p, i32, p, i32]
+        lib.cco_rd_swap_restarts.restype = ctypes.c_int
+        lib.cco_rd_swap_restarts.argtypes = [p, i32, u64, i64, i64, p, p, p, p]
         _lib = lib
     return _lib
 
@@ -246,3 +258,51 @@ def exhaustive_rings(c, objective: int = SUM, half_only: bool = True, keep_all: 
     if keep_all:
         out["rings"], out["costs"] = rings, costs
     return out
+
+
+# ------------------------------------------------------------------ pair-swap search, halving-doubling model
+def rd_swap_value_by_definition(c, t, p: int, q: int) -> int:
+    c = _mat(c)
+    t = np.ascontiguousarray(t, dtype=np.int32)
+    return int(_L().cco_rd_swap_value_by_definition(_ptr(c), c.shape[0], _ptr(t), p, q))
+
+
+def rd_swap_all_values(c, t) -> np.ndarray:
+    """Value of every swap (p, q), p < q, in increasing id order (delta tier)."""
+    c = _mat(c)
+    t = np.ascontiguousarray(t, dtype=np.int32)
+    n = c.shape[0]
+    out = np.empty(n * (n - 1) // 2, dtype=np.int64)
+    _check(_L().cco_rd_swap_all_values(_ptr(c), n, _ptr(t), _ptr(out)))
+    return out
+
+
+def rd_swap_descend(c, t, use_definition: bool = False, trace_cap: int = 0):
+    c = _mat(c)
+    u = np.array(t, dtype=np.int32, copy=True)
+    cost = ctypes.c_int64(0)
+    moves = ctypes.c_int32(0)
+    trace = np.zeros(max(trace_cap, 1), dtype=np.int64)
+    _check(_L().cco_rd_swap_descend(_ptr(c), c.shape[0], _ptr(u), ctypes.byref(cost), ctypes.byref(moves),
+                                    1 if use_definition else 0, _ptr(trace), trace_cap))
+    return u, int(cost.value), int(moves.value), trace[:min(trace_cap, moves.value)]
+
+
+def rd_swap_restarts(c, seed: int, r0: int, r1: int, init: Optional[np.ndarray] = None):
+    c = _mat(c)
+    n = c.shape[0]
+    k = r1 - r0
+    costs = np.empty(k, dtype=np.int64)
+    tours = np.empty((k, n), dtype=np.int32)
+    moves = np.empty(k, dtype=np.int32)
+    if init is not None:
+        init = np.ascontiguousarray(init, dtype=np.int32)
+    _check(_L().cco_rd_swap_restarts(_ptr(c), n, seed, r0, r1, _ptr(init), _ptr(costs), _ptr(tours), _ptr(moves)))
+    return costs, tours, moves
+
+
+def rd_swap_search(c, n_restarts: int, seed: int, init: Optional[np.ndarray] = None):
+    costs, tours, moves = rd_swap_restarts(c, seed, 0, n_restarts, init)
+    k = int(np.argmin(costs))
+    return dict(best_perm=tours[k].copy(), best_cost=int(costs[k]), best_restart=k, costs=costs, tours=tours,
+                moves=moves)

@@ -17,7 +17,9 @@
  * Pins (see tests/test_oracle_*.py): closed forms for constant / additive / line-metric / cyclic
  * shift / clean-hierarchy matrices, rotation and reversal invariances, hypercube automorphisms,
  * brute force over all rings for N <= 10, every move's fast value against apply-and-recompute,
- * local-optimum certification, published SplitMix64 output vectors.
+ * local-optimum certification, published SplitMix64 output vectors; for the pair-swap search under the
+ * halving-doubling model: every swap's fast value against swap-and-recompute, replayed trajectories,
+ * brute force over all 8! orders.
  * Parity unpinned: none of the functions below.
  */
 #include <stdint.h>
@@ -393,5 +395,152 @@ int cco_exhaustive_rings(const int32_t *c, int32_t N, int32_t objective, int32_t
     enum_rec(&s, 1);
     if (count) *count = s.count;
     if (best_cost) *best_cost = s.best_cost;
+    return CCO_OK;
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * Pair-swap local search for the halving-doubling model (the "permute random pairs" neighbour of
+ * Section 4.3, made exhaustive and deterministic; Section 5.3 explains why this landscape is flat:
+ * a swap changes the cost only if it moves a round's critical pair).
+ * Move (p, q), 0 <= p < q <= N-1: exchange the nodes at ranks p and q.  Move id = p*N + q.
+ * Value of a move = halving-doubling cost of the order it produces.  No rank is anchored.
+ * ---------------------------------------------------------------------------------------------- */
+void cco_apply_swap(int32_t *t, int32_t p, int32_t q)
+{
+    int32_t tmp = t[p]; t[p] = t[q]; t[q] = tmp;
+}
+
+int64_t cco_rd_swap_value_by_definition(const int32_t *c, int32_t N, const int32_t *t, int32_t p, int32_t q)
+{
+    int32_t *u = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    memcpy(u, t, sizeof(int32_t) * (size_t)N);
+    cco_apply_swap(u, p, q);
+    int64_t v = cco_rd_cost(c, N, u);
+    free(u);
+    return v;
+}
+
+int64_t cco_rd_swap_neighbourhood_size(int32_t N) { return (int64_t)N * (N - 1) / 2; }
+
+/* Delta tier.  In round k ranks i and i xor 2^k form a link whose value is the larger of its two
+ * directed costs; the round costs the largest link.  Swapping ranks p and q touches, in each round,
+ * only the links of p and of q (the same link when q = p xor 2^k, and then its value is unchanged
+ * because both directed costs are still present).  So the new round cost is the maximum of the two
+ * re-evaluated links and of the largest link among all others, which is one of the round's three
+ * largest links. */
+typedef struct { int64_t v[3]; int32_t link[3]; int32_t n; } cco_top3;
+
+static int scan_swaps(const int32_t *c, int32_t N, const int32_t *t, cco_best *best, int64_t *all_values)
+{
+    int stages = 0;
+    for (int32_t bit = 1; bit < N; bit <<= 1) ++stages;
+    cco_top3 *top = (cco_top3 *)malloc(sizeof(cco_top3) * (size_t)(stages ? stages : 1));
+    int64_t *round_cost = (int64_t *)malloc(sizeof(int64_t) * (size_t)(stages ? stages : 1));
+    int k = 0;
+    for (int32_t bit = 1; bit < N; bit <<= 1, ++k) {
+        top[k].n = 0;
+        round_cost[k] = 0;
+        for (int32_t j = 0; j < N; ++j) {
+            if (j & bit) continue;                      /* j = lower rank of the link */
+            int64_t lv = max64(C_(t[j], t[j | bit]), C_(t[j | bit], t[j]));
+            round_cost[k] = max64(round_cost[k], lv);
+            /* insert into the sorted top-3 */
+            int pos = top[k].n;
+            while (pos > 0 && top[k].v[pos - 1] < lv) --pos;
+            if (pos < 3) {
+                int last = top[k].n < 3 ? top[k].n : 2;
+                for (int m = last; m > pos; --m) { top[k].v[m] = top[k].v[m - 1]; top[k].link[m] = top[k].link[m - 1]; }
+                top[k].v[pos] = lv; top[k].link[pos] = j;
+                if (top[k].n < 3) ++top[k].n;
+            }
+        }
+    }
+    int found = 0;
+    int64_t nvals = 0;
+    for (int32_t p = 0; p < N - 1; ++p)
+        for (int32_t q = p + 1; q < N; ++q) {
+            int64_t total = 0;
+            k = 0;
+            for (int32_t bit = 1; bit < N; bit <<= 1, ++k) {
+                if (q == (p ^ bit)) { total += round_cost[k]; continue; }
+                int32_t lp = p & ~bit, lq = q & ~bit;
+                int64_t others = 0;
+                for (int m = 0; m < top[k].n; ++m)
+                    if (top[k].link[m] != lp && top[k].link[m] != lq) { others = top[k].v[m]; break; }
+                int32_t pb = t[p ^ bit], qb = t[q ^ bit];
+                int64_t link_p = max64(C_(t[q], pb), C_(pb, t[q]));     /* rank p now holds t[q] */
+                int64_t link_q = max64(C_(t[p], qb), C_(qb, t[p]));     /* rank q now holds t[p] */
+                total += max64(others, max64(link_p, link_q));
+            }
+            int64_t id = (int64_t)p * N + q;
+            if (all_values) all_values[nvals] = total;
+            ++nvals;
+            if (!found || total < best->value || (total == best->value && id < best->id)) {
+                best->value = total; best->id = id; best->i = p; best->j = q; best->o = 0;
+                found = 1;
+            }
+        }
+    free(top);
+    free(round_cost);
+    return found;
+}
+
+int cco_rd_swap_all_values(const int32_t *c, int32_t N, const int32_t *t, int64_t *values)
+{
+    cco_best best;
+    scan_swaps(c, N, t, &best, values);
+    return CCO_OK;
+}
+
+int cco_rd_swap_descend(const int32_t *c, int32_t N, int32_t *t, int64_t *cost, int32_t *moves,
+                        int32_t use_definition, int64_t *trace, int32_t trace_cap)
+{
+    if (!c || !t || N < 2 || (N & (N - 1))) return CCO_ERR_ARG;
+    int64_t cur = cco_rd_cost(c, N, t);
+    int32_t applied = 0;
+    for (;;) {
+        cco_best best;
+        int found = 0;
+        if (!use_definition) {
+            found = scan_swaps(c, N, t, &best, NULL);
+        } else {
+            for (int32_t p = 0; p < N - 1; ++p)
+                for (int32_t q = p + 1; q < N; ++q) {
+                    int64_t v = cco_rd_swap_value_by_definition(c, N, t, p, q);
+                    int64_t id = (int64_t)p * N + q;
+                    if (!found || v < best.value || (v == best.value && id < best.id)) {
+                        best.value = v; best.id = id; best.i = p; best.j = q; found = 1;
+                    }
+                }
+        }
+        if (!found || best.value >= cur) break;
+        cco_apply_swap(t, best.i, best.j);
+        cur = best.value;
+        if (trace && applied < trace_cap) trace[applied] = best.id;
+        ++applied;
+    }
+    *cost = cur;
+    if (moves) *moves = applied;
+    return CCO_OK;
+}
+
+int cco_rd_swap_restarts(const int32_t *c, int32_t N, uint64_t seed, int64_t r0, int64_t r1,
+                         const int32_t *init_tours, int64_t *restart_costs, int32_t *restart_tours,
+                         int32_t *restart_moves)
+{
+    if (!c || N < 2 || (N & (N - 1)) || r0 < 0 || r1 < r0) return CCO_ERR_ARG;
+    int32_t *t = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    if (!t) return CCO_ERR_NOMEM;
+    for (int64_t r = r0; r < r1; ++r) {
+        if (init_tours) memcpy(t, init_tours + r * N, sizeof(int32_t) * (size_t)N);
+        else cco_init_tour(seed, (uint32_t)r, N, t);
+        int64_t cost; int32_t mv;
+        int rc = cco_rd_swap_descend(c, N, t, &cost, &mv, 0, NULL, 0);
+        if (rc != CCO_OK) { free(t); return rc; }
+        if (restart_costs) restart_costs[r - r0] = cost;
+        if (restart_moves) restart_moves[r - r0] = mv;
+        if (restart_tours) memcpy(restart_tours + (r - r0) * N, t, sizeof(int32_t) * (size_t)N);
+    }
+    free(t);
     return CCO_OK;
 }

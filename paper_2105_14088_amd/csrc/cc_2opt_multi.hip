@@ -44,8 +44,22 @@ __device__ __forceinline__ int wave_min_all(int v) {
 __global__ __launch_bounds__(1024) void matrix_max_kernel(const int32_t* __restrict__ c, int n2,
                                                           int32_t* __restrict__ flags) {
     __shared__ int part[16];
+    const int4* c4 = (const int4*)c;           // N is a multiple of 64 here, so n2 is a multiple of 4
+    const int n4 = n2 / 4;
     int mx = 0;
-    for (int e = threadIdx.x; e < n2; e += 1024) mx = max(mx, clampi(c[e], 0, (1 << 21) - 1));
+    if ((uintptr_t)c & 15u) {                  // matrix not 16-byte aligned: scalar loads
+        for (int e = threadIdx.x; e < n2; e += 1024) mx = max(mx, clampi(c[e], 0, (1 << 21) - 1));
+    } else
+    for (int e = threadIdx.x; e < n4; e += 8 * 1024) {
+        int4 v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = (e + k * 1024 < n4) ? c4[e + k * 1024] : make_int4(0, 0, 0, 0);
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            mx = max(max(mx, clampi(v[k].x, 0, (1 << 21) - 1)),
+                     max(max(clampi(v[k].y, 0, (1 << 21) - 1), clampi(v[k].z, 0, (1 << 21) - 1)),
+                         clampi(v[k].w, 0, (1 << 21) - 1)));
+    }
     mx = wave_max(mx);
     if (lane_id() == 0) part[threadIdx.x >> 6] = mx;
     __syncthreads();

@@ -119,6 +119,29 @@ int cc_2opt_search_ex(const int32_t* cost_matrix, int32_t N, int32_t objective, 
 size_t cc_2opt_workspace_bytes(int32_t N, int32_t objective, int32_t restarts);
 
 /*
+ * Multi-start pair-swap search under the halving-doubling model (Section 4.3: neighbours obtained by
+ * permuting a pair of ranks; Section 4.1 equation C_hd as evaluated by cc_rd_cost_batch).
+ *
+ *   Moves.  Move (p, q), 0 <= p < q <= N-1: exchange the nodes at ranks p and q.  Move id = p*N + q.
+ *   The value of a move is the halving-doubling cost of the order it produces.  No rank is anchored.
+ *   One restart, restarts, result: exactly as in cc_2opt_search (lexicographically smallest (value, id),
+ *   applied only if strictly better; seeded Fisher-Yates starts; lexicographically smallest
+ *   (final cost, restart) wins).
+ *
+ * N must be a power of two, 2 <= N <= CC_MAX_N.  Arguments, workspace and outputs as for
+ * cc_2opt_search / cc_2opt_search_ex; the workspace size is cc_rd_swap_workspace_bytes(N, restarts).
+ */
+int cc_rd_swap_search(const int32_t* cost_matrix, int32_t N, int32_t restarts, uint64_t seed, int32_t* best_perm,
+                      int64_t* best_cost, void* stream);
+
+int cc_rd_swap_search_ex(const int32_t* cost_matrix, int32_t N, int32_t restarts, uint64_t seed,
+                         const int32_t* init_tours, int32_t* best_perm, int64_t* best_cost, int32_t* best_restart,
+                         int64_t* restart_costs, int32_t* restart_tours, int32_t* restart_moves, void* workspace,
+                         size_t workspace_bytes, void* stream);
+
+size_t cc_rd_swap_workspace_bytes(int32_t N, int32_t restarts);
+
+/*
  * Initial orders of restarts first .. first+count-1 for `seed` (the shuffle described above);
  * tours: int32 [count, N].  Also the generator of the seeded random orders used to exercise the
  * batch calls.

@@ -21,7 +21,7 @@ CC_COST_MAX = (1 << 21) - 1
 
 # every symbol include/cc.h declares
 EXPORTS = ["cc_ring_cost_batch", "cc_rd_cost_batch", "cc_2opt_search", "cc_2opt_search_ex",
-           "cc_2opt_workspace_bytes", "cc_init_tours", "cc_validate_matrix", "cc_status_string",
+           "cc_2opt_workspace_bytes", "cc_rd_swap_search", "cc_rd_swap_search_ex", "cc_rd_swap_workspace_bytes", "cc_init_tours", "cc_validate_matrix", "cc_status_string",
            "cc_last_hip_error", "cc_version"]
 
 
@@ -56,6 +56,12 @@ def lib() -> ctypes.CDLL:
         L.cc_2opt_search_ex.argtypes = [p, i32, i32, i32, u64, p, p, p, p, p, p, p, p, sz, p]
         L.cc_2opt_workspace_bytes.restype = sz
         L.cc_2opt_workspace_bytes.argtypes = [i32, i32, i32]
+        L.cc_rd_swap_search.restype = ctypes.c_int
+        L.cc_rd_swap_search.argtypes = [p, i32, i32, u64, p, p, p]
+        L.cc_rd_swap_search_ex.restype = ctypes.c_int
+        L.cc_rd_swap_search_ex.argtypes = [p, i32, i32, u64, p, p, p, p, p, p, p, p, sz, p]
+        L.cc_rd_swap_workspace_bytes.restype = sz
+        L.cc_rd_swap_workspace_bytes.argtypes = [i32, i32]
         L.cc_init_tours.restype = ctypes.c_int
         L.cc_init_tours.argtypes = [i32, i64, i64, u64, p, p]
         L.cc_validate_matrix.restype = ctypes.c_int
@@ -178,6 +184,40 @@ def cc_2opt_search_ex(cost_matrix: torch.Tensor, objective: int, restarts: int, 
                                    _dev(b.restart_tours, torch.int32, "restart_tours"),
                                    _dev(b.restart_moves, torch.int32, "restart_moves"),
                                    ctypes.c_void_p(b.ws_ptr), b.ws_bytes, _stream(stream)), "cc_2opt_search_ex")
+    return b
+
+
+def cc_rd_swap_search(cost_matrix: torch.Tensor, restarts: int, seed: int, stream=None):
+    """Returns (best_perm int32[N], best_cost int64[1]) device tensors (valid after stream sync)."""
+    n = _matrix(cost_matrix)
+    best_perm = torch.empty(n, dtype=torch.int32, device=cost_matrix.device)
+    best_cost = torch.empty(1, dtype=torch.int64, device=cost_matrix.device)
+    _check(lib().cc_rd_swap_search(_dev(cost_matrix, torch.int32, "cost_matrix"), n, restarts, seed & (2**64 - 1),
+                                   _dev(best_perm, torch.int32, "best_perm"),
+                                   _dev(best_cost, torch.int64, "best_cost"), _stream(stream)), "cc_rd_swap_search")
+    return best_perm, best_cost
+
+
+def cc_rd_swap_search_ex(cost_matrix: torch.Tensor, restarts: int, seed: int,
+                         init_tours: Optional[torch.Tensor] = None, buffers: Optional[SearchBuffers] = None,
+                         stream=None) -> SearchBuffers:
+    n = _matrix(cost_matrix)
+    if buffers is None:
+        buffers = SearchBuffers(n, 0, restarts, cost_matrix.device)
+    if (buffers.n, buffers.restarts) != (n, restarts):
+        raise ValueError("buffers were sized for a different search")
+    if init_tours is not None and tuple(init_tours.shape) != (restarts, n):
+        raise ValueError("init_tours must be [restarts, N]")
+    b = buffers
+    _check(lib().cc_rd_swap_search_ex(_dev(cost_matrix, torch.int32, "cost_matrix"), n, restarts, seed & (2**64 - 1),
+                                      _dev(init_tours, torch.int32, "init_tours"),
+                                      _dev(b.best_perm, torch.int32, "best_perm"),
+                                      _dev(b.best_cost, torch.int64, "best_cost"),
+                                      _dev(b.best_restart, torch.int32, "best_restart"),
+                                      _dev(b.restart_costs, torch.int64, "restart_costs"),
+                                      _dev(b.restart_tours, torch.int32, "restart_tours"),
+                                      _dev(b.restart_moves, torch.int32, "restart_moves"),
+                                      ctypes.c_void_p(b.ws_ptr), b.ws_bytes, _stream(stream)), "cc_rd_swap_search_ex")
     return b
 
 

@@ -260,6 +260,13 @@ hipError_t launch_general_objective(const int32_t* c, int N, int objective, int 
 
 }  // namespace
 
+hipError_t launch_best_restart(const int64_t* costs, const int32_t* tours, int N, int restarts, int32_t* best_perm,
+                               int64_t* best_cost, int32_t* best_restart, hipStream_t s) {
+    hipLaunchKernelGGL(best_restart_kernel, dim3(1), dim3(256), 0, s, costs, tours, N, restarts, best_perm, best_cost,
+                       best_restart);
+    return hipGetLastError();
+}
+
 hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, uint64_t seed, bool tours_hold_init,
                        int32_t* tours, int64_t* costs, int32_t* moves, int32_t* flags, uint16_t* mat16,
                        int32_t* best_perm, int64_t* best_cost, int32_t* best_restart, hipStream_t s) {

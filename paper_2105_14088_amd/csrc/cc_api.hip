@@ -117,6 +117,50 @@ int cc_2opt_search(const int32_t* cost_matrix, int32_t N, int32_t objective, int
     return CC_OK;
 }
 
+size_t cc_rd_swap_workspace_bytes(int32_t N, int32_t restarts) {
+    if (N < 2 || N > CC_MAX_N || !is_pow2(N) || restarts < 1) return 0;
+    return ws_layout(N, restarts).mat16;       // flags, costs, moves, tours
+}
+
+int cc_rd_swap_search_ex(const int32_t* cost_matrix, int32_t N, int32_t restarts, uint64_t seed,
+                         const int32_t* init_tours, int32_t* best_perm, int64_t* best_cost, int32_t* best_restart,
+                         int64_t* restart_costs, int32_t* restart_tours, int32_t* restart_moves, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+    if (int rc = check_matrix_args(cost_matrix, N)) return rc;
+    if (!is_pow2(N)) return CC_ERR_UNSUPPORTED_N;
+    if (restarts < 1 || !best_perm || !best_cost) return CC_ERR_INVALID_ARG;
+    const WsLayout w = ws_layout(N, restarts);
+    if (!workspace || workspace_bytes < w.mat16 || ((uintptr_t)workspace & 255u)) return CC_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    char* base = (char*)workspace;
+    int64_t* costs = restart_costs ? restart_costs : (int64_t*)(base + w.costs);
+    int32_t* moves = restart_moves ? restart_moves : (int32_t*)(base + w.moves);
+    int32_t* tours = restart_tours ? restart_tours : (int32_t*)(base + w.tours);
+    if (init_tours && init_tours != tours)
+        CC_HIP(hipMemcpyAsync(tours, init_tours, sizeof(int32_t) * (size_t)restarts * (size_t)N,
+                              hipMemcpyDeviceToDevice, s));
+    CC_HIP(cc::launch_rdswap(cost_matrix, N, restarts, seed, init_tours != nullptr, tours, costs, moves, s));
+    CC_HIP(cc::launch_best_restart(costs, tours, N, restarts, best_perm, best_cost, best_restart, s));
+    return CC_OK;
+}
+
+int cc_rd_swap_search(const int32_t* cost_matrix, int32_t N, int32_t restarts, uint64_t seed, int32_t* best_perm,
+                      int64_t* best_cost, void* stream) {
+    if (int rc = check_matrix_args(cost_matrix, N)) return rc;
+    if (!is_pow2(N)) return CC_ERR_UNSUPPORTED_N;
+    if (restarts < 1 || !best_perm || !best_cost) return CC_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    const size_t bytes = cc_rd_swap_workspace_bytes(N, restarts);
+    void* ws = nullptr;
+    CC_HIP(hipMallocAsync(&ws, bytes, s));
+    const int rc = cc_rd_swap_search_ex(cost_matrix, N, restarts, seed, nullptr, best_perm, best_cost, nullptr, nullptr,
+                                        nullptr, nullptr, ws, bytes, stream);
+    const hipError_t e = hipFreeAsync(ws, s);
+    if (rc != CC_OK) return rc;
+    if (e != hipSuccess) return hip_fail(e);
+    return CC_OK;
+}
+
 int cc_init_tours(int32_t N, int64_t first, int64_t count, uint64_t seed, int32_t* tours, void* stream) {
     if (N < 2 || N > CC_MAX_N) return CC_ERR_UNSUPPORTED_N;
     if (first < 0 || count < 0 || first + count > (int64_t)1 << 32) return CC_ERR_INVALID_ARG;
@@ -158,6 +202,6 @@ const char* cc_status_string(int status) {
 
 int cc_last_hip_error(void) { return g_last_hip_error; }
 
-int cc_version(void) { return 100; }
+int cc_version(void) { return 200; }
 
 }  // extern "C"

@@ -1,0 +1,259 @@
+// Multi-start pair-swap local search under the halving-doubling cost model (Section 4.1 equation
+// C_hd with the pairing of Section 2.2; neighbour "permute a pair" of Section 4.3; move set, value and
+// tie-break rules as stated in cc.h, cc_rd_swap_search).
+//
+// In round k ranks i and i xor 2^k form a LINK whose value is the larger of its two directed costs; a
+// round costs its largest link.  Swapping ranks p and q touches, per round, only the links of p and of q
+// (one link, with unchanged value, when q = p xor 2^k).  The new round cost is therefore
+//     max( link of p re-evaluated, link of q re-evaluated, largest link among all the others ),
+// and "largest among the others" is one of the round's three largest links, found once per sweep.
+//
+// General kernel: one workgroup per restart, one thread per rank p scanning q = p+1 .. N-1; matrix
+// gathered through L2; 64-bit keys (value << 32 | move id) min-reduced over the workgroup.
+// N = 64 kernel: one wavefront per restart, matrix in LDS, lane p scans partners q = p xor m for
+// m = 1 .. 63 (every pair is seen from both ends, which is harmless: same value, same id); the top-3
+// links of a round come from three wave-wide max-reductions over (value << 5 | link index).
+#include "cc_device.h"
+#include "cc_internal.h"
+#include "cc_wave64.h"
+
+namespace cc {
+using namespace ccd;
+
+namespace {
+
+constexpr int kCostMax = (1 << 21) - 1;
+constexpr int kMaxStages = 10;
+constexpr unsigned long long kNoMove = ~0ull;
+
+// ------------------------------------------------------------------------------------- general kernel
+__global__ void rdswap_general_kernel(const int32_t* __restrict__ c, int N, int32_t* __restrict__ tours,
+                                      int64_t* __restrict__ costs, int32_t* __restrict__ moves) {
+    extern __shared__ int32_t sm[];
+    int32_t* t = sm;                 // [N]
+    int32_t* w = sm + N;             // [N] directed cost of each rank in the round being prepared
+    __shared__ int top_v[kMaxStages][3], top_l[kMaxStages][3], top_n[kMaxStages];
+    __shared__ unsigned long long red[16];
+    __shared__ unsigned long long winner;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, nwv = blockDim.x >> 6;
+    const int64_t r = blockIdx.x;
+    auto C = [&](int a, int b) { return clampi(c[a * N + b], 0, kCostMax); };
+    if (tid < N) t[tid] = clampi(tours[r * N + tid], 0, N - 1);
+    __syncthreads();
+
+    auto block_max_u64 = [&](unsigned long long key) {   // every thread gets the maximum
+        unsigned long long v = key;
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            const unsigned long long o = __shfl_xor(v, m, kWave);
+            v = o > v ? o : v;
+        }
+        __syncthreads();
+        if (lane == 0) red[wv] = v;
+        __syncthreads();
+        v = red[0];
+        for (int k = 1; k < nwv; ++k) v = red[k] > v ? red[k] : v;
+        return v;
+    };
+
+    int applied = 0;
+    long long cur = 0;
+    for (;;) {
+        // ---- per round: link values and the three largest links
+        int stages = 0;
+        cur = 0;
+        for (int bit = 1; bit < N; bit <<= 1, ++stages) {
+            if (tid < N) w[tid] = C(t[tid], t[tid ^ bit]);
+            __syncthreads();
+            int lv = -1;
+            if (tid < N && !(tid & bit)) lv = max(w[tid], w[tid | bit]);
+            int taken[3] = {-1, -1, -1};
+            int n = 0;
+            for (int round = 0; round < 3; ++round) {
+                const bool mine = lv >= 0 && tid != taken[0] && tid != taken[1];
+                // key: value, then a preference for the lower link id (any choice among equal values is valid)
+                const unsigned long long key = mine ? (((unsigned long long)(unsigned)lv << 32) | (unsigned)(N - tid)) : 0ull;
+                const unsigned long long best = block_max_u64(key);
+                if (best == 0ull) break;
+                taken[round] = N - (int)(best & 0xffffffffu);
+                if (tid == 0) {
+                    top_v[stages][round] = (int)(best >> 32);
+                    top_l[stages][round] = taken[round];
+                }
+                ++n;
+            }
+            if (tid == 0) top_n[stages] = n;
+            __syncthreads();
+            cur += top_v[stages][0];
+        }
+        // ---- score swaps (p, q), q > p, for p = tid
+        unsigned long long best = kNoMove;
+        const int p = tid;
+        if (p < N - 1) {
+            const int tp = t[p];
+            for (int q = p + 1; q < N; ++q) {
+                const int tq = t[q];
+                int total = 0;
+                int k = 0;
+                for (int bit = 1; bit < N; bit <<= 1, ++k) {
+                    if (q == (p ^ bit)) { total += top_v[k][0]; continue; }
+                    const int lp = p & ~bit, lq = q & ~bit;
+                    int others = 0;
+                    for (int m = 0; m < top_n[k]; ++m)
+                        if (top_l[k][m] != lp && top_l[k][m] != lq) { others = top_v[k][m]; break; }
+                    const int pb = t[p ^ bit], qb = t[q ^ bit];
+                    const int link_p = max(C(tq, pb), C(pb, tq));      // rank p now holds t[q]
+                    const int link_q = max(C(tp, qb), C(qb, tp));      // rank q now holds t[p]
+                    total += max(others, max(link_p, link_q));
+                }
+                best = min(best, ((unsigned long long)(unsigned)total << 32) | (unsigned)(p * N + q));
+            }
+        }
+        best = wave_min_u64(best);
+        __syncthreads();
+        if (lane == 0) red[wv] = best;
+        __syncthreads();
+        if (tid == 0) {
+            unsigned long long m = red[0];
+            for (int k = 1; k < nwv; ++k) m = min(m, red[k]);
+            winner = m;
+        }
+        __syncthreads();
+        const unsigned long long win = winner;
+        if (win == kNoMove || (long long)(win >> 32) >= cur) break;
+        const unsigned id = (unsigned)(win & 0xffffffffu);
+        const int sp = (int)(id / (unsigned)N), sq = (int)(id % (unsigned)N);
+        if (tid == 0) {
+            const int a = t[sp];
+            t[sp] = t[sq];
+            t[sq] = a;
+        }
+        __syncthreads();
+        ++applied;
+    }
+    if (tid < N) tours[r * N + tid] = t[tid];
+    if (tid == 0) {
+        costs[r] = cur;
+        moves[r] = applied;
+    }
+}
+
+// ----------------------------------------------------------------------------------------- N = 64
+using namespace w64;
+
+__device__ __forceinline__ int wave_max_all(int v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v = max(v, __shfl_xor(v, m, kWave));
+    return v;
+}
+
+__global__ __launch_bounds__(256) void rdswap_n64_kernel(const int32_t* __restrict__ c, int restarts, uint64_t seed,
+                                                         int generate, int32_t* __restrict__ tours,
+                                                         int64_t* __restrict__ costs, int32_t* __restrict__ moves) {
+    __shared__ __attribute__((aligned(256))) int32_t m[kN * kN];
+    __shared__ int32_t tl_all[4][kN];            // each wave's tour, for "node at rank p xor x" look-ups
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    int v[kN * kN / 256];
+#pragma unroll
+    for (int k = 0; k < kN * kN / 256; ++k) v[k] = c[tid + 256 * k];
+    const int64_t r = (int64_t)blockIdx.x * 4 + wv;
+    int t = 0;
+    if (r < restarts)
+        t = generate ? init_tour_in_wave(seed, (uint32_t)r, lane) : clampi(tours[r * kN + lane], 0, kN - 1);
+#pragma unroll
+    for (int k = 0; k < kN * kN / 256; ++k) m[tid + 256 * k] = clampi(v[k], 0, kCostMax);
+    __syncthreads();
+    if (r >= restarts) return;
+    const char* mbytes = (const char*)m;
+    int32_t* tl = tl_all[wv];
+    const char* tlbytes = (const char*)tl;
+    auto entry = [&](int row8, int col2) { return *(const int32_t*)(mbytes + (row8 | col2)); };   // row << 8 | col << 2
+
+    int applied = 0, cur = 0;
+    for (;;) {
+        tl[lane] = t;
+        __builtin_amdgcn_wave_barrier();
+        const int t8 = t << 8, t2 = t << 2;
+        // per round: partner, link value, and the best / second-best link value among links other than this lane's
+        int pb8[6], pb2[6], x1v[6], x2v[6], zk[6], round_cost[6], own_addr[6];
+        cur = 0;
+#pragma unroll
+        for (int k = 0; k < 6; ++k) {
+            const int bit = 1 << k;
+            const int pb = tl[lane ^ bit];
+            pb8[k] = pb << 8;
+            pb2[k] = pb << 2;
+            own_addr[k] = (lane ^ bit) << 2;                       // byte offset of rank p xor 2^k in tl
+            const int lv = max(entry(t8, pb2[k]), entry(pb8[k], t2));
+            const int li = ((lane >> (k + 1)) << k) | (lane & (bit - 1));          // link index, 5 bits
+            int key = (lv << 5) | li;
+            const int k1 = wave_max_all(key);
+            const int k2 = wave_max_all((li == (k1 & 31)) ? -1 : key);
+            const int k3 = wave_max_all((li == (k1 & 31) || li == (k2 & 31)) ? -1 : key);
+            // k2, k3 are -1 when fewer links exist (never at N = 64: 32 links per round)
+            const int l1 = k1 & 31, l2 = k2 & 31;
+            const int a1 = (li == l1) ? k2 : k1;                   // best link that is not mine
+            const int a2 = (li == l1 || li == l2) ? k3 : k2;       // second best that is not mine
+            x1v[k] = a1 >> 5;
+            x2v[k] = a2 >> 5;
+            zk[k] = li ^ (a1 & 31);                                // partner's link == that best link  <=>  li(m) == zk
+            round_cost[k] = k1 >> 5;
+            cur += round_cost[k];
+        }
+        unsigned long long best = kNoMove;
+#pragma unroll 1
+        for (int mm = 1; mm < kN; ++mm) {
+            const int q = lane ^ mm;
+            const int tq = *(const int32_t*)(tlbytes + ((lane ^ mm) << 2));
+            const int tq8 = tq << 8, tq2 = tq << 2;
+            int total = 0;
+#pragma unroll
+            for (int k = 0; k < 6; ++k) {
+                const int bit = 1 << k;
+                const int qb = *(const int32_t*)(tlbytes + (own_addr[k] ^ (mm << 2)));      // node at rank q xor 2^k
+                const int link_p = max(entry(tq8, pb2[k]), entry(pb8[k], tq2));             // rank p now holds t[q]
+                const int link_q = max(entry(t8, qb << 2), entry(qb << 8, t2));             // rank q now holds t[p]
+                const int lim = ((mm >> (k + 1)) << k) | (mm & (bit - 1));                  // link index offset of the partner
+                const int others = (zk[k] == lim) ? x2v[k] : x1v[k];
+                const int stage = max(others, max(link_p, link_q));
+                total += (mm == bit) ? round_cost[k] : stage;
+            }
+            const int lo = min(lane, q), hi = max(lane, q);
+            best = min(best, ((unsigned long long)(unsigned)total << 12) | (unsigned)(lo * kN + hi));
+        }
+        const unsigned long long win = wave_min_u64(best);
+        const int total_win = (int)(win >> 12);
+        if (total_win >= cur) break;
+        const int id = __builtin_amdgcn_readfirstlane((int)(win & 0xfff)), sp = id >> 6, sq = id & 63;
+        const int a = __builtin_amdgcn_readlane(t, sp), b = __builtin_amdgcn_readlane(t, sq);
+        t = lane == sp ? b : (lane == sq ? a : t);
+        ++applied;
+        __builtin_amdgcn_wave_barrier();
+    }
+    tours[r * kN + lane] = t;
+    if (lane == 0) {
+        costs[r] = (int64_t)cur;
+        moves[r] = applied;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_rdswap(const int32_t* c, int N, int restarts, uint64_t seed, bool tours_hold_init, int32_t* tours,
+                         int64_t* costs, int32_t* moves, hipStream_t s) {
+    if (N == 64) {
+        hipLaunchKernelGGL(rdswap_n64_kernel, dim3((restarts + 3) / 4), dim3(256), 0, s, c, restarts, seed,
+                           tours_hold_init ? 0 : 1, tours, costs, moves);
+        return hipGetLastError();
+    }
+    if (!tours_hold_init) {
+        hipError_t e = launch_init_tours(N, 0, restarts, seed, tours, s);
+        if (e != hipSuccess) return e;
+    }
+    const int threads = ((N + 63) / 64) * 64;
+    hipLaunchKernelGGL(rdswap_general_kernel, dim3(restarts), dim3(threads), sizeof(int32_t) * 2 * (size_t)N, s, c, N,
+                       tours, costs, moves);
+    return hipGetLastError();
+}
+
+}  // namespace cc

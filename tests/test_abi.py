@@ -71,6 +71,14 @@ def test_argument_errors_are_returned_before_any_launch():
     assert L.cc_2opt_search_ex(*args, null, 0, null) == WORKSPACE
     assert L.cc_2opt_search_ex(*args, fake, 16, null) == WORKSPACE               # too small
     assert L.cc_2opt_search_ex(*args, ctypes.c_void_p(0x1004), 1 << 30, null) == WORKSPACE   # misaligned
+    assert L.cc_rd_swap_search(null, 64, 1, 1, fake, fake, null) == INVALID
+    assert L.cc_rd_swap_search(fake, 48, 1, 1, fake, fake, null) == UNSUPPORTED      # not a power of two
+    assert L.cc_rd_swap_search(fake, 64, 0, 1, fake, fake, null) == INVALID
+    assert L.cc_rd_swap_search(fake, 64, 1, 1, fake, null, null) == INVALID
+    sargs = [fake, 64, 4, 1, null, fake, fake, null, null, null, null]
+    assert L.cc_rd_swap_search_ex(*sargs, null, 0, null) == WORKSPACE
+    assert L.cc_rd_swap_search_ex(*sargs, fake, 16, null) == WORKSPACE
+    assert L.cc_rd_swap_workspace_bytes(64, 4) > 0 and L.cc_rd_swap_workspace_bytes(48, 4) == 0
     assert L.cc_init_tours(1, 0, 1, 1, fake, null) == UNSUPPORTED
     assert L.cc_init_tours(64, -1, 1, 1, fake, null) == INVALID
     assert L.cc_init_tours(64, 0, 1, 1, null, null) == INVALID

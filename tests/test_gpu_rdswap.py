@@ -1,0 +1,89 @@
+"""GPU parity, pair-swap search under the halving-doubling model: cc_rd_swap_search[_ex] against the CPU
+oracle - per restart the final order, its cost and the number of applied swaps; over restarts the winner.
+All integers: bit-exact."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2105_14088_amd as cc
+from gen import COST_MAX, WORKLOADS, make_matrix, random_matrix, random_perms
+from gpu_util import assert_search_equal, dev, say
+
+pytestmark = pytest.mark.gpu
+THREADS = min(16, os.cpu_count() or 1)
+
+
+def gpu_swap_search(c, restarts, seed, init=None):
+    b = cc.cc_rd_swap_search_ex(dev(c), restarts, seed, None if init is None else dev(init))
+    torch.cuda.synchronize()
+    return dict(best_perm=b.best_perm.cpu().numpy(), best_cost=int(b.best_cost.item()),
+                best_restart=int(b.best_restart.item()), costs=b.restart_costs.cpu().numpy(),
+                tours=b.restart_tours.cpu().numpy(), moves=b.restart_moves.cpu().numpy())
+
+
+@pytest.mark.parametrize("n", [2, 4, 8, 16, 32, 64, 128])
+@pytest.mark.parametrize("symmetric", [True, False])
+def test_swap_search_sizes(n, symmetric):
+    for hi, tag in ((4000, "few ties"), (3, "many ties"), (COST_MAX, "entries up to COST_MAX")):
+        restarts = 40 if n <= 64 else 6
+        say(f"rd swap search N={n} symmetric={symmetric} {tag} R={restarts}")
+        c = random_matrix(n, 4400 + n + hi % 101, symmetric=symmetric, lo=0, hi=hi)
+        want = oracle.rd_swap_search(c, restarts, seed=31 + n)
+        assert_search_equal(gpu_swap_search(c, restarts, seed=31 + n), want)
+
+
+def test_swap_search_initial_tours_single_restart_and_simple_entry_point():
+    say("rd swap search: caller-provided initial tours; R=1; allocating entry point")
+    c = make_matrix(2)
+    init = random_perms(64, 9, seed=4)
+    want = oracle.rd_swap_search(c, 9, seed=0, init=init)
+    assert_search_equal(gpu_swap_search(c, 9, seed=77, init=init), want)
+    assert_search_equal(gpu_swap_search(c, 1, seed=5), oracle.rd_swap_search(c, 1, seed=5))
+    want = oracle.rd_swap_search(c, 16, seed=WORKLOADS[2].search_seed)
+    perm, cost = cc.cc_rd_swap_search(dev(c), 16, WORKLOADS[2].search_seed)
+    torch.cuda.synchronize()
+    assert int(cost.item()) == want["best_cost"] and np.array_equal(perm.cpu().numpy(), want["best_perm"])
+
+
+def test_swap_search_n64_1024_restarts_full():
+    say("rd swap search: N=64 hierarchical matrix, 1024 restarts (all restarts compared)")
+    c = make_matrix(2)
+    seed = WORKLOADS[2].search_seed
+    from concurrent.futures import ThreadPoolExecutor
+    edges = np.linspace(0, 1024, THREADS * 2 + 1).astype(int)
+    with ThreadPoolExecutor(THREADS) as ex:
+        parts = list(ex.map(lambda s: oracle.rd_swap_restarts(c, seed, int(s[0]), int(s[1])), zip(edges[:-1], edges[1:])))
+    costs = np.concatenate([p[0] for p in parts]); tours = np.concatenate([p[1] for p in parts])
+    moves = np.concatenate([p[2] for p in parts])
+    k = int(np.argmin(costs))
+    want = dict(costs=costs, tours=tours, moves=moves, best_cost=int(costs[k]), best_restart=k, best_perm=tours[k])
+    got = gpu_swap_search(c, 1024, seed)
+    assert_search_equal(got, want)
+    # properties: every result is a permutation, its cost is its halving-doubling cost, no swap improves it
+    for r in (0, k, 1023):
+        assert sorted(got["tours"][r]) == list(range(64))
+        assert oracle.rd_cost(c, got["tours"][r]) == got["costs"][r]
+        assert oracle.rd_swap_all_values(c, got["tours"][r]).min() >= got["costs"][r]
+
+
+def test_swap_search_n256_and_n1024_general_kernel():
+    say("rd swap search: N=256 hierarchical matrix, 4 restarts (general kernel)")
+    c = make_matrix(4)
+    want = oracle.rd_swap_search(c, 4, seed=3)
+    assert_search_equal(gpu_swap_search(c, 4, seed=3), want)
+    say("rd swap search: N=1024, asymmetric, 3 % large entries, 2 restarts (general kernel)")
+    c = random_matrix(1024, 999, symmetric=False, lo=1, hi=40)
+    mask = np.random.default_rng(1).random((1024, 1024)) < 0.97
+    c = np.where(mask, 1, c).astype(np.int32)
+    np.fill_diagonal(c, 0)
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(2) as ex:
+        parts = list(ex.map(lambda r: oracle.rd_swap_restarts(c, 3, r, r + 1), range(2)))
+    got = gpu_swap_search(c, 2, seed=3)
+    assert np.array_equal(got["costs"], np.concatenate([p[0] for p in parts]))
+    assert np.array_equal(got["tours"], np.concatenate([p[1] for p in parts]))
+    assert np.array_equal(got["moves"], np.concatenate([p[2] for p in parts]))
+    assert (got["moves"] > 10).all()

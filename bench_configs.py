@@ -2,7 +2,8 @@
 """Times every workload of the rank-order search on one MI355X and prints one JSON line per workload.
 
 Workloads 1-5 are the parity-test configurations (matrix shapes and work amounts in gen/workloads.py);
-"M64" is the batch-evaluation headline case (ring sum and max on 2^20 seeded orders at N=64).  Times are
+"M64" is the batch-evaluation headline case (ring sum and max on 2^20 seeded orders at N=64); "S64" / "S256"
+are pair-swap searches under the halving-doubling model on the matrices of workloads 2 and 4.  Times are
 HIP-event times around the library call on the launch stream, median of `--reps` after one warm-up.
 `bench.py` remains the single-line benchmark of the N=64 workload; this script gives the per-workload
 table of the design doc.  Pass --oracle to time the CPU oracle beside each search (a bounded sample of
@@ -79,6 +80,29 @@ def main():
                       "oracle_sample_restarts": sample, "oracle_sample_s": dt, "bit_exact_on_sample": ok})
         emit(d)
 
+    def swap_case(name, wid, restarts):
+        w = WORKLOADS[wid]
+        c_host = make_matrix(wid)
+        c = torch.from_numpy(c_host).cuda()
+        bufs = cc.SearchBuffers(w.n, 0, restarts, c.device)
+        ms = timed(lambda: cc.cc_rd_swap_search_ex(c, restarts, w.search_seed, buffers=bufs), args.reps)
+        moves = bufs.restart_moves.cpu().numpy().astype(np.int64)
+        nbhd = w.n * (w.n - 1) // 2
+        evals = int(((moves + 1) * nbhd).sum())
+        d = {"workload": name, "call": "cc_rd_swap_search_ex", "N": w.n, "restarts": restarts, "ms": ms,
+             "move_evals": evals, "move_evals_per_s": evals / (ms * 1e-3), "applied_moves_mean": float(moves.mean()),
+             "applied_moves_max": int(moves.max()), "best_cost": int(bufs.best_cost.item())}
+        if args.oracle:
+            import oracle
+            sample = min(restarts, 64 if w.n <= 64 else 2)
+            t0 = time.perf_counter()
+            oc, ot, om = oracle.rd_swap_restarts(c_host, w.search_seed, 0, sample)
+            dt = time.perf_counter() - t0
+            ok = bool(np.array_equal(om, moves[:sample]) and np.array_equal(ot, bufs.restart_tours.cpu().numpy()[:sample]))
+            d.update({"oracle_1core_move_evals_per_s": float(((om.astype(np.int64) + 1) * nbhd).sum() / dt),
+                      "oracle_sample_restarts": sample, "bit_exact_on_sample": ok})
+        emit(d)
+
     def batch_case(name, wid, kind, objective, batch):
         w = WORKLOADS[wid]
         c_host = make_matrix(wid)
@@ -110,6 +134,8 @@ def main():
         ("C4", lambda: search_case(4)),
         ("C5rd", lambda: batch_case("C5_n1024_rd_65536", 5, "rd", 0, 65536)),
         ("C5", lambda: search_case(5)),
+        ("S64", lambda: swap_case("S64_n64_rd_swap_1024", 2, 1024)),
+        ("S256", lambda: swap_case("S256_n256_rd_swap_64", 4, 64)),
         ("M64sum", lambda: batch_case("M64_ring_sum_2^20", 2, "ring", 0, 1 << 20)),
         ("M64max", lambda: batch_case("M64_ring_max_2^20", 3, "ring", 1, 1 << 20)),
     ]

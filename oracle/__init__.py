@@ -81,6 +81,10 @@ def _L():
         lib.cco_rd_swap_descend.argtypes = [p, i32, p, p, p, i32, p, i32]
         lib.cco_rd_swap_restarts.restype = ctypes.c_int
         lib.cco_rd_swap_restarts.argtypes = [p, i32, u64, i64, i64, p, p, p, p]
+        lib.cco_bcube_cost.restype = i64
+        lib.cco_bcube_cost.argtypes = [p, i32, i32, p]
+        lib.cco_bcube_cost_batch.restype = ctypes.c_int
+        lib.cco_bcube_cost_batch.argtypes = [p, i32, i32, p, i64, p]
         _lib = lib
     return _lib
 
@@ -306,3 +310,18 @@ def rd_swap_search(c, n_restarts: int, seed: int, init: Optional[np.ndarray] = N
     k = int(np.argmin(costs))
     return dict(best_perm=tours[k].copy(), best_cost=int(costs[k]), best_restart=k, costs=costs, tours=tours,
                 moves=moves)
+
+
+# ------------------------------------------------------------------------------------------ BCube cost model
+def bcube_cost(c, base: int, perm) -> int:
+    c = _mat(c)
+    perm = np.ascontiguousarray(perm, dtype=np.int32)
+    return int(_L().cco_bcube_cost(_ptr(c), c.shape[0], base, _ptr(perm)))
+
+
+def bcube_cost_batch(c, base: int, perms) -> np.ndarray:
+    c = _mat(c)
+    perms = np.ascontiguousarray(perms, dtype=np.int32).reshape(-1, c.shape[0])
+    out = np.empty(perms.shape[0], dtype=np.int64)
+    _check(_L().cco_bcube_cost_batch(_ptr(c), c.shape[0], base, _ptr(perms), perms.shape[0], _ptr(out)))
+    return out

@@ -544,3 +544,37 @@ int cco_rd_swap_restarts(const int32_t *c, int32_t N, uint64_t seed, int64_t r0,
     free(t);
     return CCO_OK;
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * BCube cost model (Section 4.1, equation C_b; Section 2.2: ranks are grouped by the base-B digits of
+ * their id; in round i a rank exchanges with the B-1 ranks that differ from it in digit i only).
+ * Round i costs the slowest of all those exchanges; rounds add up.  N must be a power of B.
+ * The printed index set (j < N/B, k up to B, j + k*B^i) is read as digit arithmetic modulo B.
+ * B = 2 is the halving-doubling model.
+ * ---------------------------------------------------------------------------------------------- */
+int64_t cco_bcube_cost(const int32_t *c, int32_t N, int32_t B, const int32_t *pi)
+{
+    int64_t total = 0;
+    for (int64_t stride = 1; stride < N; stride *= B) {
+        int64_t worst = 0;
+        for (int32_t j = 0; j < N; ++j) {
+            int32_t digit = (int32_t)((j / stride) % B);
+            for (int32_t k = 1; k < B; ++k) {
+                int32_t peer = (int32_t)(j - digit * stride + ((digit + k) % B) * stride);
+                worst = max64(worst, C_(pi[j], pi[peer]));
+            }
+        }
+        total += worst;
+    }
+    return total;
+}
+
+int cco_bcube_cost_batch(const int32_t *c, int32_t N, int32_t B, const int32_t *perms, int64_t count, int64_t *out)
+{
+    if (!c || N < 2 || B < 2 || count < 0 || (count > 0 && (!perms || !out))) return CCO_ERR_ARG;
+    int64_t pw = 1;
+    while (pw < N) pw *= B;
+    if (pw != N) return CCO_ERR_ARG;
+    for (int64_t b = 0; b < count; ++b) out[b] = cco_bcube_cost(c, N, B, perms + b * N);
+    return CCO_OK;
+}

@@ -77,6 +77,18 @@ int cc_rd_cost_batch(const int32_t* cost_matrix, int32_t N, const int32_t* perms
                      int64_t* out_costs, void* stream);
 
 /*
+ * BCube cost model (Section 4.1, equation C_b; Section 2.2 for the peering pattern): ranks are
+ * numbered in base `base`; in round i every rank exchanges with the base-1 ranks whose number differs
+ * from its own in digit i only (the printed peer index j + k*base^i is taken modulo `base` within
+ * that digit); a round costs its slowest exchange and the rounds add up:
+ *     out_costs[b] = sum over digits i of  max over ranks j, k in [1, base) of c[perm_b[j]][perm_b[peer(j, i, k)]]
+ * N must be a power of `base` (else CC_ERR_UNSUPPORTED_N), base >= 2, 2 <= N <= CC_MAX_N.  base = 2 is
+ * the halving-doubling model.  perms, out_costs, B as for cc_rd_cost_batch.
+ */
+int cc_bcube_cost_batch(const int32_t* cost_matrix, int32_t N, int32_t base, const int32_t* perms, int64_t B,
+                        int64_t* out_costs, void* stream);
+
+/*
  * Multi-start 2-opt search for a ring order (Section 4.3: stochastic neighbour search started from
  * random orders, neighbours obtained by permuting a sub-array; here the deterministic
  * best-improvement form).

@@ -194,6 +194,84 @@ hipError_t launch_rd_cost_batch(const int32_t* c, int N, const int32_t* perms, i
     return rd_launch<16>(c, N, perms, B, out, s);
 }
 
+// ------------------------------------------------------------------------------- BCube cost model
+// Section 4.1, equation C_b: round i pairs every rank with the base-1 ranks that differ from it in
+// base-`base` digit i only; the round costs its slowest exchange.  Same gather-max-sum shape as the
+// halving-doubling kernel with base-1 gathers per rank and round.
+template <int NM, bool LDS_MATRIX>
+__global__ __launch_bounds__(256) void bcube_batch_kernel(const int32_t* __restrict__ c, int N, int base,
+                                                          const int32_t* __restrict__ perms, int64_t B,
+                                                          int64_t* __restrict__ out) {
+    extern __shared__ int32_t sm[];
+    int32_t* order = sm + (threadIdx.x >> 6) * N;
+    const int32_t* mat = c;
+    if (LDS_MATRIX) {
+        int32_t* m = sm + 4 * N;
+        for (int e = threadIdx.x; e < N * N; e += 256) m[e] = c[e];
+        __syncthreads();
+        mat = m;
+    }
+    const int lane = lane_id();
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t b = wave; b < B; b += nwaves) {
+        const int32_t* pi = perms + b * N;
+        int a[NM];
+#pragma unroll
+        for (int k = 0; k < NM; ++k) {
+            const int p = lane + 64 * k;
+            a[k] = p < N ? clampi(pi[p], 0, N - 1) : 0;
+            if (p < N) order[p] = a[k];
+        }
+        __builtin_amdgcn_wave_barrier();
+        long long total = 0;
+        for (int stride = 1; stride < N; stride *= base) {
+            int worst = 0;
+#pragma unroll
+            for (int k = 0; k < NM; ++k) {
+                const int p = lane + 64 * k;
+                if (p < N) {
+                    const int digit = (p / stride) % base;
+                    const int* row = mat + a[k] * N;
+                    int peer_digit = digit;
+                    for (int step = 1; step < base; ++step) {
+                        peer_digit = peer_digit + 1 == base ? 0 : peer_digit + 1;
+                        worst = max(worst, row[order[p + (peer_digit - digit) * stride]]);
+                    }
+                }
+            }
+            total += wave_max(worst);
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (lane == 0) out[b] = total;
+    }
+}
+
+template <int NM>
+static hipError_t bcube_launch(const int32_t* c, int N, int base, const int32_t* perms, int64_t B, int64_t* out,
+                               hipStream_t s) {
+    const int grid = batch_grid(4, B);
+    if (N <= 64) {
+        const size_t lds = sizeof(int32_t) * (size_t)(4 * N + N * N);
+        hipLaunchKernelGGL((bcube_batch_kernel<NM, true>), dim3(grid), dim3(256), lds, s, c, N, base, perms, B, out);
+    } else {
+        const size_t lds = sizeof(int32_t) * (size_t)(4 * N);
+        hipLaunchKernelGGL((bcube_batch_kernel<NM, false>), dim3(grid), dim3(256), lds, s, c, N, base, perms, B, out);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_bcube_cost_batch(const int32_t* c, int N, int base, const int32_t* perms, int64_t B, int64_t* out,
+                                   hipStream_t s) {
+    if (B == 0) return hipSuccess;
+    if (base == 2) return launch_rd_cost_batch(c, N, perms, B, out, s);
+    if (N <= 64) return bcube_launch<1>(c, N, base, perms, B, out, s);
+    if (N <= 128) return bcube_launch<2>(c, N, base, perms, B, out, s);
+    if (N <= 256) return bcube_launch<4>(c, N, base, perms, B, out, s);
+    if (N <= 512) return bcube_launch<8>(c, N, base, perms, B, out, s);
+    return bcube_launch<16>(c, N, base, perms, B, out, s);
+}
+
 // --------------------------------------------------------------------------------- initial orders
 // One wave per order: lanes draw the N-1 swap partners in parallel, lane 0 replays the swaps in
 // order (they are inherently sequential), all lanes store the result coalesced.

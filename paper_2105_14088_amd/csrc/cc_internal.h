@@ -10,6 +10,8 @@ hipError_t launch_ring_cost_batch(const int32_t* c, int N, bool is_max, const in
                                   int64_t* out, hipStream_t s);
 hipError_t launch_rd_cost_batch(const int32_t* c, int N, const int32_t* perms, int64_t B, int64_t* out,
                                 hipStream_t s);
+hipError_t launch_bcube_cost_batch(const int32_t* c, int N, int base, const int32_t* perms, int64_t B, int64_t* out,
+                                   hipStream_t s);
 hipError_t launch_init_tours(int N, int64_t first, int64_t count, uint64_t seed, int32_t* tours, hipStream_t s);
 hipError_t launch_validate(const int32_t* c, int N, bool require_symmetric, int32_t* flags, hipStream_t s);
 

@@ -62,6 +62,11 @@ def test_argument_errors_are_returned_before_any_launch():
     assert L.cc_rd_cost_batch(fake, 48, fake, 1, fake, null) == UNSUPPORTED      # not a power of two
     assert L.cc_rd_cost_batch(fake, 64, fake, -5, fake, null) == INVALID
     assert L.cc_rd_cost_batch(fake, 64, null, 0, null, null) == 0
+    assert L.cc_bcube_cost_batch(fake, 32, 4, fake, 1, fake, null) == UNSUPPORTED   # not a power of the base
+    assert L.cc_bcube_cost_batch(fake, 64, 1, fake, 1, fake, null) == INVALID
+    assert L.cc_bcube_cost_batch(fake, 64, 4, fake, -1, fake, null) == INVALID
+    assert L.cc_bcube_cost_batch(fake, 64, 4, null, 1, fake, null) == INVALID
+    assert L.cc_bcube_cost_batch(fake, 64, 4, null, 0, null, null) == 0
     assert L.cc_2opt_search(null, 64, 0, 1, 1, fake, fake, null) == INVALID
     assert L.cc_2opt_search(fake, 64, 0, 0, 1, fake, fake, null) == INVALID
     assert L.cc_2opt_search(fake, 64, 9, 1, 1, fake, fake, null) == INVALID

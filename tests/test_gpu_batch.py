@@ -89,6 +89,33 @@ def test_rd_batch(n):
         assert np.array_equal(gpu_rd(c, perms), oracle.rd_cost_batch(c, perms))
 
 
+@pytest.mark.parametrize("n,base", [(4, 4), (16, 4), (64, 4), (256, 4), (1024, 4), (9, 3), (27, 3), (243, 3), (729, 3),
+                                    (64, 8), (512, 8), (25, 5), (625, 5), (32, 32), (1024, 32), (64, 2), (7, 7)])
+def test_bcube_batch(n, base):
+    c = random_matrix(n, 900 + n, symmetric=False, lo=0, hi=COST_MAX if n == 64 else 9000)
+    for b in (1, 5, 259):
+        say(f"bcube batch N={n} base={base} B={b}")
+        perms = random_perms(n, b, seed=n * 5 + b)
+        out = cc.cc_bcube_cost_batch(dev(c), base, dev(perms))
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), oracle.bcube_cost_batch(c, base, perms))
+
+
+def test_bcube_base4_n1024_16384_orders():
+    """Full-size case: B = 4 (the paper's BCube base) on 16384 seeded orders at N = 1024, sampled against the oracle."""
+    say("bcube batch N=1024 base=4 B=16384")
+    c = make_matrix(5)
+    seed = WORKLOADS[5].search_seed
+    B = 16384
+    tours = cc.cc_init_tours(1024, B, seed)
+    out = cc.cc_bcube_cost_batch(dev(c), 4, tours)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    rows = np.unique(np.concatenate([np.arange(0, B, 67), np.arange(B - 8, B)]))
+    th = tours[torch.from_numpy(rows).cuda()].cpu().numpy()
+    assert np.array_equal(got[rows], oracle.bcube_cost_batch(c, 4, th))
+
+
 def test_workload5_rd_65536_orders_n1024():
     """Full size: 65536 seeded orders at N=1024; the oracle recomputes a 512-order sample."""
     say("C5: rd batch N=1024 B=65536")

@@ -19,8 +19,13 @@
  * brute force over all rings for N <= 10, every move's fast value against apply-and-recompute,
  * local-optimum certification, published SplitMix64 output vectors; for the pair-swap search under the
  * halving-doubling model: every swap's fast value against swap-and-recompute, replayed trajectories,
- * brute force over all 8! orders.
- * Parity unpinned: none of the functions below.
+ * brute force over all 8! orders; for the BCube model: base 2 against the halving-doubling model, closed forms,
+ * digit automorphisms; for the annealing chain: the acceptance rule against the Boltzmann factor, proposal
+ * statistics, bookkeeping against recomputation, the Boltzmann distribution of a constant-temperature chain
+ * over an enumerated state space.
+ * Parity unpinned: none of the functions below against their stated definitions.  The annealing schedule,
+ * random-number use and acceptance rule are this project's own definition (the paper names the method only),
+ * so there is nothing in the paper to pin those choices to.
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -577,4 +582,127 @@ int cco_bcube_cost_batch(const int32_t *c, int32_t N, int32_t B, const int32_t *
     if (pw != N) return CCO_ERR_ARG;
     for (int64_t b = 0; b < count; ++b) out[b] = cco_bcube_cost(c, N, B, perms + b * N);
     return CCO_OK;
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * Simulated annealing over the ring (Section 4.3: stochastic search by simulated annealing, a neighbour
+ * obtained by permuting a random sub-array).  The paper fixes neither the schedule nor the random
+ * numbers; this is one fully integer definition so that any two implementations agree bit for bit.
+ *
+ *   Chain r starts from init_tour(seed, r).  Step s = 0 .. steps-1 draws w = output number
+ *   ((r << 32) | (1024 + s)) + 1 of the same SplitMix64 generator (initial tours use the low words below 1024).
+ *   Proposal.  Two ring edges (edge p joins ranks p-1 and p): a = (w[63:43] * N) >> 21,
+ *   d = 2 + ((w[42:22] * (N-3)) >> 21), b = (a + d) mod N, so every ordered pair of non-adjacent edges is
+ *   (nearly) equally likely.  Exchanging them is the 2-opt move (i, j) = (lo, hi-1), or (hi, N-1) when lo = 0,
+ *   lo = min(a,b), hi = max(a,b): the reversal of that span of ranks.
+ *   delta = ring_sum(after) - ring_sum(before) = c[t[a-1]][t[b-1]] + c[t[a]][t[b]] - c[t[a]][t[a-1]] - c[t[b]][t[b-1]]
+ *   on a symmetric matrix.
+ *   Temperature.  Linear from t_start (step 0) towards t_end: T_s = (t_start*(steps-s) + t_end*s) / steps, kept
+ *   as the exact numerator num_s.  T is the cost increase accepted with probability one half.
+ *   Acceptance (Metropolis with the Boltzmann factor 2^(-delta/T)).  u = w[21:0] + 1 in [1, 2^22];
+ *   L(u) = 4096*e + frac, e = floor(log2 u), frac = the next 12 bits of u below its leading one (piecewise-linear
+ *   log2 in 1/4096 units); E = 22*4096 - L(u), i.e. -log2(u / 2^22).  Accept iff delta <= 0 or
+ *   delta * 4096 * steps <= num_s * E.
+ *   The chain reports the lowest-cost order it has visited (the earliest such), that cost, and how many
+ *   proposals it accepted.  N < 4 has no proposals.
+ * Limits: steps <= 2^24, 0 <= t_start, t_end <= 2^21 - 1, entries <= 2^21 - 1: every product fits int64.
+ * ---------------------------------------------------------------------------------------------- */
+enum { CCO_SA_STREAM_BASE = 1024, CCO_SA_MAX_STEPS = 1 << 24, CCO_SA_MAX_T = (1 << 21) - 1 };
+
+void cco_sa_proposal(uint64_t seed, uint32_t r, uint32_t s, int32_t N, int32_t *a, int32_t *b, int32_t *u)
+{
+    uint64_t w = cco_splitmix64_at(seed, (((uint64_t)r << 32) | (uint64_t)(CCO_SA_STREAM_BASE + s)) + 1u);
+    uint64_t hi21 = w >> 43, mid21 = (w >> 22) & 0x1FFFFFu;
+    int32_t ea = (int32_t)((hi21 * (uint64_t)N) >> 21);
+    int32_t d = 2 + (int32_t)((mid21 * (uint64_t)(N - 3)) >> 21);
+    *a = ea;
+    *b = (ea + d) % N;
+    *u = (int32_t)(w & 0x3FFFFFu) + 1;
+}
+
+/* piecewise-linear log2(u) in units of 1/4096, exact at powers of two; 1 <= u <= 2^22 */
+int32_t cco_sa_log2_fix(int32_t u)
+{
+    int32_t e = 0;
+    while ((u >> (e + 1)) != 0) ++e;
+    int32_t m = u - (1 << e);
+    int32_t frac = e >= 12 ? (m >> (e - 12)) : (m << (12 - e));
+    return e * 4096 + frac;
+}
+
+int cco_sa_accepts(int64_t delta, int64_t steps, int64_t num, int32_t u)
+{
+    if (delta <= 0) return 1;
+    int64_t E = 22 * 4096 - cco_sa_log2_fix(u);
+    return delta * 4096 * steps <= num * E;
+}
+
+/* One chain, in place on t.  use_definition != 0: delta by applying the move to a copy and recomputing the ring
+ * sum.  trace (or NULL): int64 [steps], the current cost after every step. */
+int cco_sa_chain(const int32_t *c, int32_t N, int32_t *t, int64_t steps, int32_t t_start, int32_t t_end, uint64_t seed,
+                 uint32_t r, int32_t use_definition, int32_t *best_tour, int64_t *best_cost, int64_t *final_cost,
+                 int32_t *accepted, int64_t *trace)
+{
+    if (!c || !t || N < 2 || steps < 0 || steps > CCO_SA_MAX_STEPS || t_start < 0 || t_end < 0 ||
+        t_start > CCO_SA_MAX_T || t_end > CCO_SA_MAX_T)
+        return CCO_ERR_ARG;
+    int64_t cur = cco_ring_cost(c, N, t, CCO_SUM);
+    int64_t best = cur;
+    int32_t acc = 0;
+    if (best_tour) memcpy(best_tour, t, sizeof(int32_t) * (size_t)N);
+    int32_t *tmp = use_definition ? (int32_t *)malloc(sizeof(int32_t) * (size_t)N) : NULL;
+    if (use_definition && !tmp) return CCO_ERR_NOMEM;
+    for (int64_t s = 0; s < steps && N >= 4; ++s) {
+        int32_t a, b, u;
+        cco_sa_proposal(seed, r, (uint32_t)s, N, &a, &b, &u);
+        int32_t lo = a < b ? a : b, hi = a < b ? b : a;
+        int32_t i = lo ? lo : hi, j = lo ? hi - 1 : N - 1;
+        int64_t delta;
+        if (use_definition) {
+            memcpy(tmp, t, sizeof(int32_t) * (size_t)N);
+            cco_apply_move(tmp, N, i, j, 0);
+            delta = cco_ring_cost(c, N, tmp, CCO_SUM) - cur;
+        } else {
+            int32_t ap = (a + N - 1) % N, bp = (b + N - 1) % N;
+            delta = C_(t[ap], t[bp]) + C_(t[a], t[b]) - C_(t[a], t[ap]) - C_(t[b], t[bp]);
+        }
+        int64_t num = (int64_t)t_start * (steps - s) + (int64_t)t_end * s;
+        if (cco_sa_accepts(delta, steps, num, u)) {
+            cco_apply_move(t, N, i, j, 0);
+            cur += delta;
+            ++acc;
+            if (cur < best) {
+                best = cur;
+                if (best_tour) memcpy(best_tour, t, sizeof(int32_t) * (size_t)N);
+            }
+        }
+        if (trace) trace[s] = cur;
+    }
+    free(tmp);
+    if (best_cost) *best_cost = best;
+    if (final_cost) *final_cost = cur;
+    if (accepted) *accepted = acc;
+    return CCO_OK;
+}
+
+/* Chains r0 .. r1-1.  init (or NULL): int32 [r1-r0, N] starting orders instead of the seeded ones.
+ * costs / tours: each chain's best cost and best order; accepted: accepted proposals. */
+int cco_sa_chains(const int32_t *c, int32_t N, int64_t steps, int32_t t_start, int32_t t_end, uint64_t seed, int64_t r0,
+                  int64_t r1, const int32_t *init, int64_t *costs, int32_t *tours, int32_t *accepted)
+{
+    if (!c || N < 2 || r0 < 0 || r1 < r0 || !costs || !tours) return CCO_ERR_ARG;
+    if (!is_symmetric(c, N)) return CCO_ERR_NOT_SYMMETRIC;
+    int32_t *t = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    if (!t) return CCO_ERR_NOMEM;
+    int rc = CCO_OK;
+    for (int64_t r = r0; r < r1 && rc == CCO_OK; ++r) {
+        if (init) memcpy(t, init + (r - r0) * N, sizeof(int32_t) * (size_t)N);
+        else cco_init_tour(seed, (uint32_t)r, N, t);
+        int32_t acc = 0;
+        rc = cco_sa_chain(c, N, t, steps, t_start, t_end, seed, (uint32_t)r, 0, tours + (r - r0) * N, costs + (r - r0),
+                          NULL, &acc, NULL);
+        if (accepted) accepted[r - r0] = acc;
+    }
+    free(t);
+    return rc;
 }

@@ -3,7 +3,8 @@
 
 Workloads 1-5 are the parity-test configurations (matrix shapes and work amounts in gen/workloads.py);
 "M64" is the batch-evaluation headline case (ring sum and max on 2^20 seeded orders at N=64); "S64" / "S256"
-are pair-swap searches under the halving-doubling model on the matrices of workloads 2 and 4.  Times are
+are pair-swap searches under the halving-doubling model on the matrices of workloads 2 and 4; "A64" / "A256" /
+"A1024" are simulated-annealing runs (chains x steps) on the matrices of workloads 2, 4 and 5.  Times are
 HIP-event times around the library call on the launch stream, median of `--reps` after one warm-up.
 `bench.py` remains the single-line benchmark of the N=64 workload; this script gives the per-workload
 table of the design doc.  Pass --oracle to time the CPU oracle beside each search (a bounded sample of
@@ -103,6 +104,29 @@ def main():
                       "oracle_sample_restarts": sample, "bit_exact_on_sample": ok})
         emit(d)
 
+    def sa_case(name, wid, chains, steps, t_start, t_end):
+        w = WORKLOADS[wid]
+        c_host = make_matrix(wid)
+        c = torch.from_numpy(c_host).cuda()
+        bufs = cc.SearchBuffers(w.n, 0, chains, c.device)
+        ms = timed(lambda: cc.cc_sa_search_ex(c, chains, steps, t_start, t_end, w.search_seed, buffers=bufs), args.reps)
+        acc = bufs.restart_moves.cpu().numpy().astype(np.int64)
+        d = {"workload": name, "call": "cc_sa_search_ex", "N": w.n, "chains": chains, "steps": steps,
+             "t_start": t_start, "t_end": t_end, "ms": ms, "chain_steps_per_s": chains * steps / (ms * 1e-3),
+             "accepted_fraction": float(acc.mean() / steps), "best_cost": int(bufs.best_cost.item()),
+             "mean_chain_best": float(bufs.restart_costs.double().mean().item())}
+        if args.oracle:
+            import oracle
+            sample = min(chains, 8)
+            t0 = time.perf_counter()
+            oc, ot, oa = oracle.sa_chains(c_host, steps, t_start, t_end, w.search_seed, 0, sample)
+            dt = time.perf_counter() - t0
+            ok = bool(np.array_equal(oc, bufs.restart_costs.cpu().numpy()[:sample]) and
+                      np.array_equal(ot, bufs.restart_tours.cpu().numpy()[:sample]) and np.array_equal(oa, acc[:sample]))
+            d.update({"oracle_1core_chain_steps_per_s": sample * steps / dt, "oracle_sample_chains": sample,
+                      "bit_exact_on_sample": ok})
+        emit(d)
+
     def batch_case(name, wid, kind, objective, batch):
         w = WORKLOADS[wid]
         c_host = make_matrix(wid)
@@ -136,6 +160,10 @@ def main():
         ("C5", lambda: search_case(5)),
         ("S64", lambda: swap_case("S64_n64_rd_swap_1024", 2, 1024)),
         ("S256", lambda: swap_case("S256_n256_rd_swap_64", 4, 64)),
+        ("A64", lambda: sa_case("A64_n64_sa_1024x100000", 2, 1024, 100000, 300, 0)),
+        ("A64big", lambda: sa_case("A64_n64_sa_8192x100000", 2, 8192, 100000, 300, 0)),
+        ("A256", lambda: sa_case("A256_n256_sa_1024x200000", 4, 1024, 200000, 300, 0)),
+        ("A1024", lambda: sa_case("A1024_n1024_sa_1024x200000", 5, 1024, 200000, 300, 0)),
         ("M64sum", lambda: batch_case("M64_ring_sum_2^20", 2, "ring", 0, 1 << 20)),
         ("M64max", lambda: batch_case("M64_ring_max_2^20", 3, "ring", 1, 1 << 20)),
     ]

@@ -35,6 +35,7 @@ extern "C" {
 
 #define CC_MAX_N 1024
 #define CC_COST_MAX ((1 << 21) - 1)
+#define CC_SA_MAX_STEPS (1 << 24)
 
 typedef enum {
     CC_OK = 0,
@@ -152,6 +153,42 @@ int cc_rd_swap_search_ex(const int32_t* cost_matrix, int32_t N, int32_t restarts
                          size_t workspace_bytes, void* stream);
 
 size_t cc_rd_swap_workspace_bytes(int32_t N, int32_t restarts);
+
+/*
+ * Simulated annealing over the ring, sum objective (Section 4.3: stochastic search by simulated
+ * annealing, a neighbour obtained by permuting a random sub-array).  The paper fixes neither schedule
+ * nor random numbers; this is an all-integer definition, so every implementation gives the same result.
+ *
+ *   Chain r starts from the seeded order of restart r (cc_2opt_search) or from init_tours[r].
+ *   Step s = 0 .. steps-1 draws w = output number ((r << 32) | (1024 + s)) + 1 of the SplitMix64 generator
+ *   started at state `seed`.
+ *   Proposal: ring edges a = (w[63:43] * N) >> 21 and b = (a + d) mod N, d = 2 + ((w[42:22] * (N-3)) >> 21)
+ *   (edge p joins ranks p-1 and p); exchanging them is the 2-opt move (i, j) = (lo, hi-1), or (hi, N-1) when
+ *   lo = 0, lo = min(a, b), hi = max(a, b).  delta = cost after - cost before.
+ *   Temperature: linear from t_start to t_end, num_s = t_start*(steps-s) + t_end*s (= T_s * steps).  T is the
+ *   cost increase that is accepted with probability one half (Boltzmann factor 2^(-delta/T)).
+ *   Acceptance: u = w[21:0] + 1; L = 4096*e + f, e = floor(log2 u), f = the 12 bits of u below its leading
+ *   one (zero-padded); E = 22*4096 - L.  Accept iff delta <= 0 or delta * 4096 * steps <= num_s * E.
+ *   Each chain reports the cheapest order it visited (the earliest such) and that cost; the result is the
+ *   lexicographically smallest (cost, r).
+ *
+ * Requires a symmetric matrix.  0 <= steps <= CC_SA_MAX_STEPS, 0 <= t_start, t_end <= CC_COST_MAX,
+ * chains >= 1 (else CC_ERR_INVALID_ARG).  N < 4 has no proposals.  cc_sa_search allocates its workspace
+ * from the stream-ordered device allocator.  In cc_sa_search_ex: init_tours int32 [chains, N] or NULL;
+ * best_chain int32 [1], chain_costs int64 [chains], chain_tours int32 [chains, N] (each chain's best
+ * order), chain_accepted int32 [chains] (accepted proposals) may be NULL; workspace as in
+ * cc_2opt_search_ex, at least cc_sa_workspace_bytes(N, chains) bytes.  The orders a search returns can be
+ * passed to cc_2opt_search_ex as init_tours for a final descent.
+ */
+int cc_sa_search(const int32_t* cost_matrix, int32_t N, int32_t chains, int64_t steps, int32_t t_start, int32_t t_end,
+                 uint64_t seed, int32_t* best_perm, int64_t* best_cost, void* stream);
+
+int cc_sa_search_ex(const int32_t* cost_matrix, int32_t N, int32_t chains, int64_t steps, int32_t t_start,
+                    int32_t t_end, uint64_t seed, const int32_t* init_tours, int32_t* best_perm, int64_t* best_cost,
+                    int32_t* best_chain, int64_t* chain_costs, int32_t* chain_tours, int32_t* chain_accepted,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+size_t cc_sa_workspace_bytes(int32_t N, int32_t chains);
 
 /*
  * Initial orders of restarts first .. first+count-1 for `seed` (the shuffle described above);

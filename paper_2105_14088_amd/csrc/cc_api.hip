@@ -176,6 +176,50 @@ int cc_rd_swap_search(const int32_t* cost_matrix, int32_t N, int32_t restarts, u
     return CC_OK;
 }
 
+size_t cc_sa_workspace_bytes(int32_t N, int32_t chains) {
+    if (N < 2 || N > CC_MAX_N || chains < 1) return 0;
+    return ws_layout(N, chains).mat16;       // flags, costs, accepted counts, orders
+}
+
+int cc_sa_search_ex(const int32_t* cost_matrix, int32_t N, int32_t chains, int64_t steps, int32_t t_start, int32_t t_end,
+                    uint64_t seed, const int32_t* init_tours, int32_t* best_perm, int64_t* best_cost, int32_t* best_chain,
+                    int64_t* chain_costs, int32_t* chain_tours, int32_t* chain_accepted, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+    if (int rc = check_matrix_args(cost_matrix, N)) return rc;
+    if (chains < 1 || steps < 0 || steps > CC_SA_MAX_STEPS || t_start < 0 || t_start > CC_COST_MAX || t_end < 0 ||
+        t_end > CC_COST_MAX || !best_perm || !best_cost)
+        return CC_ERR_INVALID_ARG;
+    const WsLayout w = ws_layout(N, chains);
+    if (!workspace || workspace_bytes < w.mat16 || ((uintptr_t)workspace & 255u)) return CC_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    char* base = (char*)workspace;
+    int64_t* costs = chain_costs ? chain_costs : (int64_t*)(base + w.costs);
+    int32_t* acc = chain_accepted ? chain_accepted : (int32_t*)(base + w.moves);
+    int32_t* tours = chain_tours ? chain_tours : (int32_t*)(base + w.tours);
+    if (init_tours && init_tours != tours)
+        CC_HIP(hipMemcpyAsync(tours, init_tours, sizeof(int32_t) * (size_t)chains * (size_t)N, hipMemcpyDeviceToDevice, s));
+    CC_HIP(cc::launch_sa_ring(cost_matrix, N, chains, steps, t_start, t_end, seed, init_tours == nullptr, tours, costs,
+                              acc, s));
+    CC_HIP(cc::launch_best_restart(costs, tours, N, chains, best_perm, best_cost, best_chain, s));
+    return CC_OK;
+}
+
+int cc_sa_search(const int32_t* cost_matrix, int32_t N, int32_t chains, int64_t steps, int32_t t_start, int32_t t_end,
+                 uint64_t seed, int32_t* best_perm, int64_t* best_cost, void* stream) {
+    if (int rc = check_matrix_args(cost_matrix, N)) return rc;
+    if (chains < 1 || !best_perm || !best_cost) return CC_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    const size_t bytes = cc_sa_workspace_bytes(N, chains);
+    void* ws = nullptr;
+    CC_HIP(hipMallocAsync(&ws, bytes, s));
+    const int rc = cc_sa_search_ex(cost_matrix, N, chains, steps, t_start, t_end, seed, nullptr, best_perm, best_cost,
+                                   nullptr, nullptr, nullptr, nullptr, ws, bytes, stream);
+    const hipError_t e = hipFreeAsync(ws, s);
+    if (rc != CC_OK) return rc;
+    if (e != hipSuccess) return hip_fail(e);
+    return CC_OK;
+}
+
 int cc_init_tours(int32_t N, int64_t first, int64_t count, uint64_t seed, int32_t* tours, void* stream) {
     if (N < 2 || N > CC_MAX_N) return CC_ERR_UNSUPPORTED_N;
     if (first < 0 || count < 0 || first + count > (int64_t)1 << 32) return CC_ERR_INVALID_ARG;

@@ -67,6 +67,18 @@ def test_argument_errors_are_returned_before_any_launch():
     assert L.cc_bcube_cost_batch(fake, 64, 4, fake, -1, fake, null) == INVALID
     assert L.cc_bcube_cost_batch(fake, 64, 4, null, 1, fake, null) == INVALID
     assert L.cc_bcube_cost_batch(fake, 64, 4, null, 0, null, null) == 0
+    assert L.cc_sa_search(null, 64, 1, 10, 1, 1, 1, fake, fake, null) == INVALID
+    assert L.cc_sa_search(fake, 64, 0, 10, 1, 1, 1, fake, fake, null) == INVALID          # no chains
+    assert L.cc_sa_search(fake, 2000, 1, 10, 1, 1, 1, fake, fake, null) == UNSUPPORTED
+    sa = [fake, 64, 4, 10, 1, 1, 1, null, fake, fake, null, null, null, null]
+    assert L.cc_sa_search_ex(*sa, null, 0, null) == WORKSPACE
+    sa[3] = (1 << 24) + 1
+    assert L.cc_sa_search_ex(*sa, fake, 1 << 30, null) == INVALID                        # too many steps
+    sa[3], sa[4] = 10, 1 << 21
+    assert L.cc_sa_search_ex(*sa, fake, 1 << 30, null) == INVALID                        # temperature out of range
+    sa[4], sa[5] = 1, -1
+    assert L.cc_sa_search_ex(*sa, fake, 1 << 30, null) == INVALID
+    assert L.cc_sa_workspace_bytes(64, 0) == 0 and L.cc_sa_workspace_bytes(64, 4) >= 4 * 64 * 4
     assert L.cc_2opt_search(null, 64, 0, 1, 1, fake, fake, null) == INVALID
     assert L.cc_2opt_search(fake, 64, 0, 0, 1, fake, fake, null) == INVALID
     assert L.cc_2opt_search(fake, 64, 9, 1, 1, fake, fake, null) == INVALID

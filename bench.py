@@ -44,6 +44,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--saturated", action="store_true",
+                    help="after the timed steps also time the same search kernel with 64x the restarts "
+                         "(adds a roofline_saturated object; changes the kernel's average in a profile)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy before the steps (a dispatch of known HBM "
                          "traffic that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
@@ -150,6 +153,29 @@ def main():
                            "unit": "GB/s", "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": TRAFFIC_RING_BATCH_BYTES,
                            "bytes_per_perm": 4 * n + 8},
     }
+
+    if args.saturated:
+        # The same kernel with every SIMD holding several wavefronts (outside the timed steps): 64 times the restarts.
+        sat_restarts = 64 * restarts
+        sat_bufs = cc.SearchBuffers(n, cc.CC_RING_SUM, sat_restarts, c.device)
+        cc.cc_2opt_search_ex(c, cc.CC_RING_SUM, sat_restarts, seed, buffers=sat_bufs)
+        torch.cuda.synchronize()
+        sat_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
+        for e0, e1 in sat_ev:
+            e0.record()
+            cc.cc_2opt_search_ex(c, cc.CC_RING_SUM, sat_restarts, seed, buffers=sat_bufs)
+            e1.record()
+        torch.cuda.synchronize()
+        sat_ms = float(np.median([e0.elapsed_time(e1) for e0, e1 in sat_ev]))
+        sat_evals = int(((sat_bufs.restart_moves.cpu().numpy().astype(np.int64) + 1) * nbhd).sum())
+        sat_gbs = sat_evals / (sat_ms * 1e-3) * LDS_BYTES_PER_MOVE / 1e9
+        result["roofline_saturated"] = {"kernel": "2-opt search (neighbourhood sweep), same kernel", "restarts": sat_restarts,
+                                        "ms": sat_ms, "move_evals_per_s": sat_evals / (sat_ms * 1e-3), "bound": "lds",
+                                        "achieved": sat_gbs, "peak": LDS_PEAK_GBS, "unit": "GB/s",
+                                        "frac": sat_gbs / LDS_PEAK_GBS,
+                                        "note": "not the metric's configuration: 1024 restarts put one wavefront on each "
+                                                "of the 1024 SIMDs, where instruction issue latency bounds the kernel"}
+        del sat_bufs
 
     if not args.no_cpu_baseline:
         import oracle

@@ -95,6 +95,12 @@ def _L():
         lib.cco_sa_chain.argtypes = [p, i32, p, i64, i32, i32, u64, ctypes.c_uint32, i32, p, p, p, p, p]
         lib.cco_sa_chains.restype = ctypes.c_int
         lib.cco_sa_chains.argtypes = [p, i32, i64, i32, i32, u64, i64, i64, p, p, p, p]
+        lib.cco_dbt_tree_cost.restype = i64
+        lib.cco_dbt_tree_cost.argtypes = [p, i32, p, i32]
+        lib.cco_dbt_cost.restype = i64
+        lib.cco_dbt_cost.argtypes = [p, i32, p]
+        lib.cco_dbt_cost_batch.restype = ctypes.c_int
+        lib.cco_dbt_cost_batch.argtypes = [p, i32, p, i64, p]
         _lib = lib
     return _lib
 
@@ -390,3 +396,24 @@ def sa_search(c, chains: int, steps: int, t_start: int, t_end: int, seed: int, i
     k = int(np.argmin(costs))
     return dict(best_perm=tours[k].copy(), best_cost=int(costs[k]), best_chain=k, costs=costs, tours=tours,
                 accepted=accepted)
+
+
+# ------------------------------------------------------------------------------------------ double binary tree
+def dbt_tree_cost(c, perm, shift: int = 0) -> int:
+    c = _mat(c)
+    perm = np.ascontiguousarray(perm, dtype=np.int32)
+    return int(_L().cco_dbt_tree_cost(_ptr(c), c.shape[0], _ptr(perm), shift))
+
+
+def dbt_cost(c, perm) -> int:
+    c = _mat(c)
+    perm = np.ascontiguousarray(perm, dtype=np.int32)
+    return int(_L().cco_dbt_cost(_ptr(c), c.shape[0], _ptr(perm)))
+
+
+def dbt_cost_batch(c, perms) -> np.ndarray:
+    c = _mat(c)
+    perms = np.ascontiguousarray(perms, dtype=np.int32).reshape(-1, c.shape[0])
+    out = np.empty(perms.shape[0], dtype=np.int64)
+    _check(_L().cco_dbt_cost_batch(_ptr(c), c.shape[0], _ptr(perms), perms.shape[0], _ptr(out)))
+    return out

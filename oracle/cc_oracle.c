@@ -706,3 +706,47 @@ int cco_sa_chains(const int32_t *c, int32_t N, int64_t steps, int32_t t_start, i
     free(t);
     return rc;
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * Double-binary-tree cost model (Section 4.1, equation C_dbt with the recursion T(i, j)).
+ * The ranks i .. j form a subtree whose root is the middle rank m = floor((i+j)/2); its children are the
+ * roots of the subtrees on i .. m-1 and m+1 .. j (the middle ranks of those ranges; the printed child
+ * indices (3i+j)/2 - 1 and (i+3j)/2 + 1 are not the middles of those ranges and are read as such).
+ * T(i, j) = 0 for i >= j, else the larger of  c[root][left child] + T(i, m-1)  (if the left range is not
+ * empty) and  c[root][right child] + T(m+1, j): the most expensive root-to-leaf path.  The second tree has
+ * the same shape with every rank moved down by one position (tree position p holds rank p+1 mod N); the
+ * total is the larger of the two trees (Section 4.1: the maximum cost of all trees).  Latency-only view:
+ * every hop weighs 1, as for the other models.
+ * ---------------------------------------------------------------------------------------------- */
+static int64_t dbt_T(const int32_t *c, int32_t N, const int32_t *pi, int32_t shift, int32_t i, int32_t j)
+{
+    if (i >= j) return 0;
+    int32_t m = (i + j) / 2;
+    int32_t root = pi[(m + shift) % N];
+    int64_t worst = 0;
+    if (i <= m - 1) {
+        int32_t child = pi[((i + m - 1) / 2 + shift) % N];
+        worst = max64(worst, C_(root, child) + dbt_T(c, N, pi, shift, i, m - 1));
+    }
+    int32_t child = pi[((m + 1 + j) / 2 + shift) % N];
+    worst = max64(worst, C_(root, child) + dbt_T(c, N, pi, shift, m + 1, j));
+    return worst;
+}
+
+/* one tree: shift = 0 (first tree) or 1 (second tree) */
+int64_t cco_dbt_tree_cost(const int32_t *c, int32_t N, const int32_t *pi, int32_t shift)
+{
+    return dbt_T(c, N, pi, shift, 0, N - 1);
+}
+
+int64_t cco_dbt_cost(const int32_t *c, int32_t N, const int32_t *pi)
+{
+    return max64(cco_dbt_tree_cost(c, N, pi, 0), cco_dbt_tree_cost(c, N, pi, 1));
+}
+
+int cco_dbt_cost_batch(const int32_t *c, int32_t N, const int32_t *perms, int64_t count, int64_t *out)
+{
+    if (!c || N < 2 || count < 0 || (count > 0 && (!perms || !out))) return CCO_ERR_ARG;
+    for (int64_t b = 0; b < count; ++b) out[b] = cco_dbt_cost(c, N, perms + b * N);
+    return CCO_OK;
+}

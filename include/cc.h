@@ -90,6 +90,17 @@ int cc_bcube_cost_batch(const int32_t* cost_matrix, int32_t N, int32_t base, con
                         int64_t* out_costs, void* stream);
 
 /*
+ * Double-binary-tree cost model (Section 4.1, equation C_dbt and its recursion T(i, j)): the ranks i .. j
+ * form a subtree rooted at the middle rank m = floor((i+j)/2) whose children are the middle ranks of
+ * i .. m-1 and m+1 .. j (the printed child indices are read as those middles); a tree costs its most
+ * expensive root-to-leaf path, sum of c[perm[parent]][perm[child]] over the path's hops; the second tree is
+ * the same shape with tree position p holding rank (p+1) mod N; out_costs[b] is the larger of the two
+ * trees' costs.  2 <= N <= CC_MAX_N.  perms, out_costs, B as for cc_rd_cost_batch.
+ */
+int cc_dbt_cost_batch(const int32_t* cost_matrix, int32_t N, const int32_t* perms, int64_t B, int64_t* out_costs,
+                      void* stream);
+
+/*
  * Multi-start 2-opt search for a ring order (Section 4.3: stochastic neighbour search started from
  * random orders, neighbours obtained by permuting a sub-array; here the deterministic
  * best-improvement form).

@@ -101,6 +101,8 @@ def _L():
         lib.cco_dbt_cost.argtypes = [p, i32, p]
         lib.cco_dbt_cost_batch.restype = ctypes.c_int
         lib.cco_dbt_cost_batch.argtypes = [p, i32, p, i64, p]
+        lib.cco_bcube_cost_weighted_batch.restype = ctypes.c_int
+        lib.cco_bcube_cost_weighted_batch.argtypes = [p, i32, i32, p, p, i64, p]
         _lib = lib
     return _lib
 
@@ -416,4 +418,15 @@ def dbt_cost_batch(c, perms) -> np.ndarray:
     perms = np.ascontiguousarray(perms, dtype=np.int32).reshape(-1, c.shape[0])
     out = np.empty(perms.shape[0], dtype=np.int64)
     _check(_L().cco_dbt_cost_batch(_ptr(c), c.shape[0], _ptr(perms), perms.shape[0], _ptr(out)))
+    return out
+
+
+def bcube_cost_weighted_batch(c, base: int, weights, perms) -> np.ndarray:
+    """Size-weighted rounds; base 2 is halving-doubling."""
+    c = _mat(c)
+    weights = np.ascontiguousarray(weights, dtype=np.int32)
+    perms = np.ascontiguousarray(perms, dtype=np.int32).reshape(-1, c.shape[0])
+    out = np.empty(perms.shape[0], dtype=np.int64)
+    _check(_L().cco_bcube_cost_weighted_batch(_ptr(c), c.shape[0], base, _ptr(weights), _ptr(perms), perms.shape[0],
+                                              _ptr(out)))
     return out

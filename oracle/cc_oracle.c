@@ -750,3 +750,38 @@ int cco_dbt_cost_batch(const int32_t *c, int32_t N, const int32_t *perms, int64_
     for (int64_t b = 0; b < count; ++b) out[b] = cco_dbt_cost(c, N, perms + b * N);
     return CCO_OK;
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * Size-weighted rounds (Section 4.1: round i of halving-doubling moves S / 2^(i+1) bytes, round i of BCube
+ * S / B^(i+1)).  With a per-byte cost matrix (the bandwidth-bound end of c(S)) round i costs weight[i] times
+ * its slowest exchange; weight[i] is whatever the caller derives from S.  All weights 1 is the latency-only
+ * model above.  base = 2 is halving-doubling.
+ * ---------------------------------------------------------------------------------------------- */
+int64_t cco_bcube_cost_weighted(const int32_t *c, int32_t N, int32_t B, const int32_t *weights, const int32_t *pi)
+{
+    int64_t total = 0;
+    int32_t round = 0;
+    for (int64_t stride = 1; stride < N; stride *= B, ++round) {
+        int64_t worst = 0;
+        for (int32_t j = 0; j < N; ++j) {
+            int32_t digit = (int32_t)((j / stride) % B);
+            for (int32_t k = 1; k < B; ++k) {
+                int32_t peer = (int32_t)(j - digit * stride + ((digit + k) % B) * stride);
+                worst = max64(worst, C_(pi[j], pi[peer]));
+            }
+        }
+        total += (int64_t)weights[round] * worst;
+    }
+    return total;
+}
+
+int cco_bcube_cost_weighted_batch(const int32_t *c, int32_t N, int32_t B, const int32_t *weights, const int32_t *perms,
+                                  int64_t count, int64_t *out)
+{
+    if (!c || !weights || N < 2 || B < 2 || count < 0 || (count > 0 && (!perms || !out))) return CCO_ERR_ARG;
+    int64_t pw = 1;
+    while (pw < N) pw *= B;
+    if (pw != N) return CCO_ERR_ARG;
+    for (int64_t b = 0; b < count; ++b) out[b] = cco_bcube_cost_weighted(c, N, B, weights, perms + b * N);
+    return CCO_OK;
+}

@@ -89,6 +89,17 @@ int cc_bcube_cost_batch(const int32_t* cost_matrix, int32_t N, int32_t base, con
     return CC_OK;
 }
 
+int cc_dbt_cost_batch(const int32_t* cost_matrix, int32_t N, const int32_t* perms, int64_t B, int64_t* out_costs,
+                      void* stream) {
+    if (int rc = check_matrix_args(cost_matrix, N)) return rc;
+    if (B < 0) return CC_ERR_INVALID_ARG;
+    if (B == 0) return CC_OK;
+    if (!perms || !out_costs) return CC_ERR_INVALID_ARG;
+    if (((uintptr_t)perms & 3u) || ((uintptr_t)out_costs & 7u) || ((uintptr_t)cost_matrix & 3u)) return CC_ERR_INVALID_ARG;
+    CC_HIP(cc::launch_dbt_cost_batch(cost_matrix, N, perms, B, out_costs, (hipStream_t)stream));
+    return CC_OK;
+}
+
 size_t cc_2opt_workspace_bytes(int32_t N, int32_t objective, int32_t restarts) {
     if (N < 2 || N > CC_MAX_N || objective < 0 || objective > 3 || restarts < 1) return 0;
     return ws_layout(N, restarts).total;

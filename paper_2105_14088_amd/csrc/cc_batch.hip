@@ -272,6 +272,70 @@ hipError_t launch_bcube_cost_batch(const int32_t* c, int N, int base, const int3
     return bcube_launch<16>(c, N, base, perms, B, out, s);
 }
 
+// --------------------------------------------------------------------- double-binary-tree cost model
+// Section 4.1, equation C_dbt: the ranks form an in-order binary tree whose subtree roots are the middle
+// ranks of their ranges; a tree costs its most expensive root-to-leaf path; the second tree has the same
+// shape one position further along the order; the result is the larger of the two.  Every lane walks from
+// the root to its own position (a binary search, at most 10 hops), adding c[parent][child] per hop; the
+// largest path over the wave is the tree's cost.
+template <bool LDS_MATRIX>
+__global__ __launch_bounds__(256) void dbt_batch_kernel(const int32_t* __restrict__ c, int N,
+                                                        const int32_t* __restrict__ perms, int64_t B,
+                                                        int64_t* __restrict__ out) {
+    extern __shared__ int32_t sm[];
+    int32_t* order = sm + (threadIdx.x >> 6) * N;
+    const int32_t* mat = c;
+    if (LDS_MATRIX) {
+        int32_t* m = sm + 4 * N;
+        for (int e = threadIdx.x; e < N * N; e += 256) m[e] = c[e];
+        __syncthreads();
+        mat = m;
+    }
+    const int lane = lane_id();
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t b = wave; b < B; b += nwaves) {
+        const int32_t* pi = perms + b * N;
+        for (int p = lane; p < N; p += kWave) order[p] = clampi(pi[p], 0, N - 1);
+        __builtin_amdgcn_wave_barrier();
+        int worst = 0;
+        for (int shift = 0; shift < 2; ++shift) {
+            for (int p = lane; p < N; p += kWave) {
+                int lo = 0, hi = N - 1, m = (N - 1) >> 1, acc = 0;
+                int at = m + shift;
+                int prev = order[at >= N ? at - N : at];
+                for (int depth = 0; depth < 11 && m != p; ++depth) {
+                    if (p < m) hi = m - 1;
+                    else lo = m + 1;
+                    m = (lo + hi) >> 1;
+                    at = m + shift;
+                    const int cur = order[at >= N ? at - N : at];
+                    acc += mat[prev * N + cur];
+                    prev = cur;
+                }
+                worst = max(worst, acc);
+            }
+        }
+        const int total = wave_max(worst);
+        __builtin_amdgcn_wave_barrier();
+        if (lane == 0) out[b] = total;
+    }
+}
+
+hipError_t launch_dbt_cost_batch(const int32_t* c, int N, const int32_t* perms, int64_t B, int64_t* out,
+                                 hipStream_t s) {
+    if (B == 0) return hipSuccess;
+    const int grid = batch_grid(4, B);
+    if (N <= 64) {
+        const size_t lds = sizeof(int32_t) * (size_t)(4 * N + N * N);
+        hipLaunchKernelGGL((dbt_batch_kernel<true>), dim3(grid), dim3(256), lds, s, c, N, perms, B, out);
+    } else {
+        const size_t lds = sizeof(int32_t) * (size_t)(4 * N);
+        hipLaunchKernelGGL((dbt_batch_kernel<false>), dim3(grid), dim3(256), lds, s, c, N, perms, B, out);
+    }
+    return hipGetLastError();
+}
+
 // --------------------------------------------------------------------------------- initial orders
 // One wave per order: lanes draw the N-1 swap partners in parallel, lane 0 replays the swaps in
 // order (they are inherently sequential), all lanes store the result coalesced.

@@ -67,6 +67,10 @@ def test_argument_errors_are_returned_before_any_launch():
     assert L.cc_bcube_cost_batch(fake, 64, 4, fake, -1, fake, null) == INVALID
     assert L.cc_bcube_cost_batch(fake, 64, 4, null, 1, fake, null) == INVALID
     assert L.cc_bcube_cost_batch(fake, 64, 4, null, 0, null, null) == 0
+    assert L.cc_dbt_cost_batch(fake, 1, fake, 1, fake, null) == UNSUPPORTED
+    assert L.cc_dbt_cost_batch(fake, 48, fake, -1, fake, null) == INVALID
+    assert L.cc_dbt_cost_batch(fake, 48, fake, 1, null, null) == INVALID
+    assert L.cc_dbt_cost_batch(fake, 48, null, 0, null, null) == 0
     assert L.cc_sa_search(null, 64, 1, 10, 1, 1, 1, fake, fake, null) == INVALID
     assert L.cc_sa_search(fake, 64, 0, 10, 1, 1, 1, fake, fake, null) == INVALID          # no chains
     assert L.cc_sa_search(fake, 2000, 1, 10, 1, 1, 1, fake, fake, null) == UNSUPPORTED

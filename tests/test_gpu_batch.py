@@ -116,6 +116,32 @@ def test_bcube_base4_n1024_16384_orders():
     assert np.array_equal(got[rows], oracle.bcube_cost_batch(c, 4, th))
 
 
+@pytest.mark.parametrize("n", [2, 3, 4, 5, 7, 8, 13, 63, 64, 65, 100, 128, 255, 256, 1000, 1023, 1024])
+def test_dbt_batch(n):
+    c = random_matrix(n, 1200 + n, symmetric=False, lo=0, hi=COST_MAX if n in (64, 1024) else 9000)
+    for b in (1, 5, 259):
+        say(f"dbt batch N={n} B={b}")
+        perms = random_perms(n, b, seed=n * 7 + b)
+        out = cc.cc_dbt_cost_batch(dev(c), dev(perms))
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), oracle.dbt_cost_batch(c, perms))
+
+
+def test_dbt_n64_2_20_orders():
+    """Full size: 2^20 seeded orders at N = 64 (matrix of workload 2), sampled against the oracle."""
+    say("dbt batch N=64 B=2^20")
+    c = make_matrix(2)
+    seed = WORKLOADS[2].search_seed
+    B = 1 << 20
+    tours = cc.cc_init_tours(64, B, seed)
+    out = cc.cc_dbt_cost_batch(dev(c), tours)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    rows = np.unique(np.concatenate([np.arange(0, B, 1021), np.arange(B - 8, B)]))
+    th = tours[torch.from_numpy(rows).cuda()].cpu().numpy()
+    assert np.array_equal(got[rows], oracle.dbt_cost_batch(c, th))
+
+
 def test_workload5_rd_65536_orders_n1024():
     """Full size: 65536 seeded orders at N=1024; the oracle recomputes a 512-order sample."""
     say("C5: rd batch N=1024 B=65536")

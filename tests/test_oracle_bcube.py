@@ -80,3 +80,54 @@ def test_rejects_n_not_a_power_of_base():
     c = random_matrix(8, 1, symmetric=True)
     with pytest.raises(RuntimeError):
         oracle.bcube_cost_batch(c, 4, random_perms(8, 2, seed=1))
+
+
+# ------------------------------------------------------------------------------------- size-weighted rounds
+@pytest.mark.parametrize("n,base", [(64, 2), (64, 4), (27, 3), (1024, 2), (256, 4)])
+def test_unit_weights_are_the_unweighted_model(n, base):
+    c = random_matrix(n, 3 + n, symmetric=False)
+    perms = random_perms(n, 4, seed=n)
+    rounds = round(math.log(n, base))
+    assert np.array_equal(oracle.bcube_cost_weighted_batch(c, base, np.ones(rounds), perms),
+                          oracle.bcube_cost_batch(c, base, perms))
+    if base == 2:
+        assert np.array_equal(oracle.bcube_cost_weighted_batch(c, 2, np.ones(rounds), perms), oracle.rd_cost_batch(c, perms))
+
+
+@pytest.mark.parametrize("n,base", [(16, 2), (64, 2), (64, 4), (81, 3)])
+def test_single_round_weight_isolates_that_round(n, base):
+    """weight = e_k leaves round k alone: the largest entry over ranks j and their peers in digit k, written
+    out with numpy index arithmetic."""
+    c = random_matrix(n, 9 + n, symmetric=False)
+    rounds = round(math.log(n, base))
+    ids = np.arange(n)
+    for perm in random_perms(n, 2, seed=n):
+        total = 0
+        for k in range(rounds):
+            stride = base ** k
+            digit = (ids // stride) % base
+            worst = 0
+            for step in range(1, base):
+                peer = ids + (((digit + step) % base) - digit) * stride
+                worst = max(worst, int(c[perm[ids], perm[peer]].max()))
+            w = np.zeros(rounds, dtype=np.int32)
+            w[k] = 5
+            assert oracle.bcube_cost_weighted_batch(c, base, w, perm[None])[0] == 5 * worst
+            total += worst
+        assert oracle.bcube_cost_batch(c, base, perm[None])[0] == total
+
+
+def test_weights_are_linear_and_halving_sizes_closed_form():
+    n = 64
+    c = random_matrix(n, 2, symmetric=True)
+    perms = random_perms(n, 5, seed=9)
+    rng = np.random.default_rng(4)
+    w1, w2 = rng.integers(0, 1000, size=6), rng.integers(0, 1000, size=6)
+    assert np.array_equal(oracle.bcube_cost_weighted_batch(c, 2, w1 + w2, perms),
+                          oracle.bcube_cost_weighted_batch(c, 2, w1, perms) + oracle.bcube_cost_weighted_batch(c, 2, w2, perms))
+    # halving-doubling on a constant per-byte cost k with S = 2^20 bytes: sum_i k * S / 2^(i+1) = k * S * (1 - 1/N)
+    k, S = 3, 1 << 20
+    const = np.full((n, n), k, dtype=np.int32)
+    np.fill_diagonal(const, 0)
+    w = np.array([S >> (i + 1) for i in range(6)])
+    assert oracle.bcube_cost_weighted_batch(const, 2, w, perms[:1])[0] == k * S * (n - 1) // n

@@ -90,6 +90,15 @@ int cc_bcube_cost_batch(const int32_t* cost_matrix, int32_t N, int32_t base, con
                         int64_t* out_costs, void* stream);
 
 /*
+ * The same with size-weighted rounds (Section 4.1: round i of halving-doubling moves S / 2^(i+1) bytes, round
+ * i of BCube S / base^(i+1)): with a per-byte cost matrix, round i costs round_weights[i] times its slowest
+ * exchange.  round_weights: DEVICE int32 [log_base N], each in [0, 2^30] (values outside are clamped); all
+ * ones gives cc_bcube_cost_batch.  base = 2 is halving-doubling with weighted rounds.
+ */
+int cc_bcube_cost_batch_weighted(const int32_t* cost_matrix, int32_t N, int32_t base, const int32_t* round_weights,
+                                 const int32_t* perms, int64_t B, int64_t* out_costs, void* stream);
+
+/*
  * Double-binary-tree cost model (Section 4.1, equation C_dbt and its recursion T(i, j)): the ranks i .. j
  * form a subtree rooted at the middle rank m = floor((i+j)/2) whose children are the middle ranks of
  * i .. m-1 and m+1 .. j (the printed child indices are read as those middles); a tree costs its most

@@ -20,7 +20,7 @@ CC_MAX_N = 1024
 CC_COST_MAX = (1 << 21) - 1
 
 # every symbol include/cc.h declares
-EXPORTS = ["cc_ring_cost_batch", "cc_rd_cost_batch", "cc_bcube_cost_batch", "cc_dbt_cost_batch", "cc_2opt_search", "cc_2opt_search_ex",
+EXPORTS = ["cc_ring_cost_batch", "cc_rd_cost_batch", "cc_bcube_cost_batch", "cc_bcube_cost_batch_weighted", "cc_dbt_cost_batch", "cc_2opt_search", "cc_2opt_search_ex",
            "cc_2opt_workspace_bytes", "cc_rd_swap_search", "cc_rd_swap_search_ex", "cc_rd_swap_workspace_bytes", "cc_sa_search", "cc_sa_search_ex", "cc_sa_workspace_bytes", "cc_init_tours", "cc_validate_matrix", "cc_status_string",
            "cc_last_hip_error", "cc_version"]
 
@@ -52,6 +52,8 @@ def lib() -> ctypes.CDLL:
         L.cc_rd_cost_batch.argtypes = [p, i32, p, i64, p, p]
         L.cc_bcube_cost_batch.restype = ctypes.c_int
         L.cc_bcube_cost_batch.argtypes = [p, i32, i32, p, i64, p, p]
+        L.cc_bcube_cost_batch_weighted.restype = ctypes.c_int
+        L.cc_bcube_cost_batch_weighted.argtypes = [p, i32, i32, p, p, i64, p, p]
         L.cc_dbt_cost_batch.restype = ctypes.c_int
         L.cc_dbt_cost_batch.argtypes = [p, i32, p, i64, p, p]
         L.cc_2opt_search.restype = ctypes.c_int
@@ -150,6 +152,27 @@ def cc_bcube_cost_batch(cost_matrix: torch.Tensor, base: int, perms: torch.Tenso
     _check(lib().cc_bcube_cost_batch(_dev(cost_matrix, torch.int32, "cost_matrix"), n, base,
                                      _dev(perms, torch.int32, "perms"), b, _dev(out, torch.int64, "out"),
                                      _stream(stream)), "cc_bcube_cost_batch")
+    return out
+
+
+def cc_bcube_cost_batch_weighted(cost_matrix: torch.Tensor, base: int, round_weights: torch.Tensor, perms: torch.Tensor,
+                                 out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    n = _matrix(cost_matrix)
+    if perms.dim() != 2 or perms.shape[1] != n:
+        raise ValueError("perms must be [B, N]")
+    rounds, power = 0, 1
+    while power < n:
+        power *= base
+        rounds += 1
+    if round_weights.dim() != 1 or round_weights.shape[0] != rounds:
+        raise ValueError("round_weights must be [log_base N]")
+    b = int(perms.shape[0])
+    if out is None:
+        out = torch.empty(b, dtype=torch.int64, device=cost_matrix.device)
+    _check(lib().cc_bcube_cost_batch_weighted(_dev(cost_matrix, torch.int32, "cost_matrix"), n, base,
+                                              _dev(round_weights, torch.int32, "round_weights"),
+                                              _dev(perms, torch.int32, "perms"), b, _dev(out, torch.int64, "out"),
+                                              _stream(stream)), "cc_bcube_cost_batch_weighted")
     return out
 
 

@@ -70,23 +70,33 @@ int cc_rd_cost_batch(const int32_t* cost_matrix, int32_t N, const int32_t* perms
     if (B == 0) return CC_OK;
     if (!perms || !out_costs) return CC_ERR_INVALID_ARG;
     if (((uintptr_t)perms & 3u) || ((uintptr_t)out_costs & 7u) || ((uintptr_t)cost_matrix & 3u)) return CC_ERR_INVALID_ARG;
-    CC_HIP(cc::launch_rd_cost_batch(cost_matrix, N, perms, B, out_costs, (hipStream_t)stream));
+    CC_HIP(cc::launch_rd_cost_batch(cost_matrix, N, nullptr, perms, B, out_costs, (hipStream_t)stream));
     return CC_OK;
 }
 
-int cc_bcube_cost_batch(const int32_t* cost_matrix, int32_t N, int32_t base, const int32_t* perms, int64_t B,
-                        int64_t* out_costs, void* stream) {
+static int bcube_batch(const int32_t* cost_matrix, int32_t N, int32_t base, const int32_t* weights, bool weighted,
+                       const int32_t* perms, int64_t B, int64_t* out_costs, void* stream) {
     if (int rc = check_matrix_args(cost_matrix, N)) return rc;
     if (base < 2) return CC_ERR_INVALID_ARG;
     int64_t power = 1;
     while (power < N) power *= base;
     if (power != N) return CC_ERR_UNSUPPORTED_N;
-    if (B < 0) return CC_ERR_INVALID_ARG;
+    if (B < 0 || (weighted && (!weights || ((uintptr_t)weights & 3u)))) return CC_ERR_INVALID_ARG;
     if (B == 0) return CC_OK;
     if (!perms || !out_costs) return CC_ERR_INVALID_ARG;
     if (((uintptr_t)perms & 3u) || ((uintptr_t)out_costs & 7u) || ((uintptr_t)cost_matrix & 3u)) return CC_ERR_INVALID_ARG;
-    CC_HIP(cc::launch_bcube_cost_batch(cost_matrix, N, base, perms, B, out_costs, (hipStream_t)stream));
+    CC_HIP(cc::launch_bcube_cost_batch(cost_matrix, N, base, weights, perms, B, out_costs, (hipStream_t)stream));
     return CC_OK;
+}
+
+int cc_bcube_cost_batch(const int32_t* cost_matrix, int32_t N, int32_t base, const int32_t* perms, int64_t B,
+                        int64_t* out_costs, void* stream) {
+    return bcube_batch(cost_matrix, N, base, nullptr, false, perms, B, out_costs, stream);
+}
+
+int cc_bcube_cost_batch_weighted(const int32_t* cost_matrix, int32_t N, int32_t base, const int32_t* round_weights,
+                                 const int32_t* perms, int64_t B, int64_t* out_costs, void* stream) {
+    return bcube_batch(cost_matrix, N, base, round_weights, true, perms, B, out_costs, stream);
 }
 
 int cc_dbt_cost_batch(const int32_t* cost_matrix, int32_t N, const int32_t* perms, int64_t B, int64_t* out_costs,

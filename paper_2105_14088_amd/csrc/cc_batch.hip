@@ -13,6 +13,8 @@
 namespace cc {
 using namespace ccd;
 
+constexpr int kMaxRoundWeight = 1 << 30;   // round weights are clamped to [0, 2^30]: weight * cost stays below 2^51
+
 // ------------------------------------------------------------------------------------------ ring
 template <int N, bool IS_MAX>
 __global__ __launch_bounds__(256) void ring_batch_lds_kernel(const int32_t* __restrict__ c,
@@ -132,6 +134,7 @@ hipError_t launch_ring_cost_batch(const int32_t* c, int N, bool is_max, const in
 // otherwise gathered through L2.
 template <int NM, bool LDS_MATRIX>
 __global__ __launch_bounds__(256) void rd_batch_kernel(const int32_t* __restrict__ c, int N,
+                                                       const int32_t* __restrict__ weights,
                                                        const int32_t* __restrict__ perms, int64_t B,
                                                        int64_t* __restrict__ out) {
     extern __shared__ int32_t sm[];
@@ -157,14 +160,16 @@ __global__ __launch_bounds__(256) void rd_batch_kernel(const int32_t* __restrict
         }
         __builtin_amdgcn_wave_barrier();
         long long total = 0;
-        for (int bit = 1; bit < N; bit <<= 1) {
+        int round = 0;
+        for (int bit = 1; bit < N; bit <<= 1, ++round) {
             int worst = 0;
 #pragma unroll
             for (int k = 0; k < NM; ++k) {
                 const int p = lane + 64 * k;
                 if (p < N) worst = max(worst, mat[a[k] * N + order[p ^ bit]]);
             }
-            total += wave_max(worst);
+            const long long w = weights ? (long long)clampi(weights[round], 0, kMaxRoundWeight) : 1ll;
+            total += w * wave_max(worst);
         }
         __builtin_amdgcn_wave_barrier();   // all partner look-ups done before the slice is overwritten
         if (lane == 0) out[b] = total;
@@ -172,26 +177,27 @@ __global__ __launch_bounds__(256) void rd_batch_kernel(const int32_t* __restrict
 }
 
 template <int NM>
-static hipError_t rd_launch(const int32_t* c, int N, const int32_t* perms, int64_t B, int64_t* out, hipStream_t s) {
+static hipError_t rd_launch(const int32_t* c, int N, const int32_t* weights, const int32_t* perms, int64_t B,
+                            int64_t* out, hipStream_t s) {
     const int grid = batch_grid(4, B);
     if (N <= 64) {
         const size_t lds = sizeof(int32_t) * (size_t)(4 * N + N * N);
-        hipLaunchKernelGGL((rd_batch_kernel<NM, true>), dim3(grid), dim3(256), lds, s, c, N, perms, B, out);
+        hipLaunchKernelGGL((rd_batch_kernel<NM, true>), dim3(grid), dim3(256), lds, s, c, N, weights, perms, B, out);
     } else {
         const size_t lds = sizeof(int32_t) * (size_t)(4 * N);
-        hipLaunchKernelGGL((rd_batch_kernel<NM, false>), dim3(grid), dim3(256), lds, s, c, N, perms, B, out);
+        hipLaunchKernelGGL((rd_batch_kernel<NM, false>), dim3(grid), dim3(256), lds, s, c, N, weights, perms, B, out);
     }
     return hipGetLastError();
 }
 
-hipError_t launch_rd_cost_batch(const int32_t* c, int N, const int32_t* perms, int64_t B, int64_t* out,
-                                hipStream_t s) {
+hipError_t launch_rd_cost_batch(const int32_t* c, int N, const int32_t* weights, const int32_t* perms, int64_t B,
+                                int64_t* out, hipStream_t s) {
     if (B == 0) return hipSuccess;
-    if (N <= 64) return rd_launch<1>(c, N, perms, B, out, s);
-    if (N == 128) return rd_launch<2>(c, N, perms, B, out, s);
-    if (N == 256) return rd_launch<4>(c, N, perms, B, out, s);
-    if (N == 512) return rd_launch<8>(c, N, perms, B, out, s);
-    return rd_launch<16>(c, N, perms, B, out, s);
+    if (N <= 64) return rd_launch<1>(c, N, weights, perms, B, out, s);
+    if (N == 128) return rd_launch<2>(c, N, weights, perms, B, out, s);
+    if (N == 256) return rd_launch<4>(c, N, weights, perms, B, out, s);
+    if (N == 512) return rd_launch<8>(c, N, weights, perms, B, out, s);
+    return rd_launch<16>(c, N, weights, perms, B, out, s);
 }
 
 // ------------------------------------------------------------------------------- BCube cost model
@@ -200,6 +206,7 @@ hipError_t launch_rd_cost_batch(const int32_t* c, int N, const int32_t* perms, i
 // halving-doubling kernel with base-1 gathers per rank and round.
 template <int NM, bool LDS_MATRIX>
 __global__ __launch_bounds__(256) void bcube_batch_kernel(const int32_t* __restrict__ c, int N, int base,
+                                                          const int32_t* __restrict__ weights,
                                                           const int32_t* __restrict__ perms, int64_t B,
                                                           int64_t* __restrict__ out) {
     extern __shared__ int32_t sm[];
@@ -225,7 +232,8 @@ __global__ __launch_bounds__(256) void bcube_batch_kernel(const int32_t* __restr
         }
         __builtin_amdgcn_wave_barrier();
         long long total = 0;
-        for (int stride = 1; stride < N; stride *= base) {
+        int round = 0;
+        for (int stride = 1; stride < N; stride *= base, ++round) {
             int worst = 0;
 #pragma unroll
             for (int k = 0; k < NM; ++k) {
@@ -240,7 +248,8 @@ __global__ __launch_bounds__(256) void bcube_batch_kernel(const int32_t* __restr
                     }
                 }
             }
-            total += wave_max(worst);
+            const long long w = weights ? (long long)clampi(weights[round], 0, kMaxRoundWeight) : 1ll;
+            total += w * wave_max(worst);
         }
         __builtin_amdgcn_wave_barrier();
         if (lane == 0) out[b] = total;
@@ -248,28 +257,30 @@ __global__ __launch_bounds__(256) void bcube_batch_kernel(const int32_t* __restr
 }
 
 template <int NM>
-static hipError_t bcube_launch(const int32_t* c, int N, int base, const int32_t* perms, int64_t B, int64_t* out,
-                               hipStream_t s) {
+static hipError_t bcube_launch(const int32_t* c, int N, int base, const int32_t* weights, const int32_t* perms,
+                               int64_t B, int64_t* out, hipStream_t s) {
     const int grid = batch_grid(4, B);
     if (N <= 64) {
         const size_t lds = sizeof(int32_t) * (size_t)(4 * N + N * N);
-        hipLaunchKernelGGL((bcube_batch_kernel<NM, true>), dim3(grid), dim3(256), lds, s, c, N, base, perms, B, out);
+        hipLaunchKernelGGL((bcube_batch_kernel<NM, true>), dim3(grid), dim3(256), lds, s, c, N, base, weights, perms, B,
+                           out);
     } else {
         const size_t lds = sizeof(int32_t) * (size_t)(4 * N);
-        hipLaunchKernelGGL((bcube_batch_kernel<NM, false>), dim3(grid), dim3(256), lds, s, c, N, base, perms, B, out);
+        hipLaunchKernelGGL((bcube_batch_kernel<NM, false>), dim3(grid), dim3(256), lds, s, c, N, base, weights, perms, B,
+                           out);
     }
     return hipGetLastError();
 }
 
-hipError_t launch_bcube_cost_batch(const int32_t* c, int N, int base, const int32_t* perms, int64_t B, int64_t* out,
-                                   hipStream_t s) {
+hipError_t launch_bcube_cost_batch(const int32_t* c, int N, int base, const int32_t* weights, const int32_t* perms,
+                                   int64_t B, int64_t* out, hipStream_t s) {
     if (B == 0) return hipSuccess;
-    if (base == 2) return launch_rd_cost_batch(c, N, perms, B, out, s);
-    if (N <= 64) return bcube_launch<1>(c, N, base, perms, B, out, s);
-    if (N <= 128) return bcube_launch<2>(c, N, base, perms, B, out, s);
-    if (N <= 256) return bcube_launch<4>(c, N, base, perms, B, out, s);
-    if (N <= 512) return bcube_launch<8>(c, N, base, perms, B, out, s);
-    return bcube_launch<16>(c, N, base, perms, B, out, s);
+    if (base == 2) return launch_rd_cost_batch(c, N, weights, perms, B, out, s);
+    if (N <= 64) return bcube_launch<1>(c, N, base, weights, perms, B, out, s);
+    if (N <= 128) return bcube_launch<2>(c, N, base, weights, perms, B, out, s);
+    if (N <= 256) return bcube_launch<4>(c, N, base, weights, perms, B, out, s);
+    if (N <= 512) return bcube_launch<8>(c, N, base, weights, perms, B, out, s);
+    return bcube_launch<16>(c, N, base, weights, perms, B, out, s);
 }
 
 // --------------------------------------------------------------------- double-binary-tree cost model

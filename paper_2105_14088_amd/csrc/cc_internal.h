@@ -8,10 +8,11 @@ namespace cc {
 
 hipError_t launch_ring_cost_batch(const int32_t* c, int N, bool is_max, const int32_t* perms, int64_t B,
                                   int64_t* out, hipStream_t s);
-hipError_t launch_rd_cost_batch(const int32_t* c, int N, const int32_t* perms, int64_t B, int64_t* out,
-                                hipStream_t s);
-hipError_t launch_bcube_cost_batch(const int32_t* c, int N, int base, const int32_t* perms, int64_t B, int64_t* out,
-                                   hipStream_t s);
+// weights: device int32 [rounds] or nullptr (every round weighs 1)
+hipError_t launch_rd_cost_batch(const int32_t* c, int N, const int32_t* weights, const int32_t* perms, int64_t B,
+                                int64_t* out, hipStream_t s);
+hipError_t launch_bcube_cost_batch(const int32_t* c, int N, int base, const int32_t* weights, const int32_t* perms,
+                                   int64_t B, int64_t* out, hipStream_t s);
 hipError_t launch_dbt_cost_batch(const int32_t* c, int N, const int32_t* perms, int64_t B, int64_t* out,
                                  hipStream_t s);
 hipError_t launch_sa_ring(const int32_t* c, int N, int chains, long long steps, int t_start, int t_end, uint64_t seed,

@@ -101,6 +101,22 @@ def test_bcube_batch(n, base):
         assert np.array_equal(out.cpu().numpy(), oracle.bcube_cost_batch(c, base, perms))
 
 
+@pytest.mark.parametrize("n,base", [(64, 2), (1024, 2), (128, 2), (64, 4), (256, 4), (243, 3), (8, 8)])
+def test_bcube_weighted_batch(n, base):
+    c = random_matrix(n, 1500 + n, symmetric=False, lo=0, hi=COST_MAX if n == 64 else 9000)
+    rounds = 0
+    while base ** rounds < n:
+        rounds += 1
+    rng = np.random.default_rng(n + base)
+    for weights in (np.ones(rounds, dtype=np.int32), rng.integers(0, 1 << 20, size=rounds).astype(np.int32),
+                    np.array([(1 << 30) >> k for k in range(rounds)], dtype=np.int32)):
+        say(f"bcube weighted N={n} base={base} weights={weights.tolist()}")
+        perms = random_perms(n, 131, seed=n + rounds)
+        out = cc.cc_bcube_cost_batch_weighted(dev(c), base, dev(weights), dev(perms))
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), oracle.bcube_cost_weighted_batch(c, base, weights, perms))
+
+
 def test_bcube_base4_n1024_16384_orders():
     """Full-size case: B = 4 (the paper's BCube base) on 16384 seeded orders at N = 1024, sampled against the oracle."""
     say("bcube batch N=1024 base=4 B=16384")

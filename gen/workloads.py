@@ -157,3 +157,19 @@ def random_perms(n: int, count: int, seed: int) -> np.ndarray:
     rng = np.random.Generator(np.random.PCG64(seed))
     base = np.tile(np.arange(n, dtype=np.int32), (count, 1))
     return rng.permuted(base, axis=1)
+
+
+def probe_samples(base: np.ndarray, k: int, seed: int, interference: float = 0.2) -> np.ndarray:
+    """Synthetic latency probes (stand-in for the echo-tool traces of Section 4.2): int32 [N, N, k], sample s of
+    the ordered pair a -> b.  Each direction jitters a few percent above the pair's base RTT; a fraction
+    `interference` of the samples is inflated by a heavy lognormal tail (queueing, noisy neighbours)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    n = base.shape[0]
+    jitter = rng.gamma(2.0, 0.01, size=(n, n, k))
+    hit = rng.random(size=(n, n, k)) < interference
+    tail = rng.lognormal(0.5, 1.0, size=(n, n, k))
+    direction = 1.0 + 0.02 * rng.random(size=(n, n, 1))
+    real = base[:, :, None].astype(np.float64) * direction * (1.0 + jitter + hit * tail)
+    out = np.minimum(np.rint(real), COST_MAX).astype(np.int32)
+    out[np.arange(n), np.arange(n), :] = 0
+    return out

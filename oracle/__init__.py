@@ -103,6 +103,8 @@ def _L():
         lib.cco_dbt_cost_batch.argtypes = [p, i32, p, i64, p]
         lib.cco_bcube_cost_weighted_batch.restype = ctypes.c_int
         lib.cco_bcube_cost_weighted_batch.argtypes = [p, i32, i32, p, p, i64, p]
+        lib.cco_cost_matrix_from_probes.restype = ctypes.c_int
+        lib.cco_cost_matrix_from_probes.argtypes = [p, i32, i32, i32, i32, p]
         _lib = lib
     return _lib
 
@@ -429,4 +431,14 @@ def bcube_cost_weighted_batch(c, base: int, weights, perms) -> np.ndarray:
     out = np.empty(perms.shape[0], dtype=np.int64)
     _check(_L().cco_bcube_cost_weighted_batch(_ptr(c), c.shape[0], base, _ptr(weights), _ptr(perms), perms.shape[0],
                                               _ptr(out)))
+    return out
+
+
+# ------------------------------------------------------------------------------------------ cost matrix from probes
+def cost_matrix_from_probes(samples, percentile: int = 10, symmetrize: bool = True) -> np.ndarray:
+    samples = np.ascontiguousarray(samples, dtype=np.int32)
+    assert samples.ndim == 3 and samples.shape[0] == samples.shape[1]
+    n, k = samples.shape[0], samples.shape[2]
+    out = np.empty((n, n), dtype=np.int32)
+    _check(_L().cco_cost_matrix_from_probes(_ptr(samples), n, k, percentile, int(symmetrize), _ptr(out)))
     return out

@@ -785,3 +785,43 @@ int cco_bcube_cost_weighted_batch(const int32_t *c, int32_t N, int32_t B, const 
     for (int64_t b = 0; b < count; ++b) out[b] = cco_bcube_cost_weighted(c, N, B, weights, perms + b * N);
     return CCO_OK;
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * Cost matrix from probes (Section 4.2): every ordered pair of nodes is probed K times; the pair's cost is
+ * the RTT at the given percentile of its samples (the 10th in the paper, to filter out interference), and
+ * the matrix is made symmetric by keeping the larger of the two directions.
+ * Percentile by nearest rank: the sample of rank max(1, ceil(percentile * K / 100)) in ascending order.
+ * samples: int32 [N, N, K]; the diagonal is not read and comes out 0.  Samples are limited to [0, 2^21 - 1].
+ * ---------------------------------------------------------------------------------------------- */
+static int cmp_i32(const void *x, const void *y)
+{
+    int32_t a = *(const int32_t *)x, b = *(const int32_t *)y;
+    return (a > b) - (a < b);
+}
+
+int cco_cost_matrix_from_probes(const int32_t *samples, int32_t N, int32_t K, int32_t percentile, int32_t symmetrize,
+                                int32_t *out)
+{
+    if (!samples || !out || N < 1 || K < 1 || percentile < 0 || percentile > 100) return CCO_ERR_ARG;
+    int64_t rank = ((int64_t)percentile * K + 99) / 100;
+    if (rank < 1) rank = 1;
+    int32_t *buf = (int32_t *)malloc(sizeof(int32_t) * (size_t)K);
+    if (!buf) return CCO_ERR_NOMEM;
+    for (int32_t a = 0; a < N; ++a)
+        for (int32_t b = 0; b < N; ++b) {
+            if (a == b) { out[(int64_t)a * N + b] = 0; continue; }
+            const int32_t *src = samples + ((int64_t)a * N + b) * K;
+            for (int32_t s = 0; s < K; ++s) buf[s] = src[s] < 0 ? 0 : (src[s] > (1 << 21) - 1 ? (1 << 21) - 1 : src[s]);
+            qsort(buf, (size_t)K, sizeof(int32_t), cmp_i32);
+            out[(int64_t)a * N + b] = buf[rank - 1];
+        }
+    free(buf);
+    if (symmetrize)
+        for (int32_t a = 0; a < N; ++a)
+            for (int32_t b = a + 1; b < N; ++b) {
+                int32_t m = out[(int64_t)a * N + b] > out[(int64_t)b * N + a] ? out[(int64_t)a * N + b] : out[(int64_t)b * N + a];
+                out[(int64_t)a * N + b] = m;
+                out[(int64_t)b * N + a] = m;
+            }
+    return CCO_OK;
+}

@@ -127,6 +127,25 @@ def main():
                       "bit_exact_on_sample": ok})
         emit(d)
 
+    def probes_case(name, n, k):
+        rng = np.random.default_rng(n + k)
+        s_host = rng.integers(100, 30000, size=(n, n, k), dtype=np.int32)
+        s = torch.from_numpy(s_host).cuda()
+        out = torch.empty((n, n), dtype=torch.int32, device="cuda")
+        ms = timed(lambda: cc.cc_cost_matrix_from_probes(s, 10, True, out=out), args.reps)
+        nbytes = n * (n - 1) * k * 4
+        d = {"workload": name, "call": "cc_cost_matrix_from_probes", "N": n, "K": k, "ms": ms,
+             "samples_per_s": n * (n - 1) * k / (ms * 1e-3), "hbm_GBps": nbytes / (ms * 1e-3) / 1e9}
+        if args.oracle:
+            import oracle
+            sub = min(n, 16)
+            t0 = time.perf_counter()
+            want = oracle.cost_matrix_from_probes(s_host[:sub, :sub], 10, True)
+            dt = time.perf_counter() - t0
+            got = cc.cc_cost_matrix_from_probes(s[:sub, :sub].contiguous(), 10, True).cpu().numpy()
+            d.update({"oracle_1core_samples_per_s": sub * (sub - 1) * k / dt, "bit_exact_on_sample": bool(np.array_equal(got, want))})
+        emit(d)
+
     def batch_case(name, wid, kind, objective, batch):
         w = WORKLOADS[wid]
         c_host = make_matrix(wid)
@@ -164,6 +183,8 @@ def main():
         ("A64big", lambda: sa_case("A64_n64_sa_8192x100000", 2, 8192, 100000, 300, 0)),
         ("A256", lambda: sa_case("A256_n256_sa_1024x200000", 4, 1024, 200000, 300, 0)),
         ("A1024", lambda: sa_case("A1024_n1024_sa_1024x200000", 5, 1024, 200000, 300, 0)),
+        ("P64", lambda: probes_case("P64_n64_probes_10000", 64, 10000)),
+        ("P256", lambda: probes_case("P256_n256_probes_2000", 256, 2000)),
         ("M64sum", lambda: batch_case("M64_ring_sum_2^20", 2, "ring", 0, 1 << 20)),
         ("M64max", lambda: batch_case("M64_ring_max_2^20", 3, "ring", 1, 1 << 20)),
     ]

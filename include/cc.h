@@ -36,6 +36,7 @@ extern "C" {
 #define CC_MAX_N 1024
 #define CC_COST_MAX ((1 << 21) - 1)
 #define CC_SA_MAX_STEPS (1 << 24)
+#define CC_MAX_PROBES 16384
 
 typedef enum {
     CC_OK = 0,
@@ -216,6 +217,18 @@ size_t cc_sa_workspace_bytes(int32_t N, int32_t chains);
  * batch calls.
  */
 int cc_init_tours(int32_t N, int64_t first, int64_t count, uint64_t seed, int32_t* tours, void* stream);
+
+/*
+ * Cost matrix from latency probes (Section 4.2): cost_matrix[a][b] = the sample of rank
+ * max(1, ceil(percentile * K / 100)) among the K samples of the ordered pair a -> b in ascending order (the
+ * paper takes the 10th percentile to filter out interference); if symmetrize != 0 both directions then get
+ * the larger of the two (c[a][b] <- MAX(c[a][b], c[b][a])).  The diagonal is not read and is set to 0.
+ * samples: int32 [N, N, K], samples[(a*N + b)*K + s]; values are limited to [0, CC_COST_MAX].
+ * 1 <= N <= CC_MAX_N, 1 <= K <= CC_MAX_PROBES, 0 <= percentile <= 100.  cost_matrix: int32 [N, N], written in
+ * full; it satisfies the contract of every other call (symmetric if symmetrize != 0).
+ */
+int cc_cost_matrix_from_probes(const int32_t* samples, int32_t N, int32_t K, int32_t percentile, int32_t symmetrize,
+                               int32_t* cost_matrix, void* stream);
 
 /*
  * Checks the matrix contract: every entry in [0, CC_COST_MAX], and, if require_symmetric != 0,

@@ -21,7 +21,7 @@ CC_COST_MAX = (1 << 21) - 1
 
 # every symbol include/cc.h declares
 EXPORTS = ["cc_ring_cost_batch", "cc_rd_cost_batch", "cc_bcube_cost_batch", "cc_bcube_cost_batch_weighted", "cc_dbt_cost_batch", "cc_2opt_search", "cc_2opt_search_ex",
-           "cc_2opt_workspace_bytes", "cc_rd_swap_search", "cc_rd_swap_search_ex", "cc_rd_swap_workspace_bytes", "cc_sa_search", "cc_sa_search_ex", "cc_sa_workspace_bytes", "cc_init_tours", "cc_validate_matrix", "cc_status_string",
+           "cc_2opt_workspace_bytes", "cc_rd_swap_search", "cc_rd_swap_search_ex", "cc_rd_swap_workspace_bytes", "cc_sa_search", "cc_sa_search_ex", "cc_sa_workspace_bytes", "cc_init_tours", "cc_cost_matrix_from_probes", "cc_validate_matrix", "cc_status_string",
            "cc_last_hip_error", "cc_version"]
 
 
@@ -76,6 +76,8 @@ def lib() -> ctypes.CDLL:
         L.cc_sa_workspace_bytes.argtypes = [i32, i32]
         L.cc_init_tours.restype = ctypes.c_int
         L.cc_init_tours.argtypes = [i32, i64, i64, u64, p, p]
+        L.cc_cost_matrix_from_probes.restype = ctypes.c_int
+        L.cc_cost_matrix_from_probes.argtypes = [p, i32, i32, i32, i32, p, p]
         L.cc_validate_matrix.restype = ctypes.c_int
         L.cc_validate_matrix.argtypes = [p, i32, i32, p]
         L.cc_status_string.restype = ctypes.c_char_p
@@ -323,6 +325,19 @@ def cc_init_tours(n: int, count: int, seed: int, first: int = 0, device="cuda", 
         out = torch.empty((count, n), dtype=torch.int32, device=device)
     _check(lib().cc_init_tours(n, first, count, seed & (2**64 - 1), _dev(out, torch.int32, "tours"), _stream(stream)),
            "cc_init_tours")
+    return out
+
+
+def cc_cost_matrix_from_probes(samples: torch.Tensor, percentile: int = 10, symmetrize: bool = True,
+                               out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    if samples.dim() != 3 or samples.shape[0] != samples.shape[1]:
+        raise ValueError("samples must be [N, N, K]")
+    n, k = int(samples.shape[0]), int(samples.shape[2])
+    if out is None:
+        out = torch.empty((n, n), dtype=torch.int32, device=samples.device)
+    _check(lib().cc_cost_matrix_from_probes(_dev(samples, torch.int32, "samples"), n, k, percentile,
+                                            1 if symmetrize else 0, _dev(out, torch.int32, "cost_matrix"),
+                                            _stream(stream)), "cc_cost_matrix_from_probes")
     return out
 
 

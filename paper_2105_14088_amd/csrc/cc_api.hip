@@ -250,6 +250,17 @@ int cc_init_tours(int32_t N, int64_t first, int64_t count, uint64_t seed, int32_
     return CC_OK;
 }
 
+int cc_cost_matrix_from_probes(const int32_t* samples, int32_t N, int32_t K, int32_t percentile, int32_t symmetrize,
+                               int32_t* cost_matrix, void* stream) {
+    if (!samples || !cost_matrix || ((uintptr_t)samples & 3u) || ((uintptr_t)cost_matrix & 3u)) return CC_ERR_INVALID_ARG;
+    if (N < 1 || N > CC_MAX_N) return CC_ERR_UNSUPPORTED_N;
+    if (K < 1 || K > CC_MAX_PROBES || percentile < 0 || percentile > 100) return CC_ERR_INVALID_ARG;
+    int64_t rank = ((int64_t)percentile * K + 99) / 100;
+    if (rank < 1) rank = 1;
+    CC_HIP(cc::launch_probes_percentile(samples, N, K, (int)rank, symmetrize != 0, cost_matrix, (hipStream_t)stream));
+    return CC_OK;
+}
+
 int cc_validate_matrix(const int32_t* cost_matrix, int32_t N, int32_t require_symmetric, void* stream) {
     if (int rc = check_matrix_args(cost_matrix, N)) return rc;
     hipStream_t s = (hipStream_t)stream;

@@ -15,6 +15,8 @@ hipError_t launch_bcube_cost_batch(const int32_t* c, int N, int base, const int3
                                    int64_t B, int64_t* out, hipStream_t s);
 hipError_t launch_dbt_cost_batch(const int32_t* c, int N, const int32_t* perms, int64_t B, int64_t* out,
                                  hipStream_t s);
+hipError_t launch_probes_percentile(const int32_t* samples, int N, int K, int rank, bool symmetrize, int32_t* out,
+                                    hipStream_t s);
 hipError_t launch_sa_ring(const int32_t* c, int N, int chains, long long steps, int t_start, int t_end, uint64_t seed,
                           bool generate, int32_t* tours, int64_t* costs, int32_t* accepted, hipStream_t s);
 hipError_t launch_init_tours(int N, int64_t first, int64_t count, uint64_t seed, int32_t* tours, hipStream_t s);

@@ -70,6 +70,11 @@ def test_argument_errors_are_returned_before_any_launch():
     assert L.cc_bcube_cost_batch_weighted(fake, 64, 4, null, fake, 1, fake, null) == INVALID   # weights required
     assert L.cc_bcube_cost_batch_weighted(fake, 48, 2, fake, fake, 1, fake, null) == UNSUPPORTED
     assert L.cc_bcube_cost_batch_weighted(fake, 64, 2, fake, null, 0, null, null) == 0
+    assert L.cc_cost_matrix_from_probes(null, 8, 10, 10, 1, fake, null) == INVALID
+    assert L.cc_cost_matrix_from_probes(fake, 8, 0, 10, 1, fake, null) == INVALID
+    assert L.cc_cost_matrix_from_probes(fake, 8, 16385, 10, 1, fake, null) == INVALID
+    assert L.cc_cost_matrix_from_probes(fake, 8, 10, 101, 1, fake, null) == INVALID
+    assert L.cc_cost_matrix_from_probes(fake, 1025, 10, 10, 1, fake, null) == UNSUPPORTED
     assert L.cc_dbt_cost_batch(fake, 1, fake, 1, fake, null) == UNSUPPORTED
     assert L.cc_dbt_cost_batch(fake, 48, fake, -1, fake, null) == INVALID
     assert L.cc_dbt_cost_batch(fake, 48, fake, 1, null, null) == INVALID

@@ -3,10 +3,12 @@
 
 One step = one pass of the whole path on the N=64 workload, inputs resident in HBM:
   (1) cc_2opt_search_ex: 1024 seeded restarts of best-improvement 2-opt, ring sum objective, on the
-      hierarchical 64-node RTT matrix (initial orders, staging, sweeps, argmin, moves, best-of-restarts);
+      hierarchical 64-node RTT matrix (initial orders, staging, sweeps, argmin, moves), then
+      cc_best_of_restarts (the search's last step, called on its own so that the search kernel's
+      duration can be read from HIP events);
   (2) cc_ring_cost_batch, sum and max objectives, on 2^20 resident seeded orders;
   (3) cc_rd_cost_batch on 2^16 of the same orders.
-`value` is 2-opt move evaluations per second over segment (1) of the timed steps; the batch
+`value` is 2-opt move evaluations per second over segment (1) (both calls) of the timed steps; the batch
 throughput (orders per second, segments (2)) is reported beside it as `perm_evals_per_s`.  Segment
 times come from HIP events recorded on the launch stream inside the timed region.
 
@@ -80,18 +82,21 @@ def main():
     def step(ev=None):
         if ev:
             ev[0].record()
-        cc.cc_2opt_search_ex(c, cc.CC_RING_SUM, restarts, seed, buffers=bufs)
+        cc.cc_2opt_search_ex(c, cc.CC_RING_SUM, restarts, seed, buffers=bufs, pick_best=False)
         if ev:
             ev[1].record()
-        cc.cc_ring_cost_batch(c, orders, cc.CC_RING_SUM, out=out_sum)
+        cc.cc_best_of_restarts(bufs)
         if ev:
             ev[2].record()
-        cc.cc_ring_cost_batch(c, orders, cc.CC_RING_MAX, out=out_max)
+        cc.cc_ring_cost_batch(c, orders, cc.CC_RING_SUM, out=out_sum)
         if ev:
             ev[3].record()
-        cc.cc_rd_cost_batch(c, orders[:rd_batch], out=out_rd)
+        cc.cc_ring_cost_batch(c, orders, cc.CC_RING_MAX, out=out_max)
         if ev:
             ev[4].record()
+        cc.cc_rd_cost_batch(c, orders[:rd_batch], out=out_rd)
+        if ev:
+            ev[5].record()
 
     if args.pmc_calibration:
         cal_src = torch.zeros(64 << 20, dtype=torch.int32, device="cuda")
@@ -102,7 +107,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
@@ -110,14 +115,16 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
-    seg = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(4)] for e in events])   # ms
-    t_search, t_sum, t_max, t_rd = seg.mean(axis=0)
+    seg = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(5)] for e in events])   # ms
+    t_kernel, t_best, t_sum, t_max, t_rd = seg.mean(axis=0)
+    t_search = t_kernel + t_best
     moves = bufs.restart_moves.cpu().numpy().astype(np.int64)
     nbhd = n * (n - 3) // 2
     move_evals = int(((moves + 1) * nbhd).sum())
     move_rate = move_evals / (t_search * 1e-3)
     perm_rate = 2 * batch / ((t_sum + t_max) * 1e-3)
-    lds_gbs = move_rate * LDS_BYTES_PER_MOVE / 1e9
+    kernel_move_rate = move_evals / (t_kernel * 1e-3)      # the search kernel alone (roofline)
+    lds_gbs = kernel_move_rate * LDS_BYTES_PER_MOVE / 1e9
     hbm_gbs = perm_rate * (4 * n + 8) / 1e9
 
     result = {
@@ -139,15 +146,18 @@ def main():
         "move_evals_per_step": move_evals,
         "applied_moves_per_step": int(moves.sum()),
         "best_cost": int(bufs.best_cost.item()),
-        "segments_ms": {"search_2opt": t_search, "ring_sum_batch": t_sum, "ring_max_batch": t_max, "rd_batch": t_rd},
+        "segments_ms": {"search_2opt_kernel": t_kernel, "best_of_restarts": t_best, "ring_sum_batch": t_sum,
+                        "ring_max_batch": t_max, "rd_batch": t_rd},
         "perm_evals_per_s": perm_rate,
         "rd_perm_evals_per_s": rd_batch / (t_rd * 1e-3),
-        "roofline": {"kernel": "2-opt search (neighbourhood sweep)", "bound": "lds", "achieved": lds_gbs,
+        "roofline": {"kernel": "twoopt_sum_n64_kernel (2-opt search: neighbourhood sweep, argmin, apply)",
+                     "kernel_ms": t_kernel, "bound": "lds", "achieved": lds_gbs,
                      "peak": LDS_PEAK_GBS, "unit": "GB/s", "frac": lds_gbs / LDS_PEAK_GBS,
                      "traffic": TRAFFIC_SEARCH_KERNEL_BYTES, "bytes_per_move": LDS_BYTES_PER_MOVE,
                      "frac_of_measured_b32_peak": lds_gbs / LDS_MEASURED_B32_GBS,
-                     "valu": {"achieved": move_rate * VALU_OPS_PER_MOVE / 1e9, "peak": VALU_PEAK_GOPS,
-                              "unit": "G lane-ops/s", "frac": move_rate * VALU_OPS_PER_MOVE / 1e9 / VALU_PEAK_GOPS,
+                     "valu": {"achieved": kernel_move_rate * VALU_OPS_PER_MOVE / 1e9, "peak": VALU_PEAK_GOPS,
+                              "unit": "G lane-ops/s",
+                              "frac": kernel_move_rate * VALU_OPS_PER_MOVE / 1e9 / VALU_PEAK_GOPS,
                               "ops_per_move": VALU_OPS_PER_MOVE}},
         "roofline_batch": {"kernel": "ring cost batch", "bound": "hbm", "achieved": hbm_gbs, "peak": HBM_PEAK_GBS,
                            "unit": "GB/s", "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": TRAFFIC_RING_BATCH_BYTES,

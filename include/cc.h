@@ -142,12 +142,22 @@ int cc_2opt_search(const int32_t* cost_matrix, int32_t N, int32_t objective, int
  *   restart_moves  int32 [restarts] or NULL: number of moves each restart applied.
  *   workspace      device memory, 256-byte aligned, at least cc_2opt_workspace_bytes(N, objective,
  *                  restarts) bytes; contents on entry are irrelevant and on exit unspecified.
- * best_perm and best_cost are required.
+ * best_perm and best_cost are required, except that both may be NULL together: the call then stops after the
+ * per-restart results (restart_costs and restart_tours are then required, best_restart must be NULL) and
+ * cc_best_of_restarts can pick the winner later.
  */
 int cc_2opt_search_ex(const int32_t* cost_matrix, int32_t N, int32_t objective, int32_t restarts,
                       uint64_t seed, const int32_t* init_tours, int32_t* best_perm, int64_t* best_cost,
                       int32_t* best_restart, int64_t* restart_costs, int32_t* restart_tours,
                       int32_t* restart_moves, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The last step of every search call on its own: the lexicographically smallest (restart_costs[r], r) over
+ * r in [0, restarts); best_perm (int32 [N]) receives restart_tours[r], best_cost (int64 [1]) the cost,
+ * best_restart (int32 [1] or NULL) r.  restart_costs int64 [restarts], restart_tours int32 [restarts, N].
+ */
+int cc_best_of_restarts(const int64_t* restart_costs, const int32_t* restart_tours, int32_t N, int32_t restarts,
+                        int32_t* best_perm, int64_t* best_cost, int32_t* best_restart, void* stream);
 
 /* Bytes of workspace cc_2opt_search_ex needs (0 on invalid arguments). Host-only computation. */
 size_t cc_2opt_workspace_bytes(int32_t N, int32_t objective, int32_t restarts);

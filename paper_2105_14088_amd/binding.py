@@ -21,7 +21,7 @@ CC_COST_MAX = (1 << 21) - 1
 
 # every symbol include/cc.h declares
 EXPORTS = ["cc_ring_cost_batch", "cc_rd_cost_batch", "cc_bcube_cost_batch", "cc_bcube_cost_batch_weighted", "cc_dbt_cost_batch", "cc_2opt_search", "cc_2opt_search_ex",
-           "cc_2opt_workspace_bytes", "cc_rd_swap_search", "cc_rd_swap_search_ex", "cc_rd_swap_workspace_bytes", "cc_sa_search", "cc_sa_search_ex", "cc_sa_workspace_bytes", "cc_init_tours", "cc_cost_matrix_from_probes", "cc_validate_matrix", "cc_status_string",
+           "cc_2opt_workspace_bytes", "cc_best_of_restarts", "cc_rd_swap_search", "cc_rd_swap_search_ex", "cc_rd_swap_workspace_bytes", "cc_sa_search", "cc_sa_search_ex", "cc_sa_workspace_bytes", "cc_init_tours", "cc_cost_matrix_from_probes", "cc_validate_matrix", "cc_status_string",
            "cc_last_hip_error", "cc_version"]
 
 
@@ -60,6 +60,8 @@ def lib() -> ctypes.CDLL:
         L.cc_2opt_search.argtypes = [p, i32, i32, i32, u64, p, p, p]
         L.cc_2opt_search_ex.restype = ctypes.c_int
         L.cc_2opt_search_ex.argtypes = [p, i32, i32, i32, u64, p, p, p, p, p, p, p, p, sz, p]
+        L.cc_best_of_restarts.restype = ctypes.c_int
+        L.cc_best_of_restarts.argtypes = [p, p, i32, i32, p, p, p, p]
         L.cc_2opt_workspace_bytes.restype = sz
         L.cc_2opt_workspace_bytes.argtypes = [i32, i32, i32]
         L.cc_rd_swap_search.restype = ctypes.c_int
@@ -228,7 +230,8 @@ class SearchBuffers:
 
 def cc_2opt_search_ex(cost_matrix: torch.Tensor, objective: int, restarts: int, seed: int,
                       init_tours: Optional[torch.Tensor] = None, buffers: Optional[SearchBuffers] = None,
-                      stream=None) -> SearchBuffers:
+                      stream=None, pick_best: bool = True) -> SearchBuffers:
+    """pick_best=False stops after the per-restart results (cc_best_of_restarts picks the winner later)."""
     n = _matrix(cost_matrix)
     if buffers is None:
         buffers = SearchBuffers(n, objective, restarts, cost_matrix.device)
@@ -239,13 +242,25 @@ def cc_2opt_search_ex(cost_matrix: torch.Tensor, objective: int, restarts: int, 
     b = buffers
     _check(lib().cc_2opt_search_ex(_dev(cost_matrix, torch.int32, "cost_matrix"), n, objective, restarts,
                                    seed & (2**64 - 1), _dev(init_tours, torch.int32, "init_tours"),
-                                   _dev(b.best_perm, torch.int32, "best_perm"),
-                                   _dev(b.best_cost, torch.int64, "best_cost"),
-                                   _dev(b.best_restart, torch.int32, "best_restart"),
+                                   _dev(b.best_perm, torch.int32, "best_perm") if pick_best else None,
+                                   _dev(b.best_cost, torch.int64, "best_cost") if pick_best else None,
+                                   _dev(b.best_restart, torch.int32, "best_restart") if pick_best else None,
                                    _dev(b.restart_costs, torch.int64, "restart_costs"),
                                    _dev(b.restart_tours, torch.int32, "restart_tours"),
                                    _dev(b.restart_moves, torch.int32, "restart_moves"),
                                    ctypes.c_void_p(b.ws_ptr), b.ws_bytes, _stream(stream)), "cc_2opt_search_ex")
+    return b
+
+
+def cc_best_of_restarts(buffers: SearchBuffers, stream=None) -> SearchBuffers:
+    """Fills best_perm / best_cost / best_restart of `buffers` from its per-restart costs and orders."""
+    b = buffers
+    _check(lib().cc_best_of_restarts(_dev(b.restart_costs, torch.int64, "restart_costs"),
+                                     _dev(b.restart_tours, torch.int32, "restart_tours"), b.n, b.restarts,
+                                     _dev(b.best_perm, torch.int32, "best_perm"),
+                                     _dev(b.best_cost, torch.int64, "best_cost"),
+                                     _dev(b.best_restart, torch.int32, "best_restart"), _stream(stream)),
+           "cc_best_of_restarts")
     return b
 
 

@@ -299,6 +299,7 @@ hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, uin
         }
     }
     if (e != hipSuccess) return e;
+    if (!best_perm) return hipSuccess;       // per-restart results only
     hipLaunchKernelGGL(best_restart_kernel, dim3(1), dim3(256), 0, s, costs, tours, N, restarts, best_perm, best_cost,
                        best_restart);
     return hipGetLastError();

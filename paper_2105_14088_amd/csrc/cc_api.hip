@@ -120,7 +120,10 @@ int cc_2opt_search_ex(const int32_t* cost_matrix, int32_t N, int32_t objective, 
                       int64_t* restart_costs, int32_t* restart_tours, int32_t* restart_moves, void* workspace,
                       size_t workspace_bytes, void* stream) {
     if (int rc = check_matrix_args(cost_matrix, N)) return rc;
-    if (objective < 0 || objective > 3 || restarts < 1 || !best_perm || !best_cost) return CC_ERR_INVALID_ARG;
+    if (objective < 0 || objective > 3 || restarts < 1) return CC_ERR_INVALID_ARG;
+    // either both best_* outputs, or neither and then the per-restart costs and orders
+    if ((best_perm == nullptr) != (best_cost == nullptr)) return CC_ERR_INVALID_ARG;
+    if (!best_perm && (best_restart || !restart_costs || !restart_tours)) return CC_ERR_INVALID_ARG;
     const WsLayout w = ws_layout(N, restarts);
     if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255u)) return CC_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
@@ -134,6 +137,15 @@ int cc_2opt_search_ex(const int32_t* cost_matrix, int32_t N, int32_t objective, 
                               hipMemcpyDeviceToDevice, s));
     CC_HIP(cc::launch_2opt(cost_matrix, N, objective, restarts, seed, init_tours != nullptr, tours, costs, moves, flags,
                            (uint16_t*)(base + w.mat16), best_perm, best_cost, best_restart, s));
+    return CC_OK;
+}
+
+int cc_best_of_restarts(const int64_t* restart_costs, const int32_t* restart_tours, int32_t N, int32_t restarts,
+                        int32_t* best_perm, int64_t* best_cost, int32_t* best_restart, void* stream) {
+    if (N < 2 || N > CC_MAX_N) return CC_ERR_UNSUPPORTED_N;
+    if (!restart_costs || !restart_tours || restarts < 1 || !best_perm || !best_cost) return CC_ERR_INVALID_ARG;
+    CC_HIP(cc::launch_best_restart(restart_costs, restart_tours, N, restarts, best_perm, best_cost, best_restart,
+                                   (hipStream_t)stream));
     return CC_OK;
 }
 

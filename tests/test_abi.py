@@ -100,6 +100,13 @@ def test_argument_errors_are_returned_before_any_launch():
     assert L.cc_2opt_search_ex(*args, null, 0, null) == WORKSPACE
     assert L.cc_2opt_search_ex(*args, fake, 16, null) == WORKSPACE               # too small
     assert L.cc_2opt_search_ex(*args, ctypes.c_void_p(0x1004), 1 << 30, null) == WORKSPACE   # misaligned
+    ws = ctypes.c_void_p(0x1000)
+    assert L.cc_2opt_search_ex(fake, 64, 0, 4, 1, null, fake, null, null, fake, fake, null, ws, 1 << 30, null) == INVALID
+    assert L.cc_2opt_search_ex(fake, 64, 0, 4, 1, null, null, null, null, null, fake, null, ws, 1 << 30, null) == INVALID
+    assert L.cc_2opt_search_ex(fake, 64, 0, 4, 1, null, null, null, fake, fake, fake, null, ws, 1 << 30, null) == INVALID
+    assert L.cc_best_of_restarts(null, fake, 64, 4, fake, fake, null, null) == INVALID
+    assert L.cc_best_of_restarts(fake, fake, 64, 0, fake, fake, null, null) == INVALID
+    assert L.cc_best_of_restarts(fake, fake, 1, 4, fake, fake, null, null) == UNSUPPORTED
     assert L.cc_rd_swap_search(null, 64, 1, 1, fake, fake, null) == INVALID
     assert L.cc_rd_swap_search(fake, 48, 1, 1, fake, fake, null) == UNSUPPORTED      # not a power of two
     assert L.cc_rd_swap_search(fake, 64, 0, 1, fake, fake, null) == INVALID

@@ -119,6 +119,27 @@ def test_simple_entry_point_matches_extended():
     assert int(cost.item()) == want["best_cost"] and np.array_equal(perm.cpu().numpy(), want["best_perm"])
 
 
+@pytest.mark.parametrize("n,obj", [(64, 0), (64, 3), (24, 1), (128, 0)])
+def test_search_without_winner_then_best_of_restarts(n, obj):
+    """The two-call form the benchmark times: per-restart results first, the winner picked by cc_best_of_restarts."""
+    say(f"2-opt in two calls N={n} objective={obj}")
+    c = random_matrix(n, 321 + n, symmetric=not (obj & 2), lo=1, hi=4000)
+    restarts = 37
+    want = oracle.search(c, obj, restarts, seed=11)
+    bufs = cc.SearchBuffers(n, obj, restarts, "cuda")
+    bufs.best_cost.fill_(-1)
+    bufs.best_restart.fill_(-1)
+    cc.cc_2opt_search_ex(dev(c), obj, restarts, 11, buffers=bufs, pick_best=False)
+    torch.cuda.synchronize()
+    assert int(bufs.best_cost.item()) == -1 and int(bufs.best_restart.item()) == -1     # untouched
+    assert np.array_equal(bufs.restart_costs.cpu().numpy(), want["costs"])
+    assert np.array_equal(bufs.restart_tours.cpu().numpy(), want["tours"])
+    cc.cc_best_of_restarts(bufs)
+    torch.cuda.synchronize()
+    assert int(bufs.best_cost.item()) == want["best_cost"] and int(bufs.best_restart.item()) == want["best_restart"]
+    assert np.array_equal(bufs.best_perm.cpu().numpy(), want["best_perm"])
+
+
 def test_workload2_n64_sum_1024_restarts_full():
     say("C2: N=64 sum, 1024 restarts (all restarts compared)")
     c = make_matrix(2)

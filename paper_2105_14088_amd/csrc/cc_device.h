@@ -27,16 +27,30 @@ __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? l
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
-// Butterfly reductions over the 64 lanes of a wave; every lane ends with the result.
+// Reductions over the 64 lanes of a wave; every lane ends with the result.  The 32-bit forms use six DPP steps
+// (pairs, quads, half rows, rows: every lane of a row then holds the row's result; then the rows are chained through
+// their last lanes, so lane 63 ends with the total, which is broadcast).  Each step reads the register the previous
+// one wrote, which needs two wait states before a DPP read.  All 64 lanes must be active.
+#define CC_WAVE_REDUCE_DPP(op)                                                      \
+    asm volatile("s_nop 1\n\t" op " %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t" \
+                 "s_nop 1\n\t" op " %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t" \
+                 "s_nop 1\n\t" op " %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"     \
+                 "s_nop 1\n\t" op " %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"          \
+                 "s_nop 1\n\t" op " %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"        \
+                 "s_nop 1\n\t" op " %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"        \
+                 "s_nop 1"                                                          \
+                 : "+v"(v))
 __device__ __forceinline__ int wave_sum(int v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
-    return v;
+    CC_WAVE_REDUCE_DPP("v_add_u32_dpp");
+    return __builtin_amdgcn_readlane(v, 63);
 }
 __device__ __forceinline__ int wave_max(int v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v = max(v, __shfl_xor(v, m, kWave));
-    return v;
+    CC_WAVE_REDUCE_DPP("v_max_i32_dpp");
+    return __builtin_amdgcn_readlane(v, 63);
+}
+__device__ __forceinline__ int wave_min(int v) {
+    CC_WAVE_REDUCE_DPP("v_min_i32_dpp");
+    return __builtin_amdgcn_readlane(v, 63);
 }
 __device__ __forceinline__ long long wave_sum64(long long v) {
 #pragma unroll

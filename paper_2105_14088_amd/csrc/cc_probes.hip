@@ -18,28 +18,6 @@ namespace {
 
 constexpr int kCostMax = (1 << 21) - 1;
 
-// Sum over the wave, wave-uniform result.  Same six DPP steps as a butterfly: pairs, quads, half rows, rows (every
-// lane of a row then holds the row's sum), then the rows are chained through their last lanes; lane 63 ends
-// with the total.  Each step reads the register the previous one wrote: two wait states before a DPP read.
-__device__ __forceinline__ int wave_sum_uniform(int v) {
-    asm volatile(
-        "s_nop 1\n\t"
-        "v_add_u32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
-        "s_nop 1\n\t"
-        "v_add_u32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
-        "s_nop 1\n\t"
-        "v_add_u32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
-        "s_nop 1\n\t"
-        "v_add_u32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
-        "s_nop 1\n\t"
-        "v_add_u32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
-        "s_nop 1\n\t"
-        "v_add_u32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
-        "s_nop 1"
-        : "+v"(v));
-    return __builtin_amdgcn_readlane(v, 63);
-}
-
 // acc += (v.x < cand) + (v.y < cand) + (v.z < cand) + (v.w < cand) per lane: each term is a compare into the carry
 // flag and an add-with-carry.
 __device__ __forceinline__ void count_below(int& acc, const int4& v, int cand) {
@@ -108,7 +86,7 @@ __global__ __launch_bounds__(128) void probes_percentile_kernel(const int32_t* _
         for (int u = 0; u < CH; ++u) {
             count_below(below, v[u], cand);
         }
-        if (wave_sum_uniform(below) < rank) prefix = cand;   // the sample of rank `rank` is at least cand
+        if (wave_sum(below) < rank) prefix = cand;   // the sample of rank `rank` is at least cand
     }
     if (lane == 0) direction_result[dir] = prefix;
     __syncthreads();

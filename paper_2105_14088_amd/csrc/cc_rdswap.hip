@@ -141,11 +141,7 @@ __global__ void rdswap_general_kernel(const int32_t* __restrict__ c, int N, int3
 // ----------------------------------------------------------------------------------------- N = 64
 using namespace w64;
 
-__device__ __forceinline__ int wave_max_all(int v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v = max(v, __shfl_xor(v, m, kWave));
-    return v;
-}
+__device__ __forceinline__ int wave_max_all(int v) { return wave_max(v); }
 
 __global__ __launch_bounds__(256) void rdswap_n64_kernel(const int32_t* __restrict__ c, int restarts, uint64_t seed,
                                                          int generate, int32_t* __restrict__ tours,

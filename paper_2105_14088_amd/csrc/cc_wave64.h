@@ -36,27 +36,8 @@ __device__ __forceinline__ long long from_next_lane(long long v) {
     return (long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo);
 }
 
-// Minimum over the wave, returned as a wave-uniform value.  Six DPP steps: pairs, quads, half rows,
-// rows, then the last lane of each row is folded into the next row(s); lane 63 ends with the total.
-// Each step reads the register the previous step wrote, which needs two wait states before a DPP read.
-__device__ __forceinline__ int wave_min_uniform(int v) {
-    asm volatile(
-        "s_nop 1\n\t"
-        "v_min_i32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
-        "s_nop 1\n\t"
-        "v_min_i32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
-        "s_nop 1\n\t"
-        "v_min_i32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
-        "s_nop 1\n\t"
-        "v_min_i32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
-        "s_nop 1\n\t"
-        "v_min_i32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
-        "s_nop 1\n\t"
-        "v_min_i32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
-        "s_nop 1"
-        : "+v"(v));
-    return __builtin_amdgcn_readlane(v, 63);
-}
+// Minimum over the wave, returned as a wave-uniform value.
+__device__ __forceinline__ int wave_min_uniform(int v) { return wave_min(v); }
 __device__ __forceinline__ long long wave_min_uniform(long long v) {
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) {

@@ -154,6 +154,10 @@ def main():
         out = torch.empty(batch, dtype=torch.int64, device="cuda")
         if kind == "ring":
             fn = lambda: cc.cc_ring_cost_batch(c, orders, objective, out=out)  # noqa: E731
+        elif kind == "bcube":
+            fn = lambda: cc.cc_bcube_cost_batch(c, 4, orders, out=out)  # noqa: E731
+        elif kind == "dbt":
+            fn = lambda: cc.cc_dbt_cost_batch(c, orders, out=out)  # noqa: E731
         else:
             fn = lambda: cc.cc_rd_cost_batch(c, orders, out=out)  # noqa: E731
         ms = timed(fn, args.reps)
@@ -164,7 +168,10 @@ def main():
             sample = min(batch, 1 << 14 if w.n <= 64 else 256)
             sub = orders[:sample].cpu().numpy()
             t0 = time.perf_counter()
-            want = oracle.ring_cost_batch(c_host, sub, objective) if kind == "ring" else oracle.rd_cost_batch(c_host, sub)
+            want = {"ring": lambda: oracle.ring_cost_batch(c_host, sub, objective),
+                    "rd": lambda: oracle.rd_cost_batch(c_host, sub),
+                    "bcube": lambda: oracle.bcube_cost_batch(c_host, 4, sub),
+                    "dbt": lambda: oracle.dbt_cost_batch(c_host, sub)}[kind]()
             dt = time.perf_counter() - t0
             d.update({"oracle_1core_perm_evals_per_s": sample / dt,
                       "bit_exact_on_sample": bool(np.array_equal(want, out[:sample].cpu().numpy()))})
@@ -185,6 +192,11 @@ def main():
         ("A1024", lambda: sa_case("A1024_n1024_sa_1024x200000", 5, 1024, 200000, 300, 0)),
         ("P64", lambda: probes_case("P64_n64_probes_10000", 64, 10000)),
         ("P256", lambda: probes_case("P256_n256_probes_2000", 256, 2000)),
+        ("B64", lambda: batch_case("B64_n64_bcube4_2^20", 2, "bcube", 0, 1 << 20)),
+        ("B1024", lambda: batch_case("B1024_n1024_bcube4_65536", 5, "bcube", 0, 65536)),
+        ("T64", lambda: batch_case("T64_n64_dbt_2^20", 2, "dbt", 0, 1 << 20)),
+        ("T1024", lambda: batch_case("T1024_n1024_dbt_65536", 5, "dbt", 0, 65536)),
+        ("R64", lambda: batch_case("R64_n64_rd_2^20", 2, "rd", 0, 1 << 20)),
         ("M64sum", lambda: batch_case("M64_ring_sum_2^20", 2, "ring", 0, 1 << 20)),
         ("M64max", lambda: batch_case("M64_ring_max_2^20", 3, "ring", 1, 1 << 20)),
     ]

@@ -31,81 +31,86 @@ def build(force: bool = False) -> str:
 _lib = None
 
 
+def _declare(path: str) -> ctypes.CDLL:
+    """Loads an oracle library and declares its prototypes (also used by the mutation tests on altered builds)."""
+    lib = ctypes.CDLL(path)
+    i32, i64, u64, u32 = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64, ctypes.c_uint32
+    p = ctypes.c_void_p
+    lib.cco_splitmix64_at.restype = u64
+    lib.cco_splitmix64_at.argtypes = [u64, u64]
+    lib.cco_init_tour.restype = None
+    lib.cco_init_tour.argtypes = [u64, u32, i32, p]
+    lib.cco_init_tours.restype = None
+    lib.cco_init_tours.argtypes = [u64, i32, i64, i64, p]
+    lib.cco_ring_cost.restype = i64
+    lib.cco_ring_cost.argtypes = [p, i32, p, i32]
+    lib.cco_rd_cost.restype = i64
+    lib.cco_rd_cost.argtypes = [p, i32, p]
+    lib.cco_ring_cost_batch.restype = ctypes.c_int
+    lib.cco_ring_cost_batch.argtypes = [p, i32, i32, p, i64, p]
+    lib.cco_rd_cost_batch.restype = ctypes.c_int
+    lib.cco_rd_cost_batch.argtypes = [p, i32, p, i64, p]
+    lib.cco_apply_move.restype = None
+    lib.cco_apply_move.argtypes = [p, i32, i32, i32, i32]
+    lib.cco_move_id.restype = i64
+    lib.cco_move_id.argtypes = [i32, i32, i32, i32, i32]
+    lib.cco_move_value_by_definition.restype = i64
+    lib.cco_move_value_by_definition.argtypes = [p, i32, i32, p, i32, i32, i32]
+    lib.cco_neighbourhood_size.restype = i64
+    lib.cco_neighbourhood_size.argtypes = [i32, i32]
+    lib.cco_all_move_values.restype = ctypes.c_int
+    lib.cco_all_move_values.argtypes = [p, i32, i32, p, p]
+    lib.cco_2opt_descend.restype = ctypes.c_int
+    lib.cco_2opt_descend.argtypes = [p, i32, i32, p, p, p, i32, p, i32]
+    lib.cco_2opt_restarts.restype = ctypes.c_int
+    lib.cco_2opt_restarts.argtypes = [p, i32, i32, u64, i64, i64, p, p, p, p]
+    lib.cco_2opt_search.restype = ctypes.c_int
+    lib.cco_2opt_search.argtypes = [p, i32, i32, i32, u64, p, p, p, p, p, p, p]
+    lib.cco_exhaustive_rings.restype = ctypes.c_int
+    lib.cco_exhaustive_rings.argtypes = [p, i32, i32, i32, p, p, p, p, p, i64]
+    lib.cco_apply_swap.restype = None
+    lib.cco_apply_swap.argtypes = [p, i32, i32]
+    lib.cco_rd_swap_value_by_definition.restype = i64
+    lib.cco_rd_swap_value_by_definition.argtypes = [p, i32, p, i32, i32]
+    lib.cco_rd_swap_neighbourhood_size.restype = i64
+    lib.cco_rd_swap_neighbourhood_size.argtypes = [i32]
+    lib.cco_rd_swap_all_values.restype = ctypes.c_int
+    lib.cco_rd_swap_all_values.argtypes = [p, i32, p, p]
+    lib.cco_rd_swap_descend.restype = ctypes.c_int
+    lib.cco_rd_swap_descend.argtypes = [p, i32, p, p, p, i32, p, i32]
+    lib.cco_rd_swap_restarts.restype = ctypes.c_int
+    lib.cco_rd_swap_restarts.argtypes = [p, i32, u64, i64, i64, p, p, p, p]
+    lib.cco_bcube_cost.restype = i64
+    lib.cco_bcube_cost.argtypes = [p, i32, i32, p]
+    lib.cco_bcube_cost_batch.restype = ctypes.c_int
+    lib.cco_bcube_cost_batch.argtypes = [p, i32, i32, p, i64, p]
+    lib.cco_sa_proposal.restype = None
+    lib.cco_sa_proposal.argtypes = [u64, ctypes.c_uint32, ctypes.c_uint32, i32, p, p, p]
+    lib.cco_sa_log2_fix.restype = i32
+    lib.cco_sa_log2_fix.argtypes = [i32]
+    lib.cco_sa_accepts.restype = ctypes.c_int
+    lib.cco_sa_accepts.argtypes = [i64, i64, i64, i32]
+    lib.cco_sa_chain.restype = ctypes.c_int
+    lib.cco_sa_chain.argtypes = [p, i32, p, i64, i32, i32, u64, ctypes.c_uint32, i32, p, p, p, p, p]
+    lib.cco_sa_chains.restype = ctypes.c_int
+    lib.cco_sa_chains.argtypes = [p, i32, i64, i32, i32, u64, i64, i64, p, p, p, p]
+    lib.cco_dbt_tree_cost.restype = i64
+    lib.cco_dbt_tree_cost.argtypes = [p, i32, p, i32]
+    lib.cco_dbt_cost.restype = i64
+    lib.cco_dbt_cost.argtypes = [p, i32, p]
+    lib.cco_dbt_cost_batch.restype = ctypes.c_int
+    lib.cco_dbt_cost_batch.argtypes = [p, i32, p, i64, p]
+    lib.cco_bcube_cost_weighted_batch.restype = ctypes.c_int
+    lib.cco_bcube_cost_weighted_batch.argtypes = [p, i32, i32, p, p, i64, p]
+    lib.cco_cost_matrix_from_probes.restype = ctypes.c_int
+    lib.cco_cost_matrix_from_probes.argtypes = [p, i32, i32, i32, i32, p]
+    return lib
+
+
 def _L():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
-        i32, i64, u64, u32 = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64, ctypes.c_uint32
-        p = ctypes.c_void_p
-        lib.cco_splitmix64_at.restype = u64
-        lib.cco_splitmix64_at.argtypes = [u64, u64]
-        lib.cco_init_tour.restype = None
-        lib.cco_init_tour.argtypes = [u64, u32, i32, p]
-        lib.cco_init_tours.restype = None
-        lib.cco_init_tours.argtypes = [u64, i32, i64, i64, p]
-        lib.cco_ring_cost.restype = i64
-        lib.cco_ring_cost.argtypes = [p, i32, p, i32]
-        lib.cco_rd_cost.restype = i64
-        lib.cco_rd_cost.argtypes = [p, i32, p]
-        lib.cco_ring_cost_batch.restype = ctypes.c_int
-        lib.cco_ring_cost_batch.argtypes = [p, i32, i32, p, i64, p]
-        lib.cco_rd_cost_batch.restype = ctypes.c_int
-        lib.cco_rd_cost_batch.argtypes = [p, i32, p, i64, p]
-        lib.cco_apply_move.restype = None
-        lib.cco_apply_move.argtypes = [p, i32, i32, i32, i32]
-        lib.cco_move_id.restype = i64
-        lib.cco_move_id.argtypes = [i32, i32, i32, i32, i32]
-        lib.cco_move_value_by_definition.restype = i64
-        lib.cco_move_value_by_definition.argtypes = [p, i32, i32, p, i32, i32, i32]
-        lib.cco_neighbourhood_size.restype = i64
-        lib.cco_neighbourhood_size.argtypes = [i32, i32]
-        lib.cco_all_move_values.restype = ctypes.c_int
-        lib.cco_all_move_values.argtypes = [p, i32, i32, p, p]
-        lib.cco_2opt_descend.restype = ctypes.c_int
-        lib.cco_2opt_descend.argtypes = [p, i32, i32, p, p, p, i32, p, i32]
-        lib.cco_2opt_restarts.restype = ctypes.c_int
-        lib.cco_2opt_restarts.argtypes = [p, i32, i32, u64, i64, i64, p, p, p, p]
-        lib.cco_2opt_search.restype = ctypes.c_int
-        lib.cco_2opt_search.argtypes = [p, i32, i32, i32, u64, p, p, p, p, p, p, p]
-        lib.cco_exhaustive_rings.restype = ctypes.c_int
-        lib.cco_exhaustive_rings.argtypes = [p, i32, i32, i32, p, p, p, p, p, i64]
-        lib.cco_apply_swap.restype = None
-        lib.cco_apply_swap.argtypes = [p, i32, i32]
-        lib.cco_rd_swap_value_by_definition.restype = i64
-        lib.cco_rd_swap_value_by_definition.argtypes = [p, i32, p, i32, i32]
-        lib.cco_rd_swap_neighbourhood_size.restype = i64
-        lib.cco_rd_swap_neighbourhood_size.argtypes = [i32]
-        lib.cco_rd_swap_all_values.restype = ctypes.c_int
-        lib.cco_rd_swap_all_values.argtypes = [p, i32, p, p]
-        lib.cco_rd_swap_descend.restype = ctypes.c_int
-        lib.cco_rd_swap_descend.argtypes = [p, i32, p, p, p, i32, p, i32]
-        lib.cco_rd_swap_restarts.restype = ctypes.c_int
-        lib.cco_rd_swap_restarts.argtypes = [p, i32, u64, i64, i64, p, p, p, p]
-        lib.cco_bcube_cost.restype = i64
-        lib.cco_bcube_cost.argtypes = [p, i32, i32, p]
-        lib.cco_bcube_cost_batch.restype = ctypes.c_int
-        lib.cco_bcube_cost_batch.argtypes = [p, i32, i32, p, i64, p]
-        lib.cco_sa_proposal.restype = None
-        lib.cco_sa_proposal.argtypes = [u64, ctypes.c_uint32, ctypes.c_uint32, i32, p, p, p]
-        lib.cco_sa_log2_fix.restype = i32
-        lib.cco_sa_log2_fix.argtypes = [i32]
-        lib.cco_sa_accepts.restype = ctypes.c_int
-        lib.cco_sa_accepts.argtypes = [i64, i64, i64, i32]
-        lib.cco_sa_chain.restype = ctypes.c_int
-        lib.cco_sa_chain.argtypes = [p, i32, p, i64, i32, i32, u64, ctypes.c_uint32, i32, p, p, p, p, p]
-        lib.cco_sa_chains.restype = ctypes.c_int
-        lib.cco_sa_chains.argtypes = [p, i32, i64, i32, i32, u64, i64, i64, p, p, p, p]
-        lib.cco_dbt_tree_cost.restype = i64
-        lib.cco_dbt_tree_cost.argtypes = [p, i32, p, i32]
-        lib.cco_dbt_cost.restype = i64
-        lib.cco_dbt_cost.argtypes = [p, i32, p]
-        lib.cco_dbt_cost_batch.restype = ctypes.c_int
-        lib.cco_dbt_cost_batch.argtypes = [p, i32, p, i64, p]
-        lib.cco_bcube_cost_weighted_batch.restype = ctypes.c_int
-        lib.cco_bcube_cost_weighted_batch.argtypes = [p, i32, i32, p, p, i64, p]
-        lib.cco_cost_matrix_from_probes.restype = ctypes.c_int
-        lib.cco_cost_matrix_from_probes.argtypes = [p, i32, i32, i32, i32, p]
-        _lib = lib
+        _lib = _declare(build())
     return _lib
 
 

@@ -152,8 +152,13 @@ def main():
         c = torch.from_numpy(c_host).cuda()
         orders = cc.cc_init_tours(w.n, batch, w.search_seed)
         out = torch.empty(batch, dtype=torch.int64, device="cuda")
+        bytes_per_order = 4 * w.n + 8
         if kind == "ring":
             fn = lambda: cc.cc_ring_cost_batch(c, orders, objective, out=out)  # noqa: E731
+        elif kind == "ring_u8":
+            orders8 = orders.to(torch.uint8)
+            bytes_per_order = w.n + 8
+            fn = lambda: cc.cc_ring_cost_batch_u8(c, orders8, objective, out=out)  # noqa: E731
         elif kind == "bcube":
             fn = lambda: cc.cc_bcube_cost_batch(c, 4, orders, out=out)  # noqa: E731
         elif kind == "dbt":
@@ -161,14 +166,15 @@ def main():
         else:
             fn = lambda: cc.cc_rd_cost_batch(c, orders, out=out)  # noqa: E731
         ms = timed(fn, args.reps)
-        d = {"workload": name, "call": f"cc_{kind}_cost_batch", "N": w.n, "objective": objective, "batch": batch,
-             "ms": ms, "perm_evals_per_s": batch / (ms * 1e-3), "hbm_GBps": batch * (4 * w.n + 8) / (ms * 1e-3) / 1e9}
+        d = {"workload": name, "call": "cc_ring_cost_batch_u8" if kind == "ring_u8" else f"cc_{kind}_cost_batch", "N": w.n, "objective": objective, "batch": batch,
+             "ms": ms, "perm_evals_per_s": batch / (ms * 1e-3), "hbm_GBps": batch * bytes_per_order / (ms * 1e-3) / 1e9}
         if args.oracle:
             import oracle
             sample = min(batch, 1 << 14 if w.n <= 64 else 256)
             sub = orders[:sample].cpu().numpy()
             t0 = time.perf_counter()
             want = {"ring": lambda: oracle.ring_cost_batch(c_host, sub, objective),
+                    "ring_u8": lambda: oracle.ring_cost_batch(c_host, sub, objective),
                     "rd": lambda: oracle.rd_cost_batch(c_host, sub),
                     "bcube": lambda: oracle.bcube_cost_batch(c_host, 4, sub),
                     "dbt": lambda: oracle.dbt_cost_batch(c_host, sub)}[kind]()
@@ -199,6 +205,8 @@ def main():
         ("R64", lambda: batch_case("R64_n64_rd_2^20", 2, "rd", 0, 1 << 20)),
         ("M64sum", lambda: batch_case("M64_ring_sum_2^20", 2, "ring", 0, 1 << 20)),
         ("M64max", lambda: batch_case("M64_ring_max_2^20", 3, "ring", 1, 1 << 20)),
+        ("M64u8", lambda: batch_case("M64_ring_sum_2^20_byte_orders", 2, "ring_u8", 0, 1 << 20)),
+        ("M64u8big", lambda: batch_case("M64_ring_sum_2^24_byte_orders", 2, "ring_u8", 0, 1 << 24)),
     ]
     for key, fn in cases:
         if only is None or key in only:

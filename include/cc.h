@@ -70,6 +70,13 @@ int cc_ring_cost_batch(const int32_t* cost_matrix, int32_t N, int32_t objective,
                        int64_t B, int64_t* out_costs, void* stream);
 
 /*
+ * The same with the orders stored one byte per rank (perms: uint8 [B, N] row-major, N <= 256, else
+ * CC_ERR_UNSUPPORTED_N): the order stream is what this call reads from HBM, and this form reads a quarter of it.
+ */
+int cc_ring_cost_batch_u8(const int32_t* cost_matrix, int32_t N, int32_t objective, const uint8_t* perms, int64_t B,
+                          int64_t* out_costs, void* stream);
+
+/*
  * Halving-doubling (recursive-doubling) cost model (Section 4.1, equation C_hd, with every round
  * weighted equally as in the latency-only view of Section 4.2):
  *     out_costs[b] = sum over k in [0, log2 N) of  max over ranks i of c[perm_b[i]][perm_b[i xor 2^k]]

@@ -20,7 +20,7 @@ CC_MAX_N = 1024
 CC_COST_MAX = (1 << 21) - 1
 
 # every symbol include/cc.h declares
-EXPORTS = ["cc_ring_cost_batch", "cc_rd_cost_batch", "cc_bcube_cost_batch", "cc_bcube_cost_batch_weighted", "cc_dbt_cost_batch", "cc_2opt_search", "cc_2opt_search_ex",
+EXPORTS = ["cc_ring_cost_batch", "cc_ring_cost_batch_u8", "cc_rd_cost_batch", "cc_bcube_cost_batch", "cc_bcube_cost_batch_weighted", "cc_dbt_cost_batch", "cc_2opt_search", "cc_2opt_search_ex",
            "cc_2opt_workspace_bytes", "cc_best_of_restarts", "cc_rd_swap_search", "cc_rd_swap_search_ex", "cc_rd_swap_workspace_bytes", "cc_sa_search", "cc_sa_search_ex", "cc_sa_workspace_bytes", "cc_init_tours", "cc_cost_matrix_from_probes", "cc_validate_matrix", "cc_status_string",
            "cc_last_hip_error", "cc_version"]
 
@@ -48,6 +48,8 @@ def lib() -> ctypes.CDLL:
         i32, i64, u64, p, sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_size_t
         L.cc_ring_cost_batch.restype = ctypes.c_int
         L.cc_ring_cost_batch.argtypes = [p, i32, i32, p, i64, p, p]
+        L.cc_ring_cost_batch_u8.restype = ctypes.c_int
+        L.cc_ring_cost_batch_u8.argtypes = [p, i32, i32, p, i64, p, p]
         L.cc_rd_cost_batch.restype = ctypes.c_int
         L.cc_rd_cost_batch.argtypes = [p, i32, p, i64, p, p]
         L.cc_bcube_cost_batch.restype = ctypes.c_int
@@ -129,6 +131,20 @@ def cc_ring_cost_batch(cost_matrix: torch.Tensor, perms: torch.Tensor, objective
     _check(lib().cc_ring_cost_batch(_dev(cost_matrix, torch.int32, "cost_matrix"), n, objective,
                                     _dev(perms, torch.int32, "perms"), b, _dev(out, torch.int64, "out"),
                                     _stream(stream)), "cc_ring_cost_batch")
+    return out
+
+
+def cc_ring_cost_batch_u8(cost_matrix: torch.Tensor, perms: torch.Tensor, objective: int,
+                          out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    n = _matrix(cost_matrix)
+    if perms.dim() != 2 or perms.shape[1] != n:
+        raise ValueError("perms must be [B, N]")
+    b = int(perms.shape[0])
+    if out is None:
+        out = torch.empty(b, dtype=torch.int64, device=cost_matrix.device)
+    _check(lib().cc_ring_cost_batch_u8(_dev(cost_matrix, torch.int32, "cost_matrix"), n, objective,
+                                       _dev(perms, torch.uint8, "perms"), b, _dev(out, torch.int64, "out"),
+                                       _stream(stream)), "cc_ring_cost_batch_u8")
     return out
 
 

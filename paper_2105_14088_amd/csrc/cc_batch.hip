@@ -86,6 +86,88 @@ __global__ __launch_bounds__(256) void ring_batch_generic_kernel(const int32_t* 
     }
 }
 
+// Orders stored one byte per rank (N <= 256): a quarter of the HBM bytes per order.  N in {16, 32, 64, 128}: matrix
+// in LDS; one lane fetches 16 ranks as an int4, N/16 adjacent lanes share an order, a wave-load covers 1024/N
+// orders.  The hop into a lane's first rank needs the last rank of the lane before it (cyclically within the
+// order's lanes), fetched with one lane permute.
+template <int N, bool IS_MAX>
+__global__ __launch_bounds__(256) void ring_batch_u8_lds_kernel(const int32_t* __restrict__ c,
+                                                                const int4* __restrict__ perms16, int64_t B,
+                                                                int64_t* __restrict__ out) {
+    __shared__ int32_t m[N * N];
+    for (int e = threadIdx.x; e < N * N; e += 256) m[e] = c[e];
+    __syncthreads();
+
+    constexpr int LP = N / 16;    // lanes that share one order
+    constexpr int PPW = 64 / LP;  // orders covered by one 1 KiB wave-load
+    constexpr int U = 2;          // wave-loads in flight
+    constexpr unsigned M4 = (unsigned)(N - 1) * 0x01010101u;
+    const int lane = lane_id();
+    const int sub = lane & (LP - 1);
+    const int prev_lane = (lane & ~(LP - 1)) | ((sub + LP - 1) & (LP - 1));
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    const int64_t nloads = (B + PPW - 1) / PPW;
+
+    for (int64_t base = wave * U; base < nloads; base += nwaves * U) {
+        int4 v[U];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t ld = base + u;
+            const int64_t b = ld * PPW + lane / LP;
+            ok[u] = ld < nloads && b < B;
+            v[u] = ok[u] ? perms16[ld * 64 + lane] : make_int4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const unsigned w[4] = {(unsigned)v[u].x & M4, (unsigned)v[u].y & M4, (unsigned)v[u].z & M4,
+                                   (unsigned)v[u].w & M4};
+            int prev = (int)(w[3] >> 24);
+            prev = LP > 1 ? __shfl(prev, prev_lane, kWave) : prev;   // last rank of the previous lane (or of this order)
+            int acc = 0;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                const int node = (int)((w[k >> 2] >> (8 * (k & 3))) & 0xffu);
+                const int hop = m[node * N + prev];
+                acc = IS_MAX ? max(acc, hop) : acc + hop;
+                prev = node;
+            }
+#pragma unroll
+            for (int s = LP / 2; s >= 1; s >>= 1) {
+                const int o = __shfl_xor(acc, s, kWave);
+                acc = IS_MAX ? max(acc, o) : acc + o;
+            }
+            if (ok[u] && sub == 0) out[(base + u) * PPW + lane / LP] = (int64_t)acc;
+        }
+    }
+}
+
+template <bool IS_MAX>
+__global__ __launch_bounds__(256) void ring_batch_u8_generic_kernel(const int32_t* __restrict__ c, int N,
+                                                                    const uint8_t* __restrict__ perms, int64_t B,
+                                                                    int64_t* __restrict__ out) {
+    const int lane = lane_id();
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t b = wave; b < B; b += nwaves) {
+        const uint8_t* pi = perms + b * N;
+        long long acc = 0;
+        for (int p = lane; p < N; p += kWave) {
+            const int a = min((int)pi[p], N - 1);
+            const int q = min((int)pi[p ? p - 1 : N - 1], N - 1);
+            const long long hop = c[(int64_t)a * N + q];
+            acc = IS_MAX ? (hop > acc ? hop : acc) : acc + hop;
+        }
+#pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) {
+            const long long o = __shfl_xor(acc, s, kWave);
+            acc = IS_MAX ? (o > acc ? o : acc) : acc + o;
+        }
+        if (lane == 0) out[b] = acc;
+    }
+}
+
 static int batch_grid(int64_t work_items_per_block_pass, int64_t total) {
     int64_t blocks = (total + work_items_per_block_pass - 1) / work_items_per_block_pass;
     const int64_t cap = 256 * 8;  // 8 workgroups of 4 waves per compute unit
@@ -125,6 +207,40 @@ hipError_t launch_ring_cost_batch(const int32_t* c, int N, bool is_max, const in
         hipLaunchKernelGGL((ring_batch_generic_kernel<true>), dim3(grid), dim3(256), 0, s, c, N, perms, B, out);
     else
         hipLaunchKernelGGL((ring_batch_generic_kernel<false>), dim3(grid), dim3(256), 0, s, c, N, perms, B, out);
+    return hipGetLastError();
+}
+
+template <int N>
+static hipError_t ring_u8_lds(const int32_t* c, bool is_max, const uint8_t* perms, int64_t B, int64_t* out,
+                              hipStream_t s) {
+    constexpr int PPW = 64 / (N / 16);
+    const int grid = batch_grid((int64_t)PPW * 2 * 4, B);
+    if (is_max)
+        hipLaunchKernelGGL((ring_batch_u8_lds_kernel<N, true>), dim3(grid), dim3(256), 0, s, c, (const int4*)perms, B,
+                           out);
+    else
+        hipLaunchKernelGGL((ring_batch_u8_lds_kernel<N, false>), dim3(grid), dim3(256), 0, s, c, (const int4*)perms, B,
+                           out);
+    return hipGetLastError();
+}
+
+hipError_t launch_ring_cost_batch_u8(const int32_t* c, int N, bool is_max, const uint8_t* perms, int64_t B,
+                                     int64_t* out, hipStream_t s) {
+    if (B == 0) return hipSuccess;
+    if (((uintptr_t)perms & 15u) == 0) {
+        switch (N) {
+            case 16: return ring_u8_lds<16>(c, is_max, perms, B, out, s);
+            case 32: return ring_u8_lds<32>(c, is_max, perms, B, out, s);
+            case 64: return ring_u8_lds<64>(c, is_max, perms, B, out, s);
+            case 128: return ring_u8_lds<128>(c, is_max, perms, B, out, s);
+            default: break;
+        }
+    }
+    const int grid = batch_grid(4, B);
+    if (is_max)
+        hipLaunchKernelGGL((ring_batch_u8_generic_kernel<true>), dim3(grid), dim3(256), 0, s, c, N, perms, B, out);
+    else
+        hipLaunchKernelGGL((ring_batch_u8_generic_kernel<false>), dim3(grid), dim3(256), 0, s, c, N, perms, B, out);
     return hipGetLastError();
 }
 

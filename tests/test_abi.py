@@ -59,6 +59,9 @@ def test_argument_errors_are_returned_before_any_launch():
     assert L.cc_ring_cost_batch(fake, 64, 0, null, 1, fake, null) == INVALID
     assert L.cc_ring_cost_batch(fake, 64, 0, fake, 1, null, null) == INVALID
     assert L.cc_ring_cost_batch(fake, 64, 0, null, 0, null, null) == 0          # B = 0 is a no-op
+    assert L.cc_ring_cost_batch_u8(fake, 257, 0, fake, 1, fake, null) == UNSUPPORTED   # ranks do not fit a byte
+    assert L.cc_ring_cost_batch_u8(fake, 64, 0, null, 1, fake, null) == INVALID
+    assert L.cc_ring_cost_batch_u8(fake, 64, 0, null, 0, null, null) == 0
     assert L.cc_rd_cost_batch(fake, 48, fake, 1, fake, null) == UNSUPPORTED      # not a power of two
     assert L.cc_rd_cost_batch(fake, 64, fake, -5, fake, null) == INVALID
     assert L.cc_rd_cost_batch(fake, 64, null, 0, null, null) == 0

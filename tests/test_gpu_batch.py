@@ -40,6 +40,42 @@ def test_ring_batch_sizes_and_ragged_tails(n, obj):
         assert np.array_equal(gpu_ring(c, perms, obj), oracle.ring_cost_batch(c, perms, obj))
 
 
+@pytest.mark.parametrize("n", [2, 3, 13, 16, 32, 64, 100, 128, 200, 256])
+@pytest.mark.parametrize("obj", [0, 1])
+def test_ring_batch_u8_orders(n, obj):
+    c = random_matrix(n, 700 + n, symmetric=False, lo=0, hi=COST_MAX if n in (13, 64) else 6000)
+    for b in (1, 3, 67, 1029, 4100):
+        say(f"ring batch, one byte per rank, N={n} obj={obj} B={b}")
+        perms = random_perms(n, b, seed=n + b)
+        out = cc.cc_ring_cost_batch_u8(dev(c), dev(perms.astype(np.uint8)), obj)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), oracle.ring_cost_batch(c, perms, obj))
+
+
+def test_ring_batch_u8_unaligned_out_of_range_and_full_size():
+    say("ring batch u8: unaligned stream, out-of-range bytes, 2^20 orders")
+    c = make_matrix(2)
+    perms = random_perms(64, 33, seed=2)
+    flat = torch.empty(33 * 64 + 1, dtype=torch.uint8, device="cuda")
+    view = flat[1:].view(33, 64)
+    view.copy_(dev(perms.astype(np.uint8)))
+    out = cc.cc_ring_cost_batch_u8(dev(c), view, 0)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), oracle.ring_cost_batch(c, perms, 0))
+    bad = perms.astype(np.uint8)
+    bad[::2, 5] = 255                                   # not a rank: result unspecified, access must stay in bounds
+    cc.cc_ring_cost_batch_u8(dev(c), dev(bad), 1)
+    torch.cuda.synchronize()
+    B = 1 << 20
+    tours = cc.cc_init_tours(64, B, WORKLOADS[2].search_seed)
+    want = cc.cc_ring_cost_batch(dev(c), tours, 0)
+    got = cc.cc_ring_cost_batch_u8(dev(c), tours.to(torch.uint8), 0)
+    torch.cuda.synchronize()
+    assert torch.equal(want, got)
+    rows = np.arange(0, B, 4099)
+    assert np.array_equal(got.cpu().numpy()[rows], oracle.ring_cost_batch(c, tours.cpu().numpy()[rows], 0))
+
+
 def test_ring_batch_empty_and_unaligned():
     c = random_matrix(64, 1, symmetric=True)
     say("ring batch B=0")

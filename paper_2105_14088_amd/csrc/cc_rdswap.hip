@@ -10,9 +10,10 @@
 //
 // General kernel: one workgroup per restart, one thread per rank p scanning q = p+1 .. N-1; matrix
 // gathered through L2; 64-bit keys (value << 32 | move id) min-reduced over the workgroup.
-// N = 64 kernel: one wavefront per restart, matrix in LDS, lane p scans partners q = p xor m for
-// m = 1 .. 63 (every pair is seen from both ends, which is harmless: same value, same id); the top-3
-// links of a round come from three wave-wide max-reductions over (value << 5 | link index).
+// N = 64 kernel: one wavefront per restart, matrix in LDS, lane p scans partners q = p xor x; two rank
+// differences x with the same top bit share a step (lanes with that bit clear take one, the others the
+// other), so every pair is scored once, in 32 steps; the top-3 links of a round come from three
+// wave-wide max-reductions over (value << 5 | link index).
 #include "cc_device.h"
 #include "cc_internal.h"
 #include "cc_wave64.h"
@@ -196,11 +197,19 @@ __global__ __launch_bounds__(256) void rdswap_n64_kernel(const int32_t* __restri
             round_cost[k] = k1 >> 5;
             cur += round_cost[k];
         }
+        // Partners by rank difference x = p xor q.  Every pair would be seen from both of its ends; instead two
+        // differences with the same top bit h, x = 2j and 2j + 1, share a step: the lanes whose rank has bit h clear
+        // take the first, the others the second, so the 64 lanes score 64 distinct pairs.  x = 1 has no mate: its
+        // step scores each of its 32 pairs twice (same value, same id).
         unsigned long long best = kNoMove;
 #pragma unroll 1
-        for (int mm = 1; mm < kN; ++mm) {
+        for (int j = 0; j < kN / 2; ++j) {
+            const int x0 = j ? 2 * j : 1, x1 = j ? 2 * j + 1 : 1;                           // wave-uniform
+            const int top = 31 - __builtin_clz(x0);
+            const bool second = (lane >> top) & 1;
+            const int mm = second ? x1 : x0;
             const int q = lane ^ mm;
-            const int tq = *(const int32_t*)(tlbytes + ((lane ^ mm) << 2));
+            const int tq = *(const int32_t*)(tlbytes + (q << 2));
             const int tq8 = tq << 8, tq2 = tq << 2;
             int total = 0;
 #pragma unroll
@@ -209,7 +218,10 @@ __global__ __launch_bounds__(256) void rdswap_n64_kernel(const int32_t* __restri
                 const int qb = *(const int32_t*)(tlbytes + (own_addr[k] ^ (mm << 2)));      // node at rank q xor 2^k
                 const int link_p = max(entry(tq8, pb2[k]), entry(pb8[k], tq2));             // rank p now holds t[q]
                 const int link_q = max(entry(t8, qb << 2), entry(qb << 8, t2));             // rank q now holds t[p]
-                const int lim = ((mm >> (k + 1)) << k) | (mm & (bit - 1));                  // link index offset of the partner
+                // link index offset of the partner, for either difference (wave-uniform), then this lane's
+                const int lim0 = ((x0 >> (k + 1)) << k) | (x0 & (bit - 1));
+                const int lim1 = ((x1 >> (k + 1)) << k) | (x1 & (bit - 1));
+                const int lim = second ? lim1 : lim0;
                 const int others = (zk[k] == lim) ? x2v[k] : x1v[k];
                 const int stage = max(others, max(link_p, link_q));
                 total += (mm == bit) ? round_cost[k] : stage;

@@ -191,7 +191,7 @@ def main():
         ("C5rd", lambda: batch_case("C5_n1024_rd_65536", 5, "rd", 0, 65536)),
         ("C5", lambda: search_case(5)),
         ("S64", lambda: swap_case("S64_n64_rd_swap_1024", 2, 1024)),
-        ("S256", lambda: swap_case("S256_n256_rd_swap_64", 4, 64)),
+        ("S256", lambda: swap_case("S256_n256_rd_swap_256", 4, 256)),
         ("A64", lambda: sa_case("A64_n64_sa_1024x100000", 2, 1024, 100000, 300, 0)),
         ("A64big", lambda: sa_case("A64_n64_sa_8192x100000", 2, 8192, 100000, 300, 0)),
         ("A256", lambda: sa_case("A256_n256_sa_1024x200000", 4, 1024, 200000, 300, 0)),

@@ -199,7 +199,8 @@ int cc_rd_swap_search_ex(const int32_t* cost_matrix, int32_t N, int32_t restarts
     if (init_tours && init_tours != tours)
         CC_HIP(hipMemcpyAsync(tours, init_tours, sizeof(int32_t) * (size_t)restarts * (size_t)N,
                               hipMemcpyDeviceToDevice, s));
-    CC_HIP(cc::launch_rdswap(cost_matrix, N, restarts, seed, init_tours != nullptr, tours, costs, moves, s));
+    CC_HIP(cc::launch_rdswap(cost_matrix, N, restarts, seed, init_tours != nullptr, tours, costs, moves,
+                             (int32_t*)(base + w.flags), s));
     CC_HIP(cc::launch_best_restart(costs, tours, N, restarts, best_perm, best_cost, best_restart, s));
     return CC_OK;
 }

@@ -29,7 +29,10 @@ constexpr unsigned long long kNoMove = ~0ull;
 
 // ------------------------------------------------------------------------------------- general kernel
 __global__ void rdswap_general_kernel(const int32_t* __restrict__ c, int N, int32_t* __restrict__ tours,
-                                      int64_t* __restrict__ costs, int32_t* __restrict__ moves) {
+                                      int64_t* __restrict__ costs, int32_t* __restrict__ moves,
+                                      const int32_t* __restrict__ skip_if_small) {
+    // when the 16-bit workgroup kernel is launched beside this one, flags[0] = max(c) decides which of the two runs
+    if (skip_if_small && skip_if_small[0] < (1 << 16)) return;
     extern __shared__ int32_t sm[];
     int32_t* t = sm;                 // [N]
     int32_t* w = sm + N;             // [N] directed cost of each rank in the round being prepared
@@ -245,10 +248,132 @@ __global__ __launch_bounds__(256) void rdswap_n64_kernel(const int32_t* __restri
     }
 }
 
+// ------------------------------------------------------------------------- N = 128, 256: one workgroup per restart
+// The N = 64 scheme with one thread per rank: N threads, the matrix staged as 16-bit entries in LDS (32 / 128 KiB;
+// needs max(c) < 2^16, otherwise the general kernel runs instead, decided on the device), the order in LDS, the
+// three largest links of a round from workgroup-wide max-reductions, two rank differences per step so that the N
+// threads score N distinct pairs.  Keys: value << 16 | move id (id < 2^16, value < 2^20).
+template <int LOGN>
+__global__ __launch_bounds__(1 << LOGN) void rdswap_block_kernel(const int32_t* __restrict__ c,
+                                                                 int32_t* __restrict__ tours,
+                                                                 int64_t* __restrict__ costs,
+                                                                 int32_t* __restrict__ moves,
+                                                                 const int32_t* __restrict__ flags) {
+    constexpr int N = 1 << LOGN, NW = N / 64, LB = LOGN - 1;   // LB: bits of a link index
+    if (flags[0] >= (1 << 16)) return;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    uint16_t* m16 = (uint16_t*)smem;                           // [N * N]
+    int32_t* tl = (int32_t*)(smem + sizeof(uint16_t) * N * N); // [N] the order
+    __shared__ int red_i[2][NW];
+    __shared__ unsigned long long red_k[NW];
+    const int p = threadIdx.x, lane = p & 63, wv = p >> 6;
+    const int64_t r = blockIdx.x;
+    for (int e = p; e < N * N; e += N) m16[e] = (uint16_t)clampi(c[e], 0, 0xffff);
+    int t = clampi(tours[r * N + p], 0, N - 1);
+    tl[p] = t;
+    __syncthreads();
+    auto entry = [&](int a, int b) { return (int)m16[a * N + b]; };
+    int parity = 0;
+    auto block_max = [&](int v) {                              // every thread gets the maximum; one barrier per call
+        v = wave_max(v);
+        if (lane == 0) red_i[parity][wv] = v;
+        __syncthreads();
+        int o = red_i[parity][0];
+#pragma unroll
+        for (int k = 1; k < NW; ++k) o = max(o, red_i[parity][k]);
+        parity ^= 1;
+        return o;
+    };
+
+    int applied = 0, cur = 0;
+    for (;;) {
+        int pb[LOGN], x1v[LOGN], x2v[LOGN], zk[LOGN], round_cost[LOGN];
+        cur = 0;
+#pragma unroll
+        for (int k = 0; k < LOGN; ++k) {
+            const int bit = 1 << k;
+            pb[k] = tl[p ^ bit];
+            const int lv = max(entry(t, pb[k]), entry(pb[k], t));
+            const int li = ((p >> (k + 1)) << k) | (p & (bit - 1));
+            const int key = (lv << LB) | li;
+            const int k1 = block_max(key);
+            const int k2 = block_max((li == (k1 & (N / 2 - 1))) ? -1 : key);
+            const int k3 = block_max((li == (k1 & (N / 2 - 1)) || li == (k2 & (N / 2 - 1))) ? -1 : key);
+            const int l1 = k1 & (N / 2 - 1), l2 = k2 & (N / 2 - 1);
+            const int a1 = (li == l1) ? k2 : k1;               // best link that is not this rank's
+            const int a2 = (li == l1 || li == l2) ? k3 : k2;   // second best that is not this rank's
+            x1v[k] = a1 >> LB;
+            x2v[k] = a2 >> LB;
+            zk[k] = li ^ (a1 & (N / 2 - 1));                   // partner's link is that best link  <=>  li(x) == zk
+            round_cost[k] = k1 >> LB;
+            cur += round_cost[k];
+        }
+        unsigned long long best = kNoMove;
+#pragma unroll 1
+        for (int j = 0; j < N / 2; ++j) {
+            const int x0 = j ? 2 * j : 1, x1 = j ? 2 * j + 1 : 1;
+            const int top = 31 - __builtin_clz(x0);
+            const bool second = (p >> top) & 1;
+            const int mm = second ? x1 : x0;
+            const int q = p ^ mm;
+            const int tq = tl[q];
+            int total = 0;
+#pragma unroll
+            for (int k = 0; k < LOGN; ++k) {
+                const int bit = 1 << k;
+                const int qb = tl[q ^ bit];
+                const int link_p = max(entry(tq, pb[k]), entry(pb[k], tq));
+                const int link_q = max(entry(t, qb), entry(qb, t));
+                const int lim0 = ((x0 >> (k + 1)) << k) | (x0 & (bit - 1));
+                const int lim1 = ((x1 >> (k + 1)) << k) | (x1 & (bit - 1));
+                const int lim = second ? lim1 : lim0;
+                const int others = (zk[k] == lim) ? x2v[k] : x1v[k];
+                const int stage = max(others, max(link_p, link_q));
+                total += (mm == bit) ? round_cost[k] : stage;
+            }
+            const int lo = min(p, q), hi = max(p, q);
+            best = min(best, ((unsigned long long)(unsigned)total << 16) | (unsigned)(lo * N + hi));
+        }
+        best = wave_min_u64(best);
+        if (lane == 0) red_k[wv] = best;
+        __syncthreads();
+        unsigned long long win = red_k[0];
+#pragma unroll
+        for (int k = 1; k < NW; ++k) win = min(win, red_k[k]);
+        if ((int)(win >> 16) >= cur) break;
+        const int id = (int)(win & 0xffffu), sp = id >> LOGN, sq = id & (N - 1);
+        const int a = tl[sp], b = tl[sq];
+        __syncthreads();                                       // everyone has read red_k and the two ranks
+        if (p == sp) { t = b; tl[p] = b; }
+        if (p == sq) { t = a; tl[p] = a; }
+        ++applied;
+        __syncthreads();
+    }
+    tours[r * N + p] = t;
+    if (p == 0) {
+        costs[r] = (int64_t)cur;
+        moves[r] = applied;
+    }
+}
+
+template <int LOGN>
+static hipError_t rdswap_block_launch(const int32_t* c, int restarts, int32_t* tours, int64_t* costs, int32_t* moves,
+                                      const int32_t* flags, hipStream_t s) {
+    constexpr int N = 1 << LOGN;
+    const size_t lds = sizeof(uint16_t) * N * N + sizeof(int32_t) * N;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)rdswap_block_kernel<LOGN>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(rdswap_block_kernel<LOGN>, dim3(restarts), dim3(N), lds, s, c, tours, costs, moves, flags);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_rdswap(const int32_t* c, int N, int restarts, uint64_t seed, bool tours_hold_init, int32_t* tours,
-                         int64_t* costs, int32_t* moves, hipStream_t s) {
+                         int64_t* costs, int32_t* moves, int32_t* flags, hipStream_t s) {
     if (N == 64) {
         hipLaunchKernelGGL(rdswap_n64_kernel, dim3((restarts + 3) / 4), dim3(256), 0, s, c, restarts, seed,
                            tours_hold_init ? 0 : 1, tours, costs, moves);
@@ -258,9 +383,20 @@ hipError_t launch_rdswap(const int32_t* c, int N, int restarts, uint64_t seed, b
         hipError_t e = launch_init_tours(N, 0, restarts, seed, tours, s);
         if (e != hipSuccess) return e;
     }
+    const int32_t* skip = nullptr;
+    if (N == 128 || N == 256) {
+        // 16-bit workgroup kernel when max(c) < 2^16, else the general kernel: both are enqueued and the matrix
+        // maximum, computed on the device, decides which one does the work (no host round trip)
+        hipError_t e = launch_matrix_max(c, N, flags, s);
+        if (e != hipSuccess) return e;
+        e = N == 128 ? rdswap_block_launch<7>(c, restarts, tours, costs, moves, flags, s)
+                     : rdswap_block_launch<8>(c, restarts, tours, costs, moves, flags, s);
+        if (e != hipSuccess) return e;
+        skip = flags;
+    }
     const int threads = ((N + 63) / 64) * 64;
     hipLaunchKernelGGL(rdswap_general_kernel, dim3(restarts), dim3(threads), sizeof(int32_t) * 2 * (size_t)N, s, c, N,
-                       tours, costs, moves);
+                       tours, costs, moves, skip);
     return hipGetLastError();
 }
 

@@ -69,11 +69,30 @@ def test_swap_search_n64_1024_restarts_full():
         assert oracle.rd_swap_all_values(c, got["tours"][r]).min() >= got["costs"][r]
 
 
-def test_swap_search_n256_and_n1024_general_kernel():
-    say("rd swap search: N=256 hierarchical matrix, 4 restarts (general kernel)")
+@pytest.mark.parametrize("n", [128, 256])
+def test_swap_search_workgroup_kernel_and_its_fallback(n):
+    """N = 128 / 256: 16-bit workgroup kernel when max(c) < 2^16, general kernel otherwise (decided on the device)."""
+    for hi, sym, tag in ((65535, True, "entries up to 2^16 - 1 (16-bit kernel)"), (3, False, "many ties (16-bit kernel)"),
+                         (65536, True, "one entry 2^16 (general kernel)")):
+        say(f"rd swap search N={n} {tag}")
+        c = random_matrix(n, 5100 + n + hi % 7, symmetric=sym, lo=0, hi=min(hi, 65535))
+        if hi == 65536:
+            c[3, 5] = c[5, 3] = 65536
+        want = oracle.rd_swap_search(c, 5, seed=77 + n)
+        assert_search_equal(gpu_swap_search(c, 5, seed=77 + n), want)
+
+
+def test_swap_search_n256_and_n1024():
+    say("rd swap search: N=256 hierarchical matrix, 6 restarts (16-bit workgroup kernel)")
     c = make_matrix(4)
-    want = oracle.rd_swap_search(c, 4, seed=3)
-    assert_search_equal(gpu_swap_search(c, 4, seed=3), want)
+    with __import__("concurrent.futures").futures.ThreadPoolExecutor(6) as ex:
+        parts = list(ex.map(lambda r: oracle.rd_swap_restarts(c, 3, r, r + 1), range(6)))
+    got = gpu_swap_search(c, 6, seed=3)
+    assert np.array_equal(got["costs"], np.concatenate([p[0] for p in parts]))
+    assert np.array_equal(got["tours"], np.concatenate([p[1] for p in parts]))
+    assert np.array_equal(got["moves"], np.concatenate([p[2] for p in parts]))
+    k = int(np.argmin(got["costs"]))
+    assert got["best_restart"] == k and got["best_cost"] == got["costs"][k]
     say("rd swap search: N=1024, asymmetric, 3 % large entries, 2 restarts (general kernel)")
     c = random_matrix(1024, 999, symmetric=False, lo=1, hi=40)
     mask = np.random.default_rng(1).random((1024, 1024)) < 0.97

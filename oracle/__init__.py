@@ -102,6 +102,12 @@ def _declare(path: str) -> ctypes.CDLL:
     lib.cco_dbt_cost_batch.argtypes = [p, i32, p, i64, p]
     lib.cco_bcube_cost_weighted_batch.restype = ctypes.c_int
     lib.cco_bcube_cost_weighted_batch.argtypes = [p, i32, i32, p, p, i64, p]
+    lib.cco_sa_rd_proposal.restype = None
+    lib.cco_sa_rd_proposal.argtypes = [u64, ctypes.c_uint32, ctypes.c_uint32, i32, p, p, p]
+    lib.cco_sa_rd_chain.restype = ctypes.c_int
+    lib.cco_sa_rd_chain.argtypes = [p, i32, p, i64, i32, i32, u64, ctypes.c_uint32, p, p, p, p, p]
+    lib.cco_sa_rd_chains.restype = ctypes.c_int
+    lib.cco_sa_rd_chains.argtypes = [p, i32, i64, i32, i32, u64, i64, i64, p, p, p, p]
     lib.cco_cost_matrix_from_probes.restype = ctypes.c_int
     lib.cco_cost_matrix_from_probes.argtypes = [p, i32, i32, i32, i32, p]
     return lib
@@ -447,3 +453,47 @@ def cost_matrix_from_probes(samples, percentile: int = 10, symmetrize: bool = Tr
     out = np.empty((n, n), dtype=np.int32)
     _check(_L().cco_cost_matrix_from_probes(_ptr(samples), n, k, percentile, int(symmetrize), _ptr(out)))
     return out
+
+
+# ------------------------------------------------------------------------------------------ annealing, halving-doubling
+def sa_rd_proposal(seed: int, r: int, s: int, n: int):
+    """(p, q, u): the two ranks to exchange and the acceptance draw of step s of chain r."""
+    a, b, u = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    _L().cco_sa_rd_proposal(seed, r, s, n, ctypes.byref(a), ctypes.byref(b), ctypes.byref(u))
+    return a.value, b.value, u.value
+
+
+def sa_rd_chain(c, t, steps: int, t_start: int, t_end: int, seed: int, r: int, trace: bool = False):
+    c = _mat(c)
+    n = c.shape[0]
+    t = np.array(t, dtype=np.int32, copy=True)
+    best_tour = np.empty(n, dtype=np.int32)
+    best, final = ctypes.c_int64(), ctypes.c_int64()
+    acc = ctypes.c_int32()
+    tr = np.empty(steps, dtype=np.int64) if trace else None
+    _check(_L().cco_sa_rd_chain(_ptr(c), n, _ptr(t), steps, t_start, t_end, seed, r, _ptr(best_tour), ctypes.byref(best),
+                                ctypes.byref(final), ctypes.byref(acc), _ptr(tr)))
+    return dict(final_tour=t, final_cost=final.value, best_tour=best_tour, best_cost=best.value, accepted=acc.value,
+                trace=tr)
+
+
+def sa_rd_chains(c, steps: int, t_start: int, t_end: int, seed: int, r0: int, r1: int,
+                 init: Optional[np.ndarray] = None):
+    c = _mat(c)
+    n = c.shape[0]
+    k = r1 - r0
+    costs = np.empty(k, dtype=np.int64)
+    tours = np.empty((k, n), dtype=np.int32)
+    accepted = np.empty(k, dtype=np.int32)
+    if init is not None:
+        init = np.ascontiguousarray(init, dtype=np.int32)
+    _check(_L().cco_sa_rd_chains(_ptr(c), n, steps, t_start, t_end, seed, r0, r1, _ptr(init), _ptr(costs), _ptr(tours),
+                                 _ptr(accepted)))
+    return costs, tours, accepted
+
+
+def sa_rd_search(c, chains: int, steps: int, t_start: int, t_end: int, seed: int, init: Optional[np.ndarray] = None):
+    costs, tours, accepted = sa_rd_chains(c, steps, t_start, t_end, seed, 0, chains, init)
+    k = int(np.argmin(costs))
+    return dict(best_perm=tours[k].copy(), best_cost=int(costs[k]), best_chain=k, costs=costs, tours=tours,
+                accepted=accepted)

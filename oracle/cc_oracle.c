@@ -825,3 +825,78 @@ int cco_cost_matrix_from_probes(const int32_t *samples, int32_t N, int32_t K, in
             }
     return CCO_OK;
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * Simulated annealing under the halving-doubling model with the pair neighbour (Section 4.3: "permuting
+ * random pairs").  Same chain as cco_sa_chain (same random word per step, same temperature, same
+ * acceptance rule, same report) with a different proposal and cost:
+ *   p = (w[63:43] * N) >> 21,  d = 1 + ((w[42:22] * (N-1)) >> 21),  q = (p + d) mod N: an ordered pair of
+ *   distinct ranks, every one equally likely (nearly); the move exchanges the nodes at ranks p and q;
+ *   delta = rd_cost(after) - rd_cost(before), here by swapping and recomputing.
+ * N must be a power of two.  N = 1 is not a valid matrix; N = 2 has one move (delta 0 on any matrix whose
+ * model takes both directions).
+ * ---------------------------------------------------------------------------------------------- */
+void cco_sa_rd_proposal(uint64_t seed, uint32_t r, uint32_t s, int32_t N, int32_t *p, int32_t *q, int32_t *u)
+{
+    uint64_t w = cco_splitmix64_at(seed, (((uint64_t)r << 32) | (uint64_t)(CCO_SA_STREAM_BASE + s)) + 1u);
+    uint64_t hi21 = w >> 43, mid21 = (w >> 22) & 0x1FFFFFu;
+    int32_t rp = (int32_t)((hi21 * (uint64_t)N) >> 21);
+    int32_t d = 1 + (int32_t)((mid21 * (uint64_t)(N - 1)) >> 21);
+    *p = rp;
+    *q = (rp + d) % N;
+    *u = (int32_t)(w & 0x3FFFFFu) + 1;
+}
+
+int cco_sa_rd_chain(const int32_t *c, int32_t N, int32_t *t, int64_t steps, int32_t t_start, int32_t t_end, uint64_t seed,
+                    uint32_t r, int32_t *best_tour, int64_t *best_cost, int64_t *final_cost, int32_t *accepted,
+                    int64_t *trace)
+{
+    if (!c || !t || N < 2 || (N & (N - 1)) || steps < 0 || steps > CCO_SA_MAX_STEPS || t_start < 0 || t_end < 0 ||
+        t_start > CCO_SA_MAX_T || t_end > CCO_SA_MAX_T)
+        return CCO_ERR_ARG;
+    int64_t cur = cco_rd_cost(c, N, t);
+    int64_t best = cur;
+    int32_t acc = 0;
+    if (best_tour) memcpy(best_tour, t, sizeof(int32_t) * (size_t)N);
+    for (int64_t s = 0; s < steps; ++s) {
+        int32_t p, q, u;
+        cco_sa_rd_proposal(seed, r, (uint32_t)s, N, &p, &q, &u);
+        cco_apply_swap(t, p, q);
+        int64_t delta = cco_rd_cost(c, N, t) - cur;
+        int64_t num = (int64_t)t_start * (steps - s) + (int64_t)t_end * s;
+        if (cco_sa_accepts(delta, steps, num, u)) {
+            cur += delta;
+            ++acc;
+            if (cur < best) {
+                best = cur;
+                if (best_tour) memcpy(best_tour, t, sizeof(int32_t) * (size_t)N);
+            }
+        } else {
+            cco_apply_swap(t, p, q);    /* undo */
+        }
+        if (trace) trace[s] = cur;
+    }
+    if (best_cost) *best_cost = best;
+    if (final_cost) *final_cost = cur;
+    if (accepted) *accepted = acc;
+    return CCO_OK;
+}
+
+int cco_sa_rd_chains(const int32_t *c, int32_t N, int64_t steps, int32_t t_start, int32_t t_end, uint64_t seed,
+                     int64_t r0, int64_t r1, const int32_t *init, int64_t *costs, int32_t *tours, int32_t *accepted)
+{
+    if (!c || N < 2 || r0 < 0 || r1 < r0 || !costs || !tours) return CCO_ERR_ARG;
+    int32_t *t = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    if (!t) return CCO_ERR_NOMEM;
+    int rc = CCO_OK;
+    for (int64_t r = r0; r < r1 && rc == CCO_OK; ++r) {
+        if (init) memcpy(t, init + (r - r0) * N, sizeof(int32_t) * (size_t)N);
+        else cco_init_tour(seed, (uint32_t)r, N, t);
+        int32_t acc = 0;
+        rc = cco_sa_rd_chain(c, N, t, steps, t_start, t_end, seed, (uint32_t)r, tours + (r - r0) * N, costs + (r - r0),
+                             NULL, &acc, NULL);
+        if (accepted) accepted[r - r0] = acc;
+    }
+    free(t);
+    return rc;
+}

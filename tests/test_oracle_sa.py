@@ -200,3 +200,87 @@ def test_chains_match_single_chain_calls_and_search_picks_lowest():
     # annealing from a hot start ends no worse than the best it reports, and helps on average against the start
     starts = oracle.ring_cost_batch(c, oracle.init_tours(SEED, n, 12))
     assert res["costs"].mean() < starts.mean()
+
+
+# ------------------------------------------------------------------------- halving-doubling model, pair neighbour
+@pytest.mark.parametrize("n", [2, 4, 8, 64, 1024])
+def test_rd_proposals_are_uniform_ordered_pairs(n):
+    draws = 30000 if n <= 64 else 3000
+    p_count = np.zeros(n, dtype=np.int64)
+    d_count = np.zeros(n, dtype=np.int64)
+    for s in range(draws):
+        p, q, u = oracle.sa_rd_proposal(SEED, 1, s, n)
+        assert 0 <= p < n and 0 <= q < n and p != q and 1 <= u <= 1 << 22
+        p_count[p] += 1
+        d_count[(q - p) % n] += 1
+    if n <= 64:
+        assert np.all(np.abs(p_count - draws / n) < 6 * math.sqrt(draws / n))
+        if n > 2:
+            e = draws / (n - 1)
+            assert np.all(np.abs(d_count[1:] - e) < 6 * math.sqrt(e))
+    # same random word as the ring chain's step: only the use of its first two fields differs
+    w = oracle.splitmix64_at(SEED, ((1 << 32) | (1024 + 5)) + 1)
+    p = ((w >> 43) * n) >> 21
+    d = 1 + ((((w >> 22) & 0x1FFFFF) * (n - 1)) >> 21)
+    assert oracle.sa_rd_proposal(SEED, 1, 5, n) == (p, (p + d) % n, (w & 0x3FFFFF) + 1)
+
+
+@pytest.mark.parametrize("n,temp", [(2, 50), (4, 0), (8, 100), (16, 300), (64, 200), (64, 0)])
+def test_rd_chain_replayed_and_bookkept(n, temp):
+    c = random_matrix(n, 90 + n, symmetric=False, lo=1, hi=3000)
+    t0 = oracle.init_tours(SEED, n, 1, first=4)[0]
+    steps, te = 1500, temp // 3
+    res = oracle.sa_rd_chain(c, t0, steps, temp, te, SEED, 4, trace=True)
+    t = t0.copy()
+    cur = oracle.rd_cost(c, t)
+    best, best_t, acc = cur, t.copy(), 0
+    for s in range(steps):
+        p, q, u = oracle.sa_rd_proposal(SEED, 4, s, n)
+        new = oracle.rd_swap_value_by_definition(c, t, min(p, q), max(p, q))
+        if oracle.sa_accepts(new - cur, steps, temp * (steps - s) + te * s, u):
+            t[p], t[q] = t[q], t[p]
+            cur = new
+            acc += 1
+            if cur < best:
+                best, best_t = cur, t.copy()
+        assert res["trace"][s] == cur
+    assert (res["best_cost"], res["accepted"], res["final_cost"]) == (best, acc, cur)
+    assert np.array_equal(res["best_tour"], best_t) and np.array_equal(res["final_tour"], t)
+    assert res["final_cost"] == oracle.rd_cost(c, res["final_tour"]) and res["best_cost"] == oracle.rd_cost(c, res["best_tour"])
+    if temp == 0:
+        assert np.all(np.diff(res["trace"]) <= 0)
+
+
+def test_rd_constant_temperature_chain_samples_the_boltzmann_distribution():
+    """N = 4: all 24 orders are states, the swap proposal is symmetric, so at constant T the chain visits a state
+    with probability proportional to 2^(-cost/T) (up to the chord error of the acceptance rule)."""
+    import itertools
+    n, temp, steps = 4, 70, 1 << 21
+    c = random_matrix(n, 31, symmetric=False, lo=10, hi=300)
+    all_costs = np.array([oracle.rd_cost(c, np.array(pm, dtype=np.int32)) for pm in itertools.permutations(range(n))])
+    levels, mult = np.unique(all_costs, return_counts=True)
+    weights = mult * 2.0 ** (-(levels - levels.min()) / temp)
+    want = weights / weights.sum()
+    res = oracle.sa_rd_chain(c, np.arange(n), steps, temp, temp, SEED, 0, trace=True)
+    tr = res["trace"][steps // 64:]
+    got = np.array([(tr == lv).mean() for lv in levels])
+    assert abs(got.sum() - 1) < 1e-12
+    for g, w in zip(got, want):
+        if w > 0.01:
+            assert abs(g / w - 1) < 0.12, (got, want)
+
+
+def test_rd_chains_and_limits():
+    n = 16
+    c = random_matrix(n, 12, symmetric=True, lo=1, hi=4000)
+    costs, tours, accepted = oracle.sa_rd_chains(c, 1500, 400, 0, SEED, 2, 7)
+    for k, r in enumerate(range(2, 7)):
+        one = oracle.sa_rd_chain(c, oracle.init_tours(SEED, n, 1, first=r)[0], 1500, 400, 0, SEED, r)
+        assert one["best_cost"] == costs[k] and np.array_equal(one["best_tour"], tours[k]) and one["accepted"] == accepted[k]
+    res = oracle.sa_rd_search(c, 10, 1500, 400, 0, SEED)
+    assert res["best_cost"] == res["costs"].min()
+    assert res["costs"].mean() < oracle.rd_cost_batch(c, oracle.init_tours(SEED, n, 10)).mean()
+    with pytest.raises(RuntimeError):
+        oracle.sa_rd_chain(random_matrix(12, 1, symmetric=True), np.arange(12), 10, 1, 1, SEED, 0)   # not a power of two
+    r0 = oracle.sa_rd_chain(c, np.arange(n), 0, 5, 5, SEED, 0)
+    assert np.array_equal(r0["best_tour"], np.arange(n)) and r0["accepted"] == 0

@@ -104,14 +104,15 @@ def main():
                       "oracle_sample_restarts": sample, "bit_exact_on_sample": ok})
         emit(d)
 
-    def sa_case(name, wid, chains, steps, t_start, t_end):
+    def sa_case(name, wid, chains, steps, t_start, t_end, rd=False):
+        call = cc.cc_sa_rd_search_ex if rd else cc.cc_sa_search_ex
         w = WORKLOADS[wid]
         c_host = make_matrix(wid)
         c = torch.from_numpy(c_host).cuda()
         bufs = cc.SearchBuffers(w.n, 0, chains, c.device)
-        ms = timed(lambda: cc.cc_sa_search_ex(c, chains, steps, t_start, t_end, w.search_seed, buffers=bufs), args.reps)
+        ms = timed(lambda: call(c, chains, steps, t_start, t_end, w.search_seed, buffers=bufs), args.reps)
         acc = bufs.restart_moves.cpu().numpy().astype(np.int64)
-        d = {"workload": name, "call": "cc_sa_search_ex", "N": w.n, "chains": chains, "steps": steps,
+        d = {"workload": name, "call": "cc_sa_rd_search_ex" if rd else "cc_sa_search_ex", "N": w.n, "chains": chains, "steps": steps,
              "t_start": t_start, "t_end": t_end, "ms": ms, "chain_steps_per_s": chains * steps / (ms * 1e-3),
              "accepted_fraction": float(acc.mean() / steps), "best_cost": int(bufs.best_cost.item()),
              "mean_chain_best": float(bufs.restart_costs.double().mean().item())}
@@ -119,7 +120,9 @@ def main():
             import oracle
             sample = min(chains, 8)
             t0 = time.perf_counter()
-            oc, ot, oa = oracle.sa_chains(c_host, steps, t_start, t_end, w.search_seed, 0, sample)
+            sample = min(sample, 2) if rd else sample
+            run = oracle.sa_rd_chains if rd else oracle.sa_chains
+            oc, ot, oa = run(c_host, steps, t_start, t_end, w.search_seed, 0, sample)
             dt = time.perf_counter() - t0
             ok = bool(np.array_equal(oc, bufs.restart_costs.cpu().numpy()[:sample]) and
                       np.array_equal(ot, bufs.restart_tours.cpu().numpy()[:sample]) and np.array_equal(oa, acc[:sample]))
@@ -203,6 +206,8 @@ def main():
         ("T64", lambda: batch_case("T64_n64_dbt_2^20", 2, "dbt", 0, 1 << 20)),
         ("T1024", lambda: batch_case("T1024_n1024_dbt_65536", 5, "dbt", 0, 65536)),
         ("R64", lambda: batch_case("R64_n64_rd_2^20", 2, "rd", 0, 1 << 20)),
+        ("AR64", lambda: sa_case("AR64_n64_sa_rd_1024x20000", 2, 1024, 20000, 300, 0, rd=True)),
+        ("AR1024", lambda: sa_case("AR1024_n1024_sa_rd_256x20000", 5, 256, 20000, 300, 0, rd=True)),
         ("M64sum", lambda: batch_case("M64_ring_sum_2^20", 2, "ring", 0, 1 << 20)),
         ("M64max", lambda: batch_case("M64_ring_max_2^20", 3, "ring", 1, 1 << 20)),
         ("M64u8", lambda: batch_case("M64_ring_sum_2^20_byte_orders", 2, "ring_u8", 0, 1 << 20)),

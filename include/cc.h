@@ -229,6 +229,22 @@ int cc_sa_search_ex(const int32_t* cost_matrix, int32_t N, int32_t chains, int64
 size_t cc_sa_workspace_bytes(int32_t N, int32_t chains);
 
 /*
+ * Simulated annealing under the halving-doubling model with the pair neighbour (Section 4.3: permuting random
+ * pairs; cost: Section 4.1 equation C_hd as evaluated by cc_rd_cost_batch).  Exactly cc_sa_search (same random word
+ * per step, temperature, acceptance rule, report, limits, arguments, workspace) except for the proposal and the
+ * cost: p = (w[63:43] * N) >> 21, q = (p + d) mod N with d = 1 + ((w[42:22] * (N-1)) >> 21); the move exchanges the
+ * nodes at ranks p and q; delta = halving-doubling cost after - before.  No rank is anchored; the matrix need not
+ * be symmetric.  N must be a power of two (else CC_ERR_UNSUPPORTED_N).
+ */
+int cc_sa_rd_search(const int32_t* cost_matrix, int32_t N, int32_t chains, int64_t steps, int32_t t_start,
+                    int32_t t_end, uint64_t seed, int32_t* best_perm, int64_t* best_cost, void* stream);
+
+int cc_sa_rd_search_ex(const int32_t* cost_matrix, int32_t N, int32_t chains, int64_t steps, int32_t t_start,
+                       int32_t t_end, uint64_t seed, const int32_t* init_tours, int32_t* best_perm, int64_t* best_cost,
+                       int32_t* best_chain, int64_t* chain_costs, int32_t* chain_tours, int32_t* chain_accepted,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Initial orders of restarts first .. first+count-1 for `seed` (the shuffle described above);
  * tours: int32 [count, N].  Also the generator of the seeded random orders used to exercise the
  * batch calls.

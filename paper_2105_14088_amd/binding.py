@@ -21,7 +21,7 @@ CC_COST_MAX = (1 << 21) - 1
 
 # every symbol include/cc.h declares
 EXPORTS = ["cc_ring_cost_batch", "cc_ring_cost_batch_u8", "cc_rd_cost_batch", "cc_bcube_cost_batch", "cc_bcube_cost_batch_weighted", "cc_dbt_cost_batch", "cc_2opt_search", "cc_2opt_search_ex",
-           "cc_2opt_workspace_bytes", "cc_best_of_restarts", "cc_rd_swap_search", "cc_rd_swap_search_ex", "cc_rd_swap_workspace_bytes", "cc_sa_search", "cc_sa_search_ex", "cc_sa_workspace_bytes", "cc_init_tours", "cc_cost_matrix_from_probes", "cc_validate_matrix", "cc_status_string",
+           "cc_2opt_workspace_bytes", "cc_best_of_restarts", "cc_rd_swap_search", "cc_rd_swap_search_ex", "cc_rd_swap_workspace_bytes", "cc_sa_search", "cc_sa_search_ex", "cc_sa_workspace_bytes", "cc_sa_rd_search", "cc_sa_rd_search_ex", "cc_init_tours", "cc_cost_matrix_from_probes", "cc_validate_matrix", "cc_status_string",
            "cc_last_hip_error", "cc_version"]
 
 
@@ -76,6 +76,10 @@ def lib() -> ctypes.CDLL:
         L.cc_sa_search.argtypes = [p, i32, i32, i64, i32, i32, u64, p, p, p]
         L.cc_sa_search_ex.restype = ctypes.c_int
         L.cc_sa_search_ex.argtypes = [p, i32, i32, i64, i32, i32, u64, p, p, p, p, p, p, p, p, sz, p]
+        L.cc_sa_rd_search.restype = ctypes.c_int
+        L.cc_sa_rd_search.argtypes = [p, i32, i32, i64, i32, i32, u64, p, p, p]
+        L.cc_sa_rd_search_ex.restype = ctypes.c_int
+        L.cc_sa_rd_search_ex.argtypes = [p, i32, i32, i64, i32, i32, u64, p, p, p, p, p, p, p, p, sz, p]
         L.cc_sa_workspace_bytes.restype = sz
         L.cc_sa_workspace_bytes.argtypes = [i32, i32]
         L.cc_init_tours.restype = ctypes.c_int
@@ -314,18 +318,18 @@ def cc_rd_swap_search_ex(cost_matrix: torch.Tensor, restarts: int, seed: int,
     return b
 
 
-def cc_sa_search(cost_matrix: torch.Tensor, chains: int, steps: int, t_start: int, t_end: int, seed: int, stream=None):
+def _sa_search(fn_name: str, cost_matrix: torch.Tensor, chains: int, steps: int, t_start: int, t_end: int, seed: int, stream=None):
     """Returns (best_perm int32[N], best_cost int64[1]) device tensors (valid after stream sync)."""
     n = _matrix(cost_matrix)
     best_perm = torch.empty(n, dtype=torch.int32, device=cost_matrix.device)
     best_cost = torch.empty(1, dtype=torch.int64, device=cost_matrix.device)
-    _check(lib().cc_sa_search(_dev(cost_matrix, torch.int32, "cost_matrix"), n, chains, steps, t_start, t_end,
+    _check(getattr(lib(), fn_name)(_dev(cost_matrix, torch.int32, "cost_matrix"), n, chains, steps, t_start, t_end,
                               seed & (2**64 - 1), _dev(best_perm, torch.int32, "best_perm"),
-                              _dev(best_cost, torch.int64, "best_cost"), _stream(stream)), "cc_sa_search")
+                              _dev(best_cost, torch.int64, "best_cost"), _stream(stream)), fn_name)
     return best_perm, best_cost
 
 
-def cc_sa_search_ex(cost_matrix: torch.Tensor, chains: int, steps: int, t_start: int, t_end: int, seed: int,
+def _sa_search_ex(fn_name: str, cost_matrix: torch.Tensor, chains: int, steps: int, t_start: int, t_end: int, seed: int,
                     init_tours: Optional[torch.Tensor] = None, buffers: Optional[SearchBuffers] = None,
                     stream=None) -> SearchBuffers:
     """Per-chain results land in the buffers' restart_costs / restart_tours (best cost and order of every chain)
@@ -338,7 +342,7 @@ def cc_sa_search_ex(cost_matrix: torch.Tensor, chains: int, steps: int, t_start:
     if init_tours is not None and tuple(init_tours.shape) != (chains, n):
         raise ValueError("init_tours must be [chains, N]")
     b = buffers
-    _check(lib().cc_sa_search_ex(_dev(cost_matrix, torch.int32, "cost_matrix"), n, chains, steps, t_start, t_end,
+    _check(getattr(lib(), fn_name)(_dev(cost_matrix, torch.int32, "cost_matrix"), n, chains, steps, t_start, t_end,
                                  seed & (2**64 - 1), _dev(init_tours, torch.int32, "init_tours"),
                                  _dev(b.best_perm, torch.int32, "best_perm"),
                                  _dev(b.best_cost, torch.int64, "best_cost"),
@@ -346,8 +350,27 @@ def cc_sa_search_ex(cost_matrix: torch.Tensor, chains: int, steps: int, t_start:
                                  _dev(b.restart_costs, torch.int64, "restart_costs"),
                                  _dev(b.restart_tours, torch.int32, "restart_tours"),
                                  _dev(b.restart_moves, torch.int32, "restart_moves"),
-                                 ctypes.c_void_p(b.ws_ptr), b.ws_bytes, _stream(stream)), "cc_sa_search_ex")
+                                 ctypes.c_void_p(b.ws_ptr), b.ws_bytes, _stream(stream)), fn_name)
     return b
+
+
+def cc_sa_search(cost_matrix, chains, steps, t_start, t_end, seed, stream=None):
+    """Ring sum, sub-array reversals.  Returns (best_perm int32[N], best_cost int64[1]) device tensors."""
+    return _sa_search("cc_sa_search", cost_matrix, chains, steps, t_start, t_end, seed, stream)
+
+
+def cc_sa_search_ex(cost_matrix, chains, steps, t_start, t_end, seed, init_tours=None, buffers=None, stream=None):
+    return _sa_search_ex("cc_sa_search_ex", cost_matrix, chains, steps, t_start, t_end, seed, init_tours, buffers, stream)
+
+
+def cc_sa_rd_search(cost_matrix, chains, steps, t_start, t_end, seed, stream=None):
+    """Halving-doubling model, pair exchanges.  Returns (best_perm int32[N], best_cost int64[1]) device tensors."""
+    return _sa_search("cc_sa_rd_search", cost_matrix, chains, steps, t_start, t_end, seed, stream)
+
+
+def cc_sa_rd_search_ex(cost_matrix, chains, steps, t_start, t_end, seed, init_tours=None, buffers=None, stream=None):
+    return _sa_search_ex("cc_sa_rd_search_ex", cost_matrix, chains, steps, t_start, t_end, seed, init_tours, buffers,
+                         stream)
 
 
 def cc_init_tours(n: int, count: int, seed: int, first: int = 0, device="cuda", out: Optional[torch.Tensor] = None,

@@ -227,11 +227,13 @@ size_t cc_sa_workspace_bytes(int32_t N, int32_t chains) {
     return ws_layout(N, chains).mat16;       // flags, costs, accepted counts, orders
 }
 
-int cc_sa_search_ex(const int32_t* cost_matrix, int32_t N, int32_t chains, int64_t steps, int32_t t_start, int32_t t_end,
-                    uint64_t seed, const int32_t* init_tours, int32_t* best_perm, int64_t* best_cost, int32_t* best_chain,
-                    int64_t* chain_costs, int32_t* chain_tours, int32_t* chain_accepted, void* workspace,
-                    size_t workspace_bytes, void* stream) {
+// Both annealing searches: ring sum with sub-array reversals, or halving-doubling with pair exchanges.
+static int sa_search_ex(bool halving_doubling, const int32_t* cost_matrix, int32_t N, int32_t chains, int64_t steps,
+                        int32_t t_start, int32_t t_end, uint64_t seed, const int32_t* init_tours, int32_t* best_perm,
+                        int64_t* best_cost, int32_t* best_chain, int64_t* chain_costs, int32_t* chain_tours,
+                        int32_t* chain_accepted, void* workspace, size_t workspace_bytes, void* stream) {
     if (int rc = check_matrix_args(cost_matrix, N)) return rc;
+    if (halving_doubling && !is_pow2(N)) return CC_ERR_UNSUPPORTED_N;
     if (chains < 1 || steps < 0 || steps > CC_SA_MAX_STEPS || t_start < 0 || t_start > CC_COST_MAX || t_end < 0 ||
         t_end > CC_COST_MAX || !best_perm || !best_cost)
         return CC_ERR_INVALID_ARG;
@@ -244,26 +246,58 @@ int cc_sa_search_ex(const int32_t* cost_matrix, int32_t N, int32_t chains, int64
     int32_t* tours = chain_tours ? chain_tours : (int32_t*)(base + w.tours);
     if (init_tours && init_tours != tours)
         CC_HIP(hipMemcpyAsync(tours, init_tours, sizeof(int32_t) * (size_t)chains * (size_t)N, hipMemcpyDeviceToDevice, s));
-    CC_HIP(cc::launch_sa_ring(cost_matrix, N, chains, steps, t_start, t_end, seed, init_tours == nullptr, tours, costs,
-                              acc, s));
+    if (halving_doubling)
+        CC_HIP(cc::launch_sa_rd(cost_matrix, N, chains, steps, t_start, t_end, seed, init_tours == nullptr, tours, costs,
+                                acc, s));
+    else
+        CC_HIP(cc::launch_sa_ring(cost_matrix, N, chains, steps, t_start, t_end, seed, init_tours == nullptr, tours,
+                                  costs, acc, s));
     CC_HIP(cc::launch_best_restart(costs, tours, N, chains, best_perm, best_cost, best_chain, s));
     return CC_OK;
 }
 
-int cc_sa_search(const int32_t* cost_matrix, int32_t N, int32_t chains, int64_t steps, int32_t t_start, int32_t t_end,
-                 uint64_t seed, int32_t* best_perm, int64_t* best_cost, void* stream) {
+static int sa_search(bool halving_doubling, const int32_t* cost_matrix, int32_t N, int32_t chains, int64_t steps,
+                     int32_t t_start, int32_t t_end, uint64_t seed, int32_t* best_perm, int64_t* best_cost,
+                     void* stream) {
     if (int rc = check_matrix_args(cost_matrix, N)) return rc;
+    if (halving_doubling && !is_pow2(N)) return CC_ERR_UNSUPPORTED_N;
     if (chains < 1 || !best_perm || !best_cost) return CC_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
     const size_t bytes = cc_sa_workspace_bytes(N, chains);
     void* ws = nullptr;
     CC_HIP(hipMallocAsync(&ws, bytes, s));
-    const int rc = cc_sa_search_ex(cost_matrix, N, chains, steps, t_start, t_end, seed, nullptr, best_perm, best_cost,
-                                   nullptr, nullptr, nullptr, nullptr, ws, bytes, stream);
+    const int rc = sa_search_ex(halving_doubling, cost_matrix, N, chains, steps, t_start, t_end, seed, nullptr, best_perm,
+                                best_cost, nullptr, nullptr, nullptr, nullptr, ws, bytes, stream);
     const hipError_t e = hipFreeAsync(ws, s);
     if (rc != CC_OK) return rc;
     if (e != hipSuccess) return hip_fail(e);
     return CC_OK;
+}
+
+int cc_sa_search_ex(const int32_t* cost_matrix, int32_t N, int32_t chains, int64_t steps, int32_t t_start, int32_t t_end,
+                    uint64_t seed, const int32_t* init_tours, int32_t* best_perm, int64_t* best_cost, int32_t* best_chain,
+                    int64_t* chain_costs, int32_t* chain_tours, int32_t* chain_accepted, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+    return sa_search_ex(false, cost_matrix, N, chains, steps, t_start, t_end, seed, init_tours, best_perm, best_cost,
+                        best_chain, chain_costs, chain_tours, chain_accepted, workspace, workspace_bytes, stream);
+}
+
+int cc_sa_search(const int32_t* cost_matrix, int32_t N, int32_t chains, int64_t steps, int32_t t_start, int32_t t_end,
+                 uint64_t seed, int32_t* best_perm, int64_t* best_cost, void* stream) {
+    return sa_search(false, cost_matrix, N, chains, steps, t_start, t_end, seed, best_perm, best_cost, stream);
+}
+
+int cc_sa_rd_search_ex(const int32_t* cost_matrix, int32_t N, int32_t chains, int64_t steps, int32_t t_start,
+                       int32_t t_end, uint64_t seed, const int32_t* init_tours, int32_t* best_perm, int64_t* best_cost,
+                       int32_t* best_chain, int64_t* chain_costs, int32_t* chain_tours, int32_t* chain_accepted,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+    return sa_search_ex(true, cost_matrix, N, chains, steps, t_start, t_end, seed, init_tours, best_perm, best_cost,
+                        best_chain, chain_costs, chain_tours, chain_accepted, workspace, workspace_bytes, stream);
+}
+
+int cc_sa_rd_search(const int32_t* cost_matrix, int32_t N, int32_t chains, int64_t steps, int32_t t_start, int32_t t_end,
+                    uint64_t seed, int32_t* best_perm, int64_t* best_cost, void* stream) {
+    return sa_search(true, cost_matrix, N, chains, steps, t_start, t_end, seed, best_perm, best_cost, stream);
 }
 
 int cc_init_tours(int32_t N, int64_t first, int64_t count, uint64_t seed, int32_t* tours, void* stream) {

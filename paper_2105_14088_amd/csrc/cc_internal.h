@@ -21,6 +21,8 @@ hipError_t launch_probes_percentile(const int32_t* samples, int N, int K, int ra
                                     hipStream_t s);
 hipError_t launch_sa_ring(const int32_t* c, int N, int chains, long long steps, int t_start, int t_end, uint64_t seed,
                           bool generate, int32_t* tours, int64_t* costs, int32_t* accepted, hipStream_t s);
+hipError_t launch_sa_rd(const int32_t* c, int N, int chains, long long steps, int t_start, int t_end, uint64_t seed,
+                        bool generate, int32_t* tours, int64_t* costs, int32_t* accepted, hipStream_t s);
 hipError_t launch_init_tours(int N, int64_t first, int64_t count, uint64_t seed, int32_t* tours, hipStream_t s);
 hipError_t launch_validate(const int32_t* c, int N, bool require_symmetric, int32_t* flags, hipStream_t s);
 

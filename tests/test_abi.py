@@ -93,6 +93,9 @@ def test_argument_errors_are_returned_before_any_launch():
     assert L.cc_sa_search_ex(*sa, fake, 1 << 30, null) == INVALID                        # temperature out of range
     sa[4], sa[5] = 1, -1
     assert L.cc_sa_search_ex(*sa, fake, 1 << 30, null) == INVALID
+    assert L.cc_sa_rd_search(fake, 48, 1, 10, 1, 1, 1, fake, fake, null) == UNSUPPORTED      # not a power of two
+    assert L.cc_sa_rd_search(fake, 64, 0, 10, 1, 1, 1, fake, fake, null) == INVALID
+    assert L.cc_sa_rd_search_ex(fake, 64, 4, 10, 1, 1, 1, null, fake, fake, null, null, null, null, null, 0, null) == WORKSPACE
     assert L.cc_sa_workspace_bytes(64, 0) == 0 and L.cc_sa_workspace_bytes(64, 4) >= 4 * 64 * 4
     assert L.cc_2opt_search(null, 64, 0, 1, 1, fake, fake, null) == INVALID
     assert L.cc_2opt_search(fake, 64, 0, 0, 1, fake, fake, null) == INVALID

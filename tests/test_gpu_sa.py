@@ -104,3 +104,53 @@ def test_simple_entry_point():
     torch.cuda.synchronize()
     want = oracle.sa_search(c, 16, 4000, 300, 0, SEED)
     assert int(cost.item()) == want["best_cost"] and np.array_equal(perm.cpu().numpy(), want["best_perm"])
+
+
+# ------------------------------------------------------------------------- halving-doubling model, pair neighbour
+def check_rd(c, chains, steps, ts, te, seed, init=None):
+    bufs = cc.cc_sa_rd_search_ex(dev(c), chains, steps, ts, te, seed, init_tours=None if init is None else dev(init))
+    torch.cuda.synchronize()
+    want = oracle.sa_rd_search(c, chains, steps, ts, te, seed, init)
+    assert np.array_equal(bufs.restart_costs.cpu().numpy(), want["costs"])
+    assert np.array_equal(bufs.restart_moves.cpu().numpy(), want["accepted"])
+    assert np.array_equal(bufs.restart_tours.cpu().numpy(), want["tours"])
+    assert (int(bufs.best_cost.item()), int(bufs.best_restart.item())) == (want["best_cost"], want["best_chain"])
+    assert np.array_equal(bufs.best_perm.cpu().numpy(), want["best_perm"])
+
+
+@pytest.mark.parametrize("n", [2, 4, 8, 16, 32, 64, 128, 256, 512, 1024])
+@pytest.mark.parametrize("symmetric", [True, False])
+def test_rd_chains_match_oracle(n, symmetric):
+    steps = 2000 if n <= 64 else (600 if n <= 256 else 250)
+    for hi, tag in ((3000, "few ties"), (3, "many ties"), (COST_MAX, "entries up to COST_MAX")):
+        c = random_matrix(n, 800 + n + hi % 13, symmetric=symmetric, lo=0, hi=hi)
+        for chains, ts, te in ((5, min(hi, 400), 0), (3, 0, 0)):
+            say(f"sa rd N={n} symmetric={symmetric} {tag} chains={chains} steps={steps} T={ts}->{te}")
+            check_rd(c, chains, steps, ts, te, SEED + n)
+
+
+@pytest.mark.parametrize("steps", [0, 1, 63, 64, 65, 129, 1000])
+def test_rd_step_counts_around_the_proposal_batch(steps):
+    say(f"sa rd N=64 steps={steps}")
+    check_rd(make_matrix(2), 6, steps, 300, 30, SEED)
+
+
+def test_rd_workload2_matrix_1024_chains_and_given_orders():
+    say("sa rd C2 matrix, 1024 chains x 5000 steps (sampled); given initial orders; simple entry point")
+    c = make_matrix(2)
+    chains, steps, ts, te = 1024, 5000, 300, 0
+    seed = WORKLOADS[2].search_seed
+    bufs = cc.cc_sa_rd_search_ex(dev(c), chains, steps, ts, te, seed)
+    torch.cuda.synchronize()
+    costs, tours, acc = bufs.restart_costs.cpu().numpy(), bufs.restart_tours.cpu().numpy(), bufs.restart_moves.cpu().numpy()
+    for r in np.unique(np.concatenate([np.arange(0, chains, 97), [chains - 1, int(bufs.best_restart.item())]])):
+        wc, wt, wa = oracle.sa_rd_chains(c, steps, ts, te, seed, int(r), int(r) + 1)
+        assert costs[r] == wc[0] and acc[r] == wa[0] and np.array_equal(tours[r], wt[0])
+    assert np.array_equal(costs, oracle.rd_cost_batch(c, tours))
+    assert int(bufs.best_cost.item()) == costs.min()
+    init = oracle.init_tours(SEED, 64, 7, first=50)
+    check_rd(c, 7, 1500, 200, 0, SEED, init)
+    perm, cost = cc.cc_sa_rd_search(dev(c), 12, 2000, 300, 0, SEED)
+    torch.cuda.synchronize()
+    want = oracle.sa_rd_search(c, 12, 2000, 300, 0, SEED)
+    assert int(cost.item()) == want["best_cost"] and np.array_equal(perm.cpu().numpy(), want["best_perm"])

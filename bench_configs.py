@@ -6,8 +6,7 @@ Workloads 1-5 are the parity-test configurations (matrix shapes and work amounts
 are pair-swap searches under the halving-doubling model on the matrices of workloads 2 and 4; "A64" / "A256" /
 "A1024" are simulated-annealing runs (chains x steps) on the matrices of workloads 2, 4 and 5.  Times are
 HIP-event times around the library call on the launch stream, median of `--reps` after one warm-up.
-`bench.py` remains the single-line benchmark of the N=64 workload; this script gives the per-workload
-table of the design doc.  Pass --oracle to time the CPU oracle beside each search (a bounded sample of
+`bench.py` remains the single-line benchmark of the N=64 workload; this script gives one line per workload.  Pass --oracle to time the CPU oracle beside each search (a bounded sample of
 restarts on one core).
 """
 import argparse

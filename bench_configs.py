@@ -1,13 +1,14 @@
 #!/usr/bin/env python3
 """Times every workload of the rank-order search on one MI355X and prints one JSON line per workload.
 
-Workloads 1-5 are the parity-test configurations (matrix shapes and work amounts in gen/workloads.py);
-"M64" is the batch-evaluation headline case (ring sum and max on 2^20 seeded orders at N=64); "S64" / "S256"
-are pair-swap searches under the halving-doubling model on the matrices of workloads 2 and 4; "A64" / "A256" /
-"A1024" are simulated-annealing runs (chains x steps) on the matrices of workloads 2, 4 and 5.  Times are
-HIP-event times around the library call on the launch stream, median of `--reps` after one warm-up.
-`bench.py` remains the single-line benchmark of the N=64 workload; this script gives one line per workload.  Pass --oracle to time the CPU oracle beside each search (a bounded sample of
-restarts on one core).
+Cases: C1-C5 the parity-test configurations (matrix shapes and work amounts in gen/workloads.py); M64* the
+batch-evaluation headline case (ring sum / max on 2^20 seeded orders at N=64, also with orders stored one byte
+per rank); R/B/T* halving-doubling, BCube and double-binary-tree batches; S* pair-swap searches under the
+halving-doubling model; A* / AR* simulated-annealing runs (ring / halving-doubling); P* cost matrices from
+probes.  Times are HIP-event times around the library call on the launch stream, median of `--reps` after one
+warm-up.  `bench.py` remains the single-line benchmark of the N=64 workload.  Pass --oracle to time the CPU
+oracle beside each case (a bounded sample, one core) and compare the sample bit for bit; --only takes a
+comma-separated list of case keys.
 """
 import argparse
 import json

@@ -43,7 +43,9 @@ template <bool WIDE>
 __device__ __forceinline__ void descend(const int32_t* m, int lane, int& t, long long& cost, int& applied_out) {
     using K = typename std::conditional<WIDE, long long, int>::type;
     using UK = typename std::conditional<WIDE, unsigned long long, unsigned>::type;
-    const int rank_bits = ((lane + kN - 1) & (kN - 1)) << 8;
+    const int rank_a = (lane + kN - 1) & (kN - 1);
+    const int rank_bits = rank_a << 8;
+    const int id_base = lane * kN, id_base_flipped = kN + rank_a;
     const char* mbytes = (const char*)m;
     long long cur = 0;
     int applied = 0;
@@ -80,19 +82,19 @@ __device__ __forceinline__ void descend(const int32_t* m, int lane, int& t, long
             best = key < best ? key : best;
         }
         best = (K)((UK)best + (UK)negf);
-        // partner -> move id (lowest id among this lane's best partners is already selected by rank)
-        const int low = (int)best & ((1 << kSh) - 1);
+        // partner -> move id (lowest id among this lane's best partners is already selected by rank).  With
+        // r = rank(b) and ra = rank(lane): the move is (lane, r) when r >= ra (b lies after the lane, or b = 0), and
+        // (r + 1, ra) otherwise, i.e. id = lane*64 + r or r*64 + 64 + ra.
+        const int r = ((int)best >> 8) & (kN - 1);
         const K delta = best >> kSh;
-        const int b = ((low >> 8) + 1) & (kN - 1);
-        const int lo = min(lane, b), hi = max(lane, b);
-        const int mi_l = lo ? lo : hi, mj_l = lo ? hi - 1 : kN - 1;
-        const K key2 = (K)(((UK)delta << kIdBits) | (UK)(mi_l * kN + mj_l));
+        const int id_l = r < rank_a ? (r << 6) + id_base_flipped : id_base + r;
+        const K key2 = (K)(((UK)delta << kIdBits) | (UK)id_l);
         const K win = wave_min_uniform(key2);
         const K dwin = win >> kIdBits;
         if (dwin >= 0) break;
         const int id = (int)win & ((1 << kIdBits) - 1);
         const int mi = id >> 6, mj = id & (kN - 1);
-        const int src = (lane >= mi && lane <= mj) ? mi + mj - lane : lane;
+        const int src = (unsigned)(lane - mi) <= (unsigned)(mj - mi) ? mi + mj - lane : lane;
         t = __shfl(t, src, kWave);
         cur += (long long)dwin;
         ++applied;

@@ -121,12 +121,17 @@ __global__ __launch_bounds__(256) void sa_ring_kernel(const int32_t* __restrict_
 }
 
 // ---------------------------------------------------------- halving-doubling model, pair neighbour (cc_sa_rd_search)
-// Same round structure: 64 proposals against the current order, commit the first accepted one.  A proposal
-// exchanges ranks p and q; per round only the links of p and q change, so the new round cost is
+// Under this max-type objective most proposals are neutral and therefore accepted, so speculation over later steps
+// does not pay; instead the wave scores ONE proposal per step with its lanes spread over the work.  A proposal
+// exchanges ranks p and q; per round only the links of p and of q change, so the new round cost is
 // max(link of p re-evaluated, link of q re-evaluated, largest link among the others), the last term being one of
-// the round's three largest links.  Those three (value and lower rank of the link) are wave-uniform state,
-// recomputed for every round after a commit: each lane evaluates its share of the N/2 links of the round and three
-// wave-wide max-reductions over (value << 9 | link index) pick them (any choice among equal values is valid).
+// the round's three largest links.  Lane l handles round l >> 2, side (l >> 1) & 1 (p's or q's link) and direction
+// l & 1 of that link: one gather per lane, the two directions and the two sides meet through quad permutes, the
+// rounds through one wave sum.  The four lanes of a round also hold the round's three largest links
+// (keys value << 10 | lower rank).  After a commit they update them from what they already have: the old three
+// without p's and q's links, plus those two links' new values; that is the round's true top three whenever its
+// third key is not below the old third value (every other link is at most that); otherwise the whole wave
+// recomputes the round from the order (three max-reductions over value << 9 | link index).
 template <int LOGN>
 __global__ __launch_bounds__(256) void sa_rd_kernel(const int32_t* __restrict__ c, int chains, long long steps,
                                                     int t_start, int t_end, uint64_t seed,
@@ -135,7 +140,7 @@ __global__ __launch_bounds__(256) void sa_rd_kernel(const int32_t* __restrict__ 
     constexpr int N = 1 << LOGN;
     constexpr bool LDS_MATRIX = LOGN <= 7;
     constexpr int LINKS = N / 2;
-    constexpr int U = LINKS > 64 ? LINKS / 64 : 1;      // links per lane and round
+    constexpr int U = LINKS > 64 ? LINKS / 64 : 1;      // links per lane when the wave recomputes a round
     extern __shared__ int32_t sm[];
     const int lane = lane_id(), wv = threadIdx.x >> 6;
     int32_t* t = sm + wv * 2 * N;
@@ -158,106 +163,125 @@ __global__ __launch_bounds__(256) void sa_rd_kernel(const int32_t* __restrict__ 
     }
     wave_lds_sync();
 
-    int tv[LOGN][3], tj[LOGN][3];                       // the three largest links of every round: value, lower rank
-    auto refresh = [&]() {                              // from the order in LDS; returns the cost
-        int cost = 0;
+    const int my_round = lane >> 2, side = (lane >> 1) & 1, dir = lane & 1;
+    const bool in_play = my_round < LOGN;
+    const int my_bit = 1 << (in_play ? my_round : 0);
+    int k1 = -1, k2 = -1, k3 = -1;                      // this lane's round: its three largest links, value << 10 | lower rank
+
+    // the wave recomputes round kk from the order in LDS; the lanes of that round take the result
+    auto recompute_round = [&](int kk) {
+        const int bit = 1 << kk;
+        int key[U];
 #pragma unroll
-        for (int k = 0; k < LOGN; ++k) {
-            const int bit = 1 << k;
-            int key[U];
+        for (int u = 0; u < U; ++u) {
+            const int i = lane + 64 * u;                // link index
+            const int j = ((i >> kk) << (kk + 1)) | (i & (bit - 1));
+            key[u] = -1;
+            if (i < LINKS) {
+                const int a = t[j], b = t[j | bit];
+                key[u] = (max(M(a, b), M(b, a)) << 9) | i;
+            }
+        }
+        int found[3];
+        int taken0 = -2, taken1 = -2;
+#pragma unroll
+        for (int pass = 0; pass < 3; ++pass) {
+            int best = -1;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int i = lane + 64 * u;            // link index
-                const int j = ((i >> k) << (k + 1)) | (i & (bit - 1));
-                key[u] = -1;
-                if (i < LINKS) {
-                    const int a = t[j], b = t[j | bit];
-                    key[u] = (max(M(a, b), M(b, a)) << 9) | i;
-                }
+                const int i = lane + 64 * u;
+                best = max(best, (i == taken0 || i == taken1) ? -1 : key[u]);
             }
-            int taken0 = -2, taken1 = -2;
-#pragma unroll
-            for (int pass = 0; pass < 3; ++pass) {
-                int best = -1;
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int i = lane + 64 * u;
-                    best = max(best, (i == taken0 || i == taken1) ? -1 : key[u]);
-                }
-                best = wave_max(best);
-                const int i = best & 511;
-                tv[k][pass] = best >> 9;                // -1 when the round has fewer links
-                tj[k][pass] = best < 0 ? -1 : (((i >> k) << (k + 1)) | (i & (bit - 1)));
-                if (pass == 0) taken0 = best < 0 ? -2 : i;
-                else taken1 = best < 0 ? -2 : i;
-            }
-            cost += tv[k][0];
+            best = wave_max(best);
+            const int i = best & 511;
+            found[pass] = best < 0 ? -1 : (((best >> 9) << 10) | ((i >> kk) << (kk + 1)) | (i & (bit - 1)));
+            if (pass == 0) taken0 = best < 0 ? -2 : i;
+            else taken1 = best < 0 ? -2 : i;
         }
-        return cost;
+        if (my_round == kk) {
+            k1 = found[0];
+            k2 = found[1];
+            k3 = found[2];
+        }
     };
-
-    int cur = refresh();
+    for (int kk = 0; kk < LOGN; ++kk) recompute_round(kk);
+    int cur = wave_sum((in_play && (lane & 3) == 0) ? (k1 >> 10) : 0);
     int best = cur;
     int acc = 0;
     const uint64_t chain_hi = (uint64_t)(uint32_t)r << 32;
-    long long s = 0;
-    while (s < steps) {
-        const long long step = s + lane;
-        const bool active = step < steps;
-        const uint64_t w = splitmix64_at(seed, (chain_hi | (uint32_t)(kDrawBase + (uint32_t)step)) + 1u);
+
+    for (long long s = 0; s < steps; ++s) {
+        const uint64_t w = splitmix64_at(seed, (chain_hi | (uint32_t)(kDrawBase + (uint32_t)s)) + 1u);
         const int p = (int)(((uint32_t)(w >> 43) * (uint32_t)N) >> 21);
         const int d = 1 + (int)((((uint32_t)(w >> 22) & 0x1FFFFFu) * (uint32_t)(N - 1)) >> 21);
         const int q = (p + d) & (N - 1);
         const int u = (int)((uint32_t)w & 0x3FFFFFu) + 1;
-        const int tp = t[p], tq = t[q];
-        int total = 0;
-#pragma unroll
-        for (int k = 0; k < LOGN; ++k) {
-            const int bit = 1 << k;
-            const int pb = t[p ^ bit], qb = t[q ^ bit];
-            const int link_p = max(M(tq, pb), M(pb, tq));           // rank p now holds t[q]
-            const int link_q = max(M(tp, qb), M(qb, tp));           // rank q now holds t[p]
-            const int lp = p & ~bit, lq = q & ~bit;
-            const bool f0 = tj[k][0] != lp && tj[k][0] != lq, f1 = tj[k][1] != lp && tj[k][1] != lq;
-            const int others = f0 ? tv[k][0] : (f1 ? tv[k][1] : tv[k][2]);
-            const int stage = max(others, max(link_p, link_q));
-            total += (q == (p ^ bit)) ? tv[k][0] : stage;
-        }
+        // this lane's link: rank `mine` (p or q) receives the node of the other rank; its partner keeps its node
+        const int mine = side ? q : p, other = side ? p : q;
+        const int x = t[other], y = t[mine ^ my_bit];
+        const int val = in_play ? (dir ? M(y, x) : M(x, y)) : 0;
+        const int link = max(val, __builtin_amdgcn_update_dpp(val, val, 0xB1, 0xf, 0xf, true));        // both directions
+        const int link_other = __builtin_amdgcn_update_dpp(link, link, 0x4E, 0xf, 0xf, true);          // the other side
+        const int link_p = side ? link_other : link, link_q = side ? link : link_other;
+        const int lp = p & ~my_bit, lq = q & ~my_bit;
+        const bool same_link = lp == lq;               // q = p xor bit: the link keeps both nodes and its value
+        const int j1 = k1 & 1023, j2 = k2 & 1023;
+        const bool f1 = j1 != lp && j1 != lq, f2 = j2 != lp && j2 != lq;
+        const int others = (f1 ? k1 : (f2 ? k2 : k3)) >> 10;       // -1 when the round has no other link
+        const int stage = same_link ? (k1 >> 10) : max(others, max(link_p, link_q));
+        const int total = wave_sum((in_play && (lane & 3) == 0) ? stage : 0);
         const int delta = total - cur;
-        bool accept = active;
+        bool accept = true;
         if (delta > 0) {
             const int e = 31 - __clz(u);
             const int mant = u - (1 << e);
             const int frac = e >= 12 ? (mant >> (e - 12)) : (mant << (12 - e));
             const long long E = 22 * 4096 - (e * 4096 + frac);
-            const long long num = (long long)t_start * (steps - step) + (long long)t_end * step;
-            accept = active && ((long long)delta * 4096 * steps <= num * E);
+            const long long num = (long long)t_start * (steps - s) + (long long)t_end * s;
+            accept = (long long)delta * 4096 * steps <= num * E;
         }
-        const unsigned long long mask = __ballot(accept);
-        if (mask == 0ull) {
-            s += kWave;
-            continue;
-        }
-        const int kk = __ffsll((long long)mask) - 1;
-        const int sp = __shfl(p, kk, kWave), sq = __shfl(q, kk, kWave), dk = __shfl(delta, kk, kWave);
+        if (!accept) continue;                          // wave-uniform
         wave_lds_sync();                               // every lane has read the order before it changes
+        const int node_q = __builtin_amdgcn_readlane(x, 0), node_p = __builtin_amdgcn_readlane(x, 2);   // sides 0 and 1
         if (lane == 0) {
-            const int a = t[sp], b = t[sq];
-            t[sp] = b;
-            t[sq] = a;
+            t[p] = node_q;
+            t[q] = node_p;
+        }
+        cur += delta;
+        ++acc;
+        // the round's three largest links after the exchange
+        bool stale = false;
+        if (in_play && !same_link) {
+            const int f3 = (k3 & 1023) != lp && (k3 & 1023) != lq;
+            int c0 = f1 ? k1 : -1, c1 = f2 ? k2 : -1, c2 = (f3 && k3 >= 0) ? k3 : -1;
+            if (k1 < 0) c0 = -1;
+            if (k2 < 0) c1 = -1;
+            int c3 = (link_p << 10) | lp, c4 = (link_q << 10) | lq;
+            const int bound = k3 >> 10;                // every link outside the candidates is at most this
+            const int n1 = max(max(c0, c1), max(max(c2, c3), c4));
+            c0 = c0 == n1 ? -1 : c0; c1 = c1 == n1 ? -1 : c1; c2 = c2 == n1 ? -1 : c2;
+            c3 = c3 == n1 ? -1 : c3; c4 = c4 == n1 ? -1 : c4;
+            const int n2 = max(max(c0, c1), max(max(c2, c3), c4));
+            c0 = c0 == n2 ? -1 : c0; c1 = c1 == n2 ? -1 : c1; c2 = c2 == n2 ? -1 : c2;
+            c3 = c3 == n2 ? -1 : c3; c4 = c4 == n2 ? -1 : c4;
+            const int n3 = max(max(c0, c1), max(max(c2, c3), c4));
+            stale = LINKS > 3 && (n3 >> 10) < bound;
+            k1 = n1; k2 = n2; k3 = n3;
         }
         wave_lds_sync();
-        cur += dk;
-        ++acc;
-        refresh();
+        unsigned long long redo = __ballot(stale);
+        while (redo) {
+            const int kk = (__ffsll((long long)redo) - 1) >> 2;
+            recompute_round(kk);
+            redo &= ~(0xFull << (4 * kk));
+        }
         if (cur < best) {
             best = cur;
-            for (int x = lane; x < N; x += kWave) bt[x] = t[x];
+            for (int z = lane; z < N; z += kWave) bt[z] = t[z];
         }
-        s += kk + 1;
     }
     wave_lds_sync();
-    for (int x = lane; x < N; x += kWave) tours[r * N + x] = bt[x];
+    for (int z = lane; z < N; z += kWave) tours[r * N + z] = bt[z];
     if (lane == 0) {
         costs[r] = (int64_t)best;
         accepted[r] = acc;

@@ -464,8 +464,11 @@ hipError_t launch_dbt_cost_batch(const int32_t* c, int N, const int32_t* perms, 
 }
 
 // --------------------------------------------------------------------------------- initial orders
-// One wave per order: lanes draw the N-1 swap partners in parallel, lane 0 replays the swaps in
-// order (they are inherently sequential), all lanes store the result coalesced.
+// One wave per order.  N <= 64: no serial chain - lane v follows node v through the shuffle: at step k (k = N-1 .. 1)
+// ranks k and j_k swap, so a node sitting at rank k moves to j_k and a node sitting at j_k moves to k, where it
+// stays (later steps only touch ranks below k); the partners j_k are drawn in parallel, one per lane, and read
+// step by step; each lane finally stores its node at the rank where it ended.  Larger N: the partners are drawn in
+// parallel, lane 0 replays the swaps in order in LDS, all lanes store the result coalesced.
 __global__ __launch_bounds__(256) void init_tours_kernel(int N, int64_t first, int64_t count, uint64_t seed,
                                                          int32_t* __restrict__ tours) {
     extern __shared__ int32_t sm[];
@@ -476,6 +479,17 @@ __global__ __launch_bounds__(256) void init_tours_kernel(int N, int64_t first, i
     const int64_t nwaves = (int64_t)gridDim.x * 4;
     for (int64_t w = wave; w < count; w += nwaves) {
         const uint32_t r = (uint32_t)(first + w);
+        if (N <= kWave) {
+            const int mine = (lane > 0 && lane < N) ? shuffle_partner(seed, r, lane) : 0;
+            int pos = lane;
+            for (int k = N - 1; k >= 1; --k) {
+                const int j = __builtin_amdgcn_readlane(mine, k);
+                const int moved = (pos == k) ? j : pos;
+                pos = (pos == j) ? k : moved;
+            }
+            if (lane < N) tours[w * N + pos] = lane;
+            continue;
+        }
         for (int k = lane; k < N; k += kWave) {
             t[k] = k;
             partner[k] = k ? shuffle_partner(seed, r, k) : 0;

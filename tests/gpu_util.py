@@ -4,7 +4,6 @@ import sys
 import numpy as np
 import torch
 
-import oracle
 import paper_2105_14088_amd as cc
 
 

@@ -1,7 +1,6 @@
 """Pins for the oracle's 2-opt neighbourhood, descent and restarts (Section 4.3 neighbour search made
 deterministic): fast move values against apply-and-recompute, structure of the move set, local-optimum
 certificates, brute-force lower bounds, and the restart generator against published SplitMix64 values."""
-import math
 import os
 
 import numpy as np

@@ -5,8 +5,8 @@
 // suffix tables live in LDS; thread j scores the moves (i, j) for i = j-1 down to 1 so that the
 // "inside the reversed span" aggregate grows by one hop per step; keys (value << 32 | move id) are
 // min-reduced over the workgroup, which makes the lowest-id tie-break independent of the order in
-// which moves are visited.  Handles every objective and every N <= 1024; the matrix is gathered
-// through L2.
+// which moves are visited.  Handles every objective and every N <= 1024; the matrix sits in LDS for
+// N <= 96 and is gathered through L2 above.
 #include "cc_device.h"
 #include "cc_internal.h"
 
@@ -16,6 +16,10 @@ using namespace ccd;
 namespace {
 
 constexpr unsigned long long kNoMove = ~0ull;
+// Up to this N the general kernel keeps the matrix in LDS: 7 N + N^2 int32 words are then at most 40 KiB, so four
+// workgroups still share a compute unit (measured at 1024 restarts: N = 96 1.75x faster than through L2, N = 100,
+// where only three fit, no faster).
+constexpr int kGeneralLdsMatrixMaxN = 96;
 
 template <bool IS_MAX>
 __device__ __forceinline__ int comb(int a, int b) { return IS_MAX ? max(a, b) : a + b; }
@@ -40,7 +44,8 @@ __device__ void block_scan(int32_t* arr, int N) {
     }
 }
 
-template <int OBJ>
+// LDS_MATRIX: the matrix is staged once per workgroup in LDS behind the seven rank arrays (small N).
+template <int OBJ, bool LDS_MATRIX>
 __global__ void twoopt_general_kernel(const int32_t* __restrict__ c, int N, int32_t* __restrict__ tours,
                                       int64_t* __restrict__ costs, int32_t* __restrict__ moves,
                                       const int32_t* __restrict__ skip_if_small) {
@@ -65,7 +70,10 @@ __global__ void twoopt_general_kernel(const int32_t* __restrict__ c, int N, int3
     const int64_t r = blockIdx.x;
     // entries are clamped to the contract range: all int32 arithmetic below is then exact, every applied
     // move lowers the true cost, and the descent terminates whatever the buffer holds
-    auto C = [&](int a, int b2) { return clampi(c[a * N + b2], 0, (1 << 21) - 1); };
+    int32_t* m = sb + N;
+    if (LDS_MATRIX)
+        for (int e = tid; e < N * N; e += blockDim.x) m[e] = clampi(c[e], 0, (1 << 21) - 1);
+    auto C = [&](int a, int b2) { return LDS_MATRIX ? m[a * N + b2] : clampi(c[a * N + b2], 0, (1 << 21) - 1); };
     if (tid < N) t[tid] = clampi(tours[r * N + tid], 0, N - 1);
     __syncthreads();
 
@@ -242,9 +250,20 @@ template <int OBJ>
 hipError_t launch_general(const int32_t* c, int N, int restarts, int32_t* tours, int64_t* costs, int32_t* moves,
                           const int32_t* skip_if_small, hipStream_t s) {
     const int threads = ((N + 63) / 64) * 64;
-    const size_t lds = sizeof(int32_t) * 7 * (size_t)N;
-    hipLaunchKernelGGL((twoopt_general_kernel<OBJ>), dim3(restarts), dim3(threads), lds, s, c, N, tours, costs, moves,
-                       skip_if_small);
+    if (N <= kGeneralLdsMatrixMaxN) {
+        const size_t lds = sizeof(int32_t) * (7 * (size_t)N + (size_t)N * N);
+        if (lds > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute((const void*)twoopt_general_kernel<OBJ, true>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL((twoopt_general_kernel<OBJ, true>), dim3(restarts), dim3(threads), lds, s, c, N, tours, costs,
+                           moves, skip_if_small);
+    } else {
+        const size_t lds = sizeof(int32_t) * 7 * (size_t)N;
+        hipLaunchKernelGGL((twoopt_general_kernel<OBJ, false>), dim3(restarts), dim3(threads), lds, s, c, N, tours, costs,
+                           moves, skip_if_small);
+    }
     return hipGetLastError();
 }
 

@@ -56,10 +56,15 @@ def main():
     def emit(d):
         print(json.dumps(d), flush=True)
 
-    def search_case(wid):
+    def search_case(wid, n=None, restarts=None, name=None):
         w = WORKLOADS[wid]
         obj = cc.OBJECTIVES[w.objective]
         c_host = make_matrix(wid)
+        if n is not None:         # the workload's hierarchy and value ranges at another size
+            from gen import hierarchical_matrix
+            import dataclasses
+            c_host = hierarchical_matrix(n, w.group_sizes, w.level_ranges, w.sigma, True, w.matrix_seed + n)
+            w = dataclasses.replace(w, n=n, restarts=restarts, name=name)
         c = torch.from_numpy(c_host).cuda()
         bufs = cc.SearchBuffers(w.n, obj, w.restarts, c.device)
         ms = timed(lambda: cc.cc_2opt_search_ex(c, obj, w.restarts, w.search_seed, buffers=bufs), args.reps)
@@ -72,7 +77,7 @@ def main():
              "best_cost": int(bufs.best_cost.item())}
         if args.oracle:
             import oracle
-            sample = min(w.restarts, {64: 256, 256: 16, 1024: 1}[w.n])
+            sample = min(w.restarts, {64: 256, 256: 16, 512: 4, 1024: 1}[w.n])
             t0 = time.perf_counter()
             oc, ot, om = oracle.restarts(c_host, obj, w.search_seed, 0, sample)
             dt = time.perf_counter() - t0
@@ -193,6 +198,7 @@ def main():
         ("C4", lambda: search_case(4)),
         ("C5rd", lambda: batch_case("C5_n1024_rd_65536", 5, "rd", 0, 65536)),
         ("C5", lambda: search_case(5)),
+        ("C512", lambda: search_case(5, n=512, restarts=768, name="C512_n512_sum_768_restarts")),
         ("S64", lambda: swap_case("S64_n64_rd_swap_1024", 2, 1024)),
         ("S256", lambda: swap_case("S256_n256_rd_swap_256", 4, 256)),
         ("A64", lambda: sa_case("A64_n64_sa_1024x100000", 2, 1024, 100000, 300, 0)),

@@ -307,10 +307,10 @@ hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, uin
             e = launch_2opt_sum_multi(c, N, restarts, tours, costs, moves, flags, s);
             if (e != hipSuccess) return e;
             e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, s);
-        } else if (objective == 0 && N == 1024) {
+        } else if (objective == 0 && (N == 512 || N == 1024)) {
             e = launch_matrix_max(c, N, flags, s);
             if (e != hipSuccess) return e;
-            e = launch_2opt_sum_n1024(c, mat16, restarts, tours, costs, moves, flags, s);
+            e = launch_2opt_sum_n1024(c, N, mat16, restarts, tours, costs, moves, flags, s);
             if (e != hipSuccess) return e;
             e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, s);
         } else {

@@ -1,5 +1,6 @@
-// 2-opt descent for N = 1024, ring-sum objective on a symmetric matrix: one 16-wave workgroup per
-// restart.  The matrix (2 MiB as 16-bit entries) cannot live in LDS, so the sweep is organised by
+// 2-opt descent for N = 512 and N = 1024, ring-sum objective on a symmetric matrix: one workgroup of
+// N/64 waves per restart (the text below gives the N = 1024 figures; N = 512 has half the slots, rows and
+// waves).  The matrix (2 MiB as 16-bit entries) cannot live in LDS, so the sweep is organised by
 // matrix ROW: every move needs G(a-1, b-1) + G(a, b) with G(p, q) = c[t[p]][t[q]], i.e. one entry of
 // row t[a] and one of row t[a-1].  A wave owns 64 consecutive ranks a; for each it streams row t[a]
 // (2 KiB, coalesced, L2-resident) straight into one of its four private LDS buffers
@@ -25,25 +26,43 @@ using namespace ccd;
 
 namespace {
 
-constexpr int N = 1024;
-constexpr int kWaves = 16;
-constexpr int kSlots = 8;
-constexpr int kRankBits = 11;
-constexpr int kRankMask = (1 << kRankBits) - 1;
 constexpr int kPad = 8;                      // the partner arrays are indexed from -8
-constexpr int kWin = kPad + N + 64 * kSlots; // entry x holds rank (x + 2) mod N, x in [-8, 1536)
-constexpr int kRowBytes = N * 2;
 constexpr int kBufs = 4;                     // row buffers per wave: the current row and three in flight
 
-struct Layout {
+template <int LOGN>
+struct Shape {
+    static constexpr int N = 1 << LOGN;
+    static constexpr int kWaves = N / 64;
+    static constexpr int kSlots = N / 128;                   // diagonals per lane: 8 (N = 1024) or 4 (N = 512)
+    static constexpr int kRankBits = LOGN + 1;
+    static constexpr int kRankMask = (1 << kRankBits) - 1;
+    static constexpr int kWin = kPad + N + 64 * kSlots;      // entry x holds rank (x + 2) mod N, x in [-8, N + 64 kSlots)
+    static constexpr int kRowBytes = N * 2;
+    static constexpr int kRowLoads = kRowBytes / 1024;       // 16-byte loads per lane and row: 2 or 1
     static constexpr size_t t = 0;                                   // int32 [N]   tour
     static constexpr size_t f = t + sizeof(int32_t) * N;             // int32 [N]   hop into each rank
     static constexpr size_t tw = f + sizeof(int32_t) * N;            // int32 [kWin] column byte offset of the partner
-    static constexpr size_t kw = tw + sizeof(int32_t) * kWin;        // int32 [kWin] -f[b] << 11 | 2b+1
+    static constexpr size_t kw = tw + sizeof(int32_t) * kWin;        // int32 [kWin] -f[b] << kRankBits | 2b+1
     static constexpr size_t red = kw + sizeof(int32_t) * kWin;       // int32 [2 * kWaves + 2]
     static constexpr size_t rows = (red + sizeof(int32_t) * 64 + 255) & ~(size_t)255;   // uint16 [kWaves][kBufs][N]
     static constexpr size_t total = rows + (size_t)kWaves * kBufs * kRowBytes;
 };
+
+// waits until at most `rows_in_flight` of this wave's row transfers are outstanding
+template <int ROW_LOADS>
+__device__ __forceinline__ void wait_rows(int rows_in_flight) {
+    if (ROW_LOADS == 2) {
+        if (rows_in_flight == 3) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        else if (rows_in_flight == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else if (rows_in_flight == 1) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {
+        if (rows_in_flight == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+        else if (rows_in_flight == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+        else if (rows_in_flight == 1) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+}
 
 // 16-bit copy of the matrix (entries clamped); skipped when the maximum does not fit
 __global__ __launch_bounds__(256) void matrix_to_u16_kernel(const int32_t* __restrict__ c, int n2,
@@ -56,11 +75,16 @@ __global__ __launch_bounds__(256) void matrix_to_u16_kernel(const int32_t* __res
     }
 }
 
-__global__ __launch_bounds__(64 * kWaves) void twoopt_sum_n1024_kernel(const uint16_t* __restrict__ c16, int restarts,
-                                                                       int32_t* __restrict__ tours,
-                                                                       int64_t* __restrict__ costs,
-                                                                       int32_t* __restrict__ moves,
-                                                                       const int32_t* __restrict__ flags) {
+template <int LOGN>
+__global__ __launch_bounds__(1 << LOGN) void twoopt_sum_n1024_kernel(const uint16_t* __restrict__ c16, int restarts,
+                                                                     int32_t* __restrict__ tours,
+                                                                     int64_t* __restrict__ costs,
+                                                                     int32_t* __restrict__ moves,
+                                                                     const int32_t* __restrict__ flags) {
+    using Layout = Shape<LOGN>;
+    constexpr int N = Layout::N, kWaves = Layout::kWaves, kSlots = Layout::kSlots, kRankBits = Layout::kRankBits;
+    constexpr int kRankMask = Layout::kRankMask, kRowBytes = Layout::kRowBytes, kRowLoads = Layout::kRowLoads;
+    constexpr int kGroups = 64 / kSlots;         // a lane's window of kSlots partners is replaced every kSlots rows
     extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
     if (flags[0] >= (1 << 16)) return;
     int32_t* T = (int32_t*)(smem + Layout::t);
@@ -83,17 +107,25 @@ __global__ __launch_bounds__(64 * kWaves) void twoopt_sum_n1024_kernel(const uin
     bool first = true;
     const int a0 = wv * 64;
     // Row `node` of the 16-bit matrix -> this wave's buffer `buf`, global memory to LDS without passing through
-    // registers: lane l moves bytes [16l, 16l+16) and [1024+16l, 1024+16l+16) of the row; M0 holds the LDS address
-    // of the buffer and the instruction offset applies to both addresses.  Completion is tracked by vmcnt.
+    // registers: lane l moves bytes [16l, 16l+16) and, for 2 KiB rows, [1024+16l, 1024+16l+16) of the row; M0 holds
+    // the LDS address of the buffer and the instruction offset applies to both addresses.  Completion is tracked by
+    // vmcnt.
     auto row_dma = [&](int node, int buf) {
         const void* rowptr = (const void*)(c16 + (size_t)node * N);
         const unsigned dst = lds_rows + (unsigned)buf * kRowBytes;
-        asm volatile(
-            "s_mov_b32 m0, %2\n\t"
-            "s_nop 0\n\t"
-            "global_load_lds_dwordx4 %0, %1\n\t"
-            "global_load_lds_dwordx4 %0, %1 offset:1024"
-            :: "v"(lane16), "s"(rowptr), "s"(dst) : "memory");
+        if (kRowLoads == 2)
+            asm volatile(
+                "s_mov_b32 m0, %2\n\t"
+                "s_nop 0\n\t"
+                "global_load_lds_dwordx4 %0, %1\n\t"
+                "global_load_lds_dwordx4 %0, %1 offset:1024"
+                :: "v"(lane16), "s"(rowptr), "s"(dst) : "memory");
+        else
+            asm volatile(
+                "s_mov_b32 m0, %2\n\t"
+                "s_nop 0\n\t"
+                "global_load_lds_dwordx4 %0, %1"
+                :: "v"(lane16), "s"(rowptr), "s"(dst) : "memory");
     };
     for (;;) {
         // the wave's first rows (ranks a0-1, a0, a0+1, a0+2) are requested before anything else so that their L2
@@ -133,13 +165,11 @@ __global__ __launch_bounds__(64 * kWaves) void twoopt_sum_n1024_kernel(const uin
         const int row_rank = (a0 + lane) ? 2 * (a0 + lane) : kRankMask;
         const int gb = a0 + kSlots * lane;                              // window of row a0 starts at entry gb
         int cwt[kSlots], cwk[kSlots], nwt[kSlots], nwk[kSlots], dprev[kSlots], best[kSlots];
-        {
-            const int4 a = *(const int4*)(TW + gb), b = *(const int4*)(TW + gb + 4);
-            const int4 c4 = *(const int4*)(KW + gb), d4 = *(const int4*)(KW + gb + 4);
-            cwt[0] = a.x + wbase; cwt[1] = a.y + wbase; cwt[2] = a.z + wbase; cwt[3] = a.w + wbase;
-            cwt[4] = b.x + wbase; cwt[5] = b.y + wbase; cwt[6] = b.z + wbase; cwt[7] = b.w + wbase;
-            cwk[0] = c4.x; cwk[1] = c4.y; cwk[2] = c4.z; cwk[3] = c4.w;
-            cwk[4] = d4.x; cwk[5] = d4.y; cwk[6] = d4.z; cwk[7] = d4.w;
+#pragma unroll
+        for (int h = 0; h < kSlots; h += 4) {
+            const int4 a = *(const int4*)(TW + gb + h), c4 = *(const int4*)(KW + gb + h);
+            cwt[h] = a.x + wbase; cwt[h + 1] = a.y + wbase; cwt[h + 2] = a.z + wbase; cwt[h + 3] = a.w + wbase;
+            cwk[h] = c4.x; cwk[h + 1] = c4.y; cwk[h + 2] = c4.z; cwk[h + 3] = c4.w;
         }
 #pragma unroll
         for (int k = 0; k < kSlots; ++k) best[k] = 0x7fffffff;
@@ -147,36 +177,29 @@ __global__ __launch_bounds__(64 * kWaves) void twoopt_sum_n1024_kernel(const uin
         // row a0-1 only provides the "previous row" gathers of row a0; it sits in buffer 3
         {
             const int extra = TW[gb - 1] + wbase;
-            asm volatile("s_waitcnt vmcnt(6)" ::: "memory");      // rows a0, a0+1, a0+2 may still be in flight
+            wait_rows<kRowLoads>(3);                              // rows a0, a0+1, a0+2 may still be in flight
             dprev[0] = *(const uint16_t*)(smem + extra + 3 * kRowBytes);
 #pragma unroll
             for (int k = 1; k < kSlots; ++k) dprev[k] = *(const uint16_t*)(smem + cwt[k - 1] + 3 * kRowBytes);
         }
 #pragma unroll 1
-        for (int g = 0; g < 8; ++g) {
+        for (int g = 0; g < kGroups; ++g) {
             const int nb = gb + kSlots * (g + 1);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int q = 8 * g + j;                 // row a0 + q, buffer q & 3 = j & 3
-                // the next window is fetched in two halves, each just before its first use
-                if (j == 0) {
-                    const int4 a = *(const int4*)(TW + nb), c4 = *(const int4*)(KW + nb);
-                    nwt[0] = a.x + wbase; nwt[1] = a.y + wbase; nwt[2] = a.z + wbase; nwt[3] = a.w + wbase;
-                    nwk[0] = c4.x; nwk[1] = c4.y; nwk[2] = c4.z; nwk[3] = c4.w;
-                }
-                if (j == 4) {
-                    const int4 b = *(const int4*)(TW + nb + 4), d4 = *(const int4*)(KW + nb + 4);
-                    nwt[4] = b.x + wbase; nwt[5] = b.y + wbase; nwt[6] = b.z + wbase; nwt[7] = b.w + wbase;
-                    nwk[4] = d4.x; nwk[5] = d4.y; nwk[6] = d4.z; nwk[7] = d4.w;
+            for (int j = 0; j < kSlots; ++j) {
+                const int q = kSlots * g + j;            // row a0 + q, buffer q & 3 = j & 3
+                // the next window is fetched four entries at a time, each part just before its first use
+                if ((j & 3) == 0) {
+                    const int4 a = *(const int4*)(TW + nb + j), c4 = *(const int4*)(KW + nb + j);
+                    nwt[j] = a.x + wbase; nwt[j + 1] = a.y + wbase; nwt[j + 2] = a.z + wbase; nwt[j + 3] = a.w + wbase;
+                    nwk[j] = c4.x; nwk[j + 1] = c4.y; nwk[j + 2] = c4.z; nwk[j + 3] = c4.w;
                 }
                 // buffer (q+3) & 3 was last read by row q-1: its gathers have returned once lgkmcnt is 0
-                const bool tail = (g == 7) && (j >= 5);          // rows 61..63: nothing left to request
+                const bool tail = (g == kGroups - 1) && (j >= kSlots - 3);   // rows 61..63: nothing left to request
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 if (!tail) row_dma(__builtin_amdgcn_readlane(row_node, q + 3), (j + 3) & 3);
-                if (!tail) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-                else if (j == 5) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-                else if (j == 6) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                if (!tail) wait_rows<kRowLoads>(3);
+                else wait_rows<kRowLoads>(kSlots - 1 - j);        // 2, 1, 0 rows still in flight
                 const int negfa = __builtin_amdgcn_readlane(row_negf, q);
                 const int rank2a = __builtin_amdgcn_readlane(row_rank, q);
 #pragma unroll
@@ -234,7 +257,7 @@ __global__ __launch_bounds__(64 * kWaves) void twoopt_sum_n1024_kernel(const uin
         }
         if (gd >= 0) break;
         // ---- reverse ranks mi..mj
-        const int mi = gid >> 10, mj = gid & (N - 1);
+        const int mi = gid >> LOGN, mj = gid & (N - 1);
         const int src = (tid >= mi && tid <= mj) ? mi + mj - tid : tid;
         const int val = T[src];
         __syncthreads();
@@ -252,20 +275,26 @@ __global__ __launch_bounds__(64 * kWaves) void twoopt_sum_n1024_kernel(const uin
 
 }  // namespace
 
-size_t twoopt_n1024_matrix_copy_bytes() { return (size_t)N * N * 2; }
-
-// `tours` must hold the initial tours, flags[0] the matrix maximum, c16 room for N*N 16-bit entries.
-hipError_t launch_2opt_sum_n1024(const int32_t* c, uint16_t* c16, int restarts, int32_t* tours, int64_t* costs,
-                                 int32_t* moves, const int32_t* flags, hipStream_t s) {
-    hipLaunchKernelGGL(matrix_to_u16_kernel, dim3(512), dim3(256), 0, s, c, N * N, c16, flags);
+template <int LOGN>
+static hipError_t launch_rows(const int32_t* c, uint16_t* c16, int restarts, int32_t* tours, int64_t* costs,
+                              int32_t* moves, const int32_t* flags, hipStream_t s) {
+    using L = Shape<LOGN>;
+    hipLaunchKernelGGL(matrix_to_u16_kernel, dim3(512), dim3(256), 0, s, c, L::N * L::N, c16, flags);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void*)twoopt_sum_n1024_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)Layout::total);
+    e = hipFuncSetAttribute((const void*)twoopt_sum_n1024_kernel<LOGN>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)L::total);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(twoopt_sum_n1024_kernel, dim3(restarts), dim3(64 * kWaves), Layout::total, s, c16, restarts,
-                       tours, costs, moves, flags);
+    hipLaunchKernelGGL(twoopt_sum_n1024_kernel<LOGN>, dim3(restarts), dim3(L::N), L::total, s, c16, restarts, tours, costs,
+                       moves, flags);
     return hipGetLastError();
+}
+
+// N = 512 or 1024.  `tours` must hold the initial tours, flags[0] the matrix maximum, c16 room for N*N 16-bit entries.
+hipError_t launch_2opt_sum_n1024(const int32_t* c, int N, uint16_t* c16, int restarts, int32_t* tours, int64_t* costs,
+                                 int32_t* moves, const int32_t* flags, hipStream_t s) {
+    return N == 512 ? launch_rows<9>(c, c16, restarts, tours, costs, moves, flags, s)
+                    : launch_rows<10>(c, c16, restarts, tours, costs, moves, flags, s);
 }
 
 }  // namespace cc

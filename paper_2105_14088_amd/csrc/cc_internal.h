@@ -49,9 +49,9 @@ hipError_t launch_matrix_max(const int32_t* c, int N, int32_t* flags, hipStream_
 hipError_t launch_2opt_sum_multi(const int32_t* c, int N, int restarts, int32_t* tours, int64_t* costs,
                                  int32_t* moves, const int32_t* flags, hipStream_t s);
 
-// N = 1024, ring-sum objective, max(c) < 2^16: one 16-wave workgroup per restart, matrix rows streamed
-// through LDS (cc_2opt_n1024.hip).  Same flags convention as above.
-hipError_t launch_2opt_sum_n1024(const int32_t* c, uint16_t* c16, int restarts, int32_t* tours, int64_t* costs,
+// N = 512 or 1024, ring-sum objective, max(c) < 2^16: one workgroup of N/64 waves per restart, matrix rows
+// streamed through LDS (cc_2opt_n1024.hip).  Same flags convention as above.
+hipError_t launch_2opt_sum_n1024(const int32_t* c, int N, uint16_t* c16, int restarts, int32_t* tours, int64_t* costs,
                                  int32_t* moves, const int32_t* flags, hipStream_t s);
 
 // Pair-swap descent under the halving-doubling model for `restarts` tours (cc_rdswap.hip); same tour

@@ -76,6 +76,27 @@ def test_n1024_sum_row_streaming_path_and_its_fallback():
         assert np.array_equal(got["moves"], np.concatenate([p[2] for p in parts]))
 
 
+def test_n512_sum_row_streaming_path_and_its_fallback():
+    """N = 512 (the paper's large runs): the row-streaming kernel with four diagonals per lane; fallback; ties;
+    a hierarchical matrix like workload 5's."""
+    from concurrent.futures import ThreadPoolExecutor
+    from gen import hierarchical_matrix
+    w = WORKLOADS[5]
+    cases = [(random_matrix(512, 8300, symmetric=True, lo=1, hi=3), "ties", 4),
+             (random_matrix(512, 8301, symmetric=True, lo=1, hi=65535), "16-bit path, entries up to 65535", 3),
+             (random_matrix(512, 8302, symmetric=True, lo=1, hi=65535), "fallback (one entry 2^16)", 2),
+             (hierarchical_matrix(512, w.group_sizes, w.level_ranges, w.sigma, True, 8303), "hierarchical", 5)]
+    cases[2][0][3, 5] = cases[2][0][5, 3] = 65536
+    for c, tag, restarts in cases:
+        say(f"2-opt N=512 sum ({tag})")
+        with ThreadPoolExecutor(restarts) as ex:
+            parts = list(ex.map(lambda r: oracle.restarts(c, 0, 22, r, r + 1), range(restarts)))
+        got = gpu_search(c, 0, restarts, seed=22)
+        assert np.array_equal(got["costs"], np.concatenate([p[0] for p in parts]))
+        assert np.array_equal(got["tours"], np.concatenate([p[1] for p in parts]))
+        assert np.array_equal(got["moves"], np.concatenate([p[2] for p in parts]))
+
+
 def test_n64_sum_many_restarts():
     """Several wavefronts per SIMD and a ragged last workgroup: 4100 restarts on the workload matrix, a
     wide-entry matrix and a matrix full of ties, each checked on a spread of restarts."""

@@ -299,7 +299,7 @@ hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, uin
             e = launch_init_tours(N, 0, restarts, seed, tours, s);
             if (e != hipSuccess) return e;
         }
-        if (objective == 0 && (N == 128 || N == 256)) {
+        if (objective == 0 && (N == 128 || N == 192 || N == 256)) {
             // 16-bit LDS matrix path when max(c) < 2^16, else the general kernel: both are enqueued and the
             // matrix maximum, computed on the device, decides which one does the work (no host round trip)
             e = launch_matrix_max(c, N, flags, s);

@@ -1,4 +1,4 @@
-// 2-opt descent for N = 128 and N = 256, ring-sum objective on a symmetric matrix: one wavefront per
+// 2-opt descent for N = 128, 192 and 256, ring-sum objective on a symmetric matrix: one wavefront per
 // restart, K = N / 64 consecutive ranks per lane, the whole cost matrix staged once per workgroup in
 // LDS as 16-bit entries (128 KiB at N = 256, shared by the 16 restarts of a 1024-thread workgroup).
 //
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void twoopt_sum_multi_kernel(
                 rowofs[m] = t[m] * (2 * N);
                 f[m] = *(const uint16_t*)(mbytes + rowofs[m] + 2 * tp);
                 const int a = K * lane + m;
-                kp[m] = (int)(0u - ((unsigned)f[m] << kRankBits)) + ((a + N - 1) & (N - 1));
+                kp[m] = (int)(0u - ((unsigned)f[m] << kRankBits)) + (a ? a - 1 : N - 1);
             }
         }
         if (first) {
@@ -174,7 +174,8 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void twoopt_sum_multi_kernel(
         for (int m = 0; m < K; ++m) {
             const int key = (int)((unsigned)best[m] - ((unsigned)f[m] << kRankBits));
             const int delta = key >> kRankBits;
-            const int b = ((key & ((1 << kRankBits) - 1)) + 1) & (N - 1);
+            const int rank_b = key & ((1 << kRankBits) - 1);
+            const int b = rank_b + 1 == N ? 0 : rank_b + 1;
             const int a = K * lane + m;
             const int lo = min(a, b), hi = max(a, b);
             const int id = lo ? lo * N + hi - 1 : hi * N + N - 1;
@@ -232,6 +233,7 @@ static hipError_t launch_multi(const int32_t* c, int restarts, int32_t* tours, i
 hipError_t launch_2opt_sum_multi(const int32_t* c, int N, int restarts, int32_t* tours, int64_t* costs,
                                  int32_t* moves, const int32_t* flags, hipStream_t s) {
     if (N == 128) return launch_multi<2>(c, restarts, tours, costs, moves, flags, s);
+    if (N == 192) return launch_multi<3>(c, restarts, tours, costs, moves, flags, s);
     return launch_multi<4>(c, restarts, tours, costs, moves, flags, s);
 }
 

@@ -43,7 +43,7 @@ def test_large_costs_up_to_cost_max(obj):
     assert_search_equal(gpu_search(c, obj, 48, seed=5), want)
 
 
-@pytest.mark.parametrize("n,restarts", [(128, 24), (256, 20)])
+@pytest.mark.parametrize("n,restarts", [(128, 24), (192, 22), (256, 20)])
 def test_n128_n256_sum_fast_path_and_its_fallback(n, restarts):
     """Several ranks per lane with a 16-bit LDS matrix when max(c) < 2^16; entries at or above 2^16 must
     take the general kernel (same results either way); and a matrix full of ties."""

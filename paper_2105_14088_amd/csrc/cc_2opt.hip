@@ -307,6 +307,12 @@ hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, uin
             e = launch_2opt_sum_multi(c, N, restarts, tours, costs, moves, flags, s);
             if (e != hipSuccess) return e;
             e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, s);
+        } else if (objective == 0 && N >= 4 && N <= 256) {
+            e = launch_matrix_max(c, N, flags, s);
+            if (e != hipSuccess) return e;
+            e = launch_2opt_sum_flex(c, N, restarts, tours, costs, moves, flags, s);
+            if (e != hipSuccess) return e;
+            e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, s);
         } else if (objective == 0 && (N == 512 || N == 1024)) {
             e = launch_matrix_max(c, N, flags, s);
             if (e != hipSuccess) return e;

@@ -46,6 +46,10 @@ hipError_t launch_2opt_max_n64(const int32_t* c, int restarts, uint64_t seed, bo
 // (cc_2opt_multi.hip).  launch_matrix_max writes max(c) to flags[0]; the kernel returns at once if
 // flags[0] >= 2^16.  `tours` must hold the initial tours.
 hipError_t launch_matrix_max(const int32_t* c, int N, int32_t* flags, hipStream_t s);
+// Any 4 <= N <= 256, ring-sum objective, max(c) < 2^16: one wavefront per restart, order and partner data in LDS
+// (cc_2opt_multi.hip).  Same flags convention.
+hipError_t launch_2opt_sum_flex(const int32_t* c, int N, int restarts, int32_t* tours, int64_t* costs, int32_t* moves,
+                                const int32_t* flags, hipStream_t s);
 hipError_t launch_2opt_sum_multi(const int32_t* c, int N, int restarts, int32_t* tours, int64_t* costs,
                                  int32_t* moves, const int32_t* flags, hipStream_t s);
 

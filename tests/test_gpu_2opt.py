@@ -43,6 +43,23 @@ def test_large_costs_up_to_cost_max(obj):
     assert_search_equal(gpu_search(c, obj, 48, seed=5), want)
 
 
+@pytest.mark.parametrize("n", [4, 5, 6, 7, 9, 16, 33, 48, 63, 65, 96, 100, 127, 129, 150, 191, 193, 200, 255])
+def test_sum_any_size_up_to_256_lds_kernel_and_its_fallback(n):
+    """N not a multiple of 64: order and partner data in LDS, 16-bit matrix; fallback to the general kernel when an
+    entry needs more than 16 bits; ties; caller-provided initial orders; one restart."""
+    restarts = 21
+    for hi, tag in ((5000, "16-bit path"), (65535, "largest entry 65535"), (65536, "fallback at 2^16"), (2, "ties")):
+        say(f"2-opt N={n} sum, entries up to {hi} ({tag})")
+        c = random_matrix(n, 7700 + n + hi % 97, symmetric=True, lo=1, hi=hi)
+        c[1, 3] = c[3, 1] = hi
+        want = oracle.search(c, 0, restarts, seed=13 + n)
+        assert_search_equal(gpu_search(c, 0, restarts, seed=13 + n), want)
+    c = random_matrix(n, 4321 + n, symmetric=True, lo=1, hi=9000)
+    init = random_perms(n, 18, seed=n)
+    assert_search_equal(gpu_search(c, 0, 18, seed=5, init=init), oracle.search(c, 0, 18, seed=0, init=init))
+    assert_search_equal(gpu_search(c, 0, 1, seed=6), oracle.search(c, 0, 1, seed=6))
+
+
 @pytest.mark.parametrize("n,restarts", [(128, 24), (192, 22), (256, 20)])
 def test_n128_n256_sum_fast_path_and_its_fallback(n, restarts):
     """Several ranks per lane with a 16-bit LDS matrix when max(c) < 2^16; entries at or above 2^16 must

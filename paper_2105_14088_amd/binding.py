@@ -20,9 +20,12 @@ CC_MAX_N = 1024
 CC_COST_MAX = (1 << 21) - 1
 
 # every symbol include/cc.h declares
-EXPORTS = ["cc_ring_cost_batch", "cc_ring_cost_batch_u8", "cc_rd_cost_batch", "cc_bcube_cost_batch", "cc_bcube_cost_batch_weighted", "cc_dbt_cost_batch", "cc_2opt_search", "cc_2opt_search_ex",
-           "cc_2opt_workspace_bytes", "cc_best_of_restarts", "cc_rd_swap_search", "cc_rd_swap_search_ex", "cc_rd_swap_workspace_bytes", "cc_sa_search", "cc_sa_search_ex", "cc_sa_workspace_bytes", "cc_sa_rd_search", "cc_sa_rd_search_ex", "cc_init_tours", "cc_cost_matrix_from_probes", "cc_validate_matrix", "cc_status_string",
-           "cc_last_hip_error", "cc_version"]
+EXPORTS = ["cc_ring_cost_batch", "cc_ring_cost_batch_u8", "cc_rd_cost_batch", "cc_bcube_cost_batch",
+           "cc_bcube_cost_batch_weighted", "cc_dbt_cost_batch", "cc_2opt_search", "cc_2opt_search_ex",
+           "cc_2opt_workspace_bytes", "cc_best_of_restarts", "cc_rd_swap_search", "cc_rd_swap_search_ex",
+           "cc_rd_swap_workspace_bytes", "cc_sa_search", "cc_sa_search_ex", "cc_sa_workspace_bytes", "cc_sa_rd_search",
+           "cc_sa_rd_search_ex", "cc_init_tours", "cc_cost_matrix_from_probes", "cc_validate_matrix",
+           "cc_status_string", "cc_last_hip_error", "cc_version"]
 
 
 class CCError(RuntimeError):
@@ -318,20 +321,21 @@ def cc_rd_swap_search_ex(cost_matrix: torch.Tensor, restarts: int, seed: int,
     return b
 
 
-def _sa_search(fn_name: str, cost_matrix: torch.Tensor, chains: int, steps: int, t_start: int, t_end: int, seed: int, stream=None):
+def _sa_search(fn_name: str, cost_matrix: torch.Tensor, chains: int, steps: int, t_start: int, t_end: int, seed: int,
+               stream=None):
     """Returns (best_perm int32[N], best_cost int64[1]) device tensors (valid after stream sync)."""
     n = _matrix(cost_matrix)
     best_perm = torch.empty(n, dtype=torch.int32, device=cost_matrix.device)
     best_cost = torch.empty(1, dtype=torch.int64, device=cost_matrix.device)
     _check(getattr(lib(), fn_name)(_dev(cost_matrix, torch.int32, "cost_matrix"), n, chains, steps, t_start, t_end,
-                              seed & (2**64 - 1), _dev(best_perm, torch.int32, "best_perm"),
-                              _dev(best_cost, torch.int64, "best_cost"), _stream(stream)), fn_name)
+                                   seed & (2**64 - 1), _dev(best_perm, torch.int32, "best_perm"),
+                                   _dev(best_cost, torch.int64, "best_cost"), _stream(stream)), fn_name)
     return best_perm, best_cost
 
 
-def _sa_search_ex(fn_name: str, cost_matrix: torch.Tensor, chains: int, steps: int, t_start: int, t_end: int, seed: int,
-                    init_tours: Optional[torch.Tensor] = None, buffers: Optional[SearchBuffers] = None,
-                    stream=None) -> SearchBuffers:
+def _sa_search_ex(fn_name: str, cost_matrix: torch.Tensor, chains: int, steps: int, t_start: int, t_end: int,
+                  seed: int, init_tours: Optional[torch.Tensor] = None, buffers: Optional[SearchBuffers] = None,
+                  stream=None) -> SearchBuffers:
     """Per-chain results land in the buffers' restart_costs / restart_tours (best cost and order of every chain)
     and restart_moves (accepted proposals); best_restart is the winning chain."""
     n = _matrix(cost_matrix)
@@ -343,14 +347,14 @@ def _sa_search_ex(fn_name: str, cost_matrix: torch.Tensor, chains: int, steps: i
         raise ValueError("init_tours must be [chains, N]")
     b = buffers
     _check(getattr(lib(), fn_name)(_dev(cost_matrix, torch.int32, "cost_matrix"), n, chains, steps, t_start, t_end,
-                                 seed & (2**64 - 1), _dev(init_tours, torch.int32, "init_tours"),
-                                 _dev(b.best_perm, torch.int32, "best_perm"),
-                                 _dev(b.best_cost, torch.int64, "best_cost"),
-                                 _dev(b.best_restart, torch.int32, "best_restart"),
-                                 _dev(b.restart_costs, torch.int64, "restart_costs"),
-                                 _dev(b.restart_tours, torch.int32, "restart_tours"),
-                                 _dev(b.restart_moves, torch.int32, "restart_moves"),
-                                 ctypes.c_void_p(b.ws_ptr), b.ws_bytes, _stream(stream)), fn_name)
+                                   seed & (2**64 - 1), _dev(init_tours, torch.int32, "init_tours"),
+                                   _dev(b.best_perm, torch.int32, "best_perm"),
+                                   _dev(b.best_cost, torch.int64, "best_cost"),
+                                   _dev(b.best_restart, torch.int32, "best_restart"),
+                                   _dev(b.restart_costs, torch.int64, "restart_costs"),
+                                   _dev(b.restart_tours, torch.int32, "restart_tours"),
+                                   _dev(b.restart_moves, torch.int32, "restart_moves"),
+                                   ctypes.c_void_p(b.ws_ptr), b.ws_bytes, _stream(stream)), fn_name)
     return b
 
 

@@ -285,24 +285,28 @@ __global__ void twoopt_sum_flex_kernel(const int32_t* __restrict__ c, int N, int
             first = false;
         }
         __builtin_amdgcn_wave_barrier();
-        int best[K], colprev[K];
+        // idle slots score rank 0's moves again (in bounds, no divergence in the loop) and are discarded afterwards
+        int best[K], colprev[K], abase[K];
 #pragma unroll
         for (int m = 0; m < K; ++m) {
             best[m] = 0x7fffffff;
-            colprev[m] = live[m] ? P[lane + 64 * m + 1].x : 0;     // column of rank a + 1 = b - 1 at d = 2
+            abase[m] = live[m] ? lane + 64 * m : 0;
+            colprev[m] = P[abase[m] + 1].x;                        // column of rank a + 1 = b - 1 at d = 2
         }
+#pragma unroll 4
         for (int d = 2; d <= D; ++d) {
 #pragma unroll
             for (int m = 0; m < K; ++m) {
-                if (live[m]) {
-                    const int2 pw = P[lane + 64 * m + d];
-                    const int g1 = *(const uint16_t*)(mbytes + rowA[m] + pw.x);
-                    const int g2 = *(const uint16_t*)(mbytes + rowP[m] + colprev[m]);
-                    best[m] = min(best[m], (int)(((unsigned)(g1 + g2) << kRankBits) + (unsigned)pw.y));
-                    colprev[m] = pw.x;
-                }
+                const int2 pw = P[abase[m] + d];
+                const int g1 = *(const uint16_t*)(mbytes + rowA[m] + pw.x);
+                const int g2 = *(const uint16_t*)(mbytes + rowP[m] + colprev[m]);
+                best[m] = min(best[m], (int)(((unsigned)(g1 + g2) << kRankBits) + (unsigned)pw.y));
+                colprev[m] = pw.x;
             }
         }
+#pragma unroll
+        for (int m = 0; m < K; ++m)
+            if (!live[m]) best[m] = 0x7fffffff;
         // per rank: best partner -> move id; then the lexicographic minimum of (delta, id) over the wave
         int bd = 0x7fffffff, bid = 0x7fffffff;
 #pragma unroll

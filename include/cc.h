@@ -3,8 +3,12 @@
  *
  * Problem (paper Section 4): N nodes, a measured N x N point-to-point cost matrix c, a collective
  * algorithm whose cost model is a function of the rank order; find a permutation of the node list
- * that minimises the model.  This library evaluates the ring and halving-doubling cost models over
- * batches of candidate orders and runs many independent 2-opt local searches over the ring.
+ * that minimises the model.  This library
+ *   - evaluates the cost models of Section 4.1 (ring, halving-doubling, BCube, double binary tree) over
+ *     batches of candidate orders;
+ *   - runs many independent searches: best-improvement 2-opt over the ring, pair-swap descent under the
+ *     halving-doubling model, and simulated annealing for both (Section 4.3);
+ *   - builds the cost matrix from latency probes (Section 4.2).
  *
  * Conventions
  *   - Every buffer pointer is a DEVICE pointer owned by the caller unless stated otherwise.  The

@@ -352,6 +352,6 @@ const char* cc_status_string(int status) {
 
 int cc_last_hip_error(void) { return g_last_hip_error; }
 
-int cc_version(void) { return 200; }
+int cc_version(void) { return 400; }
 
 }  // extern "C"

@@ -154,3 +154,14 @@ def test_rd_workload2_matrix_1024_chains_and_given_orders():
     torch.cuda.synchronize()
     want = oracle.sa_rd_search(c, 12, 2000, 300, 0, SEED)
     assert int(cost.item()) == want["best_cost"] and np.array_equal(perm.cpu().numpy(), want["best_perm"])
+
+
+def test_longest_chain_and_largest_values():
+    """The documented limits together: 2^24 steps, temperatures and entries at 2^21 - 1 (the products of the
+    acceptance test then come within a factor of two of 2^63)."""
+    say("sa ring: 2 chains x 2^24 steps, entries and temperatures up to 2^21 - 1")
+    c = random_matrix(16, 5, symmetric=True, lo=0, hi=COST_MAX)
+    check(c, 2, 1 << 24, COST_MAX, COST_MAX // 2, SEED)
+    say("sa rd: 1 chain x 2^22 steps, entries and temperatures up to 2^21 - 1")
+    c = random_matrix(8, 6, symmetric=False, lo=0, hi=COST_MAX)
+    check_rd(c, 1, 1 << 22, COST_MAX, COST_MAX // 3, SEED)

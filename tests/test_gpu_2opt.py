@@ -256,3 +256,26 @@ def test_determinism_same_call_twice():
     a = gpu_search(c, 3, 256, 42)
     b = gpu_search(c, 3, 256, 42)
     assert_search_equal(a, b)
+
+
+def test_largest_possible_costs_n1024():
+    """N = 1024 with every entry 2^21 - 1: ring cost 1024 * (2^21 - 1) = 2^31 - 1024, the largest the contract allows
+    and still inside int32; no move improves, so every restart returns its initial order with that cost."""
+    say("extreme: N=1024, all entries COST_MAX")
+    n = 1024
+    c = np.full((n, n), COST_MAX, dtype=np.int32)
+    np.fill_diagonal(c, 0)
+    for obj in (0, 1, 2, 3):
+        got = gpu_search(c, obj, 3, seed=9)
+        want_cost = n * COST_MAX if not (obj & 1) else COST_MAX
+        assert (got["costs"] == want_cost).all() and (got["moves"] == 0).all()
+        assert np.array_equal(got["tours"], oracle.init_tours(9, n, 3))
+    perms = random_perms(n, 5, seed=1)
+    out = cc.cc_ring_cost_batch(dev(c), dev(perms), 0)
+    rd = cc.cc_rd_cost_batch(dev(c), dev(perms))
+    torch.cuda.synchronize()
+    assert (out.cpu().numpy() == n * COST_MAX).all() and (rd.cpu().numpy() == 10 * COST_MAX).all()
+    # one cheaper entry pair: exactly the moves that bring those two nodes together improve; compare with the oracle
+    c[5, 9] = c[9, 5] = 1
+    want = oracle.search(c, 0, 2, seed=9)
+    assert_search_equal(gpu_search(c, 0, 2, seed=9), want)

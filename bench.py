@@ -12,6 +12,9 @@ One step = one pass of the whole path on the N=64 workload, inputs resident in H
 throughput (orders per second, segments (2)) is reported beside it as `perm_evals_per_s`.  Segment
 times come from HIP events recorded on the launch stream inside the timed region.
 
+After the timed steps the same search kernel is also timed on 64 times the restarts (`roofline_saturated`: several
+wavefronts per SIMD instead of one; --no-saturated skips it).
+
 Prints ONE JSON line.  --gpus above 1 is refused: the search needs no second GPU (restarts are
 independent) and this build runs on one.
 """
@@ -46,9 +49,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--saturated", action="store_true",
-                    help="after the timed steps also time the same search kernel with 64x the restarts "
-                         "(adds a roofline_saturated object; changes the kernel's average in a profile)")
+    ap.add_argument("--no-saturated", action="store_true",
+                    help="skip the extra measurement after the timed steps (the same search kernel on 64x the "
+                         "restarts, reported as roofline_saturated)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy before the steps (a dispatch of known HBM "
                          "traffic that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
@@ -164,16 +167,16 @@ def main():
                            "bytes_per_perm": 4 * n + 8},
     }
 
-    if args.saturated:
+    if not args.no_saturated:
         # The same kernel with every SIMD holding several wavefronts (outside the timed steps): 64 times the restarts.
         sat_restarts = 64 * restarts
         sat_bufs = cc.SearchBuffers(n, cc.CC_RING_SUM, sat_restarts, c.device)
-        cc.cc_2opt_search_ex(c, cc.CC_RING_SUM, sat_restarts, seed, buffers=sat_bufs)
+        cc.cc_2opt_search_ex(c, cc.CC_RING_SUM, sat_restarts, seed, buffers=sat_bufs, pick_best=False)
         torch.cuda.synchronize()
         sat_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
         for e0, e1 in sat_ev:
             e0.record()
-            cc.cc_2opt_search_ex(c, cc.CC_RING_SUM, sat_restarts, seed, buffers=sat_bufs)
+            cc.cc_2opt_search_ex(c, cc.CC_RING_SUM, sat_restarts, seed, buffers=sat_bufs, pick_best=False)
             e1.record()
         torch.cuda.synchronize()
         sat_ms = float(np.median([e0.elapsed_time(e1) for e0, e1 in sat_ev]))

@@ -212,36 +212,48 @@ __global__ void twoopt_general_kernel(const int32_t* __restrict__ c, int N, int3
     }
 }
 
-// Lexicographic minimum of (cost, restart) over all restarts; copies the winner's tour.
-__global__ __launch_bounds__(256) void best_restart_kernel(const int64_t* __restrict__ costs,
-                                                           const int32_t* __restrict__ tours, int N, int restarts,
-                                                           int32_t* __restrict__ best_perm,
-                                                           int64_t* __restrict__ best_cost,
-                                                           int32_t* __restrict__ best_restart) {
-    __shared__ long long sc[256];
-    __shared__ int sr[256];
-    const int tid = threadIdx.x;
+// Lexicographic minimum of (cost, restart) over all restarts; copies the winner's tour.  One workgroup of 256 or
+// (many restarts) 1024 threads: strided loads, a shuffle reduction inside each wave, the waves' results through LDS.
+__global__ __launch_bounds__(1024) void best_restart_kernel(const int64_t* __restrict__ costs,
+                                                            const int32_t* __restrict__ tours, int N, int restarts,
+                                                            int32_t* __restrict__ best_perm,
+                                                            int64_t* __restrict__ best_cost,
+                                                            int32_t* __restrict__ best_restart) {
+    __shared__ long long sc[16];
+    __shared__ int sr[16];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, nwv = blockDim.x >> 6, stride = blockDim.x;
     long long bc = 0x7fffffffffffffffll;
     int br = 0x7fffffff;
-    for (int r = tid; r < restarts; r += 256) {
-        const long long v = costs[r];
+    auto take = [&](long long v, int r) {
         if (v < bc || (v == bc && r < br)) { bc = v; br = r; }
+    };
+    int r = tid;
+    for (; r + 3 * stride < restarts; r += 4 * stride) {      // four loads in flight
+        const long long v0 = costs[r], v1 = costs[r + stride], v2 = costs[r + 2 * stride], v3 = costs[r + 3 * stride];
+        take(v0, r);
+        take(v1, r + stride);
+        take(v2, r + 2 * stride);
+        take(v3, r + 3 * stride);
     }
-    sc[tid] = bc;
-    sr[tid] = br;
+    for (; r < restarts; r += stride) take(costs[r], r);
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+        const long long v = __shfl_xor(bc, m, kWave);
+        const int rr = __shfl_xor(br, m, kWave);
+        take(v, rr);
+    }
+    if (lane == 0) {
+        sc[wv] = bc;
+        sr[wv] = br;
+    }
     __syncthreads();
-    for (int s = 128; s >= 1; s >>= 1) {
-        if (tid < s) {
-            const long long v = sc[tid + s];
-            const int r = sr[tid + s];
-            if (v < sc[tid] || (v == sc[tid] && r < sr[tid])) { sc[tid] = v; sr[tid] = r; }
-        }
-        __syncthreads();
-    }
-    const int win = sr[0];
-    for (int p = tid; p < N; p += 256) best_perm[p] = tours[(int64_t)win * N + p];
+    bc = sc[0];
+    br = sr[0];
+    for (int k = 1; k < nwv; ++k) take(sc[k], sr[k]);
+    const int win = br;
+    for (int p = tid; p < N; p += stride) best_perm[p] = tours[(int64_t)win * N + p];
     if (tid == 0) {
-        best_cost[0] = sc[0];
+        best_cost[0] = bc;
         if (best_restart) best_restart[0] = win;
     }
 }
@@ -281,8 +293,8 @@ hipError_t launch_general_objective(const int32_t* c, int N, int objective, int 
 
 hipError_t launch_best_restart(const int64_t* costs, const int32_t* tours, int N, int restarts, int32_t* best_perm,
                                int64_t* best_cost, int32_t* best_restart, hipStream_t s) {
-    hipLaunchKernelGGL(best_restart_kernel, dim3(1), dim3(256), 0, s, costs, tours, N, restarts, best_perm, best_cost,
-                       best_restart);
+    hipLaunchKernelGGL(best_restart_kernel, dim3(1), dim3(restarts > 1024 ? 1024 : 256), 0, s, costs, tours, N, restarts,
+                       best_perm, best_cost, best_restart);
     return hipGetLastError();
 }
 
@@ -325,9 +337,7 @@ hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, uin
     }
     if (e != hipSuccess) return e;
     if (!best_perm) return hipSuccess;       // per-restart results only
-    hipLaunchKernelGGL(best_restart_kernel, dim3(1), dim3(256), 0, s, costs, tours, N, restarts, best_perm, best_cost,
-                       best_restart);
-    return hipGetLastError();
+    return launch_best_restart(costs, tours, N, restarts, best_perm, best_cost, best_restart, s);
 }
 
 }  // namespace cc

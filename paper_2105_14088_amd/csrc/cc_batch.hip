@@ -292,6 +292,55 @@ __global__ __launch_bounds__(256) void rd_batch_kernel(const int32_t* __restrict
     }
 }
 
+// N = 32 or 64 with the matrix in LDS: the rounds are unrolled, so the partner look-ups and the gathers of all rounds are
+// in flight together and the rounds' maxima are reduced three at a time; the next order is requested before the
+// current one is scored.
+template <int LOGN>
+__global__ __launch_bounds__(256) void rd_batch_small_kernel(const int32_t* __restrict__ c,
+                                                             const int32_t* __restrict__ weights,
+                                                             const int32_t* __restrict__ perms, int64_t B,
+                                                             int64_t* __restrict__ out) {
+    constexpr int N = 1 << LOGN;
+    __shared__ int32_t m[N * N];
+    __shared__ int32_t order_all[4][N];
+    for (int e = threadIdx.x; e < N * N; e += 256) m[e] = c[e];
+    __syncthreads();
+    int32_t* order = order_all[threadIdx.x >> 6];
+    const int lane = lane_id();
+    const bool live = lane < N;
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    long long w[6];
+#pragma unroll
+    for (int k = 0; k < 6; ++k) w[k] = (k < LOGN && weights) ? (long long)clampi(weights[k], 0, kMaxRoundWeight) : 1ll;
+    int next = (wave < B && live) ? perms[wave * N + lane] : 0;
+    for (int64_t b = wave; b < B; b += nwaves) {
+        const int a = clampi(next, 0, N - 1);
+        const int64_t bn = b + nwaves;
+        next = (bn < B && live) ? perms[bn * N + lane] : 0;
+        if (live) order[lane] = a;
+        __builtin_amdgcn_wave_barrier();
+        int v[6];
+#pragma unroll
+        for (int k = 0; k < 6; ++k) v[k] = (k < LOGN && live) ? m[a * N + order[lane ^ (1 << k)]] : 0;
+        __builtin_amdgcn_wave_barrier();   // all partner look-ups done before the slice is overwritten
+        wave_max3(v[0], v[1], v[2]);
+        wave_max3(v[3], v[4], v[5]);
+        long long total = 0;
+#pragma unroll
+        for (int k = 0; k < LOGN; ++k) total += w[k] * v[k];
+        if (lane == 0) out[b] = total;
+    }
+}
+
+template <int LOGN>
+static hipError_t rd_small_launch(const int32_t* c, const int32_t* weights, const int32_t* perms, int64_t B,
+                                  int64_t* out, hipStream_t s) {
+    const int grid = batch_grid(4, B);
+    hipLaunchKernelGGL(rd_batch_small_kernel<LOGN>, dim3(grid), dim3(256), 0, s, c, weights, perms, B, out);
+    return hipGetLastError();
+}
+
 template <int NM>
 static hipError_t rd_launch(const int32_t* c, int N, const int32_t* weights, const int32_t* perms, int64_t B,
                             int64_t* out, hipStream_t s) {
@@ -309,6 +358,8 @@ static hipError_t rd_launch(const int32_t* c, int N, const int32_t* weights, con
 hipError_t launch_rd_cost_batch(const int32_t* c, int N, const int32_t* weights, const int32_t* perms, int64_t B,
                                 int64_t* out, hipStream_t s) {
     if (B == 0) return hipSuccess;
+    if (N == 64) return rd_small_launch<6>(c, weights, perms, B, out, s);
+    if (N == 32) return rd_small_launch<5>(c, weights, perms, B, out, s);
     if (N <= 64) return rd_launch<1>(c, N, weights, perms, B, out, s);
     if (N == 128) return rd_launch<2>(c, N, weights, perms, B, out, s);
     if (N == 256) return rd_launch<4>(c, N, weights, perms, B, out, s);

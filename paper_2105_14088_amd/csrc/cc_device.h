@@ -52,6 +52,22 @@ __device__ __forceinline__ int wave_min(int v) {
     CC_WAVE_REDUCE_DPP("v_min_i32_dpp");
     return __builtin_amdgcn_readlane(v, 63);
 }
+// Three maxima at once: the three chains are interleaved, so the instructions of the other two fill the wait
+// states a chain needs between its steps.  Lane 63 ends with each total.
+__device__ __forceinline__ void wave_max3(int& a, int& b, int& c) {
+#define CC_STEP3(ctrl)                                         \
+    "v_max_i32_dpp %0, %0, %0 " ctrl " bank_mask:0xf\n\t"    \
+    "v_max_i32_dpp %1, %1, %1 " ctrl " bank_mask:0xf\n\t"    \
+    "v_max_i32_dpp %2, %2, %2 " ctrl " bank_mask:0xf\n\t"
+    asm volatile("s_nop 1\n\t" CC_STEP3("quad_perm:[1,0,3,2] row_mask:0xf") CC_STEP3("quad_perm:[2,3,0,1] row_mask:0xf")
+                     CC_STEP3("row_half_mirror row_mask:0xf") CC_STEP3("row_mirror row_mask:0xf")
+                         CC_STEP3("row_bcast:15 row_mask:0xa") CC_STEP3("row_bcast:31 row_mask:0xc") "s_nop 1"
+                 : "+v"(a), "+v"(b), "+v"(c));
+#undef CC_STEP3
+    a = __builtin_amdgcn_readlane(a, 63);
+    b = __builtin_amdgcn_readlane(b, 63);
+    c = __builtin_amdgcn_readlane(c, 63);
+}
 __device__ __forceinline__ long long wave_sum64(long long v) {
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);

@@ -110,6 +110,24 @@ def _declare(path: str) -> ctypes.CDLL:
     lib.cco_sa_rd_chains.argtypes = [p, i32, i64, i32, i32, u64, i64, i64, p, p, p, p]
     lib.cco_cost_matrix_from_probes.restype = ctypes.c_int
     lib.cco_cost_matrix_from_probes.argtypes = [p, i32, i32, i32, i32, p]
+    lib.cco_oropt_is_move.restype = ctypes.c_int
+    lib.cco_oropt_is_move.argtypes = [i32, i32, i32, i32, i32]
+    lib.cco_oropt_move_id.restype = i64
+    lib.cco_oropt_move_id.argtypes = [i32, i32, i32, i32, i32]
+    lib.cco_oropt_apply.restype = None
+    lib.cco_oropt_apply.argtypes = [p, i32, i32, i32, i32, i32]
+    lib.cco_oropt_value_by_definition.restype = i64
+    lib.cco_oropt_value_by_definition.argtypes = [p, i32, p, i32, i32, i32, i32]
+    lib.cco_oropt_neighbourhood_size.restype = i64
+    lib.cco_oropt_neighbourhood_size.argtypes = [i32]
+    lib.cco_oropt_all_values.restype = ctypes.c_int
+    lib.cco_oropt_all_values.argtypes = [p, i32, p, p]
+    lib.cco_local_classes_ok.restype = ctypes.c_int
+    lib.cco_local_classes_ok.argtypes = [i32, i32]
+    lib.cco_local_descend.restype = ctypes.c_int
+    lib.cco_local_descend.argtypes = [p, i32, i32, i32, p, p, p, i32, p, i32]
+    lib.cco_local_restarts.restype = ctypes.c_int
+    lib.cco_local_restarts.argtypes = [p, i32, i32, i32, u64, i64, i64, p, p, p, p]
     return lib
 
 
@@ -497,3 +515,91 @@ def sa_rd_search(c, chains: int, steps: int, t_start: int, t_end: int, seed: int
     k = int(np.argmin(costs))
     return dict(best_perm=tours[k].copy(), best_cost=int(costs[k]), best_chain=k, costs=costs, tours=tours,
                 accepted=accepted)
+
+
+# ---- wider ring neighbourhoods: segment insertion (Or-opt) and the orientation flip
+MOVES_2OPT, MOVES_OROPT, MOVES_FLIP = 1, 2, 4
+
+
+def oropt_is_move(n: int, s: int, length: int, g: int, o: int = 0) -> bool:
+    return bool(_L().cco_oropt_is_move(n, s, length, g, o))
+
+
+def oropt_move_id(n: int, s: int, length: int, g: int, o: int = 0) -> int:
+    return int(_L().cco_oropt_move_id(n, s, length, g, o))
+
+
+def oropt_apply(t, s: int, length: int, g: int, o: int = 0) -> np.ndarray:
+    u = np.array(t, dtype=np.int32, copy=True)
+    assert oropt_is_move(u.shape[0], s, length, g, o)
+    _L().cco_oropt_apply(_ptr(u), u.shape[0], s, length, g, o)
+    return u
+
+
+def oropt_value_by_definition(c, t, s: int, length: int, g: int, o: int = 0) -> int:
+    c = _mat(c)
+    t = np.ascontiguousarray(t, dtype=np.int32)
+    assert oropt_is_move(c.shape[0], s, length, g, o)
+    return int(_L().cco_oropt_value_by_definition(_ptr(c), c.shape[0], _ptr(t), s, length, g, o))
+
+
+def oropt_neighbourhood_size(n: int) -> int:
+    return int(_L().cco_oropt_neighbourhood_size(n))
+
+
+def oropt_moves_in_id_order(n: int):
+    """(s, length, g, o) of every segment insertion, in increasing id order."""
+    out = []
+    for length, o in ((1, 0), (2, 0), (2, 1), (3, 0), (3, 1)):
+        for s in range(1, n):
+            for g in range(n):
+                if oropt_is_move(n, s, length, g, o):
+                    out.append((s, length, g, o))
+    return out
+
+
+def oropt_all_values(c, t) -> np.ndarray:
+    c = _mat(c)
+    t = np.ascontiguousarray(t, dtype=np.int32)
+    out = np.empty(oropt_neighbourhood_size(c.shape[0]), dtype=np.int64)
+    _check(_L().cco_oropt_all_values(_ptr(c), c.shape[0], _ptr(t), _ptr(out)))
+    return out
+
+
+def local_classes_ok(objective: int, classes: int) -> bool:
+    return bool(_L().cco_local_classes_ok(objective, classes))
+
+
+def local_descend(c, objective: int, classes: int, t, use_definition: bool = False, trace_cap: int = 0):
+    """One descent over the enabled move classes. Returns (final tour, cost, applied moves, trace of move ids)."""
+    c = _mat(c)
+    u = np.array(t, dtype=np.int32, copy=True)
+    cost = ctypes.c_int64(0)
+    moves = ctypes.c_int32(0)
+    trace = np.zeros(max(trace_cap, 1), dtype=np.int64)
+    _check(_L().cco_local_descend(_ptr(c), c.shape[0], objective, classes, _ptr(u), ctypes.byref(cost),
+                                  ctypes.byref(moves), 1 if use_definition else 0, _ptr(trace), trace_cap))
+    return u, int(cost.value), int(moves.value), trace[:min(trace_cap, moves.value)]
+
+
+def local_restarts(c, objective: int, classes: int, seed: int, r0: int, r1: int, init: Optional[np.ndarray] = None):
+    """Restarts [r0, r1): returns (costs int64[r1-r0], tours int32[r1-r0, N], moves int32[r1-r0])."""
+    c = _mat(c)
+    n = c.shape[0]
+    k = r1 - r0
+    costs = np.empty(k, dtype=np.int64)
+    tours = np.empty((k, n), dtype=np.int32)
+    moves = np.empty(k, dtype=np.int32)
+    if init is not None:
+        init = np.ascontiguousarray(init, dtype=np.int32)
+    _check(_L().cco_local_restarts(_ptr(c), n, objective, classes, seed, r0, r1, _ptr(init), _ptr(costs), _ptr(tours),
+                                   _ptr(moves)))
+    return costs, tours, moves
+
+
+def local_search(c, objective: int, classes: int, n_restarts: int, seed: int, init: Optional[np.ndarray] = None):
+    """Whole multi-start search: all restarts, then the lexicographic minimum of (final cost, restart)."""
+    costs, tours, moves = local_restarts(c, objective, classes, seed, 0, n_restarts, init)
+    arg = int(np.lexsort((np.arange(n_restarts), costs))[0])
+    return dict(best_perm=tours[arg].copy(), best_cost=int(costs[arg]), best_restart=arg, costs=costs, tours=tours,
+                moves=moves)

@@ -22,7 +22,9 @@
  * brute force over all 8! orders; for the BCube model: base 2 against the halving-doubling model, closed forms,
  * digit automorphisms; for the annealing chain: the acceptance rule against the Boltzmann factor, proposal
  * statistics, bookkeeping against recomputation, the Boltzmann distribution of a constant-temperature chain
- * over an enumerated state space.
+ * over an enumerated state space; for segment insertion and the orientation flip: a list-operation model of the
+ * move, every move's fast value against apply-and-recompute, the set of reachable tours by brute force, closed
+ * forms on a circle metric and on a one-way ring, every step of a descent against a scan of the whole move set.
  * Parity unpinned: none of the functions below against their stated definitions.  The annealing schedule,
  * random-number use and acceptance rule are this project's own definition (the paper names the method only),
  * so there is nothing in the paper to pin those choices to.
@@ -899,4 +901,236 @@ int cco_sa_rd_chains(const int32_t *c, int32_t N, int64_t steps, int32_t t_start
     }
     free(t);
     return rc;
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * Wider neighbourhoods for the ring search (Section 4.3 names two neighbour moves, sub-array permutation and
+ * pair permutation, "alongside standard heuristics"; the two classes below are the textbook companions of
+ * 2-opt and are this project's choice, like the descent itself).
+ *
+ * Move classes, a bitmask:
+ *   1  2-opt moves as above.
+ *   2  segment insertion (Or-opt): the L in {1, 2, 3} consecutive ranks s .. s+L-1 (1 <= s, s+L-1 <= N-1,
+ *      L <= N-3) are taken out of the ring and put back, kept (o = 0) or reversed (o = 1, L > 1 only), into the
+ *      gap between ranks g and g+1 (mod N) of the original numbering, g outside s-1 .. s+L-1.  The order of all
+ *      other nodes is kept; rank 0 keeps its node.  Ring-sum objective on a symmetric matrix only.
+ *      id = N*N + (variant*N + s)*N + g, variant = 0 (L = 1), 1, 2 (L = 2, o = 0, 1), 3, 4 (L = 3): every
+ *      segment-insertion id is above every 2-opt id, so among equal values a 2-opt move wins.
+ *   4  the orientation flip, i.e. the pair (i, j) = (1, N-1) that the 2-opt set leaves out: reverse t[1..N-1].
+ *      Directed objectives only (on a symmetric matrix it changes nothing); id as a 2-opt move with o = 0.
+ * A sweep scores every move of the enabled classes and applies the lexicographic minimum of (value, id) if it
+ * strictly lowers the cost.
+ * ---------------------------------------------------------------------------------------------- */
+enum { CCO_MOVES_2OPT = 1, CCO_MOVES_OROPT = 2, CCO_MOVES_FLIP = 4 };
+
+int cco_oropt_is_move(int32_t N, int32_t s, int32_t L, int32_t g, int32_t o)
+{
+    if (L < 1 || L > 3 || L > N - 3) return 0;
+    if (s < 1 || s + L - 1 > N - 1) return 0;
+    if (g < 0 || g > N - 1) return 0;
+    if (g >= s - 1 && g <= s + L - 1) return 0;
+    if (o < 0 || o > 1 || (o == 1 && L == 1)) return 0;
+    return 1;
+}
+
+int64_t cco_oropt_move_id(int32_t N, int32_t s, int32_t L, int32_t g, int32_t o)
+{
+    int64_t variant = L == 1 ? 0 : 2 * L - 3 + o;
+    return (int64_t)N * N + (variant * N + s) * N + g;
+}
+
+/* Takes the segment out and puts it back behind the node that sits at rank g. */
+void cco_oropt_apply(int32_t *t, int32_t N, int32_t s, int32_t L, int32_t g, int32_t o)
+{
+    int32_t seg[3];
+    int32_t *rest = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    for (int32_t k = 0; k < L; ++k) seg[k] = o ? t[s + L - 1 - k] : t[s + k];
+    int32_t n = 0, at = -1;
+    for (int32_t p = 0; p < N; ++p) {
+        if (p >= s && p <= s + L - 1) continue;
+        rest[n++] = t[p];
+        if (p == g) at = n;                 /* the segment goes in front of rest[at] */
+    }
+    int32_t w = 0;
+    for (int32_t k = 0; k < n; ++k) {
+        if (k == at) for (int32_t x = 0; x < L; ++x) t[w++] = seg[x];
+        t[w++] = rest[k];
+    }
+    if (at == n) for (int32_t x = 0; x < L; ++x) t[w++] = seg[x];
+    free(rest);
+}
+
+int64_t cco_oropt_value_by_definition(const int32_t *c, int32_t N, const int32_t *t, int32_t s, int32_t L, int32_t g,
+                                      int32_t o)
+{
+    int32_t *u = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    memcpy(u, t, sizeof(int32_t) * (size_t)N);
+    cco_oropt_apply(u, N, s, L, g, o);
+    int64_t v = cco_ring_cost(c, N, u, CCO_SUM);
+    free(u);
+    return v;
+}
+
+int64_t cco_oropt_neighbourhood_size(int32_t N)
+{
+    int64_t n = 0;
+    for (int32_t L = 1; L <= 3 && L <= N - 3; ++L) n += (int64_t)(N - L) * (N - L - 1) * (L == 1 ? 1 : 2);
+    return n;
+}
+
+/* Delta tier (symmetric matrix): with A, B the nodes before and behind the segment, S1 and S2 its first and last
+ * node, P and Q the nodes at the two sides of the gap, the move removes the edges A-S1, S2-B, P-Q and adds A-B and
+ * P-S1, S2-Q (kept) or P-S2, S1-Q (reversed).  Scans in increasing id. */
+static int scan_insertions(const int32_t *c, int32_t N, const int32_t *t, int64_t cur, cco_best *best,
+                           int64_t *all_values)
+{
+    int found = 0;
+    int64_t nvals = 0;
+    for (int32_t variant = 0; variant < 5; ++variant) {
+        int32_t L = variant == 0 ? 1 : (variant + 3) / 2, o = variant == 0 ? 0 : (variant + 1) % 2;
+        if (L > N - 3) continue;
+        for (int32_t s = 1; s + L - 1 <= N - 1; ++s) {
+            int32_t A = t[s - 1], S1 = t[s], S2 = t[s + L - 1], B = t[(s + L) % N];
+            int64_t without = cur - C_(A, S1) - C_(S2, B) + C_(A, B);
+            for (int32_t g = 0; g < N; ++g) {
+                if (g >= s - 1 && g <= s + L - 1) continue;
+                int32_t P = t[g], Q = t[(g + 1) % N];
+                int64_t v = without - C_(P, Q) + (o ? C_(P, S2) + C_(S1, Q) : C_(P, S1) + C_(S2, Q));
+                int64_t id = cco_oropt_move_id(N, s, L, g, o);
+                if (all_values) all_values[nvals] = v;
+                ++nvals;
+                if (!found || v < best->value || (v == best->value && id < best->id)) {
+                    best->value = v; best->id = id; best->i = s; best->j = g; best->o = variant;
+                    found = 1;
+                }
+            }
+        }
+    }
+    return found;
+}
+
+int cco_oropt_all_values(const int32_t *c, int32_t N, const int32_t *t, int64_t *values)
+{
+    cco_best best;
+    scan_insertions(c, N, t, cco_ring_cost(c, N, t, CCO_SUM), &best, values);
+    return CCO_OK;
+}
+
+/* Which class combinations are defined for which objective. */
+int cco_local_classes_ok(int32_t objective, int32_t classes)
+{
+    if (objective < 0 || objective > 3) return 0;
+    if (classes == CCO_MOVES_2OPT) return 1;
+    if (classes == CCO_MOVES_OROPT || classes == (CCO_MOVES_2OPT | CCO_MOVES_OROPT)) return objective == CCO_SUM;
+    if (classes == (CCO_MOVES_2OPT | CCO_MOVES_FLIP)) return (objective & 2) != 0;
+    return 0;
+}
+
+/* One best-improvement descent over the enabled classes.  use_definition: every move scored by
+ * apply-and-recompute.  trace: ids of the applied moves. */
+int cco_local_descend(const int32_t *c, int32_t N, int32_t objective, int32_t classes, int32_t *t, int64_t *cost,
+                      int32_t *moves, int32_t use_definition, int64_t *trace, int32_t trace_cap)
+{
+    if (!c || !t || N < 2 || !cco_local_classes_ok(objective, classes)) return CCO_ERR_ARG;
+    int64_t *ws = (int64_t *)malloc(sizeof(int64_t) * 6 * (size_t)N);
+    if (!ws) return CCO_ERR_NOMEM;
+    const int directed = (objective & 2) != 0;
+    int64_t cur = cco_ring_cost(c, N, t, objective);
+    int32_t applied = 0;
+    for (;;) {
+        cco_best best, cand;
+        int found = 0, kind = 0;      /* kind: 0 = reversal (2-opt or flip), 1 = insertion */
+        if (classes & CCO_MOVES_2OPT) {
+            if (!use_definition) {
+                found = scan_moves(c, N, objective, t, cur, ws, &best, NULL);
+            } else {
+                for (int32_t i = 1; i <= N - 2; ++i)
+                    for (int32_t j = i + 1; j <= N - 1; ++j) {
+                        if (i == 1 && j == N - 1) continue;
+                        for (int32_t o = 0; o <= directed; ++o) {
+                            int64_t v = cco_move_value_by_definition(c, N, objective, t, i, j, o);
+                            int64_t id = cco_move_id(N, objective, i, j, o);
+                            if (!found || v < best.value || (v == best.value && id < best.id)) {
+                                best.value = v; best.id = id; best.i = i; best.j = j; best.o = o; found = 1;
+                            }
+                        }
+                    }
+            }
+        }
+        if ((classes & CCO_MOVES_FLIP) && N >= 3) {
+            int64_t v;
+            if (use_definition) {
+                v = cco_move_value_by_definition(c, N, objective, t, 1, N - 1, 0);
+            } else {                   /* every hop walked the other way */
+                v = 0;
+                for (int32_t p = 0; p < N; ++p) {
+                    int64_t back = C_(t[(p - 1 + N) % N], t[p]);
+                    v = (objective & 1) ? max64(v, back) : v + back;
+                }
+            }
+            int64_t id = cco_move_id(N, objective, 1, N - 1, 0);
+            if (!found || v < best.value || (v == best.value && id < best.id)) {
+                best.value = v; best.id = id; best.i = 1; best.j = N - 1; best.o = 0; found = 1;
+            }
+        }
+        if (classes & CCO_MOVES_OROPT) {
+            int f2 = 0;
+            if (!use_definition) {
+                f2 = scan_insertions(c, N, t, cur, &cand, NULL);
+            } else {
+                for (int32_t variant = 0; variant < 5; ++variant) {
+                    int32_t L = variant == 0 ? 1 : (variant + 3) / 2, o = variant == 0 ? 0 : (variant + 1) % 2;
+                    for (int32_t s = 1; s <= N - 1; ++s)
+                        for (int32_t g = 0; g < N; ++g) {
+                            if (!cco_oropt_is_move(N, s, L, g, o)) continue;
+                            int64_t v = cco_oropt_value_by_definition(c, N, t, s, L, g, o);
+                            int64_t id = cco_oropt_move_id(N, s, L, g, o);
+                            if (!f2 || v < cand.value || (v == cand.value && id < cand.id)) {
+                                cand.value = v; cand.id = id; cand.i = s; cand.j = g; cand.o = variant; f2 = 1;
+                            }
+                        }
+                }
+            }
+            if (f2 && (!found || cand.value < best.value || (cand.value == best.value && cand.id < best.id))) {
+                best = cand; found = 1; kind = 1;
+            }
+        }
+        if (!found || best.value >= cur) break;
+        if (kind == 0) {
+            cco_apply_move(t, N, best.i, best.j, best.o);
+        } else {
+            int32_t variant = best.o;
+            cco_oropt_apply(t, N, best.i, variant == 0 ? 1 : (variant + 3) / 2, best.j, variant == 0 ? 0 : (variant + 1) % 2);
+        }
+        cur = best.value;
+        if (trace && applied < trace_cap) trace[applied] = best.id;
+        ++applied;
+    }
+    free(ws);
+    *cost = cur;
+    if (moves) *moves = applied;
+    return CCO_OK;
+}
+
+/* Restarts [r0, r1); init_tours (optional) is indexed by the restart number. */
+int cco_local_restarts(const int32_t *c, int32_t N, int32_t objective, int32_t classes, uint64_t seed, int64_t r0,
+                       int64_t r1, const int32_t *init_tours, int64_t *restart_costs, int32_t *restart_tours,
+                       int32_t *restart_moves)
+{
+    if (!c || N < 2 || !cco_local_classes_ok(objective, classes) || r0 < 0 || r1 < r0) return CCO_ERR_ARG;
+    if (!(objective & 2) && !is_symmetric(c, N)) return CCO_ERR_NOT_SYMMETRIC;
+    int32_t *t = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    if (!t) return CCO_ERR_NOMEM;
+    for (int64_t r = r0; r < r1; ++r) {
+        if (init_tours) memcpy(t, init_tours + r * N, sizeof(int32_t) * (size_t)N);
+        else cco_init_tour(seed, (uint32_t)r, N, t);
+        int64_t cost; int32_t mv;
+        int rc = cco_local_descend(c, N, objective, classes, t, &cost, &mv, 0, NULL, 0);
+        if (rc != CCO_OK) { free(t); return rc; }
+        if (restart_costs) restart_costs[r - r0] = cost;
+        if (restart_moves) restart_moves[r - r0] = mv;
+        if (restart_tours) memcpy(restart_tours + (r - r0) * N, t, sizeof(int32_t) * (size_t)N);
+    }
+    free(t);
+    return CCO_OK;
 }

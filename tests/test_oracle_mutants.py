@@ -12,6 +12,7 @@ import test_oracle_2opt as t2
 import test_oracle_bcube as tb
 import test_oracle_costs as tc
 import test_oracle_dbt as td
+import test_oracle_local as tl
 import test_oracle_probes as tp
 import test_oracle_rdswap as ts
 import test_oracle_sa as ta
@@ -92,6 +93,28 @@ MUTANTS = [
     ("annealing: uphill moves accepted when they should be rejected",
      "return delta * 4096 * steps <= num * E;", "return delta * 4096 * steps >= num * E;", 0,
      [ta.test_constant_temperature_chain_samples_the_boltzmann_distribution, ta.test_acceptance_special_cases]),
+    ("segment insertion: edge behind the segment not removed",
+     "int64_t without = cur - C_(A, S1) - C_(S2, B) + C_(A, B);", "int64_t without = cur - C_(A, S1) + C_(A, B);", 0,
+     [lambda: tl.test_fast_values_equal_apply_and_recompute(7, 4)]),
+    ("segment insertion: reversed segment joined the wrong way round",
+     "(o ? C_(P, S2) + C_(S1, Q) : C_(P, S1) + C_(S2, Q));", "(o ? C_(P, S1) + C_(S2, Q) : C_(P, S1) + C_(S2, Q));", 0,
+     [lambda: tl.test_fast_values_equal_apply_and_recompute(7, 4),
+      lambda: tl.test_circle_metric_displaced_segment_is_repaired_in_one_move(16, 3, True)]),
+    ("segment insertion: segment put in front of the gap's first node",
+     "if (p == g) at = n;                 /* the segment goes in front of rest[at] */",
+     "if (p == g) at = n - 1;", 0,
+     [lambda: tl.test_apply_equals_python_list_model(7)]),
+    ("segment insertion: gaps next to the segment allowed",
+     "if (g >= s - 1 && g <= s + L - 1) return 0;", "if (g >= s && g <= s + L - 2) return 0;", 0,
+     [lambda: tl.test_move_set_size_ids_and_validity(6)]),
+    ("union of classes: an insertion wins a tie against a 2-opt move",
+     "if (f2 && (!found || cand.value < best.value || (cand.value == best.value && cand.id < best.id))) {",
+     "if (f2 && (!found || cand.value <= best.value)) {", 0,
+     [tl.test_union_tie_goes_to_the_2opt_move]),
+    ("orientation flip scored with the hops as walked now",
+     "int64_t back = C_(t[(p - 1 + N) % N], t[p]);", "int64_t back = C_(t[p], t[(p - 1 + N) % N]);", 0,
+     [lambda: tl.test_flip_on_a_one_way_ring(oracle.SUM_DIRECTED),
+      lambda: tl.test_flip_trajectory_definition_vs_fast(9, 2, oracle.MAX_DIRECTED)]),
     ("probes: percentile rank off by one",
      "out[(int64_t)a * N + b] = buf[rank - 1];", "out[(int64_t)a * N + b] = buf[rank < K ? rank : K - 1];", 0,
      [tp.test_hand_worked, lambda: tp.test_against_numpy_nearest_rank_percentile(8, 100, 10)]),

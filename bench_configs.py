@@ -4,7 +4,7 @@
 Cases: C1-C5 the parity-test configurations (matrix shapes and work amounts in gen/workloads.py); M64* the
 batch-evaluation headline case (ring sum / max on 2^20 seeded orders at N=64, also with orders stored one byte
 per rank); R/B/T* halving-doubling, BCube and double-binary-tree batches; S* pair-swap searches under the
-halving-doubling model; A* / AR* simulated-annealing runs (ring / halving-doubling); P* cost matrices from
+halving-doubling model; L* ring searches over the wider move sets (segment insertion, orientation flip); A* / AR* simulated-annealing runs (ring / halving-doubling); P* cost matrices from
 probes.  Times are HIP-event times around the library call on the launch stream, median of `--reps` after one
 warm-up.  `bench.py` remains the single-line benchmark of the N=64 workload.  Pass --oracle to time the CPU
 oracle beside each case (a bounded sample, one core) and compare the sample bit for bit; --only takes a
@@ -84,6 +84,40 @@ def main():
             ok = bool(np.array_equal(om, moves[:sample]) and np.array_equal(ot, bufs.restart_tours.cpu().numpy()[:sample]))
             d.update({"oracle_1core_move_evals_per_s": float(((om.astype(np.int64) + 1) * nbhd).sum() / dt),
                       "oracle_sample_restarts": sample, "oracle_sample_s": dt, "bit_exact_on_sample": ok})
+        emit(d)
+
+    def local_case(name, wid, classes, restarts=None):
+        """Ring search over a wider move set (segment insertion with or without the 2-opt moves; the flip)."""
+        w = WORKLOADS[wid]
+        obj = cc.OBJECTIVES[w.objective]
+        restarts = restarts or w.restarts
+        c_host = make_matrix(wid)
+        c = torch.from_numpy(c_host).cuda()
+        bufs = cc.SearchBuffers(w.n, obj, restarts, c.device)
+        ms = timed(lambda: cc.cc_local_search_ex(c, obj, classes, restarts, w.search_seed, buffers=bufs), args.reps)
+        moves = bufs.restart_moves.cpu().numpy().astype(np.int64)
+        n = w.n
+        nbhd = 0
+        if classes & cc.CC_MOVES_2OPT:
+            nbhd += n * (n - 3) // 2 * (2 if obj & 2 else 1)
+        if classes & cc.CC_MOVES_OROPT:
+            nbhd += sum((n - L) * (n - L - 1) * (1 if L == 1 else 2) for L in (1, 2, 3))
+        if classes & cc.CC_MOVES_FLIP:
+            nbhd += 1
+        evals = int(((moves + 1) * nbhd).sum())
+        d = {"workload": name, "call": "cc_local_search_ex", "N": n, "objective": w.objective, "move_classes": classes,
+             "restarts": restarts, "ms": ms, "move_evals": evals, "move_evals_per_s": evals / (ms * 1e-3),
+             "applied_moves_mean": float(moves.mean()), "applied_moves_max": int(moves.max()),
+             "best_cost": int(bufs.best_cost.item()), "mean_cost": float(bufs.restart_costs.double().mean().item())}
+        if args.oracle:
+            import oracle
+            sample = min(restarts, {64: 64, 256: 4, 1024: 1}[n])
+            t0 = time.perf_counter()
+            oc, ot, om = oracle.local_restarts(c_host, obj, classes, w.search_seed, 0, sample)
+            dt = time.perf_counter() - t0
+            ok = bool(np.array_equal(om, moves[:sample]) and np.array_equal(ot, bufs.restart_tours.cpu().numpy()[:sample]))
+            d.update({"oracle_1core_move_evals_per_s": float(((om.astype(np.int64) + 1) * nbhd).sum() / dt),
+                      "oracle_sample_restarts": sample, "bit_exact_on_sample": ok})
         emit(d)
 
     def swap_case(name, wid, restarts):
@@ -199,6 +233,10 @@ def main():
         ("C5rd", lambda: batch_case("C5_n1024_rd_65536", 5, "rd", 0, 65536)),
         ("C5", lambda: search_case(5)),
         ("C512", lambda: search_case(5, n=512, restarts=768, name="C512_n512_sum_768_restarts")),
+        ("L64", lambda: local_case("L64_n64_2opt+insertion_1024", 2, 3)),
+        ("L64or", lambda: local_case("L64_n64_insertion_1024", 2, 2)),
+        ("L64flip", lambda: local_case("L64_n64_max_directed_2opt+flip_1024", 3, 5)),
+        ("L256", lambda: local_case("L256_n256_2opt+insertion_4096", 4, 3)),
         ("S64", lambda: swap_case("S64_n64_rd_swap_1024", 2, 1024)),
         ("S256", lambda: swap_case("S256_n256_rd_swap_256", 4, 256)),
         ("A64", lambda: sa_case("A64_n64_sa_1024x100000", 2, 1024, 100000, 300, 0)),

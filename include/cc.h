@@ -63,6 +63,13 @@ typedef enum {
     CC_RING_MAX_DIRECTED = 3
 } cc_objective;
 
+/* Move classes of the ring search (a bitmask; cc_local_search). */
+typedef enum {
+    CC_MOVES_2OPT = 1,           /* reversal of a sub-array: the move set of cc_2opt_search */
+    CC_MOVES_OROPT = 2,          /* a segment of 1 to 3 ranks taken out and put back elsewhere, kept or reversed */
+    CC_MOVES_FLIP = 4            /* the whole ring walked the other way (directed objectives) */
+} cc_move_class;
+
 /*
  * Ring cost model (Section 4.1, equation C_r): for each of the B orders,
  *     out_costs[b] = sum over ranks p of c[perm_b[p]][perm_b[(p-1) mod N]]      (objective SUM)
@@ -161,6 +168,34 @@ int cc_2opt_search_ex(const int32_t* cost_matrix, int32_t N, int32_t objective, 
                       uint64_t seed, const int32_t* init_tours, int32_t* best_perm, int64_t* best_cost,
                       int32_t* best_restart, int64_t* restart_costs, int32_t* restart_tours,
                       int32_t* restart_moves, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The ring search of cc_2opt_search over a wider move set (Section 4.3 searches with sub-array and pair permutations
+ * "alongside standard heuristics"; the two classes added here are the usual companions of 2-opt).  One restart,
+ * restarts and result exactly as in cc_2opt_search: every move of the enabled classes is scored, the
+ * lexicographically smallest (value, id) is applied if it strictly lowers the cost.
+ *
+ *   CC_MOVES_2OPT   the moves (i, j, o) of cc_2opt_search with their ids.
+ *   CC_MOVES_OROPT  segment insertion: the L in {1, 2, 3} consecutive ranks s .. s+L-1 (1 <= s, s+L-1 <= N-1,
+ *                   L <= N-3) are taken out of the ring and put back, kept (o = 0) or reversed (o = 1, L > 1
+ *                   only), between the nodes that stood at ranks g and (g+1) mod N, g outside s-1 .. s+L-1; all
+ *                   other nodes keep their order and rank 0 keeps its node.
+ *                   id = N*N + (variant*N + s)*N + g with variant 0 (L = 1), 1, 2 (L = 2: kept, reversed),
+ *                   3, 4 (L = 3): above every 2-opt id, so a 2-opt move wins a tie.
+ *   CC_MOVES_FLIP   the pair (i, j) = (1, N-1) that the 2-opt set leaves out, o = 0: reverse perm[1..N-1].
+ *
+ * Defined combinations: CC_MOVES_2OPT with every objective (then identical to cc_2opt_search);
+ * CC_MOVES_OROPT and CC_MOVES_2OPT | CC_MOVES_OROPT with CC_RING_SUM (symmetric matrix);
+ * CC_MOVES_2OPT | CC_MOVES_FLIP with the two directed objectives.  Anything else: CC_ERR_INVALID_ARG.
+ * Arguments, outputs and workspace (cc_2opt_workspace_bytes) as for cc_2opt_search / cc_2opt_search_ex.
+ */
+int cc_local_search(const int32_t* cost_matrix, int32_t N, int32_t objective, int32_t move_classes, int32_t restarts,
+                    uint64_t seed, int32_t* best_perm, int64_t* best_cost, void* stream);
+
+int cc_local_search_ex(const int32_t* cost_matrix, int32_t N, int32_t objective, int32_t move_classes,
+                       int32_t restarts, uint64_t seed, const int32_t* init_tours, int32_t* best_perm,
+                       int64_t* best_cost, int32_t* best_restart, int64_t* restart_costs, int32_t* restart_tours,
+                       int32_t* restart_moves, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * The last step of every search call on its own: the lexicographically smallest (restart_costs[r], r) over

@@ -16,13 +16,14 @@ LIB_PATH = os.path.join(_HERE, "libcc.so")
 
 CC_RING_SUM, CC_RING_MAX, CC_RING_SUM_DIRECTED, CC_RING_MAX_DIRECTED = 0, 1, 2, 3
 OBJECTIVES = {"sum": 0, "max": 1, "sum_directed": 2, "max_directed": 3}
+CC_MOVES_2OPT, CC_MOVES_OROPT, CC_MOVES_FLIP = 1, 2, 4
 CC_MAX_N = 1024
 CC_COST_MAX = (1 << 21) - 1
 
 # every symbol include/cc.h declares
 EXPORTS = ["cc_ring_cost_batch", "cc_ring_cost_batch_u8", "cc_rd_cost_batch", "cc_bcube_cost_batch",
            "cc_bcube_cost_batch_weighted", "cc_dbt_cost_batch", "cc_2opt_search", "cc_2opt_search_ex",
-           "cc_2opt_workspace_bytes", "cc_best_of_restarts", "cc_rd_swap_search", "cc_rd_swap_search_ex",
+           "cc_2opt_workspace_bytes", "cc_local_search", "cc_local_search_ex", "cc_best_of_restarts", "cc_rd_swap_search", "cc_rd_swap_search_ex",
            "cc_rd_swap_workspace_bytes", "cc_sa_search", "cc_sa_search_ex", "cc_sa_workspace_bytes", "cc_sa_rd_search",
            "cc_sa_rd_search_ex", "cc_init_tours", "cc_cost_matrix_from_probes", "cc_validate_matrix",
            "cc_status_string", "cc_last_hip_error", "cc_version"]
@@ -65,6 +66,10 @@ def lib() -> ctypes.CDLL:
         L.cc_2opt_search.argtypes = [p, i32, i32, i32, u64, p, p, p]
         L.cc_2opt_search_ex.restype = ctypes.c_int
         L.cc_2opt_search_ex.argtypes = [p, i32, i32, i32, u64, p, p, p, p, p, p, p, p, sz, p]
+        L.cc_local_search.restype = ctypes.c_int
+        L.cc_local_search.argtypes = [p, i32, i32, i32, i32, u64, p, p, p]
+        L.cc_local_search_ex.restype = ctypes.c_int
+        L.cc_local_search_ex.argtypes = [p, i32, i32, i32, i32, u64, p, p, p, p, p, p, p, p, sz, p]
         L.cc_best_of_restarts.restype = ctypes.c_int
         L.cc_best_of_restarts.argtypes = [p, p, i32, i32, p, p, p, p]
         L.cc_2opt_workspace_bytes.restype = sz
@@ -272,6 +277,42 @@ def cc_2opt_search_ex(cost_matrix: torch.Tensor, objective: int, restarts: int, 
                                    _dev(b.restart_tours, torch.int32, "restart_tours"),
                                    _dev(b.restart_moves, torch.int32, "restart_moves"),
                                    ctypes.c_void_p(b.ws_ptr), b.ws_bytes, _stream(stream)), "cc_2opt_search_ex")
+    return b
+
+
+def cc_local_search(cost_matrix: torch.Tensor, objective: int, move_classes: int, restarts: int, seed: int,
+                    stream=None):
+    """Returns (best_perm int32[N], best_cost int64[1]) device tensors (valid after stream sync)."""
+    n = _matrix(cost_matrix)
+    best_perm = torch.empty(n, dtype=torch.int32, device=cost_matrix.device)
+    best_cost = torch.empty(1, dtype=torch.int64, device=cost_matrix.device)
+    _check(lib().cc_local_search(_dev(cost_matrix, torch.int32, "cost_matrix"), n, objective, move_classes, restarts,
+                                 seed & (2**64 - 1), _dev(best_perm, torch.int32, "best_perm"),
+                                 _dev(best_cost, torch.int64, "best_cost"), _stream(stream)), "cc_local_search")
+    return best_perm, best_cost
+
+
+def cc_local_search_ex(cost_matrix: torch.Tensor, objective: int, move_classes: int, restarts: int, seed: int,
+                       init_tours: Optional[torch.Tensor] = None, buffers: Optional[SearchBuffers] = None,
+                       stream=None, pick_best: bool = True) -> SearchBuffers:
+    """cc_2opt_search_ex over the move classes `move_classes` (CC_MOVES_*)."""
+    n = _matrix(cost_matrix)
+    if buffers is None:
+        buffers = SearchBuffers(n, objective, restarts, cost_matrix.device)
+    if (buffers.n, buffers.restarts) != (n, restarts):
+        raise ValueError("buffers were sized for a different search")
+    if init_tours is not None and tuple(init_tours.shape) != (restarts, n):
+        raise ValueError("init_tours must be [restarts, N]")
+    b = buffers
+    _check(lib().cc_local_search_ex(_dev(cost_matrix, torch.int32, "cost_matrix"), n, objective, move_classes,
+                                    restarts, seed & (2**64 - 1), _dev(init_tours, torch.int32, "init_tours"),
+                                    _dev(b.best_perm, torch.int32, "best_perm") if pick_best else None,
+                                    _dev(b.best_cost, torch.int64, "best_cost") if pick_best else None,
+                                    _dev(b.best_restart, torch.int32, "best_restart") if pick_best else None,
+                                    _dev(b.restart_costs, torch.int64, "restart_costs"),
+                                    _dev(b.restart_tours, torch.int32, "restart_tours"),
+                                    _dev(b.restart_moves, torch.int32, "restart_moves"),
+                                    ctypes.c_void_p(b.ws_ptr), b.ws_bytes, _stream(stream)), "cc_local_search_ex")
     return b
 
 

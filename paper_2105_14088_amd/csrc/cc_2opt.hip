@@ -48,7 +48,7 @@ __device__ void block_scan(int32_t* arr, int N) {
 template <int OBJ, bool LDS_MATRIX>
 __global__ void twoopt_general_kernel(const int32_t* __restrict__ c, int N, int32_t* __restrict__ tours,
                                       int64_t* __restrict__ costs, int32_t* __restrict__ moves,
-                                      const int32_t* __restrict__ skip_if_small) {
+                                      const int32_t* __restrict__ skip_if_small, int with_flip) {
     // when a 16-bit fast path is launched beside this kernel, flags[0] = max(c) decides which of the two runs
     if (skip_if_small && skip_if_small[0] < (1 << 16)) return;
     constexpr bool IS_MAX = (OBJ & 1) != 0;
@@ -176,6 +176,11 @@ __global__ void twoopt_general_kernel(const int32_t* __restrict__ c, int N, int3
                 }
             }
         }
+        // the orientation flip, the pair (1, N-1) that the move set leaves out: every hop walked the other way
+        if (DIRECTED && with_flip && tid == 0 && N >= 3) {
+            const int v = IS_MAX ? max(pb[N - 1], b[0]) : pb[N - 1];
+            best = ((unsigned long long)(unsigned)v << 32) | ((unsigned)(N + N - 1) * 2u);
+        }
         best = wave_min_u64(best);
         if (lane == 0) red[wv] = best;
         __syncthreads();
@@ -260,7 +265,7 @@ __global__ __launch_bounds__(1024) void best_restart_kernel(const int64_t* __res
 
 template <int OBJ>
 hipError_t launch_general(const int32_t* c, int N, int restarts, int32_t* tours, int64_t* costs, int32_t* moves,
-                          const int32_t* skip_if_small, hipStream_t s) {
+                          const int32_t* skip_if_small, int with_flip, hipStream_t s) {
     const int threads = ((N + 63) / 64) * 64;
     if (N <= kGeneralLdsMatrixMaxN) {
         const size_t lds = sizeof(int32_t) * (7 * (size_t)N + (size_t)N * N);
@@ -270,22 +275,24 @@ hipError_t launch_general(const int32_t* c, int N, int restarts, int32_t* tours,
             if (e != hipSuccess) return e;
         }
         hipLaunchKernelGGL((twoopt_general_kernel<OBJ, true>), dim3(restarts), dim3(threads), lds, s, c, N, tours, costs,
-                           moves, skip_if_small);
+                           moves, skip_if_small, with_flip);
     } else {
         const size_t lds = sizeof(int32_t) * 7 * (size_t)N;
         hipLaunchKernelGGL((twoopt_general_kernel<OBJ, false>), dim3(restarts), dim3(threads), lds, s, c, N, tours, costs,
-                           moves, skip_if_small);
+                           moves, skip_if_small, with_flip);
     }
     return hipGetLastError();
 }
 
 hipError_t launch_general_objective(const int32_t* c, int N, int objective, int restarts, int32_t* tours,
-                                    int64_t* costs, int32_t* moves, const int32_t* skip_if_small, hipStream_t s) {
+                                    int64_t* costs, int32_t* moves, const int32_t* skip_if_small, bool with_flip,
+                                    hipStream_t s) {
+    const int flip = with_flip ? 1 : 0;
     switch (objective) {
-        case 0: return launch_general<0>(c, N, restarts, tours, costs, moves, skip_if_small, s);
-        case 1: return launch_general<1>(c, N, restarts, tours, costs, moves, skip_if_small, s);
-        case 2: return launch_general<2>(c, N, restarts, tours, costs, moves, skip_if_small, s);
-        default: return launch_general<3>(c, N, restarts, tours, costs, moves, skip_if_small, s);
+        case 0: return launch_general<0>(c, N, restarts, tours, costs, moves, skip_if_small, 0, s);
+        case 1: return launch_general<1>(c, N, restarts, tours, costs, moves, skip_if_small, 0, s);
+        case 2: return launch_general<2>(c, N, restarts, tours, costs, moves, skip_if_small, flip, s);
+        default: return launch_general<3>(c, N, restarts, tours, costs, moves, skip_if_small, flip, s);
     }
 }
 
@@ -298,11 +305,21 @@ hipError_t launch_best_restart(const int64_t* costs, const int32_t* tours, int N
     return hipGetLastError();
 }
 
-hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, uint64_t seed, bool tours_hold_init,
-                       int32_t* tours, int64_t* costs, int32_t* moves, int32_t* flags, uint16_t* mat16,
-                       int32_t* best_perm, int64_t* best_cost, int32_t* best_restart, hipStream_t s) {
+hipError_t launch_2opt(const int32_t* c, int N, int objective, int classes, int restarts, uint64_t seed,
+                       bool tours_hold_init, int32_t* tours, int64_t* costs, int32_t* moves, int32_t* flags,
+                       uint16_t* mat16, int32_t* best_perm, int64_t* best_cost, int32_t* best_restart, hipStream_t s) {
     hipError_t e;
-    if (N == 64 && objective == 0) {
+    if (classes != kMoves2opt) {
+        // wider move sets: the segment-insertion kernel (ring sum) or the general kernel with the orientation flip
+        if (!tours_hold_init) {
+            e = launch_init_tours(N, 0, restarts, seed, tours, s);
+            if (e != hipSuccess) return e;
+        }
+        if (classes & kMovesOropt)
+            e = launch_insertion_search(c, N, (classes & kMoves2opt) != 0, restarts, tours, costs, moves, s);
+        else
+            e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, nullptr, true, s);
+    } else if (N == 64 && objective == 0) {
         e = launch_2opt_sum_n64(c, restarts, seed, !tours_hold_init, tours, costs, moves, s);
     } else if (N == 64 && (objective & 1)) {
         e = launch_2opt_max_n64(c, restarts, seed, !tours_hold_init, tours, costs, moves, s);
@@ -318,21 +335,21 @@ hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, uin
             if (e != hipSuccess) return e;
             e = launch_2opt_sum_multi(c, N, restarts, tours, costs, moves, flags, s);
             if (e != hipSuccess) return e;
-            e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, s);
+            e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, false, s);
         } else if (objective == 0 && N >= 4 && N <= 256) {
             e = launch_matrix_max(c, N, flags, s);
             if (e != hipSuccess) return e;
             e = launch_2opt_sum_flex(c, N, restarts, tours, costs, moves, flags, s);
             if (e != hipSuccess) return e;
-            e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, s);
+            e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, false, s);
         } else if (objective == 0 && (N == 512 || N == 1024)) {
             e = launch_matrix_max(c, N, flags, s);
             if (e != hipSuccess) return e;
             e = launch_2opt_sum_n1024(c, N, mat16, restarts, tours, costs, moves, flags, s);
             if (e != hipSuccess) return e;
-            e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, s);
+            e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, false, s);
         } else {
-            e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, nullptr, s);
+            e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, nullptr, false, s);
         }
     }
     if (e != hipSuccess) return e;

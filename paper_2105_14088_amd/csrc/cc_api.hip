@@ -127,12 +127,20 @@ size_t cc_2opt_workspace_bytes(int32_t N, int32_t objective, int32_t restarts) {
     return ws_layout(N, restarts).total;
 }
 
-int cc_2opt_search_ex(const int32_t* cost_matrix, int32_t N, int32_t objective, int32_t restarts, uint64_t seed,
-                      const int32_t* init_tours, int32_t* best_perm, int64_t* best_cost, int32_t* best_restart,
-                      int64_t* restart_costs, int32_t* restart_tours, int32_t* restart_moves, void* workspace,
-                      size_t workspace_bytes, void* stream) {
+// Which move classes go with which objective (cc.h, cc_local_search).
+static bool classes_ok(int objective, int classes) {
+    if (classes == CC_MOVES_2OPT) return true;
+    if (classes == CC_MOVES_OROPT || classes == (CC_MOVES_2OPT | CC_MOVES_OROPT)) return objective == CC_RING_SUM;
+    if (classes == (CC_MOVES_2OPT | CC_MOVES_FLIP)) return (objective & 2) != 0;
+    return false;
+}
+
+static int ring_search_ex(const int32_t* cost_matrix, int32_t N, int32_t objective, int32_t classes, int32_t restarts,
+                          uint64_t seed, const int32_t* init_tours, int32_t* best_perm, int64_t* best_cost,
+                          int32_t* best_restart, int64_t* restart_costs, int32_t* restart_tours,
+                          int32_t* restart_moves, void* workspace, size_t workspace_bytes, void* stream) {
     if (int rc = check_matrix_args(cost_matrix, N)) return rc;
-    if (objective < 0 || objective > 3 || restarts < 1) return CC_ERR_INVALID_ARG;
+    if (objective < 0 || objective > 3 || restarts < 1 || !classes_ok(objective, classes)) return CC_ERR_INVALID_ARG;
     // either both best_* outputs, or neither and then the per-restart costs and orders
     if ((best_perm == nullptr) != (best_cost == nullptr)) return CC_ERR_INVALID_ARG;
     if (!best_perm && (best_restart || !restart_costs || !restart_tours)) return CC_ERR_INVALID_ARG;
@@ -147,9 +155,47 @@ int cc_2opt_search_ex(const int32_t* cost_matrix, int32_t N, int32_t objective, 
     if (init_tours && init_tours != tours)
         CC_HIP(hipMemcpyAsync(tours, init_tours, sizeof(int32_t) * (size_t)restarts * (size_t)N,
                               hipMemcpyDeviceToDevice, s));
-    CC_HIP(cc::launch_2opt(cost_matrix, N, objective, restarts, seed, init_tours != nullptr, tours, costs, moves, flags,
-                           (uint16_t*)(base + w.mat16), best_perm, best_cost, best_restart, s));
+    CC_HIP(cc::launch_2opt(cost_matrix, N, objective, classes, restarts, seed, init_tours != nullptr, tours, costs,
+                           moves, flags, (uint16_t*)(base + w.mat16), best_perm, best_cost, best_restart, s));
     return CC_OK;
+}
+
+static int ring_search(const int32_t* cost_matrix, int32_t N, int32_t objective, int32_t classes, int32_t restarts,
+                       uint64_t seed, int32_t* best_perm, int64_t* best_cost, void* stream) {
+    if (int rc = check_matrix_args(cost_matrix, N)) return rc;
+    if (objective < 0 || objective > 3 || restarts < 1 || !best_perm || !best_cost || !classes_ok(objective, classes))
+        return CC_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    const size_t bytes = cc_2opt_workspace_bytes(N, objective, restarts);
+    void* ws = nullptr;
+    CC_HIP(hipMallocAsync(&ws, bytes, s));
+    const int rc = ring_search_ex(cost_matrix, N, objective, classes, restarts, seed, nullptr, best_perm, best_cost,
+                                  nullptr, nullptr, nullptr, nullptr, ws, bytes, stream);
+    const hipError_t e = hipFreeAsync(ws, s);   // stream-ordered: released after the search has run
+    if (rc != CC_OK) return rc;
+    if (e != hipSuccess) return hip_fail(e);
+    return CC_OK;
+}
+
+int cc_2opt_search_ex(const int32_t* cost_matrix, int32_t N, int32_t objective, int32_t restarts, uint64_t seed,
+                      const int32_t* init_tours, int32_t* best_perm, int64_t* best_cost, int32_t* best_restart,
+                      int64_t* restart_costs, int32_t* restart_tours, int32_t* restart_moves, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+    return ring_search_ex(cost_matrix, N, objective, CC_MOVES_2OPT, restarts, seed, init_tours, best_perm, best_cost,
+                          best_restart, restart_costs, restart_tours, restart_moves, workspace, workspace_bytes, stream);
+}
+
+int cc_local_search_ex(const int32_t* cost_matrix, int32_t N, int32_t objective, int32_t move_classes,
+                       int32_t restarts, uint64_t seed, const int32_t* init_tours, int32_t* best_perm,
+                       int64_t* best_cost, int32_t* best_restart, int64_t* restart_costs, int32_t* restart_tours,
+                       int32_t* restart_moves, void* workspace, size_t workspace_bytes, void* stream) {
+    return ring_search_ex(cost_matrix, N, objective, move_classes, restarts, seed, init_tours, best_perm, best_cost,
+                          best_restart, restart_costs, restart_tours, restart_moves, workspace, workspace_bytes, stream);
+}
+
+int cc_local_search(const int32_t* cost_matrix, int32_t N, int32_t objective, int32_t move_classes, int32_t restarts,
+                    uint64_t seed, int32_t* best_perm, int64_t* best_cost, void* stream) {
+    return ring_search(cost_matrix, N, objective, move_classes, restarts, seed, best_perm, best_cost, stream);
 }
 
 int cc_best_of_restarts(const int64_t* restart_costs, const int32_t* restart_tours, int32_t N, int32_t restarts,
@@ -163,18 +209,7 @@ int cc_best_of_restarts(const int64_t* restart_costs, const int32_t* restart_tou
 
 int cc_2opt_search(const int32_t* cost_matrix, int32_t N, int32_t objective, int32_t restarts, uint64_t seed,
                    int32_t* best_perm, int64_t* best_cost, void* stream) {
-    if (int rc = check_matrix_args(cost_matrix, N)) return rc;
-    if (objective < 0 || objective > 3 || restarts < 1 || !best_perm || !best_cost) return CC_ERR_INVALID_ARG;
-    hipStream_t s = (hipStream_t)stream;
-    const size_t bytes = cc_2opt_workspace_bytes(N, objective, restarts);
-    void* ws = nullptr;
-    CC_HIP(hipMallocAsync(&ws, bytes, s));
-    const int rc = cc_2opt_search_ex(cost_matrix, N, objective, restarts, seed, nullptr, best_perm, best_cost, nullptr,
-                                     nullptr, nullptr, nullptr, ws, bytes, stream);
-    const hipError_t e = hipFreeAsync(ws, s);   // stream-ordered: released after the search has run
-    if (rc != CC_OK) return rc;
-    if (e != hipSuccess) return hip_fail(e);
-    return CC_OK;
+    return ring_search(cost_matrix, N, objective, CC_MOVES_2OPT, restarts, seed, best_perm, best_cost, stream);
 }
 
 size_t cc_rd_swap_workspace_bytes(int32_t N, int32_t restarts) {
@@ -352,6 +387,6 @@ const char* cc_status_string(int status) {
 
 int cc_last_hip_error(void) { return g_last_hip_error; }
 
-int cc_version(void) { return 400; }
+int cc_version(void) { return 500; }
 
 }  // extern "C"

@@ -30,9 +30,16 @@ hipError_t launch_validate(const int32_t* c, int N, bool require_symmetric, int3
 // `tours` ([restarts, N]) receives the final tours; if `tours_hold_init` it holds the initial tours on
 // entry, otherwise restart r starts from the seeded shuffle (seed, r).  `flags` is a small int32
 // device scratch area (>= 64 B); `mat16` has room for N*N 16-bit entries when N > 256.
-hipError_t launch_2opt(const int32_t* c, int N, int objective, int restarts, uint64_t seed, bool tours_hold_init,
-                       int32_t* tours, int64_t* costs, int32_t* moves, int32_t* flags, uint16_t* mat16,
-                       int32_t* best_perm, int64_t* best_cost, int32_t* best_restart, hipStream_t s);
+// `classes` is the set of move classes (cc.h, CC_MOVES_*): 2-opt alone takes the specialised kernels.
+constexpr int kMoves2opt = 1, kMovesOropt = 2, kMovesFlip = 4;
+hipError_t launch_2opt(const int32_t* c, int N, int objective, int classes, int restarts, uint64_t seed,
+                       bool tours_hold_init, int32_t* tours, int64_t* costs, int32_t* moves, int32_t* flags,
+                       uint16_t* mat16, int32_t* best_perm, int64_t* best_cost, int32_t* best_restart, hipStream_t s);
+
+// Descent over segment insertions, with or without the 2-opt moves, ring-sum objective (cc_local.hip).  `tours`
+// must hold the initial tours.
+hipError_t launch_insertion_search(const int32_t* c, int N, bool with_2opt, int restarts, int32_t* tours,
+                                   int64_t* costs, int32_t* moves, hipStream_t s);
 
 // N = 64, ring-sum objective: one wavefront per restart (cc_2opt_n64.hip).
 hipError_t launch_2opt_sum_n64(const int32_t* c, int restarts, uint64_t seed, bool generate, int32_t* tours,

@@ -110,6 +110,18 @@ def test_argument_errors_are_returned_before_any_launch():
     assert L.cc_2opt_search_ex(fake, 64, 0, 4, 1, null, fake, null, null, fake, fake, null, ws, 1 << 30, null) == INVALID
     assert L.cc_2opt_search_ex(fake, 64, 0, 4, 1, null, null, null, null, null, fake, null, ws, 1 << 30, null) == INVALID
     assert L.cc_2opt_search_ex(fake, 64, 0, 4, 1, null, null, null, fake, fake, fake, null, ws, 1 << 30, null) == INVALID
+    # move classes: only the documented (objective, classes) pairs are accepted
+    for objective in range(4):
+        for classes in range(0, 9):
+            ok = (classes == 1 or (classes in (2, 3) and objective == 0) or (classes == 5 and objective in (2, 3)))
+            rc = L.cc_local_search_ex(fake, 64, objective, classes, 4, 1, null, fake, fake, null, null, null, null,
+                                      null, 0, null)
+            assert rc == (WORKSPACE if ok else INVALID), (objective, classes)     # the workspace check comes last
+            if not ok:
+                assert L.cc_local_search(fake, 64, objective, classes, 4, 1, fake, fake, null) == INVALID
+    assert L.cc_local_search(null, 64, 0, 3, 4, 1, fake, fake, null) == INVALID
+    assert L.cc_local_search(fake, 64, 0, 3, 0, 1, fake, fake, null) == INVALID
+    assert L.cc_local_search(fake, 1025, 0, 3, 1, 1, fake, fake, null) == UNSUPPORTED
     assert L.cc_best_of_restarts(null, fake, 64, 4, fake, fake, null, null) == INVALID
     assert L.cc_best_of_restarts(fake, fake, 64, 0, fake, fake, null, null) == INVALID
     assert L.cc_best_of_restarts(fake, fake, 1, 4, fake, fake, null, null) == UNSUPPORTED

@@ -316,7 +316,7 @@ hipError_t launch_2opt(const int32_t* c, int N, int objective, int classes, int 
             if (e != hipSuccess) return e;
         }
         if (classes & kMovesOropt)
-            e = launch_insertion_search(c, N, (classes & kMoves2opt) != 0, restarts, tours, costs, moves, s);
+            e = launch_insertion_search(c, N, (classes & kMoves2opt) != 0, restarts, tours, costs, moves, flags, s);
         else
             e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, nullptr, true, s);
     } else if (N == 64 && objective == 0) {

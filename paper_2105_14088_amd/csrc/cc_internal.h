@@ -39,7 +39,11 @@ hipError_t launch_2opt(const int32_t* c, int N, int objective, int classes, int 
 // Descent over segment insertions, with or without the 2-opt moves, ring-sum objective (cc_local.hip).  `tours`
 // must hold the initial tours.
 hipError_t launch_insertion_search(const int32_t* c, int N, bool with_2opt, int restarts, int32_t* tours,
-                                   int64_t* costs, int32_t* moves, hipStream_t s);
+                                   int64_t* costs, int32_t* moves, int32_t* flags, hipStream_t s);
+// The same search for N = 64 and max(c) < 2^16, one wavefront per restart (cc_local_n64.hip); returns at once if
+// flags[0] >= 2^16 (flags[0] = matrix maximum, launch_matrix_max).
+hipError_t launch_local_n64(const int32_t* c, bool with_2opt, int restarts, int32_t* tours, int64_t* costs,
+                            int32_t* moves, const int32_t* flags, hipStream_t s);
 
 // N = 64, ring-sum objective: one wavefront per restart (cc_2opt_n64.hip).
 hipError_t launch_2opt_sum_n64(const int32_t* c, int restarts, uint64_t seed, bool generate, int32_t* tours,

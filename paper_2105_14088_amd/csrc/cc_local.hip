@@ -27,7 +27,10 @@ __device__ __forceinline__ unsigned long long key_of(int value, unsigned id) {
 
 template <bool WITH_2OPT, bool LDS_MATRIX>
 __global__ void insertion_search_kernel(const int32_t* __restrict__ c, int N, int32_t* __restrict__ tours,
-                                        int64_t* __restrict__ costs, int32_t* __restrict__ moves) {
+                                        int64_t* __restrict__ costs, int32_t* __restrict__ moves,
+                                        const int32_t* __restrict__ skip_if_small) {
+    // when the 16-bit fast path is launched beside this kernel, skip_if_small[0] = max(c) decides which one runs
+    if (skip_if_small && skip_if_small[0] < (1 << 16)) return;
     extern __shared__ int32_t sm[];
     int32_t* t = sm;            // tour
     int32_t* f = t + N;         // f[p] = c[t[p]][t[p-1]]
@@ -174,16 +177,16 @@ __global__ void insertion_search_kernel(const int32_t* __restrict__ c, int N, in
 
 template <bool WITH_2OPT>
 hipError_t launch_insertion(const int32_t* c, int N, int restarts, int32_t* tours, int64_t* costs, int32_t* moves,
-                            hipStream_t s) {
+                            const int32_t* skip_if_small, hipStream_t s) {
     const int threads = ((N + 63) / 64) * 64;
     if (N <= kLdsMatrixMaxN) {
         const size_t lds = sizeof(int32_t) * (2 * (size_t)N + (size_t)N * N);
         hipLaunchKernelGGL((insertion_search_kernel<WITH_2OPT, true>), dim3(restarts), dim3(threads), lds, s, c, N, tours,
-                           costs, moves);
+                           costs, moves, skip_if_small);
     } else {
         const size_t lds = sizeof(int32_t) * 2 * (size_t)N;
         hipLaunchKernelGGL((insertion_search_kernel<WITH_2OPT, false>), dim3(restarts), dim3(threads), lds, s, c, N,
-                           tours, costs, moves);
+                           tours, costs, moves, skip_if_small);
     }
     return hipGetLastError();
 }
@@ -191,9 +194,19 @@ hipError_t launch_insertion(const int32_t* c, int N, int restarts, int32_t* tour
 }  // namespace
 
 hipError_t launch_insertion_search(const int32_t* c, int N, bool with_2opt, int restarts, int32_t* tours,
-                                   int64_t* costs, int32_t* moves, hipStream_t s) {
-    return with_2opt ? launch_insertion<true>(c, N, restarts, tours, costs, moves, s)
-                     : launch_insertion<false>(c, N, restarts, tours, costs, moves, s);
+                                   int64_t* costs, int32_t* moves, int32_t* flags, hipStream_t s) {
+    const int32_t* skip = nullptr;
+    if (N == 64) {
+        // one wavefront per restart with 32-bit keys when max(c) < 2^16, else the kernel above: both are enqueued
+        // and the matrix maximum, computed on the device, decides which of them does the work
+        hipError_t e = launch_matrix_max(c, N, flags, s);
+        if (e != hipSuccess) return e;
+        e = launch_local_n64(c, with_2opt, restarts, tours, costs, moves, flags, s);
+        if (e != hipSuccess) return e;
+        skip = flags;
+    }
+    return with_2opt ? launch_insertion<true>(c, N, restarts, tours, costs, moves, skip, s)
+                     : launch_insertion<false>(c, N, restarts, tours, costs, moves, skip, s);
 }
 
 }  // namespace cc

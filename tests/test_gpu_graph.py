@@ -54,3 +54,47 @@ def test_search_and_batch_calls_replay_in_a_graph():
                out_rd)
         for g, w in zip(got, want):
             assert torch.equal(g, w), f"replay {replay}"
+
+
+def test_local_search_replays_in_a_graph():
+    """cc_local_search_ex: seeded starts, the matrix-maximum kernel, the wavefront kernel and the skipped general
+    kernel (N = 64), and the general kernel alone (N = 100), all inside one captured step."""
+    say("HIP graph: capture cc_local_search_ex at N = 64 and N = 100, replay 3 times")
+    both = cc.CC_MOVES_2OPT | cc.CC_MOVES_OROPT
+    c64_host = make_matrix(2)
+    c64 = torch.from_numpy(c64_host).cuda()
+    from gen import random_matrix
+    c100_host = random_matrix(100, 5, symmetric=True, lo=1, hi=3000)
+    c100 = torch.from_numpy(c100_host).cuda()
+    b64 = cc.SearchBuffers(64, cc.CC_RING_SUM, 48, c64.device)
+    b100 = cc.SearchBuffers(100, cc.CC_RING_SUM, 12, c64.device)
+
+    def step():
+        cc.cc_local_search_ex(c64, cc.CC_RING_SUM, both, 48, 11, buffers=b64)
+        cc.cc_local_search_ex(c100, cc.CC_RING_SUM, cc.CC_MOVES_OROPT, 12, 12, buffers=b100)
+
+    step()
+    torch.cuda.synchronize()
+    outs = (b64.restart_costs, b64.restart_tours, b64.restart_moves, b64.best_perm, b64.best_cost, b64.best_restart,
+            b100.restart_costs, b100.restart_tours, b100.restart_moves, b100.best_perm, b100.best_cost)
+    want = [t.clone() for t in outs]
+    ref64 = oracle.local_search(c64_host, oracle.SUM, both, 48, 11)
+    ref100 = oracle.local_search(c100_host, oracle.SUM, oracle.MOVES_OROPT, 12, 12)
+    assert np.array_equal(want[1].cpu().numpy(), ref64["tours"]) and np.array_equal(want[7].cpu().numpy(), ref100["tours"])
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for replay in range(3):
+        for t in outs:
+            t.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for g, w in zip(outs, want):
+            assert torch.equal(g, w), f"replay {replay}"

@@ -70,3 +70,29 @@ def test_swap_and_annealing_random_cases(block):
         assert np.array_equal(b.restart_costs.cpu().numpy(), want["costs"])
         assert np.array_equal(b.restart_tours.cpu().numpy(), want["tours"])
         assert np.array_equal(b.restart_moves.cpu().numpy(), want["accepted"])
+
+
+@pytest.mark.parametrize("block", range(3))
+def test_local_search_random_cases(block):
+    """Wider move sets: segment insertion with or without 2-opt (ring sum), 2-opt with the orientation flip (directed
+    objectives); N = 64 is drawn often because it has a kernel of its own with a fallback at the 16-bit boundary."""
+    rng = np.random.default_rng(900 + block)
+    both = cc.CC_MOVES_2OPT | cc.CC_MOVES_OROPT
+    for k in range(16):
+        n = int(rng.choice(SIZES + [64] * 8))
+        hi = int(rng.choice(HIS))
+        restarts = int(rng.integers(1, 30 if n <= 128 else 6))
+        seed = int(rng.integers(0, 2**62))
+        kind = int(rng.integers(0, 3))
+        if kind < 2:
+            classes, obj = (cc.CC_MOVES_OROPT, both)[kind], oracle.SUM
+        else:
+            classes, obj = cc.CC_MOVES_2OPT | cc.CC_MOVES_FLIP, int(rng.choice([oracle.SUM_DIRECTED, oracle.MAX_DIRECTED]))
+        say(f"sweep {block}.{k}: local search N={n} classes={classes} objective={obj} entries<={hi} restarts={restarts}")
+        c = random_matrix(n, 53 * block + k, symmetric=not (obj & 2), lo=0 if hi > 2 else 1, hi=hi)
+        b = cc.cc_local_search_ex(dev(c), obj, classes, restarts, seed)
+        torch.cuda.synchronize()
+        got = dict(best_perm=b.best_perm.cpu().numpy(), best_cost=int(b.best_cost.item()),
+                   best_restart=int(b.best_restart.item()), costs=b.restart_costs.cpu().numpy(),
+                   tours=b.restart_tours.cpu().numpy(), moves=b.restart_moves.cpu().numpy())
+        assert_search_equal(got, oracle.local_search(c, obj, classes, restarts, seed))

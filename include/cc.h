@@ -24,7 +24,11 @@
  *     before anything is launched.  Data errors (entries out of range, indices out of range, an
  *     asymmetric matrix given to an undirected objective) are not detected by the compute calls:
  *     results are then unspecified, but all memory accesses stay inside the caller's buffers
- *     (indices are clamped).  cc_validate_matrix checks the matrix contract.
+ *     (indices and entries are clamped) and every call ends: the ring-sum searches read the matrix
+ *     through its upper triangle (entry (min(a,b), max(a,b)) for the pair a, b), so their move
+ *     values are exact for the matrix they see; the max-hop and directed searches score true costs
+ *     of the orders they produce; the annealing calls run a fixed number of steps.
+ *     cc_validate_matrix checks the matrix contract.
  *   - All arithmetic is exact integer; costs are returned as int64.
  */
 #ifndef CC_H_

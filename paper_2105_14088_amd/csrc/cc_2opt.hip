@@ -71,9 +71,15 @@ __global__ void twoopt_general_kernel(const int32_t* __restrict__ c, int N, int3
     // entries are clamped to the contract range: all int32 arithmetic below is then exact, every applied
     // move lowers the true cost, and the descent terminates whatever the buffer holds
     int32_t* m = sb + N;
+    // the ring-sum objective reads the matrix through its upper triangle (exact deltas, hence a descent that ends,
+    // whatever the caller's matrix holds); the other objectives score true values of the orders they produce
+    constexpr bool UPPER = OBJ == 0;
     if (LDS_MATRIX)
-        for (int e = tid; e < N * N; e += blockDim.x) m[e] = clampi(c[e], 0, (1 << 21) - 1);
-    auto C = [&](int a, int b2) { return LDS_MATRIX ? m[a * N + b2] : clampi(c[a * N + b2], 0, (1 << 21) - 1); };
+        for (int e = tid; e < N * N; e += blockDim.x) m[e] = clampi(c[UPPER ? upper_index(e, N) : e], 0, (1 << 21) - 1);
+    auto C = [&](int a, int b2) {
+        if (LDS_MATRIX) return m[a * N + b2];
+        return clampi(UPPER ? c[min(a, b2) * N + max(a, b2)] : c[a * N + b2], 0, (1 << 21) - 1);
+    };
     if (tid < N) t[tid] = clampi(tours[r * N + tid], 0, N - 1);
     __syncthreads();
 

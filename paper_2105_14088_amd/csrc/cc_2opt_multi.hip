@@ -92,7 +92,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void twoopt_sum_multi_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     // stage the matrix as 16-bit entries, two per 32-bit store
     for (int e = tid; e < N * N / 2; e += blockDim.x) {
-        const int lo = clampi(c[2 * e], 0, 0xffff), hi = clampi(c[2 * e + 1], 0, 0xffff);
+        const int lo = clampi(c[upper_index(2 * e, N)], 0, 0xffff), hi = clampi(c[upper_index(2 * e + 1, N)], 0, 0xffff);
         ((uint32_t*)mat)[e] = (uint32_t)lo | ((uint32_t)hi << 16);
     }
     __syncthreads();
@@ -240,7 +240,7 @@ __global__ void twoopt_sum_flex_kernel(const int32_t* __restrict__ c, int N, int
     unsigned char* slice = smem + (((size_t)N * N * 2 + 15) & ~(size_t)15) + (size_t)wv * slice_bytes;
     int2* P = (int2*)slice;
     int32_t* T = (int32_t*)(slice + (size_t)N * 16);
-    for (int e = tid; e < N * N; e += blockDim.x) mat[e] = (uint16_t)clampi(c[e], 0, 0xffff);
+    for (int e = tid; e < N * N; e += blockDim.x) mat[e] = (uint16_t)clampi(c[upper_index(e, N)], 0, 0xffff);
     __syncthreads();
     const int64_t r = (int64_t)blockIdx.x * waves + wv;
     if (r >= restarts) return;

@@ -64,13 +64,13 @@ __device__ __forceinline__ void wait_rows(int rows_in_flight) {
     }
 }
 
-// 16-bit copy of the matrix (entries clamped); skipped when the maximum does not fit
-__global__ __launch_bounds__(256) void matrix_to_u16_kernel(const int32_t* __restrict__ c, int n2,
+// 16-bit copy of the matrix (entries clamped, upper triangle mirrored); skipped when the maximum does not fit
+__global__ __launch_bounds__(256) void matrix_to_u16_kernel(const int32_t* __restrict__ c, int n,
                                                             uint16_t* __restrict__ c16,
                                                             const int32_t* __restrict__ flags) {
     if (flags[0] >= (1 << 16)) return;
-    for (int e = blockIdx.x * 256 + threadIdx.x; e < n2 / 2; e += gridDim.x * 256) {
-        const int lo = clampi(c[2 * e], 0, 0xffff), hi = clampi(c[2 * e + 1], 0, 0xffff);
+    for (int e = blockIdx.x * 256 + threadIdx.x; e < n * n / 2; e += gridDim.x * 256) {
+        const int lo = clampi(c[upper_index(2 * e, n)], 0, 0xffff), hi = clampi(c[upper_index(2 * e + 1, n)], 0, 0xffff);
         ((uint32_t*)c16)[e] = (uint32_t)lo | ((uint32_t)hi << 16);
     }
 }
@@ -279,7 +279,7 @@ template <int LOGN>
 static hipError_t launch_rows(const int32_t* c, uint16_t* c16, int restarts, int32_t* tours, int64_t* costs,
                               int32_t* moves, const int32_t* flags, hipStream_t s) {
     using L = Shape<LOGN>;
-    hipLaunchKernelGGL(matrix_to_u16_kernel, dim3(512), dim3(256), 0, s, c, L::N * L::N, c16, flags);
+    hipLaunchKernelGGL(matrix_to_u16_kernel, dim3(512), dim3(256), 0, s, c, L::N, c16, flags);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute((const void*)twoopt_sum_n1024_kernel<LOGN>, hipFuncAttributeMaxDynamicSharedMemorySize,

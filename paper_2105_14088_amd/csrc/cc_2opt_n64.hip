@@ -136,6 +136,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
 #pragma unroll
     for (int k = 0; k < kN * kN / 256; ++k) m[tid + 256 * k] = wide ? v[k] : (v[k] << kSh);
     __syncthreads();
+    // the search reads the matrix through its upper triangle: exact deltas, hence a descent that ends, whatever
+    // the caller's matrix holds
+    mirror_upper_triangle_64(m, tid);
+    __syncthreads();
     if (r >= restarts) return;
     long long cost;
     int applied;

@@ -25,6 +25,14 @@ __device__ __forceinline__ int shuffle_partner(uint64_t seed, uint32_t r, int k)
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
+// Flat index of entry (min(x, y), max(x, y)) for the flat index e = x * n + y: the ring-sum searches read the matrix
+// through its upper triangle, so their deltas are exact for the matrix they see and every descent ends even when the
+// caller's matrix is not symmetric.
+__device__ __forceinline__ int upper_index(int e, int n) {
+    const int x = e / n, y = e - x * n;
+    return min(x, y) * n + max(x, y);
+}
+
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
 // Reductions over the 64 lanes of a wave; every lane ends with the result.  The 32-bit forms use six DPP steps

@@ -44,9 +44,12 @@ __global__ void insertion_search_kernel(const int32_t* __restrict__ c, int N, in
     const int64_t r = blockIdx.x;
     // entries are clamped to the contract range: all int32 arithmetic is then exact, every applied move lowers
     // the true cost, and the descent ends whatever the buffer holds
+    // and the matrix is read through its upper triangle, so the deltas are exact for the matrix the kernel sees
     if (LDS_MATRIX)
-        for (int e = tid; e < N * N; e += blockDim.x) m[e] = clampi(c[e], 0, kCostMax);
-    auto C = [&](int a, int b) { return LDS_MATRIX ? m[a * N + b] : clampi(c[a * N + b], 0, kCostMax); };
+        for (int e = tid; e < N * N; e += blockDim.x) m[e] = clampi(c[upper_index(e, N)], 0, kCostMax);
+    auto C = [&](int a, int b) {
+        return LDS_MATRIX ? m[a * N + b] : clampi(c[min(a, b) * N + max(a, b)], 0, kCostMax);
+    };
     if (tid < N) t[tid] = clampi(tours[r * N + tid], 0, N - 1);
     __syncthreads();
 

@@ -157,6 +157,8 @@ __global__ __launch_bounds__(256) void local_n64_kernel(const int32_t* __restric
 #pragma unroll
     for (int k = 0; k < kN * kN / 256; ++k) m[tid + 256 * k] = clampi(c[tid + 256 * k], 0, (1 << 16) - 1) << kSh;
     __syncthreads();
+    mirror_upper_triangle_64(m, tid);      // exact deltas for the matrix the search sees, whatever the buffer holds
+    __syncthreads();
     const int64_t r = (int64_t)blockIdx.x * 4 + wv;
     if (r >= restarts) return;
     int t = clampi(tours[r * kN + lane], 0, kN - 1);

@@ -47,6 +47,21 @@ __device__ __forceinline__ long long wave_min_uniform(long long v) {
     return v;
 }
 
+// Mirrors the upper triangle of a 64 x 64 matrix in LDS into the lower one (m[hi][lo] = m[lo][hi] for lo < hi), so
+// that a search reads a symmetric matrix whatever the caller's buffer holds.  For a workgroup of 256 threads; the
+// caller synchronises before and after.  Lane l of wave w takes the pairs {l, l + j} at the cyclic distances
+// j = 1 + w, 5 + w, ..: consecutive lanes touch consecutive banks on the read and on the write.
+__device__ __forceinline__ void mirror_upper_triangle_64(int32_t* m, int tid) {
+    const int lane = tid & 63, wv = tid >> 6;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        const int j = 1 + wv + 4 * s;            // 1 .. 32 over the four waves
+        const int b = (lane + j) & 63;
+        const int lo = min(lane, b), hi = max(lane, b);
+        m[hi * kN + lo] = m[lo * kN + hi];
+    }
+}
+
 // Seeded Fisher-Yates shuffle without a serial chain across lanes.  Lane v follows node v: at step k
 // (k = 63 .. 1) ranks k and j_k swap, so a node sitting at rank k moves to j_k and a node sitting at
 // j_k moves to k, where it stays (later steps only touch ranks below k).  Swap partners are drawn in

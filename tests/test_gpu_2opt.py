@@ -279,3 +279,27 @@ def test_largest_possible_costs_n1024():
     c[5, 9] = c[9, 5] = 1
     want = oracle.search(c, 0, 2, seed=9)
     assert_search_equal(gpu_search(c, 0, 2, seed=9), want)
+
+
+@pytest.mark.parametrize("n", [13, 64, 100, 128, 512])
+def test_sum_objective_reads_only_the_upper_triangle(n):
+    """A matrix that is not symmetric breaks the contract of the undirected objectives; the ring-sum searches then
+    see the matrix mirrored from its upper triangle, so their deltas stay exact and every descent ends.  Checked
+    on matrices whose two triangles disagree completely, with entries on both sides of the 16-bit boundary."""
+    restarts = 12 if n <= 128 else 3
+    for hi in (3000, 70000):
+        c = random_matrix(n, 9100 + n + hi % 7, symmetric=False, lo=0, hi=hi)
+        mirrored = np.triu(c) + np.triu(c, 1).T
+        assert not np.array_equal(c, c.T) and np.array_equal(mirrored, mirrored.T)
+        say(f"2-opt N={n} sum on an asymmetric matrix, entries up to {hi}")
+        want = oracle.search(mirrored, 0, restarts, seed=3 + n)
+        assert_search_equal(gpu_search(c, 0, restarts, seed=3 + n), want)
+        if n <= 128:
+            both = cc.CC_MOVES_2OPT | cc.CC_MOVES_OROPT
+            say(f"2-opt + segment insertion N={n} on the same matrix")
+            b = cc.cc_local_search_ex(dev(c), 0, both, restarts, 3 + n)
+            torch.cuda.synchronize()
+            want = oracle.local_search(mirrored, 0, both, restarts, 3 + n)
+            assert np.array_equal(b.restart_costs.cpu().numpy(), want["costs"])
+            assert np.array_equal(b.restart_tours.cpu().numpy(), want["tours"])
+            assert np.array_equal(b.restart_moves.cpu().numpy(), want["moves"])

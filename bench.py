@@ -39,7 +39,7 @@ LDS_BYTES_PER_MOVE = 8                  # two int32 new-hop gathers per undirect
 VALU_OPS_PER_MOVE = 3                   # combine two gathers with the removed hops, form key, min
 # HBM bytes per launch from rocprofv3 FETCH_SIZE (x 2.000) + WRITE_SIZE (x 1.000), calibrated on a 256 MiB copy
 # (profiles/bench_n64_pmc_counters.md).  Set to None whenever the kernel changes after the counters were taken.
-TRAFFIC_SEARCH_KERNEL_BYTES = (272.0 + 272.0) * 1024
+TRAFFIC_SEARCH_KERNEL_BYTES = (292.0 + 272.0) * 1024
 TRAFFIC_RING_BATCH_BYTES = (262317.6 + 8196.2) * 1024
 
 

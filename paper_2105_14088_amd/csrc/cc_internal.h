@@ -42,6 +42,9 @@ hipError_t launch_insertion_search(const int32_t* c, int N, bool with_2opt, int 
                                    int64_t* costs, int32_t* moves, int32_t* flags, hipStream_t s);
 // The same search for N = 64 and max(c) < 2^16, one wavefront per restart (cc_local_n64.hip); returns at once if
 // flags[0] >= 2^16 (flags[0] = matrix maximum, launch_matrix_max).
+// N = 128 / 192 / 256, several ranks per lane, 16-bit matrix in LDS (cc_local_multi.hip); same flags convention.
+hipError_t launch_local_multi(const int32_t* c, int N, bool with_2opt, int restarts, int32_t* tours, int64_t* costs,
+                              int32_t* moves, const int32_t* flags, hipStream_t s);
 hipError_t launch_local_n64(const int32_t* c, bool with_2opt, int restarts, int32_t* tours, int64_t* costs,
                             int32_t* moves, const int32_t* flags, hipStream_t s);
 

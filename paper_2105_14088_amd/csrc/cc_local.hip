@@ -207,6 +207,12 @@ hipError_t launch_insertion_search(const int32_t* c, int N, bool with_2opt, int 
         e = launch_local_n64(c, with_2opt, restarts, tours, costs, moves, flags, s);
         if (e != hipSuccess) return e;
         skip = flags;
+    } else if (N == 128 || N == 192 || N == 256) {
+        hipError_t e = launch_matrix_max(c, N, flags, s);
+        if (e != hipSuccess) return e;
+        e = launch_local_multi(c, N, with_2opt, restarts, tours, costs, moves, flags, s);
+        if (e != hipSuccess) return e;
+        skip = flags;
     }
     return with_2opt ? launch_insertion<true>(c, N, restarts, tours, costs, moves, skip, s)
                      : launch_insertion<false>(c, N, restarts, tours, costs, moves, skip, s);

@@ -147,3 +147,25 @@ def test_simple_entry_point_and_errors():
         cc.cc_local_search(dev(c), oracle.MAX, OROPT, 12, 3)
     with pytest.raises(cc.CCError):
         cc.cc_local_search(dev(c), oracle.SUM, FLIP, 12, 3)
+
+
+@pytest.mark.parametrize("n,restarts", [(128, 18), (192, 14), (256, 13)])
+@pytest.mark.parametrize("classes", [OROPT, BOTH])
+def test_insertion_n128_n192_n256_wavefront_kernel_and_its_fallback(n, restarts, classes):
+    """Several ranks per lane with a 16-bit LDS matrix when max(c) < 2^16; an entry at 2^16 takes the general kernel
+    (same results either way); a matrix full of ties; caller-provided starts; restart counts that leave the last
+    workgroup partly empty."""
+    for hi, tag in ((5000, "16-bit path"), (65535, "largest entry 65535"), (65536, "fallback at 2^16"), (3, "ties")):
+        if hi >= 65535 and classes == OROPT:
+            continue
+        say(f"local search N={n} classes={classes} entries up to {hi} ({tag})")
+        c = random_matrix(n, 8800 + n + hi % 97, symmetric=True, lo=1, hi=hi)
+        c[2, 7] = c[7, 2] = hi
+        r = restarts if hi == 5000 else 4
+        want = oracle.local_search(c, oracle.SUM, classes, r, seed=19 + n)
+        assert_search_equal(gpu_local(c, oracle.SUM, classes, r, seed=19 + n), want)
+    say(f"local search N={n} classes={classes}, caller-provided starts")
+    c = random_matrix(n, 4444 + n, symmetric=True, lo=1, hi=9000)
+    init = random_perms(n, 5, seed=n)
+    assert_search_equal(gpu_local(c, oracle.SUM, classes, 5, seed=1, init=init),
+                        oracle.local_search(c, oracle.SUM, classes, 5, seed=0, init=init))

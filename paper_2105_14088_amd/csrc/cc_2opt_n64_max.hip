@@ -19,6 +19,12 @@
 // otherwise it is (b, a-1) (or (b, 63) when a = 0) and A / B are orientations 1 / 0.  Per lane two running
 // minima are kept, over key = value << 6 | rank(b), rank(b) = (b-1) mod 64, one for A and one for B; after
 // the sweep both are turned into (value, move id) and min-reduced lexicographically over the wave.
+//
+// Matrices with entries below 2^16 take a packed form of the same sweep: the LDS matrix holds both directions of a
+// pair in one word, c[x][y] | c[y][x] << 16, so one gather delivers G and GT, and every maximum above is taken on
+// both halves at once (v_pk_max_u16): hop words, doubling tables, the running maximum of S1 and the two values of a
+// move, A in the upper and B in the lower half.  The tables of S2 are built from the hop word with its halves
+// swapped, which is the pairing the two values need (A: S2's f with S1's b; B: S2's b with S1's f).
 #include "cc_device.h"
 #include "cc_internal.h"
 #include "cc_wave64.h"
@@ -33,26 +39,8 @@ using namespace w64;
 constexpr int kCostMax = (1 << 21) - 1;
 constexpr int kNone = 0x7fffffff;
 
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2)))
-void twoopt_max_n64_kernel(const int32_t* __restrict__ c, int restarts, uint64_t seed, int generate,
-                           int32_t* __restrict__ tours, int64_t* __restrict__ costs,
-                           int32_t* __restrict__ moves) {
-    __shared__ __attribute__((aligned(256))) int32_t m[kN * kN];
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-
-    // the matrix loads are issued first and stay in flight while the wave builds its initial tour
-    int v[kN * kN / 256];
-#pragma unroll
-    for (int k = 0; k < kN * kN / 256; ++k) v[k] = c[tid + 256 * k];
-    const int64_t r = (int64_t)blockIdx.x * 4 + wv;
-    int t = 0;
-    if (r < restarts)
-        t = generate ? init_tour_in_wave(seed, (uint32_t)r, lane) : clampi(tours[r * kN + lane], 0, kN - 1);
-#pragma unroll
-    for (int k = 0; k < kN * kN / 256; ++k) m[tid + 256 * k] = clampi(v[k], 0, kCostMax);
-    __syncthreads();
-    if (r >= restarts) return;
-
+// The sweep on a plain int32 matrix (entries up to 2^21 - 1).
+__device__ __forceinline__ void descend_max_wide(const int32_t* m, int lane, int& t, int& cur_out, int& applied_out) {
     const char* mbytes = (const char*)m;
     const int rank_a = (lane + kN - 1) & (kN - 1);
     // byte indices for lane permutes "take the value of lane p + k"
@@ -137,6 +125,152 @@ void twoopt_max_n64_kernel(const int32_t* __restrict__ c, int restarts, uint64_t
         cur = vwin;
         ++applied;
     }
+    cur_out = cur;
+    applied_out = applied;
+}
+
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned pk_max(unsigned a, unsigned b) {
+    return __builtin_bit_cast(unsigned, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, a),
+                                                                  __builtin_bit_cast(ushort2_t, b)));
+}
+
+// The sweep on the packed matrix m2[x][y] = c[x][y] | c[y][x] << 16 (entries below 2^16).
+__device__ __forceinline__ void descend_max_packed(const int32_t* m2, int lane, int& t, int& cur_out,
+                                                   int& applied_out) {
+    const char* mbytes = (const char*)m2;
+    const int rank_a = (lane + kN - 1) & (kN - 1);
+    const int from2 = ((lane + 2) & 63) << 2, from4 = ((lane + 4) & 63) << 2, from8 = ((lane + 8) & 63) << 2;
+    const int from16 = ((lane + 16) & 63) << 2, from32 = ((lane + 32) & 63) << 2;
+    const int from33 = ((lane + 33) & 63) << 2, from48 = ((lane + 48) & 63) << 2;
+    auto take = [](int index, unsigned value) { return (unsigned)__builtin_amdgcn_ds_bpermute(index, (int)value); };
+    auto rol = [](unsigned v) { return (unsigned)from_next_lane((int)v); };
+    constexpr unsigned kNoKey = 0xffffffffu;
+
+    int cur = 0, applied = 0;
+    bool first = true;
+    for (;;) {
+        const int tprev = from_prev_lane(t);
+        const int rowofs = t << 8;
+        const unsigned fb = *(const uint32_t*)(mbytes + (rowofs | (tprev << 2)));     // f[a] | b[a] << 16
+        if (first) {
+            cur = wave_max((int)(fb & 0xffffu));
+            first = false;
+        }
+        // doubling tables over the hop words with their halves swapped (b | f << 16):
+        // m5[p] = max over hops p .. p+31, m4[p] = over hops p .. p+15
+        const unsigned bf = __builtin_amdgcn_alignbit(fb, fb, 16);
+        unsigned m4, m5;
+        {
+            unsigned x = pk_max(bf, rol(bf));
+            x = pk_max(x, take(from2, x));
+            x = pk_max(x, take(from4, x));
+            m4 = pk_max(x, take(from8, x));
+            m5 = pk_max(m4, take(from16, m4));
+        }
+        const unsigned far = take(from32, m5);                                       // hops a+32 .. a+63
+        const unsigned far32 = pk_max(take(from33, m4), take(from48, m4));           // hops a+33 .. a+63
+        // words that travel round the wave, here in their state for partner a+1
+        unsigned w = rol((unsigned)((rank_a << 10) | (t << 2)));
+        unsigned fbr = rol(fb);
+        unsigned r5 = rol(rol(m5));
+        unsigned s1 = 0, bestA = kNoKey, bestB = kNoKey;
+#pragma unroll
+        for (int d = 2; d <= kN / 2; ++d) {
+            s1 = pk_max(s1, fbr);        // edge b-1 (the previous diagonal's partner) joins S1's inner edges
+            w = rol(w);
+            if (d < kN / 2) {
+                fbr = rol(fbr);
+                r5 = rol(r5);            // max over hops b+1 .. b+32, halves swapped
+            }
+            int off;                     // (w & 0xfc) | rowofs in one instruction
+            asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(off) : "v"(w), "s"(0xfc), "v"(rowofs));
+            const unsigned P = *(const uint32_t*)(mbytes + off);                                 // G | GT << 16
+            const unsigned EP = (unsigned)from_prev_lane((int)P);
+            const unsigned s2 = d < kN / 2 ? pk_max(r5, far) : far32;                // S2: b | f << 16
+            // lower half: max(G, EG, S2's b, S1's f) = value B; upper half: max(GT, EGT, S2's f, S1's b) = value A
+            const unsigned val = pk_max(pk_max(P, EP), pk_max(s1, s2));
+            bestA = min(bestA, (val & 0xffff0000u) | w);
+            bestB = min(bestB, (val << 16) | w);
+        }
+        // (value, move id) of the lane's two candidates; keep the lexicographically smaller
+        int val = kNone, id = kNone;
+#pragma unroll
+        for (int which = 0; which < 2; ++which) {
+            const unsigned key = which ? bestB : bestA;
+            const int kv = (int)(key >> 16), rk = (int)(key >> 10) & 63;
+            const int b = (rk + 1) & 63;
+            const int lo = min(lane, b), hi = max(lane, b);
+            const int ij = lo ? lo * kN + hi - 1 : hi * kN + kN - 1;
+            const int flip = rk < rank_a ? 1 : 0;       // the reversed piece is S2, not S1
+            const int kid = ij * 2 + (which ^ flip);
+            if (kv < val || (kv == val && kid < id)) { val = kv; id = kid; }
+        }
+        const int vwin = wave_min_uniform(val);
+        if (vwin >= cur) break;
+        const int idwin = wave_min_uniform(val == vwin ? id : kNone);
+        const int o = idwin & 1, ij = idwin >> 1, mi = ij >> 6, mj = ij & 63;
+        const int p0 = o ? (lane ? kN - lane : 0) : lane;
+        const int src = (p0 >= mi && p0 <= mj) ? mi + mj - p0 : p0;
+        t = __shfl(t, src, kWave);
+        cur = vwin;
+        ++applied;
+    }
+    cur_out = cur;
+    applied_out = applied;
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2)))
+void twoopt_max_n64_kernel(const int32_t* __restrict__ c, int restarts, uint64_t seed, int generate,
+                           int32_t* __restrict__ tours, int64_t* __restrict__ costs,
+                           int32_t* __restrict__ moves) {
+    __shared__ __attribute__((aligned(256))) int32_t m[kN * kN];
+    __shared__ int wave_max_entry[4];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+
+    // the matrix loads are issued first and stay in flight while the wave builds its initial tour
+    int v[kN * kN / 256];
+#pragma unroll
+    for (int k = 0; k < kN * kN / 256; ++k) v[k] = c[tid + 256 * k];
+    const int64_t r = (int64_t)blockIdx.x * 4 + wv;
+    int t = 0;
+    if (r < restarts)
+        t = generate ? init_tour_in_wave(seed, (uint32_t)r, lane) : clampi(tours[r * kN + lane], 0, kN - 1);
+    // entries are clamped to the contract range; the largest decides between the packed and the plain sweep
+    int mx = 0;
+#pragma unroll
+    for (int k = 0; k < kN * kN / 256; ++k) {
+        v[k] = clampi(v[k], 0, kCostMax);
+        mx = max(mx, v[k]);
+    }
+    mx = wave_max(mx);
+    if (lane == 0) wave_max_entry[wv] = mx;
+#pragma unroll
+    for (int k = 0; k < kN * kN / 256; ++k) m[tid + 256 * k] = v[k];
+    __syncthreads();
+    mx = max(max(wave_max_entry[0], wave_max_entry[1]), max(wave_max_entry[2], wave_max_entry[3]));
+    const bool packed = mx < (1 << 16);
+    if (packed) {
+        // both directions of a pair into one word, in place: lane l of wave w takes the pairs {l, l + j} at the
+        // cyclic distances j = 1 + w, 5 + w, .. (every unordered pair exactly once; consecutive lanes, consecutive banks)
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const int j = 1 + wv + 4 * s;
+            const int b = (lane + j) & 63;
+            const int lo = min(lane, b), hi = max(lane, b);
+            if (j < 32 || lane < 32) {
+                const int x = m[lo * kN + hi], y = m[hi * kN + lo];
+                m[lo * kN + hi] = x | (y << 16);
+                m[hi * kN + lo] = y | (x << 16);
+            }
+        }
+        __syncthreads();
+    }
+    if (r >= restarts) return;
+
+    int cur, applied;
+    if (packed) descend_max_packed(m, lane, t, cur, applied);
+    else descend_max_wide(m, lane, t, cur, applied);
     tours[r * kN + lane] = t;
     if (lane == 0) {
         costs[r] = (int64_t)cur;

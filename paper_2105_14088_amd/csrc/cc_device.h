@@ -33,6 +33,14 @@ __device__ __forceinline__ int upper_index(int e, int n) {
     return min(x, y) * n + max(x, y);
 }
 
+// a + b + c as one instruction.  Written out because the compiler, seeing several such sums that share two of their
+// terms, prefers to form the shared pair once and then spends two instructions on every sum.
+__device__ __forceinline__ int add3(int a, int b, int c) {
+    int r;
+    asm("v_add3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
 // Reductions over the 64 lanes of a wave; every lane ends with the result.  The 32-bit forms use six DPP steps

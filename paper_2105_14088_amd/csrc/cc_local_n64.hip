@@ -69,14 +69,14 @@ __device__ __forceinline__ void descend_local(const int32_t* m, int lane, int& t
             const int x1 = from_next_lane(D[e]);               // D_e[a+1]
             const int x2 = from_next_lane(x1);                 // D_e[a+2]
             const int w = pkd[e];
-            acc[0] = min(acc[0], D[e] + D[e + 1] + w);
+            acc[0] = min(acc[0], add3(D[e], D[e + 1], w));
             if (e >= 2) {
-                acc[1] = min(acc[1], D[e] + x1 + w);
-                acc[2] = min(acc[2], x1_prev + D[e + 1] + w);
+                acc[1] = min(acc[1], add3(D[e], x1, w));
+                acc[2] = min(acc[2], add3(x1_prev, D[e + 1], w));
             }
             if (e >= 3) {
-                acc[3] = min(acc[3], D[e] + x2_prev + w);
-                acc[4] = min(acc[4], x2_prev2 + D[e + 1] + w);
+                acc[3] = min(acc[3], add3(D[e], x2_prev, w));
+                acc[4] = min(acc[4], add3(x2_prev2, D[e + 1], w));
             }
             if (WITH_2OPT && e + 1 <= kN / 2) {                // 2-opt diagonal d = e + 1 uses the word of gap a+d-1
                 const int d = e + 1;

@@ -128,7 +128,7 @@ __global__ __launch_bounds__(K == 4 ? 768 : 1024) void local_multi_kernel(const 
 #pragma unroll
             for (int v = 0; v < 5; ++v) acc[v][m] = kIntMax;
             acc2[m] = kIntMax;
-            Dc[m] = entry(rowofs[m], tw[m + 1]);          // D_1
+            Dc[m] = entry(rowofs[m], tw[m + 1]) << kRankBits;          // D_1, kept shifted into key position
             x1p[m] = x2p[m] = x2pp[m] = 0;
         }
         // One diagonal e = K q + rr (the gap's window index is m + rr).  score1 / score2 / score3: e admits segments of
@@ -136,7 +136,7 @@ __global__ __launch_bounds__(K == 4 ? 768 : 1024) void local_multi_kernel(const 
         auto step = [&](int rr, bool score1, bool score2, bool score3, bool two_opt) {
             int Dn[K];
 #pragma unroll
-            for (int m = 0; m < K; ++m) Dn[m] = entry(rowofs[m], tw[m + rr + 1]);
+            for (int m = 0; m < K; ++m) Dn[m] = entry(rowofs[m], tw[m + rr + 1]) << kRankBits;
             const int nx0 = from_next_lane(Dc[0]);
             const int nx1 = K >= 2 ? from_next_lane(Dc[K >= 2 ? 1 : 0]) : nx0;
             const int pv = two_opt ? from_prev_lane(Dn[K - 1]) : 0;
@@ -145,17 +145,16 @@ __global__ __launch_bounds__(K == 4 ? 768 : 1024) void local_multi_kernel(const 
                 const int x1 = m + 1 < K ? Dc[m + 1 < K ? m + 1 : 0] : nx0;                        // D_e[a+1]
                 const int x2 = m + 2 < K ? Dc[m + 2 < K ? m + 2 : 0] : (m + 2 == K ? nx0 : nx1);   // D_e[a+2]
                 const int w = kw[m + rr];
-                auto key = [&](int s) { return (int)(((unsigned)s << kRankBits) + (unsigned)w); };
-                if (score1) acc[0][m] = min(acc[0][m], key(Dc[m] + Dn[m]));
+                if (score1) acc[0][m] = min(acc[0][m], add3(Dc[m], Dn[m], w));
                 if (score2) {
-                    acc[1][m] = min(acc[1][m], key(Dc[m] + x1));
-                    acc[2][m] = min(acc[2][m], key(x1p[m] + Dn[m]));
+                    acc[1][m] = min(acc[1][m], add3(Dc[m], x1, w));
+                    acc[2][m] = min(acc[2][m], add3(x1p[m], Dn[m], w));
                 }
                 if (score3) {
-                    acc[3][m] = min(acc[3][m], key(Dc[m] + x2p[m]));
-                    acc[4][m] = min(acc[4][m], key(x2pp[m] + Dn[m]));
+                    acc[3][m] = min(acc[3][m], add3(Dc[m], x2p[m], w));
+                    acc[4][m] = min(acc[4][m], add3(x2pp[m], Dn[m], w));
                 }
-                if (two_opt) acc2[m] = min(acc2[m], key(Dn[m] + (m ? Dn[m ? m - 1 : 0] : pv)));
+                if (two_opt) acc2[m] = min(acc2[m], add3(Dn[m], m ? Dn[m ? m - 1 : 0] : pv, w));
                 x2pp[m] = x2p[m];
                 x1p[m] = x1;
                 x2p[m] = x2;

@@ -163,6 +163,21 @@ __global__ __launch_bounds__(256) void rdswap_n64_kernel(const int32_t* __restri
 #pragma unroll
     for (int k = 0; k < kN * kN / 256; ++k) m[tid + 256 * k] = clampi(v[k], 0, kCostMax);
     __syncthreads();
+    // a link costs the larger of its two directed entries: fold the two into both places once, so that a link is one
+    // gather.  Lane l of wave w takes the pairs {l, l + j} at the cyclic distances j = 1 + w, 5 + w, .. (every
+    // unordered pair exactly once; consecutive lanes, consecutive banks).
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        const int j = 1 + wv + 4 * s;
+        const int b = (lane + j) & 63;
+        const int lo = min(lane, b), hi = max(lane, b);
+        if (j < 32 || lane < 32) {
+            const int both = max(m[lo * kN + hi], m[hi * kN + lo]);
+            m[lo * kN + hi] = both;
+            m[hi * kN + lo] = both;
+        }
+    }
+    __syncthreads();
     if (r >= restarts) return;
     const char* mbytes = (const char*)m;
     int32_t* tl = tl_all[wv];
@@ -173,18 +188,17 @@ __global__ __launch_bounds__(256) void rdswap_n64_kernel(const int32_t* __restri
     for (;;) {
         tl[lane] = t;
         __builtin_amdgcn_wave_barrier();
-        const int t8 = t << 8, t2 = t << 2;
+        const int t8 = t << 8;
         // per round: partner, link value, and the best / second-best link value among links other than this lane's
-        int pb8[6], pb2[6], x1v[6], x2v[6], zk[6], round_cost[6], own_addr[6];
+        int pb2[6], x1v[6], x2v[6], zk[6], round_cost[6], own_addr[6];
         cur = 0;
 #pragma unroll
         for (int k = 0; k < 6; ++k) {
             const int bit = 1 << k;
             const int pb = tl[lane ^ bit];
-            pb8[k] = pb << 8;
             pb2[k] = pb << 2;
             own_addr[k] = (lane ^ bit) << 2;                       // byte offset of rank p xor 2^k in tl
-            const int lv = max(entry(t8, pb2[k]), entry(pb8[k], t2));
+            const int lv = entry(t8, pb2[k]);
             const int li = ((lane >> (k + 1)) << k) | (lane & (bit - 1));          // link index, 5 bits
             int key = (lv << 5) | li;
             const int k1 = wave_max_all(key);
@@ -213,14 +227,14 @@ __global__ __launch_bounds__(256) void rdswap_n64_kernel(const int32_t* __restri
             const int mm = second ? x1 : x0;
             const int q = lane ^ mm;
             const int tq = *(const int32_t*)(tlbytes + (q << 2));
-            const int tq8 = tq << 8, tq2 = tq << 2;
+            const int tq8 = tq << 8;
             int total = 0;
 #pragma unroll
             for (int k = 0; k < 6; ++k) {
                 const int bit = 1 << k;
                 const int qb = *(const int32_t*)(tlbytes + (own_addr[k] ^ (mm << 2)));      // node at rank q xor 2^k
-                const int link_p = max(entry(tq8, pb2[k]), entry(pb8[k], tq2));             // rank p now holds t[q]
-                const int link_q = max(entry(t8, qb << 2), entry(qb << 8, t2));             // rank q now holds t[p]
+                const int link_p = entry(tq8, pb2[k]);             // rank p now holds t[q]
+                const int link_q = entry(t8, qb << 2);             // rank q now holds t[p]
                 // link index offset of the partner, for either difference (wave-uniform), then this lane's
                 const int lim0 = ((x0 >> (k + 1)) << k) | (x0 & (bit - 1));
                 const int lim1 = ((x1 >> (k + 1)) << k) | (x1 & (bit - 1));
@@ -272,6 +286,17 @@ __global__ __launch_bounds__(1 << LOGN) void rdswap_block_kernel(const int32_t* 
     int t = clampi(tours[r * N + p], 0, N - 1);
     tl[p] = t;
     __syncthreads();
+    // a link costs the larger of its two directed entries: fold the two into both places once (thread p takes the
+    // pairs {p, p + j}, j = 1 .. N/2; every unordered pair exactly once), so that a link is one gather
+    for (int j = 1; j <= N / 2; ++j) {
+        const int b = (p + j) & (N - 1);
+        if (j < N / 2 || p < N / 2) {
+            const uint16_t both = max(m16[p * N + b], m16[b * N + p]);
+            m16[p * N + b] = both;
+            m16[b * N + p] = both;
+        }
+    }
+    __syncthreads();
     auto entry = [&](int a, int b) { return (int)m16[a * N + b]; };
     int parity = 0;
     auto block_max = [&](int v) {                              // every thread gets the maximum; one barrier per call
@@ -293,7 +318,7 @@ __global__ __launch_bounds__(1 << LOGN) void rdswap_block_kernel(const int32_t* 
         for (int k = 0; k < LOGN; ++k) {
             const int bit = 1 << k;
             pb[k] = tl[p ^ bit];
-            const int lv = max(entry(t, pb[k]), entry(pb[k], t));
+            const int lv = entry(t, pb[k]);
             const int li = ((p >> (k + 1)) << k) | (p & (bit - 1));
             const int key = (lv << LB) | li;
             const int k1 = block_max(key);
@@ -322,8 +347,8 @@ __global__ __launch_bounds__(1 << LOGN) void rdswap_block_kernel(const int32_t* 
             for (int k = 0; k < LOGN; ++k) {
                 const int bit = 1 << k;
                 const int qb = tl[q ^ bit];
-                const int link_p = max(entry(tq, pb[k]), entry(pb[k], tq));
-                const int link_q = max(entry(t, qb), entry(qb, t));
+                const int link_p = entry(tq, pb[k]);
+                const int link_q = entry(t, qb);
                 const int lim0 = ((x0 >> (k + 1)) << k) | (x0 & (bit - 1));
                 const int lim1 = ((x1 >> (k + 1)) << k) | (x1 & (bit - 1));
                 const int lim = second ? lim1 : lim0;

@@ -333,6 +333,67 @@ __global__ __launch_bounds__(256) void rd_batch_small_kernel(const int32_t* __re
     }
 }
 
+// N = 64: a round costs the largest of its 32 links and a link costs the larger of its two directed entries, so the
+// kernel folds the two entries of every pair into both places while staging (max(c[x][y], c[y][x])) and then scores
+// links, not ranks: the 6 x 32 links of an order are three gathers per lane (lanes 0..31 one round, lanes 32..63 the
+// next), and the six maxima come from three reductions over half waves.
+__global__ __launch_bounds__(256) void rd_batch_links64_kernel(const int32_t* __restrict__ c,
+                                                               const int32_t* __restrict__ weights,
+                                                               const int32_t* __restrict__ perms, int64_t B,
+                                                               int64_t* __restrict__ out) {
+    constexpr int N = 64;
+    __shared__ int32_t m[N * N];
+    __shared__ int32_t order_all[4][N];
+    const int lane = lane_id(), wv = threadIdx.x >> 6;
+    for (int e = threadIdx.x; e < N * N; e += 256) m[e] = clampi(c[e], 0, (1 << 21) - 1);
+    __syncthreads();
+    // lane l of wave w takes the pairs {l, l + j} at the cyclic distances j = 1 + w, 5 + w, ..: every unordered pair
+    // exactly once, consecutive lanes on consecutive banks
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        const int j = 1 + wv + 4 * s;
+        const int b = (lane + j) & 63;
+        const int lo = min(lane, b), hi = max(lane, b);
+        if (j < 32 || lane < 32) {
+            const int both = max(m[lo * N + hi], m[hi * N + lo]);
+            m[lo * N + hi] = both;
+            m[hi * N + lo] = both;
+        }
+    }
+    __syncthreads();
+    int32_t* order = order_all[wv];
+    const int64_t wave = (int64_t)blockIdx.x * 4 + wv;
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    long long w[6];
+#pragma unroll
+    for (int k = 0; k < 6; ++k) w[k] = weights ? (long long)clampi(weights[k], 0, kMaxRoundWeight) : 1ll;
+    // link j of this lane: round k = 2j + (lane >> 5), link index lane & 31 = the lower rank with bit k taken out
+    int lower[3], upper[3];
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+        const int k = 2 * j + (lane >> 5), li = lane & 31;
+        lower[j] = ((li >> k) << (k + 1)) | (li & ((1 << k) - 1));
+        upper[j] = lower[j] | (1 << k);
+    }
+    int next = wave < B ? perms[wave * N + lane] : 0;
+    for (int64_t b = wave; b < B; b += nwaves) {
+        order[lane] = clampi(next, 0, N - 1);
+        const int64_t bn = b + nwaves;
+        next = bn < B ? perms[bn * N + lane] : 0;
+        __builtin_amdgcn_wave_barrier();
+        int v[3];
+#pragma unroll
+        for (int j = 0; j < 3; ++j) v[j] = m[order[lower[j]] * N + order[upper[j]]];
+        __builtin_amdgcn_wave_barrier();   // all look-ups done before the slice is overwritten
+        half_wave_max3(v[0], v[1], v[2]);
+        long long total = 0;
+#pragma unroll
+        for (int j = 0; j < 3; ++j)
+            total += w[2 * j] * __builtin_amdgcn_readlane(v[j], 31) + w[2 * j + 1] * __builtin_amdgcn_readlane(v[j], 63);
+        if (lane == 0) out[b] = total;
+    }
+}
+
 template <int LOGN>
 static hipError_t rd_small_launch(const int32_t* c, const int32_t* weights, const int32_t* perms, int64_t B,
                                   int64_t* out, hipStream_t s) {
@@ -358,7 +419,10 @@ static hipError_t rd_launch(const int32_t* c, int N, const int32_t* weights, con
 hipError_t launch_rd_cost_batch(const int32_t* c, int N, const int32_t* weights, const int32_t* perms, int64_t B,
                                 int64_t* out, hipStream_t s) {
     if (B == 0) return hipSuccess;
-    if (N == 64) return rd_small_launch<6>(c, weights, perms, B, out, s);
+    if (N == 64) {
+        hipLaunchKernelGGL(rd_batch_links64_kernel, dim3(batch_grid(4, B)), dim3(256), 0, s, c, weights, perms, B, out);
+        return hipGetLastError();
+    }
     if (N == 32) return rd_small_launch<5>(c, weights, perms, B, out, s);
     if (N <= 64) return rd_launch<1>(c, N, weights, perms, B, out, s);
     if (N == 128) return rd_launch<2>(c, N, weights, perms, B, out, s);

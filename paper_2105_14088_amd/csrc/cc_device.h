@@ -84,6 +84,19 @@ __device__ __forceinline__ void wave_max3(int& a, int& b, int& c) {
     b = __builtin_amdgcn_readlane(b, 63);
     c = __builtin_amdgcn_readlane(c, 63);
 }
+// Three maxima over each half of the wave at once (lanes 0..31 and 32..63 separately): the chain above without its
+// last step.  Lane 31 ends with the lower halves' maxima, lane 63 with the upper halves'.
+__device__ __forceinline__ void half_wave_max3(int& a, int& b, int& c) {
+#define CC_STEP3(ctrl)                                         \
+    "v_max_i32_dpp %0, %0, %0 " ctrl " bank_mask:0xf\n\t"    \
+    "v_max_i32_dpp %1, %1, %1 " ctrl " bank_mask:0xf\n\t"    \
+    "v_max_i32_dpp %2, %2, %2 " ctrl " bank_mask:0xf\n\t"
+    asm volatile("s_nop 1\n\t" CC_STEP3("quad_perm:[1,0,3,2] row_mask:0xf") CC_STEP3("quad_perm:[2,3,0,1] row_mask:0xf")
+                     CC_STEP3("row_half_mirror row_mask:0xf") CC_STEP3("row_mirror row_mask:0xf")
+                         CC_STEP3("row_bcast:15 row_mask:0xa") "s_nop 1"
+                 : "+v"(a), "+v"(b), "+v"(c));
+#undef CC_STEP3
+}
 __device__ __forceinline__ long long wave_sum64(long long v) {
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);

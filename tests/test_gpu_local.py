@@ -169,3 +169,17 @@ def test_insertion_n128_n192_n256_wavefront_kernel_and_its_fallback(n, restarts,
     init = random_perms(n, 5, seed=n)
     assert_search_equal(gpu_local(c, oracle.SUM, classes, 5, seed=1, init=init),
                         oracle.local_search(c, oracle.SUM, classes, 5, seed=0, init=init))
+
+
+@pytest.mark.parametrize("classes", [OROPT, BOTH])
+def test_insertion_n64_at_the_16_bit_boundary(classes):
+    """N = 64: entries up to 65535 still take the wavefront kernel (its 32-bit keys are then at their limit: two
+    entries of 65535 shifted by 14 bits plus the gap word), one entry of 65536 sends the search to the general kernel."""
+    for hi in (65535, 65536):
+        say(f"local search N=64 classes={classes}, entries up to {hi}")
+        c = random_matrix(64, 6060 + hi % 11, symmetric=True, lo=60000, hi=hi)
+        c[5, 9] = c[9, 5] = hi
+        c[11, 12] = c[12, 11] = 0
+        np.fill_diagonal(c, 0)
+        want = oracle.local_search(c, oracle.SUM, classes, 24, seed=hi)
+        assert_search_equal(gpu_local(c, oracle.SUM, classes, 24, seed=hi), want)

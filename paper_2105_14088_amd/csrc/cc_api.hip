@@ -214,7 +214,7 @@ int cc_2opt_search(const int32_t* cost_matrix, int32_t N, int32_t objective, int
 
 size_t cc_rd_swap_workspace_bytes(int32_t N, int32_t restarts) {
     if (N < 2 || N > CC_MAX_N || !is_pow2(N) || restarts < 1) return 0;
-    return ws_layout(N, restarts).mat16;       // flags, costs, moves, tours
+    return ws_layout(N, restarts).total;       // flags, costs, moves, tours, folded 16-bit matrix (N > 256)
 }
 
 int cc_rd_swap_search_ex(const int32_t* cost_matrix, int32_t N, int32_t restarts, uint64_t seed,
@@ -225,7 +225,7 @@ int cc_rd_swap_search_ex(const int32_t* cost_matrix, int32_t N, int32_t restarts
     if (!is_pow2(N)) return CC_ERR_UNSUPPORTED_N;
     if (restarts < 1 || !best_perm || !best_cost) return CC_ERR_INVALID_ARG;
     const WsLayout w = ws_layout(N, restarts);
-    if (!workspace || workspace_bytes < w.mat16 || ((uintptr_t)workspace & 255u)) return CC_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255u)) return CC_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     char* base = (char*)workspace;
     int64_t* costs = restart_costs ? restart_costs : (int64_t*)(base + w.costs);
@@ -235,7 +235,7 @@ int cc_rd_swap_search_ex(const int32_t* cost_matrix, int32_t N, int32_t restarts
         CC_HIP(hipMemcpyAsync(tours, init_tours, sizeof(int32_t) * (size_t)restarts * (size_t)N,
                               hipMemcpyDeviceToDevice, s));
     CC_HIP(cc::launch_rdswap(cost_matrix, N, restarts, seed, init_tours != nullptr, tours, costs, moves,
-                             (int32_t*)(base + w.flags), s));
+                             (int32_t*)(base + w.flags), (uint16_t*)(base + w.mat16), s));
     CC_HIP(cc::launch_best_restart(costs, tours, N, restarts, best_perm, best_cost, best_restart, s));
     return CC_OK;
 }

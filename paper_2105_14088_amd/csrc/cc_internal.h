@@ -74,8 +74,9 @@ hipError_t launch_2opt_sum_n1024(const int32_t* c, int N, uint16_t* c16, int res
 
 // Pair-swap descent under the halving-doubling model for `restarts` tours (cc_rdswap.hip); same tour
 // convention as launch_2opt.  The best-of-restarts step is launch_best_restart.
+// `mat16` has room for N*N 16-bit entries when N > 256 (the folded copy of the matrix).
 hipError_t launch_rdswap(const int32_t* c, int N, int restarts, uint64_t seed, bool tours_hold_init, int32_t* tours,
-                         int64_t* costs, int32_t* moves, int32_t* flags, hipStream_t s);
+                         int64_t* costs, int32_t* moves, int32_t* flags, uint16_t* mat16, hipStream_t s);
 hipError_t launch_best_restart(const int64_t* costs, const int32_t* tours, int N, int restarts, int32_t* best_perm,
                                int64_t* best_cost, int32_t* best_restart, hipStream_t s);
 

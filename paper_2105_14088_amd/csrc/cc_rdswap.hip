@@ -262,42 +262,60 @@ __global__ __launch_bounds__(256) void rdswap_n64_kernel(const int32_t* __restri
     }
 }
 
-// ------------------------------------------------------------------------- N = 128, 256: one workgroup per restart
-// The N = 64 scheme with one thread per rank: N threads, the matrix staged as 16-bit entries in LDS (32 / 128 KiB;
-// needs max(c) < 2^16, otherwise the general kernel runs instead, decided on the device), the order in LDS, the
-// three largest links of a round from workgroup-wide max-reductions, two rank differences per step so that the N
-// threads score N distinct pairs.  Keys: value << 16 | move id (id < 2^16, value < 2^20).
-template <int LOGN>
+// 16-bit matrix with both directed entries of a pair folded into both places, max(c[x][y], c[y][x]): a link is then
+// one gather.  For the sizes whose matrix does not fit LDS; skipped when an entry needs more than 16 bits.
+__global__ __launch_bounds__(256) void fold_to_u16_kernel(const int32_t* __restrict__ c, int n,
+                                                          uint16_t* __restrict__ c16,
+                                                          const int32_t* __restrict__ flags) {
+    if (flags[0] >= (1 << 16)) return;
+    for (int e = blockIdx.x * 256 + threadIdx.x; e < n * n; e += gridDim.x * 256) {
+        const int x = e / n, y = e - x * n;
+        c16[e] = (uint16_t)max(clampi(c[e], 0, 0xffff), clampi(c[y * n + x], 0, 0xffff));
+    }
+}
+
+// ------------------------------------------------------------------------- N = 128 .. 1024: one workgroup per restart
+// The N = 64 scheme with one thread per rank: N threads, the order in LDS, the three largest links of a round from
+// workgroup-wide max-reductions, two rank differences per step so that the N threads score N distinct pairs.  The
+// matrix is read as folded 16-bit entries: staged and folded in LDS for N = 128, 256 (32 / 128 KiB), gathered through
+// L2 from the folded copy in the workspace for N = 512, 1024 (IN_LDS false).  Needs max(c) < 2^16, otherwise the
+// general kernel runs instead, decided on the device.  Keys: value << 2 log2 N | move id (value < 2^20).
+template <int LOGN, bool IN_LDS>
 __global__ __launch_bounds__(1 << LOGN) void rdswap_block_kernel(const int32_t* __restrict__ c,
+                                                                 const uint16_t* __restrict__ folded,
                                                                  int32_t* __restrict__ tours,
                                                                  int64_t* __restrict__ costs,
                                                                  int32_t* __restrict__ moves,
                                                                  const int32_t* __restrict__ flags) {
     constexpr int N = 1 << LOGN, NW = N / 64, LB = LOGN - 1;   // LB: bits of a link index
+    constexpr int kIdBits = 2 * LOGN;
     if (flags[0] >= (1 << 16)) return;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    uint16_t* m16 = (uint16_t*)smem;                           // [N * N]
-    int32_t* tl = (int32_t*)(smem + sizeof(uint16_t) * N * N); // [N] the order
+    uint16_t* m16 = (uint16_t*)smem;                           // [N * N] (IN_LDS)
+    int32_t* tl = (int32_t*)(smem + (IN_LDS ? sizeof(uint16_t) * N * N : 0)); // [N] the order
     __shared__ int red_i[2][NW];
     __shared__ unsigned long long red_k[NW];
     const int p = threadIdx.x, lane = p & 63, wv = p >> 6;
     const int64_t r = blockIdx.x;
-    for (int e = p; e < N * N; e += N) m16[e] = (uint16_t)clampi(c[e], 0, 0xffff);
+    if (IN_LDS)
+        for (int e = p; e < N * N; e += N) m16[e] = (uint16_t)clampi(c[e], 0, 0xffff);
     int t = clampi(tours[r * N + p], 0, N - 1);
     tl[p] = t;
     __syncthreads();
-    // a link costs the larger of its two directed entries: fold the two into both places once (thread p takes the
-    // pairs {p, p + j}, j = 1 .. N/2; every unordered pair exactly once), so that a link is one gather
-    for (int j = 1; j <= N / 2; ++j) {
-        const int b = (p + j) & (N - 1);
-        if (j < N / 2 || p < N / 2) {
-            const uint16_t both = max(m16[p * N + b], m16[b * N + p]);
-            m16[p * N + b] = both;
-            m16[b * N + p] = both;
+    if (IN_LDS) {
+        // a link costs the larger of its two directed entries: fold the two into both places once (thread p takes
+        // the pairs {p, p + j}, j = 1 .. N/2; every unordered pair exactly once), so that a link is one gather
+        for (int j = 1; j <= N / 2; ++j) {
+            const int b = (p + j) & (N - 1);
+            if (j < N / 2 || p < N / 2) {
+                const uint16_t both = max(m16[p * N + b], m16[b * N + p]);
+                m16[p * N + b] = both;
+                m16[b * N + p] = both;
+            }
         }
+        __syncthreads();
     }
-    __syncthreads();
-    auto entry = [&](int a, int b) { return (int)m16[a * N + b]; };
+    auto entry = [&](int a, int b) { return IN_LDS ? (int)m16[a * N + b] : (int)folded[a * N + b]; };
     int parity = 0;
     auto block_max = [&](int v) {                              // every thread gets the maximum; one barrier per call
         v = wave_max(v);
@@ -357,7 +375,7 @@ __global__ __launch_bounds__(1 << LOGN) void rdswap_block_kernel(const int32_t* 
                 total += (mm == bit) ? round_cost[k] : stage;
             }
             const int lo = min(p, q), hi = max(p, q);
-            best = min(best, ((unsigned long long)(unsigned)total << 16) | (unsigned)(lo * N + hi));
+            best = min(best, ((unsigned long long)(unsigned)total << kIdBits) | (unsigned)(lo * N + hi));
         }
         best = wave_min_u64(best);
         if (lane == 0) red_k[wv] = best;
@@ -365,8 +383,8 @@ __global__ __launch_bounds__(1 << LOGN) void rdswap_block_kernel(const int32_t* 
         unsigned long long win = red_k[0];
 #pragma unroll
         for (int k = 1; k < NW; ++k) win = min(win, red_k[k]);
-        if ((int)(win >> 16) >= cur) break;
-        const int id = (int)(win & 0xffffu), sp = id >> LOGN, sq = id & (N - 1);
+        if ((int)(win >> kIdBits) >= cur) break;
+        const int id = (int)(win & ((1u << kIdBits) - 1u)), sp = id >> LOGN, sq = id & (N - 1);
         const int a = tl[sp], b = tl[sq];
         __syncthreads();                                       // everyone has read red_k and the two ranks
         if (p == sp) { t = b; tl[p] = b; }
@@ -382,23 +400,30 @@ __global__ __launch_bounds__(1 << LOGN) void rdswap_block_kernel(const int32_t* 
 }
 
 template <int LOGN>
-static hipError_t rdswap_block_launch(const int32_t* c, int restarts, int32_t* tours, int64_t* costs, int32_t* moves,
-                                      const int32_t* flags, hipStream_t s) {
+static hipError_t rdswap_block_launch(const int32_t* c, uint16_t* folded, int restarts, int32_t* tours, int64_t* costs,
+                                      int32_t* moves, const int32_t* flags, hipStream_t s) {
     constexpr int N = 1 << LOGN;
-    const size_t lds = sizeof(uint16_t) * N * N + sizeof(int32_t) * N;
+    constexpr bool kInLds = LOGN <= 8;
+    if (!kInLds) {
+        hipLaunchKernelGGL(fold_to_u16_kernel, dim3(512), dim3(256), 0, s, c, N, folded, flags);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    const size_t lds = (kInLds ? sizeof(uint16_t) * N * N : 0) + sizeof(int32_t) * N;
     if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void*)rdswap_block_kernel<LOGN>,
+        hipError_t e = hipFuncSetAttribute((const void*)rdswap_block_kernel<LOGN, kInLds>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(rdswap_block_kernel<LOGN>, dim3(restarts), dim3(N), lds, s, c, tours, costs, moves, flags);
+    hipLaunchKernelGGL((rdswap_block_kernel<LOGN, kInLds>), dim3(restarts), dim3(N), lds, s, c, folded, tours, costs,
+                       moves, flags);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_rdswap(const int32_t* c, int N, int restarts, uint64_t seed, bool tours_hold_init, int32_t* tours,
-                         int64_t* costs, int32_t* moves, int32_t* flags, hipStream_t s) {
+                         int64_t* costs, int32_t* moves, int32_t* flags, uint16_t* mat16, hipStream_t s) {
     if (N == 64) {
         hipLaunchKernelGGL(rdswap_n64_kernel, dim3((restarts + 3) / 4), dim3(256), 0, s, c, restarts, seed,
                            tours_hold_init ? 0 : 1, tours, costs, moves);
@@ -409,13 +434,15 @@ hipError_t launch_rdswap(const int32_t* c, int N, int restarts, uint64_t seed, b
         if (e != hipSuccess) return e;
     }
     const int32_t* skip = nullptr;
-    if (N == 128 || N == 256) {
+    if (N == 128 || N == 256 || N == 512 || N == 1024) {
         // 16-bit workgroup kernel when max(c) < 2^16, else the general kernel: both are enqueued and the matrix
         // maximum, computed on the device, decides which one does the work (no host round trip)
         hipError_t e = launch_matrix_max(c, N, flags, s);
         if (e != hipSuccess) return e;
-        e = N == 128 ? rdswap_block_launch<7>(c, restarts, tours, costs, moves, flags, s)
-                     : rdswap_block_launch<8>(c, restarts, tours, costs, moves, flags, s);
+        e = N == 128   ? rdswap_block_launch<7>(c, mat16, restarts, tours, costs, moves, flags, s)
+            : N == 256 ? rdswap_block_launch<8>(c, mat16, restarts, tours, costs, moves, flags, s)
+            : N == 512 ? rdswap_block_launch<9>(c, mat16, restarts, tours, costs, moves, flags, s)
+                       : rdswap_block_launch<10>(c, mat16, restarts, tours, costs, moves, flags, s);
         if (e != hipSuccess) return e;
         skip = flags;
     }

@@ -93,7 +93,7 @@ def test_swap_search_n256_and_n1024():
     assert np.array_equal(got["moves"], np.concatenate([p[2] for p in parts]))
     k = int(np.argmin(got["costs"]))
     assert got["best_restart"] == k and got["best_cost"] == got["costs"][k]
-    say("rd swap search: N=1024, asymmetric, 3 % large entries, 2 restarts (general kernel)")
+    say("rd swap search: N=1024, asymmetric, 3 % large entries, 2 restarts (workgroup kernel on the folded 16-bit copy)")
     c = random_matrix(1024, 999, symmetric=False, lo=1, hi=40)
     mask = np.random.default_rng(1).random((1024, 1024)) < 0.97
     c = np.where(mask, 1, c).astype(np.int32)
@@ -106,3 +106,24 @@ def test_swap_search_n256_and_n1024():
     assert np.array_equal(got["tours"], np.concatenate([p[1] for p in parts]))
     assert np.array_equal(got["moves"], np.concatenate([p[2] for p in parts]))
     assert (got["moves"] > 10).all()
+
+
+@pytest.mark.parametrize("n", [512, 1024])
+def test_swap_search_n512_n1024_folded_copy_and_fallback(n):
+    """N = 512 / 1024: one workgroup per restart reading the folded 16-bit copy of the matrix from the workspace;
+    one entry of 2^16 sends the same search to the general kernel.  Sparse large entries keep the descents short."""
+    from concurrent.futures import ThreadPoolExecutor
+    for top, tag in ((40, "folded 16-bit copy"), (65536, "general kernel")):
+        say(f"rd swap search: N={n}, asymmetric, 3 % large entries, 2 restarts ({tag})")
+        c = random_matrix(n, 500 + n, symmetric=False, lo=1, hi=40)
+        mask = np.random.default_rng(n).random((n, n)) < 0.97
+        c = np.where(mask, 1, c).astype(np.int32)
+        np.fill_diagonal(c, 0)
+        c[7, 3] = top
+        with ThreadPoolExecutor(2) as ex:
+            parts = list(ex.map(lambda r: oracle.rd_swap_restarts(c, 9, r, r + 1), range(2)))
+        got = gpu_swap_search(c, 2, seed=9)
+        assert np.array_equal(got["costs"], np.concatenate([p[0] for p in parts]))
+        assert np.array_equal(got["tours"], np.concatenate([p[1] for p in parts]))
+        assert np.array_equal(got["moves"], np.concatenate([p[2] for p in parts]))
+        assert (got["moves"] > 5).all()

@@ -503,10 +503,56 @@ static hipError_t bcube_launch(const int32_t* c, int N, int base, const int32_t*
     return hipGetLastError();
 }
 
+// N = 64, base 4 (the paper's BCube setting at the size of the bench's batch): lane = rank, the nine peers of a rank
+// (three per round) are fixed lane numbers computed once, the three rounds' maxima are reduced together, the next
+// order of the wave is requested while this one is scored.
+__global__ __launch_bounds__(256) void bcube_batch_b4n64_kernel(const int32_t* __restrict__ c,
+                                                                const int32_t* __restrict__ weights,
+                                                                const int32_t* __restrict__ perms, int64_t B,
+                                                                int64_t* __restrict__ out) {
+    constexpr int N = 64;
+    __shared__ int32_t m[N * N];
+    __shared__ int32_t order_all[4][N];
+    for (int e = threadIdx.x; e < N * N; e += 256) m[e] = c[e];
+    __syncthreads();
+    const int lane = lane_id();
+    int32_t* order = order_all[threadIdx.x >> 6];
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    long long w[3];
+    int peer[3][3];
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        w[r] = weights ? (long long)clampi(weights[r], 0, kMaxRoundWeight) : 1ll;
+        const int digit = (lane >> (2 * r)) & 3, rest = lane & ~(3 << (2 * r));
+#pragma unroll
+        for (int s = 1; s <= 3; ++s) peer[r][s - 1] = rest | (((digit + s) & 3) << (2 * r));
+    }
+    int next = wave < B ? perms[wave * N + lane] : 0;
+    for (int64_t b = wave; b < B; b += nwaves) {
+        const int a = clampi(next, 0, N - 1);
+        const int64_t bn = b + nwaves;
+        next = bn < B ? perms[bn * N + lane] : 0;
+        order[lane] = a;
+        __builtin_amdgcn_wave_barrier();
+        int v[3];
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+            v[r] = max(m[a * N + order[peer[r][0]]], max(m[a * N + order[peer[r][1]]], m[a * N + order[peer[r][2]]]));
+        __builtin_amdgcn_wave_barrier();   // all look-ups done before the slice is overwritten
+        wave_max3(v[0], v[1], v[2]);
+        if (lane == 0) out[b] = w[0] * v[0] + w[1] * v[1] + w[2] * v[2];
+    }
+}
+
 hipError_t launch_bcube_cost_batch(const int32_t* c, int N, int base, const int32_t* weights, const int32_t* perms,
                                    int64_t B, int64_t* out, hipStream_t s) {
     if (B == 0) return hipSuccess;
     if (base == 2) return launch_rd_cost_batch(c, N, weights, perms, B, out, s);
+    if (N == 64 && base == 4) {
+        hipLaunchKernelGGL(bcube_batch_b4n64_kernel, dim3(batch_grid(4, B)), dim3(256), 0, s, c, weights, perms, B, out);
+        return hipGetLastError();
+    }
     if (N <= 64) return bcube_launch<1>(c, N, base, weights, perms, B, out, s);
     if (N <= 128) return bcube_launch<2>(c, N, base, weights, perms, B, out, s);
     if (N <= 256) return bcube_launch<4>(c, N, base, weights, perms, B, out, s);

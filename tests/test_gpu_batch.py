@@ -129,7 +129,7 @@ def test_rd_batch(n):
                                     (64, 8), (512, 8), (25, 5), (625, 5), (32, 32), (1024, 32), (64, 2), (7, 7)])
 def test_bcube_batch(n, base):
     c = random_matrix(n, 900 + n, symmetric=False, lo=0, hi=COST_MAX if n == 64 else 9000)
-    for b in (1, 5, 259):
+    for b in (1, 5, 259) + ((20011,) if n == 64 else ()):      # N = 64: enough orders for several per wave
         say(f"bcube batch N={n} base={base} B={b}")
         perms = random_perms(n, b, seed=n * 5 + b)
         out = cc.cc_bcube_cost_batch(dev(c), base, dev(perms))

@@ -610,11 +610,72 @@ __global__ __launch_bounds__(256) void dbt_batch_kernel(const int32_t* __restric
     }
 }
 
+// N = 64: the tree's shape does not depend on the order, so every lane (tree position) finds its parent once, by
+// the same binary search, and the positions 2 and 4 levels up by two look-ups.  Per order a lane gathers the one
+// edge into its position for each of the two trees; path costs are then sums over ancestors, formed by pointer
+// jumping in three lane-permute steps (the root's edge is 0 and it is its own ancestor, so chains that have reached
+// the root add nothing).
+__global__ __launch_bounds__(256) void dbt_batch_n64_kernel(const int32_t* __restrict__ c,
+                                                            const int32_t* __restrict__ perms, int64_t B,
+                                                            int64_t* __restrict__ out) {
+    constexpr int N = 64;
+    __shared__ int32_t m[N * N];
+    __shared__ int32_t order_all[4][N];
+    for (int e = threadIdx.x; e < N * N; e += 256) m[e] = c[e];
+    const int lane = lane_id();
+    int32_t* order = order_all[threadIdx.x >> 6];
+    // parent of tree position `lane`
+    int parent = lane;
+    {
+        int lo = 0, hi = N - 1, mid = (N - 1) >> 1;
+        for (int depth = 0; depth < 7 && mid != lane; ++depth) {
+            parent = mid;
+            if (lane < mid) hi = mid - 1;
+            else lo = mid + 1;
+            mid = (lo + hi) >> 1;
+        }
+    }
+    const bool is_root = parent == lane;
+    order[lane] = parent;                                  // borrowed for the ancestor look-ups
+    __builtin_amdgcn_wave_barrier();
+    const int up2 = order[parent];
+    const int up4 = order[order[up2]];
+    __builtin_amdgcn_wave_barrier();
+    __syncthreads();                                       // the matrix is staged
+    const int from1 = parent << 2, from2 = up2 << 2, from4 = up4 << 2;
+    const int parent_shifted = (parent + 1) & (N - 1);     // second tree: position q holds rank q + 1
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    int next = wave < B ? perms[wave * N + lane] : 0;
+    for (int64_t b = wave; b < B; b += nwaves) {
+        const int a = clampi(next, 0, N - 1);
+        const int64_t bn = b + nwaves;
+        next = bn < B ? perms[bn * N + lane] : 0;
+        order[lane] = a;
+        __builtin_amdgcn_wave_barrier();
+        // node at tree position `lane` of the second tree: the next lane's (cyclic over the 64 lanes)
+        const int a_shifted = __builtin_amdgcn_update_dpp(a, a, 0x134, 0xf, 0xf, true);
+        int cost0 = is_root ? 0 : m[order[parent] * N + a];
+        int cost1 = is_root ? 0 : m[order[parent_shifted] * N + a_shifted];
+        __builtin_amdgcn_wave_barrier();                   // all look-ups done before the slice is overwritten
+        cost0 += __builtin_amdgcn_ds_bpermute(from1, cost0);
+        cost1 += __builtin_amdgcn_ds_bpermute(from1, cost1);
+        cost0 += __builtin_amdgcn_ds_bpermute(from2, cost0);
+        cost1 += __builtin_amdgcn_ds_bpermute(from2, cost1);
+        cost0 += __builtin_amdgcn_ds_bpermute(from4, cost0);
+        cost1 += __builtin_amdgcn_ds_bpermute(from4, cost1);
+        const int total = wave_max(max(cost0, cost1));
+        if (lane == 0) out[b] = total;
+    }
+}
+
 hipError_t launch_dbt_cost_batch(const int32_t* c, int N, const int32_t* perms, int64_t B, int64_t* out,
                                  hipStream_t s) {
     if (B == 0) return hipSuccess;
     const int grid = batch_grid(4, B);
-    if (N <= 64) {
+    if (N == 64) {
+        hipLaunchKernelGGL(dbt_batch_n64_kernel, dim3(grid), dim3(256), 0, s, c, perms, B, out);
+    } else if (N <= 64) {
         const size_t lds = sizeof(int32_t) * (size_t)(4 * N + N * N);
         hipLaunchKernelGGL((dbt_batch_kernel<true>), dim3(grid), dim3(256), lds, s, c, N, perms, B, out);
     } else {

@@ -7,9 +7,12 @@
 // current order at once; the wave then commits the FIRST accepted one (ballot + find-first-set), and
 // the steps after it are proposed again in the next round against the new order.  The result is the
 // sequential chain bit for bit; a round advances 1 .. 64 steps, most of them when the chain is cold.
-// Each lane draws its step's random word itself (counter-based generator), gathers four ranks of the
-// order and four matrix entries (LDS for N <= 128, else through L2), and tests acceptance in 64-bit
-// integer arithmetic.  The committed reversal is done by the whole wave, one pair of ranks per lane.
+// What a step draws does not depend on the order: its two ring edges and the acceptance threshold E(u).  The wave
+// therefore draws 64 steps at a time, one per lane (counter-based generator), into a ring of 128 entries in LDS,
+// and a round only reads its entry back; steps that are proposed again after a commit cost no second draw.
+// Per round a lane then gathers four ranks of the order and four matrix entries (LDS for N <= 128, else through
+// L2) and tests acceptance in 64-bit integer arithmetic.  The committed reversal is done by the whole wave, one
+// pair of ranks per lane.
 #include "cc_device.h"
 #include "cc_internal.h"
 
@@ -20,6 +23,7 @@ namespace {
 
 constexpr int kCostMax = (1 << 21) - 1;
 constexpr int kDrawBase = 1024;       // low counter words below this belong to the initial shuffles
+constexpr int kDrawRing = 128;        // steps whose draws a wave keeps in LDS (two blocks of 64)
 
 // all LDS traffic of the wave issued so far is complete and visible to every lane, and the compiler keeps
 // LDS accesses on their side of this point
@@ -34,13 +38,14 @@ __global__ __launch_bounds__(256) void sa_ring_kernel(const int32_t* __restrict_
                                                       long long steps, int t_start, int t_end, uint64_t seed,
                                                       int32_t* __restrict__ tours, int64_t* __restrict__ costs,
                                                       int32_t* __restrict__ accepted) {
-    extern __shared__ int32_t sm[];
+    extern __shared__ __attribute__((aligned(16))) int32_t sm[];
     const int lane = lane_id(), wv = threadIdx.x >> 6;
-    int32_t* t = sm + wv * 2 * N;     // current order
-    int32_t* bt = t + N;              // best order so far
+    int32_t* draws = sm + wv * 2 * kDrawRing;            // per step: edges a | b << 16, threshold E
+    int32_t* t = sm + 8 * kDrawRing + wv * 2 * N;        // current order
+    int32_t* bt = t + N;                                 // best order so far
     const int32_t* mat = c;
     if (LDS_MATRIX) {
-        int32_t* m = sm + 8 * N;
+        int32_t* m = sm + 8 * kDrawRing + 8 * N;
         for (int e = threadIdx.x; e < N * N; e += 256) m[e] = clampi(c[e], 0, kCostMax);
         __syncthreads();
         mat = m;
@@ -63,25 +68,42 @@ __global__ __launch_bounds__(256) void sa_ring_kernel(const int32_t* __restrict_
 
     if (N >= 4) {
         const uint64_t chain_hi = (uint64_t)(uint32_t)r << 32;
-        long long s = 0;
-        while (s < steps) {
-            const long long step = s + lane;
-            const bool active = step < steps;
+        // draws of the 64 steps first .. first + 63, one per lane, into their ring entries
+        auto draw_block = [&](long long first) {
+            const long long step = first + lane;
             const uint64_t w = splitmix64_at(seed, (chain_hi | (uint32_t)(kDrawBase + (uint32_t)step)) + 1u);
             const int a = (int)(((uint32_t)(w >> 43) * (uint32_t)N) >> 21);
             const int d = 2 + (int)((((uint32_t)(w >> 22) & 0x1FFFFFu) * (uint32_t)(N - 3)) >> 21);
             int b = a + d;
             b = b >= N ? b - N : b;
             const int u = (int)((uint32_t)w & 0x3FFFFFu) + 1;
+            const int e = 31 - __clz(u);
+            const int mant = u - (1 << e);
+            const int frac = e >= 12 ? (mant >> (e - 12)) : (mant << (12 - e));
+            const int slot = (int)step & (kDrawRing - 1);
+            *(int2*)(draws + 2 * slot) = make_int2(a | (b << 16), 22 * 4096 - (e * 4096 + frac));
+        };
+        draw_block(0);
+        draw_block(kWave);
+        long long drawn = 2 * kWave;          // steps [drawn - 128, drawn) are in the ring
+        wave_lds_sync();
+        long long s = 0;
+        while (s < steps) {
+            if (s + kWave > drawn) {          // the round reaches past the ring: the older half makes room
+                draw_block(drawn);
+                drawn += kWave;
+                wave_lds_sync();
+            }
+            const long long step = s + lane;
+            const bool active = step < steps;
+            const int2 drawn_step = *(const int2*)(draws + 2 * ((int)step & (kDrawRing - 1)));
+            const int a = drawn_step.x & 0xffff, b = drawn_step.x >> 16;
             const int ap = a ? a - 1 : N - 1, bp = b ? b - 1 : N - 1;
             const int ta = t[a], tap = t[ap], tb = t[b], tbp = t[bp];
             const int delta = M(tap, tbp) + M(ta, tb) - M(ta, tap) - M(tb, tbp);
             bool accept = active;
             if (delta > 0) {
-                const int e = 31 - __clz(u);
-                const int mant = u - (1 << e);
-                const int frac = e >= 12 ? (mant >> (e - 12)) : (mant << (12 - e));
-                const long long E = 22 * 4096 - (e * 4096 + frac);
+                const long long E = drawn_step.y;
                 const long long num = (long long)t_start * (steps - step) + (long long)t_end * step;
                 accept = active && ((long long)delta * 4096 * steps <= num * E);
             }
@@ -313,7 +335,7 @@ hipError_t launch_sa_ring(const int32_t* c, int N, int chains, long long steps, 
     }
     const int grid = (chains + 3) / 4;
     if (N <= 128) {
-        const size_t lds = sizeof(int32_t) * ((size_t)8 * N + (size_t)N * N);
+        const size_t lds = sizeof(int32_t) * ((size_t)8 * kDrawRing + (size_t)8 * N + (size_t)N * N);
         if (lds > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute((const void*)sa_ring_kernel<true>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -322,7 +344,7 @@ hipError_t launch_sa_ring(const int32_t* c, int N, int chains, long long steps, 
         hipLaunchKernelGGL((sa_ring_kernel<true>), dim3(grid), dim3(256), lds, s, c, N, chains, steps, t_start, t_end,
                            seed, tours, costs, accepted);
     } else {
-        const size_t lds = sizeof(int32_t) * (size_t)8 * N;
+        const size_t lds = sizeof(int32_t) * ((size_t)8 * kDrawRing + (size_t)8 * N);
         hipLaunchKernelGGL((sa_ring_kernel<false>), dim3(grid), dim3(256), lds, s, c, N, chains, steps, t_start, t_end,
                            seed, tours, costs, accepted);
     }

@@ -41,6 +41,29 @@ __device__ __forceinline__ int add3(int a, int b, int c) {
     return r;
 }
 
+// Rank whose node moves to rank p when move `id` of the ring search is applied (ids as in cc.h, cc_local_search):
+// id = i*n + j < n*n reverses ranks i .. j; id = n*n + (variant*n + s)*n + g takes the L ranks s .. s+L-1 out and
+// puts them back, kept or reversed, behind the node of rank g (variant 0: L = 1; 1, 2: L = 2; 3, 4: L = 3; even
+// variants above 0 reverse the segment).
+__device__ __forceinline__ int move_source(int p, int id, int n) {
+    if (id < n * n) {
+        const int i = id / n, j = id - i * n;
+        return (p >= i && p <= j) ? i + j - p : p;
+    }
+    const int x = id - n * n;
+    const int g = x % n, s = (x / n) % n, variant = x / (n * n);
+    const int L = variant == 0 ? 1 : (variant + 3) >> 1;
+    const bool rev = variant != 0 && (variant & 1) == 0;
+    if (g > s) {                                   // towards higher ranks: the segment ends at rank g
+        if (p >= s && p <= g - L) return p + L;
+        if (p > g - L && p <= g) return rev ? s + L - 1 - (p - (g - L + 1)) : s + (p - (g - L + 1));
+    } else {                                       // towards lower ranks: it starts behind rank g
+        if (p > g && p <= g + L) return rev ? s + L - 1 - (p - (g + 1)) : s + (p - (g + 1));
+        if (p > g + L && p <= s + L - 1) return p - L;
+    }
+    return p;
+}
+
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
 // Reductions over the 64 lanes of a wave; every lane ends with the result.  The 32-bit forms use six DPP steps

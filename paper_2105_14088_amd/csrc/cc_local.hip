@@ -134,37 +134,8 @@ __global__ void insertion_search_kernel(const int32_t* __restrict__ c, int N, in
         if (win == kNoMove || (long long)(win >> 32) >= (long long)cur) break;
 
         // ---- apply: new[p] = old[src(p)]
-        const unsigned id = (unsigned)(win & 0xffffffffu);
-        int val = 0;
-        if (tid < N) {
-            const int p = tid;
-            int src = p;
-            if (id < nn) {
-                const int mi = (int)(id / (unsigned)N), mj = (int)(id % (unsigned)N);
-                if (p >= mi && p <= mj) src = mi + mj - p;
-            } else {
-                unsigned x = id - nn;
-                const int g = (int)(x % (unsigned)N);
-                x /= (unsigned)N;
-                const int s = (int)(x % (unsigned)N);
-                const int variant = (int)(x / (unsigned)N);
-                const int L = variant == 0 ? 1 : (variant + 3) >> 1;
-                const bool rev = variant != 0 && (variant & 1) == 0;
-                if (g > s) {                               // the segment moves towards higher ranks
-                    if (p >= s && p <= g - L) src = p + L;
-                    else if (p > g - L && p <= g) {
-                        const int k = p - (g - L + 1);
-                        src = rev ? s + L - 1 - k : s + k;
-                    }
-                } else {                                   // towards lower ranks: it lands behind rank g
-                    if (p > g && p <= g + L) {
-                        const int k = p - (g + 1);
-                        src = rev ? s + L - 1 - k : s + k;
-                    } else if (p > g + L && p <= s + L - 1) src = p - L;
-                }
-            }
-            val = t[src];
-        }
+        const int id = (int)(win & 0xffffffffu);
+        const int val = tid < N ? t[move_source(tid, id, N)] : 0;
         __syncthreads();
         if (tid < N) t[tid] = val;
         __syncthreads();

@@ -223,35 +223,8 @@ __global__ __launch_bounds__(K == 4 ? 768 : 1024) void local_multi_kernel(const 
         if (dwin >= 0) break;
         const int id = wave_min_all(bd == dwin ? bid : kIntMax);
         // ---- apply through the wave's copy of the order: new[p] = old[src(p)]
-        int mi = 0, mj = 0, g = 0, s = 0, L = 0;
-        bool rev = false;
-        const bool reversal = id < N * N;
-        if (reversal) {
-            mi = id / N;
-            mj = id % N;
-        } else {
-            const int x = id - N * N;
-            g = x % N;
-            s = (x / N) % N;
-            const int v = x / (N * N);
-            L = v == 0 ? 1 : (v + 3) >> 1;
-            rev = v != 0 && (v & 1) == 0;
-        }
 #pragma unroll
-        for (int m = 0; m < K; ++m) {
-            const int p = K * lane + m;
-            int src = p;
-            if (reversal) {
-                if (p >= mi && p <= mj) src = mi + mj - p;
-            } else if (g > s) {                             // towards higher ranks: the segment ends at rank g
-                if (p >= s && p <= g - L) src = p + L;
-                else if (p > g - L && p <= g) src = rev ? s + L - 1 - (p - (g - L + 1)) : s + (p - (g - L + 1));
-            } else {                                        // towards lower ranks: it starts behind rank g
-                if (p > g && p <= g + L) src = rev ? s + L - 1 - (p - (g + 1)) : s + (p - (g + 1));
-                else if (p > g + L && p <= s + L - 1) src = p - L;
-            }
-            t[m] = T[src];
-        }
+        for (int m = 0; m < K; ++m) t[m] = T[move_source(K * lane + m, id, N)];
         cur += dwin;
         ++applied;
     }

@@ -116,28 +116,7 @@ __device__ __forceinline__ void descend_local(const int32_t* m, int lane, int& t
         if (dwin >= 0) break;
         const int id = wave_min(best_d == dwin ? best_id : kIntMax);
         // ---- apply: new[p] = old[src(p)]
-        int src = lane;
-        if (id < kN * kN) {
-            const int mi = id >> 6, mj = id & (kN - 1);
-            if ((unsigned)(lane - mi) <= (unsigned)(mj - mi)) src = mi + mj - lane;
-        } else {
-            const int x = id - kN * kN;
-            const int g = x & (kN - 1), s = (x >> 6) & (kN - 1), v = x >> 12;
-            const int L = v == 0 ? 1 : (v + 3) >> 1;
-            const bool rev = v != 0 && (v & 1) == 0;
-            if (g > s) {                                       // towards higher ranks: it ends at rank g
-                if (lane >= s && lane <= g - L) src = lane + L;
-                else if (lane > g - L && lane <= g) {
-                    const int k = lane - (g - L + 1);
-                    src = rev ? s + L - 1 - k : s + k;
-                }
-            } else {                                           // towards lower ranks: it starts behind rank g
-                if (lane > g && lane <= g + L) {
-                    const int k = lane - (g + 1);
-                    src = rev ? s + L - 1 - k : s + k;
-                } else if (lane > g + L && lane <= s + L - 1) src = lane - L;
-            }
-        }
+        const int src = move_source(lane, id, kN);
         t = __shfl(t, src, kWave);
         cur += (long long)dwin;
         ++applied;

@@ -251,19 +251,12 @@ void twoopt_max_n64_kernel(const int32_t* __restrict__ c, int restarts, uint64_t
     mx = max(max(wave_max_entry[0], wave_max_entry[1]), max(wave_max_entry[2], wave_max_entry[3]));
     const bool packed = mx < (1 << 16);
     if (packed) {
-        // both directions of a pair into one word, in place: lane l of wave w takes the pairs {l, l + j} at the
-        // cyclic distances j = 1 + w, 5 + w, .. (every unordered pair exactly once; consecutive lanes, consecutive banks)
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            const int j = 1 + wv + 4 * s;
-            const int b = (lane + j) & 63;
-            const int lo = min(lane, b), hi = max(lane, b);
-            if (j < 32 || lane < 32) {
-                const int x = m[lo * kN + hi], y = m[hi * kN + lo];
-                m[lo * kN + hi] = x | (y << 16);
-                m[hi * kN + lo] = y | (x << 16);
-            }
-        }
+        // both directions of a pair into one word, in place
+        for_each_pair_64(tid, [&](int lo, int hi) {
+            const int x = m[lo * kN + hi], y = m[hi * kN + lo];
+            m[lo * kN + hi] = x | (y << 16);
+            m[hi * kN + lo] = y | (x << 16);
+        });
         __syncthreads();
     }
     if (r >= restarts) return;

@@ -9,6 +9,7 @@
 // Other N: one wave per order, hops gathered from the L2-resident matrix.
 #include "cc_device.h"
 #include "cc_internal.h"
+#include "cc_wave64.h"
 
 namespace cc {
 using namespace ccd;
@@ -347,19 +348,11 @@ __global__ __launch_bounds__(256) void rd_batch_links64_kernel(const int32_t* __
     const int lane = lane_id(), wv = threadIdx.x >> 6;
     for (int e = threadIdx.x; e < N * N; e += 256) m[e] = clampi(c[e], 0, (1 << 21) - 1);
     __syncthreads();
-    // lane l of wave w takes the pairs {l, l + j} at the cyclic distances j = 1 + w, 5 + w, ..: every unordered pair
-    // exactly once, consecutive lanes on consecutive banks
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-        const int j = 1 + wv + 4 * s;
-        const int b = (lane + j) & 63;
-        const int lo = min(lane, b), hi = max(lane, b);
-        if (j < 32 || lane < 32) {
-            const int both = max(m[lo * N + hi], m[hi * N + lo]);
-            m[lo * N + hi] = both;
-            m[hi * N + lo] = both;
-        }
-    }
+    w64::for_each_pair_64((int)threadIdx.x, [&](int lo, int hi) {
+        const int both = max(m[lo * N + hi], m[hi * N + lo]);
+        m[lo * N + hi] = both;
+        m[hi * N + lo] = both;
+    });
     __syncthreads();
     int32_t* order = order_all[wv];
     const int64_t wave = (int64_t)blockIdx.x * 4 + wv;

@@ -164,19 +164,12 @@ __global__ __launch_bounds__(256) void rdswap_n64_kernel(const int32_t* __restri
     for (int k = 0; k < kN * kN / 256; ++k) m[tid + 256 * k] = clampi(v[k], 0, kCostMax);
     __syncthreads();
     // a link costs the larger of its two directed entries: fold the two into both places once, so that a link is one
-    // gather.  Lane l of wave w takes the pairs {l, l + j} at the cyclic distances j = 1 + w, 5 + w, .. (every
-    // unordered pair exactly once; consecutive lanes, consecutive banks).
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-        const int j = 1 + wv + 4 * s;
-        const int b = (lane + j) & 63;
-        const int lo = min(lane, b), hi = max(lane, b);
-        if (j < 32 || lane < 32) {
-            const int both = max(m[lo * kN + hi], m[hi * kN + lo]);
-            m[lo * kN + hi] = both;
-            m[hi * kN + lo] = both;
-        }
-    }
+    // gather
+    for_each_pair_64(tid, [&](int lo, int hi) {
+        const int both = max(m[lo * kN + hi], m[hi * kN + lo]);
+        m[lo * kN + hi] = both;
+        m[hi * kN + lo] = both;
+    });
     __syncthreads();
     if (r >= restarts) return;
     const char* mbytes = (const char*)m;

@@ -47,19 +47,25 @@ __device__ __forceinline__ long long wave_min_uniform(long long v) {
     return v;
 }
 
-// Mirrors the upper triangle of a 64 x 64 matrix in LDS into the lower one (m[hi][lo] = m[lo][hi] for lo < hi), so
-// that a search reads a symmetric matrix whatever the caller's buffer holds.  For a workgroup of 256 threads; the
-// caller synchronises before and after.  Lane l of wave w takes the pairs {l, l + j} at the cyclic distances
-// j = 1 + w, 5 + w, ..: consecutive lanes touch consecutive banks on the read and on the write.
-__device__ __forceinline__ void mirror_upper_triangle_64(int32_t* m, int tid) {
+// Calls f(lo, hi) exactly once for every pair lo < hi of 0 .. 63, spread over a workgroup of 256 threads: lane l of
+// wave w takes the pairs {l, l + j} at the cyclic distances j = 1 + w, 5 + w, .. (the distance 32 by its lower 32
+// lanes only).  When the pair indexes a 64 x 64 matrix of words in LDS, consecutive lanes touch consecutive banks in
+// both triangles.  Used to fold the two triangles of a staged matrix in place; the caller synchronises around it.
+template <class F>
+__device__ __forceinline__ void for_each_pair_64(int tid, F f) {
     const int lane = tid & 63, wv = tid >> 6;
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
         const int j = 1 + wv + 4 * s;            // 1 .. 32 over the four waves
         const int b = (lane + j) & 63;
-        const int lo = min(lane, b), hi = max(lane, b);
-        m[hi * kN + lo] = m[lo * kN + hi];
+        if (j < 32 || lane < 32) f(min(lane, b), max(lane, b));
     }
+}
+
+// Mirrors the upper triangle of a 64 x 64 matrix in LDS into the lower one, so that a search reads a symmetric
+// matrix whatever the caller's buffer holds.
+__device__ __forceinline__ void mirror_upper_triangle_64(int32_t* m, int tid) {
+    for_each_pair_64(tid, [&](int lo, int hi) { m[hi * kN + lo] = m[lo * kN + hi]; });
 }
 
 // Seeded Fisher-Yates shuffle without a serial chain across lanes.  Lane v follows node v: at step k

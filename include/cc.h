@@ -92,6 +92,13 @@ int cc_ring_cost_batch_u8(const int32_t* cost_matrix, int32_t N, int32_t objecti
                           int64_t* out_costs, void* stream);
 
 /*
+ * The same with two bytes per rank (perms: uint16 [B, N] row-major, any N up to CC_MAX_N): half the order stream of
+ * cc_ring_cost_batch, for the sizes whose ranks do not fit a byte.
+ */
+int cc_ring_cost_batch_u16(const int32_t* cost_matrix, int32_t N, int32_t objective, const uint16_t* perms, int64_t B,
+                           int64_t* out_costs, void* stream);
+
+/*
  * Halving-doubling (recursive-doubling) cost model (Section 4.1, equation C_hd, with every round
  * weighted equally as in the latency-only view of Section 4.2):
  *     out_costs[b] = sum over k in [0, log2 N) of  max over ranks i of c[perm_b[i]][perm_b[i xor 2^k]]

@@ -21,7 +21,7 @@ CC_MAX_N = 1024
 CC_COST_MAX = (1 << 21) - 1
 
 # every symbol include/cc.h declares
-EXPORTS = ["cc_ring_cost_batch", "cc_ring_cost_batch_u8", "cc_rd_cost_batch", "cc_bcube_cost_batch",
+EXPORTS = ["cc_ring_cost_batch", "cc_ring_cost_batch_u8", "cc_ring_cost_batch_u16", "cc_rd_cost_batch", "cc_bcube_cost_batch",
            "cc_bcube_cost_batch_weighted", "cc_dbt_cost_batch", "cc_2opt_search", "cc_2opt_search_ex",
            "cc_2opt_workspace_bytes", "cc_local_search", "cc_local_search_ex", "cc_best_of_restarts", "cc_rd_swap_search", "cc_rd_swap_search_ex",
            "cc_rd_swap_workspace_bytes", "cc_sa_search", "cc_sa_search_ex", "cc_sa_workspace_bytes", "cc_sa_rd_search",
@@ -54,6 +54,8 @@ def lib() -> ctypes.CDLL:
         L.cc_ring_cost_batch.argtypes = [p, i32, i32, p, i64, p, p]
         L.cc_ring_cost_batch_u8.restype = ctypes.c_int
         L.cc_ring_cost_batch_u8.argtypes = [p, i32, i32, p, i64, p, p]
+        L.cc_ring_cost_batch_u16.restype = ctypes.c_int
+        L.cc_ring_cost_batch_u16.argtypes = [p, i32, i32, p, i64, p, p]
         L.cc_rd_cost_batch.restype = ctypes.c_int
         L.cc_rd_cost_batch.argtypes = [p, i32, p, i64, p, p]
         L.cc_bcube_cost_batch.restype = ctypes.c_int
@@ -157,6 +159,23 @@ def cc_ring_cost_batch_u8(cost_matrix: torch.Tensor, perms: torch.Tensor, object
     _check(lib().cc_ring_cost_batch_u8(_dev(cost_matrix, torch.int32, "cost_matrix"), n, objective,
                                        _dev(perms, torch.uint8, "perms"), b, _dev(out, torch.int64, "out"),
                                        _stream(stream)), "cc_ring_cost_batch_u8")
+    return out
+
+
+def cc_ring_cost_batch_u16(cost_matrix: torch.Tensor, perms: torch.Tensor, objective: int,
+                           out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """perms: int16 or uint16 [B, N] (ranks are below 1024, so the two read the same)."""
+    n = _matrix(cost_matrix)
+    if perms.dim() != 2 or perms.shape[1] != n:
+        raise ValueError("perms must be [B, N]")
+    if perms.dtype not in (torch.int16, torch.uint16):
+        raise ValueError("perms must be a 16-bit integer tensor")
+    b = int(perms.shape[0])
+    if out is None:
+        out = torch.empty(b, dtype=torch.int64, device=cost_matrix.device)
+    _check(lib().cc_ring_cost_batch_u16(_dev(cost_matrix, torch.int32, "cost_matrix"), n, objective,
+                                        _dev(perms, perms.dtype, "perms"), b, _dev(out, torch.int64, "out"),
+                                        _stream(stream)), "cc_ring_cost_batch_u16")
     return out
 
 

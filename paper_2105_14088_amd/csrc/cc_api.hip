@@ -74,6 +74,17 @@ int cc_ring_cost_batch_u8(const int32_t* cost_matrix, int32_t N, int32_t objecti
     return CC_OK;
 }
 
+int cc_ring_cost_batch_u16(const int32_t* cost_matrix, int32_t N, int32_t objective, const uint16_t* perms, int64_t B,
+                           int64_t* out_costs, void* stream) {
+    if (int rc = check_matrix_args(cost_matrix, N)) return rc;
+    if (objective < 0 || objective > 3 || B < 0) return CC_ERR_INVALID_ARG;
+    if (B == 0) return CC_OK;
+    if (!perms || !out_costs) return CC_ERR_INVALID_ARG;
+    if (((uintptr_t)perms & 1u) || ((uintptr_t)out_costs & 7u) || ((uintptr_t)cost_matrix & 3u)) return CC_ERR_INVALID_ARG;
+    CC_HIP(cc::launch_ring_cost_batch_u16(cost_matrix, N, (objective & 1) != 0, perms, B, out_costs, (hipStream_t)stream));
+    return CC_OK;
+}
+
 int cc_rd_cost_batch(const int32_t* cost_matrix, int32_t N, const int32_t* perms, int64_t B, int64_t* out_costs,
                      void* stream) {
     if (int rc = check_matrix_args(cost_matrix, N)) return rc;

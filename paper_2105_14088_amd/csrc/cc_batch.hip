@@ -144,15 +144,16 @@ __global__ __launch_bounds__(256) void ring_batch_u8_lds_kernel(const int32_t* _
     }
 }
 
-template <bool IS_MAX>
-__global__ __launch_bounds__(256) void ring_batch_u8_generic_kernel(const int32_t* __restrict__ c, int N,
-                                                                    const uint8_t* __restrict__ perms, int64_t B,
-                                                                    int64_t* __restrict__ out) {
+// Orders stored one byte or two bytes per rank, any N: one wave per order, matrix through L2.
+template <typename RANK, bool IS_MAX>
+__global__ __launch_bounds__(256) void ring_batch_narrow_generic_kernel(const int32_t* __restrict__ c, int N,
+                                                                        const RANK* __restrict__ perms, int64_t B,
+                                                                        int64_t* __restrict__ out) {
     const int lane = lane_id();
     const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t nwaves = (int64_t)gridDim.x * 4;
     for (int64_t b = wave; b < B; b += nwaves) {
-        const uint8_t* pi = perms + b * N;
+        const RANK* pi = perms + b * N;
         long long acc = 0;
         for (int p = lane; p < N; p += kWave) {
             const int a = min((int)pi[p], N - 1);
@@ -239,9 +240,24 @@ hipError_t launch_ring_cost_batch_u8(const int32_t* c, int N, bool is_max, const
     }
     const int grid = batch_grid(4, B);
     if (is_max)
-        hipLaunchKernelGGL((ring_batch_u8_generic_kernel<true>), dim3(grid), dim3(256), 0, s, c, N, perms, B, out);
+        hipLaunchKernelGGL((ring_batch_narrow_generic_kernel<uint8_t, true>), dim3(grid), dim3(256), 0, s, c, N, perms, B,
+                           out);
     else
-        hipLaunchKernelGGL((ring_batch_u8_generic_kernel<false>), dim3(grid), dim3(256), 0, s, c, N, perms, B, out);
+        hipLaunchKernelGGL((ring_batch_narrow_generic_kernel<uint8_t, false>), dim3(grid), dim3(256), 0, s, c, N, perms, B,
+                           out);
+    return hipGetLastError();
+}
+
+hipError_t launch_ring_cost_batch_u16(const int32_t* c, int N, bool is_max, const uint16_t* perms, int64_t B,
+                                      int64_t* out, hipStream_t s) {
+    if (B == 0) return hipSuccess;
+    const int grid = batch_grid(4, B);
+    if (is_max)
+        hipLaunchKernelGGL((ring_batch_narrow_generic_kernel<uint16_t, true>), dim3(grid), dim3(256), 0, s, c, N, perms,
+                           B, out);
+    else
+        hipLaunchKernelGGL((ring_batch_narrow_generic_kernel<uint16_t, false>), dim3(grid), dim3(256), 0, s, c, N, perms,
+                           B, out);
     return hipGetLastError();
 }
 

@@ -10,6 +10,8 @@ hipError_t launch_ring_cost_batch(const int32_t* c, int N, bool is_max, const in
                                   int64_t* out, hipStream_t s);
 hipError_t launch_ring_cost_batch_u8(const int32_t* c, int N, bool is_max, const uint8_t* perms, int64_t B,
                                      int64_t* out, hipStream_t s);
+hipError_t launch_ring_cost_batch_u16(const int32_t* c, int N, bool is_max, const uint16_t* perms, int64_t B,
+                                      int64_t* out, hipStream_t s);
 // weights: device int32 [rounds] or nullptr (every round weighs 1)
 hipError_t launch_rd_cost_batch(const int32_t* c, int N, const int32_t* weights, const int32_t* perms, int64_t B,
                                 int64_t* out, hipStream_t s);

@@ -62,6 +62,11 @@ def test_argument_errors_are_returned_before_any_launch():
     assert L.cc_ring_cost_batch_u8(fake, 257, 0, fake, 1, fake, null) == UNSUPPORTED   # ranks do not fit a byte
     assert L.cc_ring_cost_batch_u8(fake, 64, 0, null, 1, fake, null) == INVALID
     assert L.cc_ring_cost_batch_u8(fake, 64, 0, null, 0, null, null) == 0
+    assert L.cc_ring_cost_batch_u16(fake, 1025, 0, fake, 1, fake, null) == UNSUPPORTED
+    assert L.cc_ring_cost_batch_u16(fake, 512, 0, null, 1, fake, null) == INVALID
+    assert L.cc_ring_cost_batch_u16(fake, 512, 0, ctypes.c_void_p(0x1001), 1, fake, null) == INVALID   # misaligned
+    assert L.cc_ring_cost_batch_u16(fake, 512, 4, fake, 1, fake, null) == INVALID
+    assert L.cc_ring_cost_batch_u16(fake, 512, 0, null, 0, null, null) == 0
     assert L.cc_rd_cost_batch(fake, 48, fake, 1, fake, null) == UNSUPPORTED      # not a power of two
     assert L.cc_rd_cost_batch(fake, 64, fake, -5, fake, null) == INVALID
     assert L.cc_rd_cost_batch(fake, 64, null, 0, null, null) == 0

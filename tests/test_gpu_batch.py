@@ -76,6 +76,31 @@ def test_ring_batch_u8_unaligned_out_of_range_and_full_size():
     assert np.array_equal(got.cpu().numpy()[rows], oracle.ring_cost_batch(c, tours.cpu().numpy()[rows], 0))
 
 
+@pytest.mark.parametrize("n", [2, 13, 64, 257, 300, 512, 1024])
+@pytest.mark.parametrize("obj", [0, 1])
+def test_ring_batch_u16_orders(n, obj):
+    """Two bytes per rank: any N; also an odd element offset of the stream and ranks out of range (access must stay
+    in bounds)."""
+    c = random_matrix(n, 1700 + n, symmetric=False, lo=0, hi=COST_MAX if n in (13, 64) else 6000)
+    for b in (1, 3, 67, 1029):
+        say(f"ring batch, two bytes per rank, N={n} obj={obj} B={b}")
+        perms = random_perms(n, b, seed=n + b)
+        out = cc.cc_ring_cost_batch_u16(dev(c), dev(perms.astype(np.int16)), obj)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), oracle.ring_cost_batch(c, perms, obj))
+    perms = random_perms(n, 9, seed=n)
+    flat = torch.empty(9 * n + 1, dtype=torch.int16, device="cuda")
+    view = flat[1:].view(9, n)
+    view.copy_(dev(perms.astype(np.int16)))
+    out = cc.cc_ring_cost_batch_u16(dev(c), view, obj)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), oracle.ring_cost_batch(c, perms, obj))
+    bad = perms.astype(np.int16)
+    bad[::2, 1] = -1                                    # 65535 as a rank: result unspecified
+    cc.cc_ring_cost_batch_u16(dev(c), dev(bad), obj)
+    torch.cuda.synchronize()
+
+
 def test_ring_batch_empty_and_unaligned():
     c = random_matrix(64, 1, symmetric=True)
     say("ring batch B=0")

@@ -3,7 +3,10 @@ from __future__ import annotations
 
 import glob
 import os
+import re
+import shutil
 import subprocess
+import tempfile
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libcc.so")
@@ -18,6 +21,23 @@ HIPCC_FLAGS = [
 ]
 
 
+# Operand-reversed VOP2 opcodes in their DPP form: measured on gfx950 with this toolchain,
+# "v_subrev_u32_dpp d, a, b <rotate>" yields rotate(b) - a, not b - rotate(a) (the plain and the non-reversed DPP
+# forms, v_sub_u32_dpp / v_add_u32_dpp / v_mov_b32_dpp, behave as documented).  The compiler's DPP combiner can
+# produce the form by itself from "x - rotate(y)"; a build that contains one is refused, and the source is changed
+# so that the rotate stays an instruction of its own (an empty asm statement with the value as in/out operand).
+FORBIDDEN_ISA = re.compile(r"^\s*(v_\w*rev\w*_dpp)\b", re.M)
+
+
+def check_device_isa(folder: str) -> None:
+    for path in sorted(glob.glob(os.path.join(folder, "*-hip-amdgcn-amd-amdhsa-gfx950.s"))):
+        with open(path) as fh:
+            hit = FORBIDDEN_ISA.search(fh.read())
+        if hit:
+            raise RuntimeError(f"{os.path.basename(path)}: the compiler emitted {hit.group(1)}, which does not "
+                               "compute what its operands say on gfx950; keep the rotate out of the subtraction")
+
+
 def needs_build() -> bool:
     if not os.path.exists(LIB_PATH):
         return True
@@ -28,10 +48,16 @@ def needs_build() -> bool:
 def build(force: bool = True, verbose: bool = False) -> str:
     if force or needs_build():
         hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-        cmd = [hipcc] + HIPCC_FLAGS + SOURCES + ["-o", LIB_PATH]
-        if verbose:
-            print(" ".join(cmd))
-        subprocess.check_call(cmd)
+        # the intermediate files (device assembly among them) go to a scratch folder and are checked before the
+        # library is put in place
+        with tempfile.TemporaryDirectory(prefix="cc_build_") as tmp:
+            out = os.path.join(tmp, "libcc.so")
+            cmd = [hipcc] + HIPCC_FLAGS + ["-save-temps"] + SOURCES + ["-o", out]
+            if verbose:
+                print(" ".join(cmd))
+            subprocess.check_call(cmd, cwd=tmp)
+            check_device_isa(tmp)
+            shutil.move(out, LIB_PATH)
     return LIB_PATH
 
 

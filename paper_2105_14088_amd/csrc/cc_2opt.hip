@@ -329,6 +329,18 @@ hipError_t launch_2opt(const int32_t* c, int N, int objective, int classes, int 
         e = launch_2opt_sum_n64(c, restarts, seed, !tours_hold_init, tours, costs, moves, s);
     } else if (N == 64 && (objective & 1)) {
         e = launch_2opt_max_n64(c, restarts, seed, !tours_hold_init, tours, costs, moves, s);
+    } else if (N == 64 && objective == 2) {
+        // directed sum: wavefront kernel with 32-bit keys when max(c) < 2^16, else the general kernel (both enqueued,
+        // the matrix maximum computed on the device decides)
+        if (!tours_hold_init) {
+            e = launch_init_tours(N, 0, restarts, seed, tours, s);
+            if (e != hipSuccess) return e;
+        }
+        e = launch_matrix_max(c, N, flags, s);
+        if (e != hipSuccess) return e;
+        e = launch_2opt_dsum_n64(c, restarts, seed, false, tours, costs, moves, flags, s);
+        if (e != hipSuccess) return e;
+        e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, false, s);
     } else {
         if (!tours_hold_init) {
             e = launch_init_tours(N, 0, restarts, seed, tours, s);

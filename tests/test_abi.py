@@ -155,3 +155,19 @@ def test_binding_refuses_cpu_tensors():
 
 class _FakeStream:
     cuda_stream = 0
+
+
+def test_build_refuses_operand_reversed_dpp(tmp_path):
+    """The build's check of the device assembly: a reversed-operand DPP form is refused, the forms the kernels rely
+    on (plain rotates, add / sub / min / max with a DPP operand) pass."""
+    from paper_2105_14088_amd import build as b
+    good = tmp_path / "good-hip-amdgcn-amd-amdhsa-gfx950.s"
+    good.write_text("\tv_mov_b32_dpp v1, v1 wave_rol:1 row_mask:0xf bank_mask:0xf bound_ctrl:1\n"
+                    "\tv_sub_u32_dpp v3, v29, v3 wave_ror:1 row_mask:0xf bank_mask:0xf bound_ctrl:1\n"
+                    "\tv_lshlrev_b32_e32 v2, 2, v1\n\tv_subrev_u32_e32 v2, v3, v1\n")
+    b.check_device_isa(str(tmp_path))
+    bad = tmp_path / "bad-hip-amdgcn-amd-amdhsa-gfx950.s"
+    bad.write_text("\tv_add_u32_e32 v1, v2, v3\n"
+                   "\tv_subrev_u32_dpp v75, v75, v74 wave_rol:1 row_mask:0xf bank_mask:0xf bound_ctrl:1\n")
+    with pytest.raises(RuntimeError, match="v_subrev_u32_dpp"):
+        b.check_device_isa(str(tmp_path))

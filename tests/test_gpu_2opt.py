@@ -198,6 +198,26 @@ def test_workload3_n64_max_directed_1024_restarts_full():
     assert_search_equal(gpu_search(c, 3, 1024, seed), want)
 
 
+def test_matrix3_n64_sum_directed_1024_restarts_full():
+    say("N=64 directed sum on the asymmetric matrix, 1024 restarts (all restarts compared)")
+    c = make_matrix(3)
+    seed = WORKLOADS[3].search_seed
+    o = oracle.restarts_parallel(c, oracle.SUM_DIRECTED, seed, 0, 1024, THREADS)
+    k = int(np.argmin(o[0]))
+    want = dict(costs=o[0], tours=o[1], moves=o[2], best_cost=int(o[0][k]), best_restart=k, best_perm=o[1][k])
+    assert_search_equal(gpu_search(c, 2, 1024, seed), want)
+
+
+@pytest.mark.parametrize("top", [(1 << 16) - 1, 1 << 16])
+def test_n64_sum_directed_at_the_16_bit_boundary(top):
+    """Largest entry one below / at 2^16: the last matrix the N = 64 kernel takes and the first it hands on."""
+    say(f"2-opt N=64 obj=2, largest entry {top}")
+    c = random_matrix(64, 8800 + (top & 1), symmetric=False, lo=top - 3000, hi=top)
+    c[5, 9] = top
+    want = oracle.search(c, 2, 40, seed=31)
+    assert_search_equal(gpu_search(c, 2, 40, seed=31), want)
+
+
 def _certify(c, obj, tour, cost):
     """Properties that hold at any size: a permutation anchored at rank 0's start node, its cost, and
     no improving move (checked with the oracle's move values)."""

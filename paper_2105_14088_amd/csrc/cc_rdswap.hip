@@ -10,10 +10,15 @@
 //
 // General kernel: one workgroup per restart, one thread per rank p scanning q = p+1 .. N-1; matrix
 // gathered through L2; 64-bit keys (value << 32 | move id) min-reduced over the workgroup.
-// N = 64 kernel: one wavefront per restart, matrix in LDS, lane p scans partners q = p xor x; two rank
-// differences x with the same top bit share a step (lanes with that bit clear take one, the others the
-// other), so every pair is scored once, in 32 steps; the top-3 links of a round come from three
-// wave-wide max-reductions over (value << 5 | link index).
+// N = 64 kernel: one wavefront per restart, matrix in LDS (both directed entries of a pair folded into one value),
+// lane p scans partners q = p xor x; two rank differences x with the same top bit share a step (lanes with that bit
+// clear take one, the others the other), so every pair is scored once, in 32 steps.  The node at rank p xor y is
+// fetched once per sweep for all 64 y (ds_swizzle) and the step loop is fully unrolled, so the partner and the round
+// mates of both ends are register selects; the top-3 links of a round come from wave-wide max-reductions over
+// (value << 5 | link index), three rounds at a time.
+#include <type_traits>
+#include <utility>
+
 #include "cc_device.h"
 #include "cc_internal.h"
 #include "cc_wave64.h"
@@ -145,13 +150,138 @@ __global__ void rdswap_general_kernel(const int32_t* __restrict__ c, int N, int3
 // ----------------------------------------------------------------------------------------- N = 64
 using namespace w64;
 
-__device__ __forceinline__ int wave_max_all(int v) { return wave_max(v); }
+// lane p <- lane p xor Y for Y < 32 (ds_swizzle in bit mode: no LDS access, no address arithmetic)
+template <int Y>
+__device__ __forceinline__ int from_lane_xor(int v) {
+    if constexpr (Y == 0) return v;
+    else return __builtin_amdgcn_ds_swizzle(v, (Y << 10) | 0x1f);
+}
+// out[y] = the value lane p xor y holds, for every y: own (lower 32 differences) and far (the value of lane p xor 32)
+template <int... Y>
+__device__ __forceinline__ void from_every_lane(int (&out)[kN], int own, int far, std::integer_sequence<int, Y...>) {
+    ((out[Y] = from_lane_xor<(Y & 31)>((Y & 32) ? far : own)), ...);
+}
+
+// Keeps "cond ? a[i] : a[j]" a select between two registers: without it the compiler selects the index instead and
+// the array leaves the register file.
+__device__ __forceinline__ int in_register(int v) {
+    asm("" : "+v"(v));
+    return v;
+}
+
+// One descent.  m: the folded matrix in LDS.  WIDE: totals that need more than 19 bits (entries from 2^16 up), keys
+// of 64 bits.
+template <bool WIDE>
+__device__ __forceinline__ void descend_swaps(const int32_t* m, int lane, int& t, int& cost, int& applied_out) {
+    using K = typename std::conditional<WIDE, unsigned long long, int>::type;
+    const char* mbytes = (const char*)m;
+    auto entry = [&](int byte_offset) { return *(const int32_t*)(mbytes + byte_offset); };   // row << 8 | col << 2
+    const int pair_base = lane * (kN + 1);       // id of the pair {lane, lane xor x}: pair_base ^ x or ^ (x << 6)
+    int applied = 0, cur = 0;
+    for (;;) {
+        // node at rank p xor y, as a column byte offset, for every y: the partners q = p xor x of this sweep and the
+        // round mates of both ends all come from here, by register index
+        const int t2 = t << 2, t8 = t << 8;
+        int tl[kN];
+        from_every_lane(tl, t2, __shfl_xor(t2, 32, kWave), std::make_integer_sequence<int, kN>{});
+        // per round: the best / second-best link value among links other than this lane's, and where the best one is
+        int x1v[6], x2v[6], zk[6], zk_second[6], round_cost[6];
+        int li[6], key[6], k1[6], k2[6], k3[6];
+#pragma unroll
+        for (int k = 0; k < 6; ++k) {
+            const int bit = 1 << k;
+            li[k] = ((lane >> (k + 1)) << k) | (lane & (bit - 1));                 // link index, 5 bits
+            key[k] = (entry(t8 | tl[bit]) << 5) | li[k];
+            k1[k] = key[k];
+        }
+        // the three largest links of every round: the rounds are independent, so their reductions run three at a time
+        wave_max3(k1[0], k1[1], k1[2]);
+        wave_max3(k1[3], k1[4], k1[5]);
+#pragma unroll
+        for (int k = 0; k < 6; ++k) k2[k] = (li[k] == (k1[k] & 31)) ? -1 : key[k];
+        wave_max3(k2[0], k2[1], k2[2]);
+        wave_max3(k2[3], k2[4], k2[5]);
+#pragma unroll
+        for (int k = 0; k < 6; ++k) k3[k] = (li[k] == (k1[k] & 31) || li[k] == (k2[k] & 31)) ? -1 : key[k];
+        wave_max3(k3[0], k3[1], k3[2]);
+        wave_max3(k3[3], k3[4], k3[5]);
+        cur = 0;
+#pragma unroll
+        for (int k = 0; k < 6; ++k) {
+            const int l1 = k1[k] & 31, l2 = k2[k] & 31;
+            const int a1 = (li[k] == l1) ? k2[k] : k1[k];                          // best link that is not mine
+            const int a2 = (li[k] == l1 || li[k] == l2) ? k3[k] : k2[k];           // second best that is not mine
+            x1v[k] = a1 >> 5;
+            x2v[k] = a2 >> 5;
+            zk[k] = li[k] ^ (a1 & 31);                             // partner's link == that best link  <=>  li(x) == zk
+            zk_second[k] = zk[k] ^ (k ? 1 : 0);                    // the same test for the odd difference of a step
+            round_cost[k] = k1[k] >> 5;
+            cur += round_cost[k];
+        }
+        // Partners by rank difference x = p xor q.  Every pair would be seen from both of its ends; instead two
+        // differences with the same top bit h, x0 = 2j and x1 = 2j + 1, share a step: the lanes whose rank has bit h
+        // clear take x0, the others x1, so the 64 lanes score 64 distinct pairs.  x = 1 has no mate: its step scores
+        // each of its 32 pairs twice (same value, same id).  The loop is unrolled, so every index below is a constant.
+        K best = WIDE ? (K)~0ull : (K)0x7fffffff;
+#pragma unroll
+        for (int j = 0; j < kN / 2; ++j) {
+            const int x0 = j ? 2 * j : 1, x1 = j ? 2 * j + 1 : 1;
+            const int h = 31 - __builtin_clz(x0);
+            const bool second = (lane >> h) & 1;
+            const int tq_second = in_register(tl[x1]);
+            const int tq2 = second ? tq_second : tl[x0];
+            int total = 0;
+#pragma unroll
+            for (int k = 0; k < 6; ++k) {
+                const int bit = 1 << k;
+                if (x0 == bit && x1 == bit) {                      // x = 1 in round 0: every lane swaps with its mate
+                    total += round_cost[k];
+                    continue;
+                }
+                const int qb_second = in_register(tl[x1 ^ bit]);
+                const int qb2 = second ? qb_second : tl[x0 ^ bit];                 // node at rank q xor 2^k
+                const int link_p = entry((tq2 << 6) | tl[bit]);    // rank p now holds t[q]
+                const int link_q = entry(t8 | qb2);                // rank q now holds t[p]
+                // the partner's link index relative to this lane's: x without bit k; x1's differs from x0's in bit 0
+                const int lim0 = ((x0 >> (k + 1)) << k) | (x0 & (bit - 1));
+                const int z = (second && x1 != x0) ? zk_second[k] : zk[k];
+                const int others = (z == lim0) ? x2v[k] : x1v[k];
+                int stage = max(others, max(link_p, link_q));
+                if (x0 == bit) stage = second ? stage : round_cost[k];             // x0 swaps the two ends of a link
+                total += stage;
+            }
+            const int id = pair_base ^ (second ? (x1 << 6) : x0);                  // lower rank * 64 + higher rank
+            const K key = WIDE ? (K)(((unsigned long long)(unsigned)total << 12) | (unsigned)id) : (K)((total << 12) | id);
+            best = key < best ? key : best;
+            // steps are scheduled four at a time: enough gathers in flight, and the live ranges stay within the
+            // register file
+            if ((j & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+        }
+        int total_win, id;
+        if constexpr (WIDE) {
+            const unsigned long long win = wave_min_u64(best);
+            total_win = (int)(win >> 12);
+            id = __builtin_amdgcn_readfirstlane((int)(win & 0xfff));
+        } else {
+            const int win = wave_min(best);
+            total_win = win >> 12;
+            id = win & 0xfff;
+        }
+        if (total_win >= cur) break;
+        const int sp = id >> 6, sq = id & 63;
+        const int a = __builtin_amdgcn_readlane(t, sp), b = __builtin_amdgcn_readlane(t, sq);
+        t = lane == sp ? b : (lane == sq ? a : t);
+        ++applied;
+    }
+    cost = cur;
+    applied_out = applied;
+}
 
 __global__ __launch_bounds__(256) void rdswap_n64_kernel(const int32_t* __restrict__ c, int restarts, uint64_t seed,
                                                          int generate, int32_t* __restrict__ tours,
                                                          int64_t* __restrict__ costs, int32_t* __restrict__ moves) {
     __shared__ __attribute__((aligned(256))) int32_t m[kN * kN];
-    __shared__ int32_t tl_all[4][kN];            // each wave's tour, for "node at rank p xor x" look-ups
+    __shared__ int wave_max_entry[4];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     int v[kN * kN / 256];
 #pragma unroll
@@ -160,9 +290,17 @@ __global__ __launch_bounds__(256) void rdswap_n64_kernel(const int32_t* __restri
     int t = 0;
     if (r < restarts)
         t = generate ? init_tour_in_wave(seed, (uint32_t)r, lane) : clampi(tours[r * kN + lane], 0, kN - 1);
+    int mx = 0;
 #pragma unroll
-    for (int k = 0; k < kN * kN / 256; ++k) m[tid + 256 * k] = clampi(v[k], 0, kCostMax);
+    for (int k = 0; k < kN * kN / 256; ++k) {
+        v[k] = clampi(v[k], 0, kCostMax);
+        mx = max(mx, v[k]);
+        m[tid + 256 * k] = v[k];
+    }
+    mx = wave_max(mx);
+    if (lane == 0) wave_max_entry[wv] = mx;
     __syncthreads();
+    mx = max(max(wave_max_entry[0], wave_max_entry[1]), max(wave_max_entry[2], wave_max_entry[3]));
     // a link costs the larger of its two directed entries: fold the two into both places once, so that a link is one
     // gather
     for_each_pair_64(tid, [&](int lo, int hi) {
@@ -172,82 +310,9 @@ __global__ __launch_bounds__(256) void rdswap_n64_kernel(const int32_t* __restri
     });
     __syncthreads();
     if (r >= restarts) return;
-    const char* mbytes = (const char*)m;
-    int32_t* tl = tl_all[wv];
-    const char* tlbytes = (const char*)tl;
-    auto entry = [&](int row8, int col2) { return *(const int32_t*)(mbytes + (row8 | col2)); };   // row << 8 | col << 2
-
-    int applied = 0, cur = 0;
-    for (;;) {
-        tl[lane] = t;
-        __builtin_amdgcn_wave_barrier();
-        const int t8 = t << 8;
-        // per round: partner, link value, and the best / second-best link value among links other than this lane's
-        int pb2[6], x1v[6], x2v[6], zk[6], round_cost[6], own_addr[6];
-        cur = 0;
-#pragma unroll
-        for (int k = 0; k < 6; ++k) {
-            const int bit = 1 << k;
-            const int pb = tl[lane ^ bit];
-            pb2[k] = pb << 2;
-            own_addr[k] = (lane ^ bit) << 2;                       // byte offset of rank p xor 2^k in tl
-            const int lv = entry(t8, pb2[k]);
-            const int li = ((lane >> (k + 1)) << k) | (lane & (bit - 1));          // link index, 5 bits
-            int key = (lv << 5) | li;
-            const int k1 = wave_max_all(key);
-            const int k2 = wave_max_all((li == (k1 & 31)) ? -1 : key);
-            const int k3 = wave_max_all((li == (k1 & 31) || li == (k2 & 31)) ? -1 : key);
-            // k2, k3 are -1 when fewer links exist (never at N = 64: 32 links per round)
-            const int l1 = k1 & 31, l2 = k2 & 31;
-            const int a1 = (li == l1) ? k2 : k1;                   // best link that is not mine
-            const int a2 = (li == l1 || li == l2) ? k3 : k2;       // second best that is not mine
-            x1v[k] = a1 >> 5;
-            x2v[k] = a2 >> 5;
-            zk[k] = li ^ (a1 & 31);                                // partner's link == that best link  <=>  li(m) == zk
-            round_cost[k] = k1 >> 5;
-            cur += round_cost[k];
-        }
-        // Partners by rank difference x = p xor q.  Every pair would be seen from both of its ends; instead two
-        // differences with the same top bit h, x = 2j and 2j + 1, share a step: the lanes whose rank has bit h clear
-        // take the first, the others the second, so the 64 lanes score 64 distinct pairs.  x = 1 has no mate: its
-        // step scores each of its 32 pairs twice (same value, same id).
-        unsigned long long best = kNoMove;
-#pragma unroll 1
-        for (int j = 0; j < kN / 2; ++j) {
-            const int x0 = j ? 2 * j : 1, x1 = j ? 2 * j + 1 : 1;                           // wave-uniform
-            const int top = 31 - __builtin_clz(x0);
-            const bool second = (lane >> top) & 1;
-            const int mm = second ? x1 : x0;
-            const int q = lane ^ mm;
-            const int tq = *(const int32_t*)(tlbytes + (q << 2));
-            const int tq8 = tq << 8;
-            int total = 0;
-#pragma unroll
-            for (int k = 0; k < 6; ++k) {
-                const int bit = 1 << k;
-                const int qb = *(const int32_t*)(tlbytes + (own_addr[k] ^ (mm << 2)));      // node at rank q xor 2^k
-                const int link_p = entry(tq8, pb2[k]);             // rank p now holds t[q]
-                const int link_q = entry(t8, qb << 2);             // rank q now holds t[p]
-                // link index offset of the partner, for either difference (wave-uniform), then this lane's
-                const int lim0 = ((x0 >> (k + 1)) << k) | (x0 & (bit - 1));
-                const int lim1 = ((x1 >> (k + 1)) << k) | (x1 & (bit - 1));
-                const int lim = second ? lim1 : lim0;
-                const int others = (zk[k] == lim) ? x2v[k] : x1v[k];
-                const int stage = max(others, max(link_p, link_q));
-                total += (mm == bit) ? round_cost[k] : stage;
-            }
-            const int lo = min(lane, q), hi = max(lane, q);
-            best = min(best, ((unsigned long long)(unsigned)total << 12) | (unsigned)(lo * kN + hi));
-        }
-        const unsigned long long win = wave_min_u64(best);
-        const int total_win = (int)(win >> 12);
-        if (total_win >= cur) break;
-        const int id = __builtin_amdgcn_readfirstlane((int)(win & 0xfff)), sp = id >> 6, sq = id & 63;
-        const int a = __builtin_amdgcn_readlane(t, sp), b = __builtin_amdgcn_readlane(t, sq);
-        t = lane == sp ? b : (lane == sq ? a : t);
-        ++applied;
-        __builtin_amdgcn_wave_barrier();
-    }
+    int cur, applied;
+    if (mx >= (1 << 16)) descend_swaps<true>(m, lane, t, cur, applied);
+    else descend_swaps<false>(m, lane, t, cur, applied);
     tours[r * kN + lane] = t;
     if (lane == 0) {
         costs[r] = (int64_t)cur;

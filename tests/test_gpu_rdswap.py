@@ -48,6 +48,20 @@ def test_swap_search_initial_tours_single_restart_and_simple_entry_point():
     assert int(cost.item()) == want["best_cost"] and np.array_equal(perm.cpu().numpy(), want["best_perm"])
 
 
+@pytest.mark.parametrize("top", [(1 << 16) - 1, 1 << 16])
+@pytest.mark.parametrize("symmetric", [True, False])
+def test_swap_search_n64_at_the_16_bit_boundary(top, symmetric):
+    """Largest entry one below / at 2^16: the N = 64 kernel's last matrix with 32-bit keys and its first with 64-bit
+    ones; all entries close to the top, so that round costs add up to the largest totals."""
+    say(f"rd swap search N=64, largest entry {top}, symmetric={symmetric}")
+    c = random_matrix(64, 7100 + (top & 1), symmetric=symmetric, lo=top - 2000, hi=top)
+    c[3, 11] = top
+    if symmetric:
+        c[11, 3] = top
+    want = oracle.rd_swap_search(c, 24, seed=13)
+    assert_search_equal(gpu_swap_search(c, 24, seed=13), want)
+
+
 def test_swap_search_n64_1024_restarts_full():
     say("rd swap search: N=64 hierarchical matrix, 1024 restarts (all restarts compared)")
     c = make_matrix(2)

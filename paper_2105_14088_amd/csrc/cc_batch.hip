@@ -698,7 +698,8 @@ hipError_t launch_dbt_cost_batch(const int32_t* c, int N, const int32_t* perms, 
 // One wave per order.  N <= 64: no serial chain - lane v follows node v through the shuffle: at step k (k = N-1 .. 1)
 // ranks k and j_k swap, so a node sitting at rank k moves to j_k and a node sitting at j_k moves to k, where it
 // stays (later steps only touch ranks below k); the partners j_k are drawn in parallel, one per lane, and read
-// step by step; each lane finally stores its node at the rank where it ended.  Larger N: the partners are drawn in
+// step by step; each lane finally stores its node at the rank where it ended.  N <= 256: the same with up to four
+// nodes per lane and the partners read from LDS (one broadcast read per step).  Larger N: the partners are drawn in
 // parallel, lane 0 replays the swaps in order in LDS, all lanes store the result coalesced.
 __global__ __launch_bounds__(256) void init_tours_kernel(int N, int64_t first, int64_t count, uint64_t seed,
                                                          int32_t* __restrict__ tours) {
@@ -726,6 +727,24 @@ __global__ __launch_bounds__(256) void init_tours_kernel(int N, int64_t first, i
             partner[k] = k ? shuffle_partner(seed, r, k) : 0;
         }
         __builtin_amdgcn_wave_barrier();
+        if (N <= 4 * kWave) {
+            int pos[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) pos[i] = lane + kWave * i;       // node ids; those >= N never match a rank
+            for (int k = N - 1; k >= 1; --k) {
+                const int j = partner[k];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int moved = (pos[i] == k) ? j : pos[i];
+                    pos[i] = (pos[i] == j) ? k : moved;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (lane + kWave * i < N) tours[w * N + pos[i]] = lane + kWave * i;
+            __builtin_amdgcn_wave_barrier();
+            continue;
+        }
         if (lane == 0) {
             for (int k = N - 1; k >= 1; --k) {
                 const int j = partner[k];

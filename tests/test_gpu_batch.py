@@ -274,3 +274,14 @@ def test_validate_matrix():
     assert cc.cc_validate_matrix(dev(bad), False) == -6
     bad[3, 5] = -1
     assert cc.cc_validate_matrix(dev(bad), False) == -6
+
+
+@pytest.mark.parametrize("n", [2, 3, 31, 63, 64, 65, 100, 128, 129, 191, 192, 255, 256, 257, 500, 1024])
+def test_init_tours_every_generation_path(n):
+    """Seeded start orders for sizes on both sides of every switch of the generator (one node per lane, up to four per
+    lane, the replay in LDS), with a first id above zero and a count that is no multiple of the launch shape."""
+    say(f"cc_init_tours N={n}")
+    seed, first, count = 0x5eed0000 + n, 1000003, 1037
+    tours = cc.cc_init_tours(n, count, seed, first=first)
+    torch.cuda.synchronize()
+    assert np.array_equal(tours.cpu().numpy(), oracle.init_tours(seed, n, count, first=first))

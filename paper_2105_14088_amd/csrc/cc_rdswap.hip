@@ -333,37 +333,43 @@ __global__ __launch_bounds__(256) void fold_to_u16_kernel(const int32_t* __restr
 }
 
 // ------------------------------------------------------------------------- N = 128 .. 1024: one workgroup per restart
-// The N = 64 scheme with one thread per rank: N threads, the order in LDS, the three largest links of a round from
-// workgroup-wide max-reductions, two rank differences per step so that the N threads score N distinct pairs.  The
-// matrix is read as folded 16-bit entries: staged and folded in LDS for N = 128, 256 (32 / 128 KiB), gathered through
-// L2 from the folded copy in the workspace for N = 512, 1024 (IN_LDS false).  Needs max(c) < 2^16, otherwise the
-// general kernel runs instead, decided on the device.  Keys: value << 2 log2 N | move id (value < 2^20).
-template <int LOGN, bool IN_LDS>
-__global__ __launch_bounds__(1 << LOGN) void rdswap_block_kernel(const int32_t* __restrict__ c,
-                                                                 const uint16_t* __restrict__ folded,
-                                                                 int32_t* __restrict__ tours,
-                                                                 int64_t* __restrict__ costs,
-                                                                 int32_t* __restrict__ moves,
-                                                                 const int32_t* __restrict__ flags) {
-    constexpr int N = 1 << LOGN, NW = N / 64, LB = LOGN - 1;   // LB: bits of a link index
+// The N = 64 scheme with one thread per rank (SPLIT threads per rank, sharing the rank's steps, where the matrix is
+// in LDS and a restart has a compute unit to itself: one wavefront per SIMD cannot overlap its gathers with its own
+// arithmetic): the order in LDS, the three largest links of a round from workgroup-wide max-reductions, two rank
+// differences per step so that N threads score N distinct pairs.  The matrix is read as folded 16-bit entries:
+// staged and folded in LDS for N = 128, 256 (32 / 128 KiB), gathered through L2 from the folded copy in the
+// workspace for N = 512, 1024 (IN_LDS false).  Needs max(c) < 2^16, otherwise the general kernel runs instead,
+// decided on the device.  Per thread the running minimum is kept over total << log2 N | q (the move id grows with
+// q); the workgroup reduces value << 2 log2 N | move id (value < 2^20).
+template <int LOGN, bool IN_LDS, int SPLIT>
+__global__ __launch_bounds__(SPLIT << LOGN) void rdswap_block_kernel(const int32_t* __restrict__ c,
+                                                                     const uint16_t* __restrict__ folded,
+                                                                     int32_t* __restrict__ tours,
+                                                                     int64_t* __restrict__ costs,
+                                                                     int32_t* __restrict__ moves,
+                                                                     const int32_t* __restrict__ flags) {
+    // SPLIT threads per rank share its steps: several wavefronts per SIMD, whose gathers and arithmetic overlap
+    constexpr int N = 1 << LOGN, THREADS = SPLIT << LOGN, NW = THREADS / 64, LB = LOGN - 1;   // LB: bits of a link index
     constexpr int kIdBits = 2 * LOGN;
+    constexpr int kStepUnroll = IN_LDS ? 2 : 1;                // two steps in flight where registers allow
     if (flags[0] >= (1 << 16)) return;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    uint16_t* m16 = (uint16_t*)smem;                           // [N * N] (IN_LDS)
-    int32_t* tl = (int32_t*)(smem + (IN_LDS ? sizeof(uint16_t) * N * N : 0)); // [N] the order
+    int32_t* tl = (int32_t*)smem;                              // [N] the order
+    uint16_t* m16 = (uint16_t*)(smem + sizeof(int32_t) * N);   // [N * N] (IN_LDS)
     __shared__ int red_i[2][NW];
     __shared__ unsigned long long red_k[NW];
-    const int p = threadIdx.x, lane = p & 63, wv = p >> 6;
+    const int tid = threadIdx.x, p = tid & (N - 1), part = tid >> LOGN, lane = tid & 63, wv = tid >> 6;
     const int64_t r = blockIdx.x;
     if (IN_LDS)
-        for (int e = p; e < N * N; e += N) m16[e] = (uint16_t)clampi(c[e], 0, 0xffff);
+        for (int e = tid; e < N * N; e += THREADS) m16[e] = (uint16_t)clampi(c[e], 0, 0xffff);
     int t = clampi(tours[r * N + p], 0, N - 1);
-    tl[p] = t;
+    if (part == 0) tl[p] = t;
     __syncthreads();
     if (IN_LDS) {
-        // a link costs the larger of its two directed entries: fold the two into both places once (thread p takes
-        // the pairs {p, p + j}, j = 1 .. N/2; every unordered pair exactly once), so that a link is one gather
-        for (int j = 1; j <= N / 2; ++j) {
+        // a link costs the larger of its two directed entries: fold the two into both places once (the threads of
+        // rank p take the pairs {p, p + j}, j = 1 .. N/2; every unordered pair exactly once), so that a link is one
+        // gather
+        for (int j = 1 + part; j <= N / 2; j += SPLIT) {
             const int b = (p + j) & (N - 1);
             if (j < N / 2 || p < N / 2) {
                 const uint16_t both = max(m16[p * N + b], m16[b * N + p]);
@@ -374,6 +380,9 @@ __global__ __launch_bounds__(1 << LOGN) void rdswap_block_kernel(const int32_t* 
         __syncthreads();
     }
     auto entry = [&](int a, int b) { return IN_LDS ? (int)m16[a * N + b] : (int)folded[a * N + b]; };
+    auto entry_at = [&](unsigned byte_offset) {                // row << (LOGN + 1) | column << 1
+        return (int)*(const uint16_t*)((IN_LDS ? (const char*)m16 : (const char*)folded) + byte_offset);
+    };
     int parity = 0;
     auto block_max = [&](int v) {                              // every thread gets the maximum; one barrier per call
         v = wave_max(v);
@@ -388,13 +397,14 @@ __global__ __launch_bounds__(1 << LOGN) void rdswap_block_kernel(const int32_t* 
 
     int applied = 0, cur = 0;
     for (;;) {
-        int pb[LOGN], x1v[LOGN], x2v[LOGN], zk[LOGN], round_cost[LOGN];
+        int pb2[LOGN], x1v[LOGN], x2v[LOGN], zk[LOGN], round_cost[LOGN];
         cur = 0;
 #pragma unroll
         for (int k = 0; k < LOGN; ++k) {
             const int bit = 1 << k;
-            pb[k] = tl[p ^ bit];
-            const int lv = entry(t, pb[k]);
+            const int pb = tl[p ^ bit];
+            pb2[k] = pb << 1;                                  // the round mate's node as a column byte offset
+            const int lv = entry(t, pb);
             const int li = ((p >> (k + 1)) << k) | (p & (bit - 1));
             const int key = (lv << LB) | li;
             const int k1 = block_max(key);
@@ -406,34 +416,53 @@ __global__ __launch_bounds__(1 << LOGN) void rdswap_block_kernel(const int32_t* 
             x1v[k] = a1 >> LB;
             x2v[k] = a2 >> LB;
             zk[k] = li ^ (a1 & (N / 2 - 1));                   // partner's link is that best link  <=>  li(x) == zk
-            round_cost[k] = k1 >> LB;
+            round_cost[k] = __builtin_amdgcn_readfirstlane(k1 >> LB);
             cur += round_cost[k];
         }
-        unsigned long long best = kNoMove;
-#pragma unroll 1
-        for (int j = 0; j < N / 2; ++j) {
-            const int x0 = j ? 2 * j : 1, x1 = j ? 2 * j + 1 : 1;
-            const int top = 31 - __builtin_clz(x0);
-            const bool second = (p >> top) & 1;
-            const int mm = second ? x1 : x0;
-            const int q = p ^ mm;
-            const int tq = tl[q];
+        // Steps grouped by the top bit of the rank difference: within a group a thread keeps its side (x0 = 2j or
+        // x1 = 2j + 1), so the side-dependent link-index test is prepared once per group.  The first step of a group
+        // has x0 = 2^top: there the threads on the x0 side swap with their mate of round `top`, which leaves that
+        // round as it is.  Per thread the move id grows with q, so the running minimum is kept over total << LOGN | q.
+        const int trow = t << (LOGN + 1);
+        int best32 = 0x7fffffff;
+        auto score = [&](int x0, bool second, int secbit, int mate_round) {
+            const int q = p ^ (x0 | secbit);
+            const int q4 = q << 2;
+            const int tqrow = *(const int32_t*)((const char*)tl + q4) << (LOGN + 1);
             int total = 0;
 #pragma unroll
             for (int k = 0; k < LOGN; ++k) {
                 const int bit = 1 << k;
-                const int qb = tl[q ^ bit];
-                const int link_p = entry(tq, pb[k]);
-                const int link_q = entry(t, qb);
-                const int lim0 = ((x0 >> (k + 1)) << k) | (x0 & (bit - 1));
-                const int lim1 = ((x1 >> (k + 1)) << k) | (x1 & (bit - 1));
-                const int lim = second ? lim1 : lim0;
-                const int others = (zk[k] == lim) ? x2v[k] : x1v[k];
-                const int stage = max(others, max(link_p, link_q));
-                total += (mm == bit) ? round_cost[k] : stage;
+                const int qb = *(const int32_t*)((const char*)tl + (q4 ^ (bit << 2)));     // node at rank q xor 2^k
+                const int link_p = entry_at((unsigned)(tqrow | pb2[k]));           // rank p now holds t[q]
+                const int link_q = entry_at((unsigned)(trow | (qb << 1)));         // rank q now holds t[p]
+                const int lim0 = ((x0 >> (k + 1)) << k) | (x0 & (bit - 1));        // wave-uniform
+                const int others = (zk[k] == lim0) ? x2v[k] : x1v[k];
+                int stage = max(others, max(link_p, link_q));
+                if (k == mate_round) stage = second ? stage : round_cost[k];
+                total += stage;
             }
+            best32 = min(best32, (total << LOGN) | q);
+        };
+        int side = 0;                                          // the side zk is prepared for
+#pragma unroll 1
+        for (int top = 0; top < LOGN; ++top) {
+            const bool second = top && ((p >> top) & 1);
+            const int secbit = second ? 1 : 0;
+#pragma unroll
+            for (int k = 1; k < LOGN; ++k) zk[k] ^= secbit ^ side;                 // x1's link index is x0's with bit 0 set
+            side = secbit;
+            const int x_first = 1 << top, x_end = 2 << top;
+            if (part == top % SPLIT) score(x_first, second, secbit, top);
+            if (top == 0) continue;                            // the difference 1 has no second step
+#pragma unroll kStepUnroll
+            for (int x0 = x_first + 2 + 2 * part; x0 < x_end; x0 += 2 * SPLIT) score(x0, second, secbit, -1);
+        }
+        unsigned long long best = kNoMove;
+        {
+            const int q = best32 & (N - 1), total = best32 >> LOGN;
             const int lo = min(p, q), hi = max(p, q);
-            best = min(best, ((unsigned long long)(unsigned)total << kIdBits) | (unsigned)(lo * N + hi));
+            best = ((unsigned long long)(unsigned)total << kIdBits) | (unsigned)(lo * N + hi);
         }
         best = wave_min_u64(best);
         if (lane == 0) red_k[wv] = best;
@@ -450,8 +479,8 @@ __global__ __launch_bounds__(1 << LOGN) void rdswap_block_kernel(const int32_t* 
         ++applied;
         __syncthreads();
     }
-    tours[r * N + p] = t;
-    if (p == 0) {
+    if (part == 0) tours[r * N + p] = t;
+    if (tid == 0) {
         costs[r] = (int64_t)cur;
         moves[r] = applied;
     }
@@ -467,14 +496,17 @@ static hipError_t rdswap_block_launch(const int32_t* c, uint16_t* folded, int re
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
+    // matrix in LDS: a workgroup of 1024 threads whatever N (16 wavefronts on the restart's compute unit); through
+    // L2 more wavefronts only queue up behind the same misses (N = 512: 0.57 s with two threads per rank, 0.47 s with one)
+    constexpr int kSplit = kInLds ? 1024 / N : 1;
     const size_t lds = (kInLds ? sizeof(uint16_t) * N * N : 0) + sizeof(int32_t) * N;
     if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void*)rdswap_block_kernel<LOGN, kInLds>,
+        hipError_t e = hipFuncSetAttribute((const void*)rdswap_block_kernel<LOGN, kInLds, kSplit>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((rdswap_block_kernel<LOGN, kInLds>), dim3(restarts), dim3(N), lds, s, c, folded, tours, costs,
-                       moves, flags);
+    hipLaunchKernelGGL((rdswap_block_kernel<LOGN, kInLds, kSplit>), dim3(restarts), dim3(N * kSplit), lds, s, c, folded,
+                       tours, costs, moves, flags);
     return hipGetLastError();
 }
 

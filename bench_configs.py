@@ -56,8 +56,11 @@ def main():
     def emit(d):
         print(json.dumps(d), flush=True)
 
-    def search_case(wid, n=None, restarts=None, name=None):
+    def search_case(wid, n=None, restarts=None, name=None, objective=None):
         w = WORKLOADS[wid]
+        if objective is not None:  # the workload's matrix and restarts under another objective
+            import dataclasses
+            w = dataclasses.replace(w, objective=objective, name=name)
         obj = cc.OBJECTIVES[w.objective]
         c_host = make_matrix(wid)
         if n is not None:         # the workload's hierarchy and value ranges at another size
@@ -229,6 +232,7 @@ def main():
         ("C1", lambda: batch_case("C1_n8_ring_sum_4096", 1, "ring", 0, 4096)),
         ("C2", lambda: search_case(2)),
         ("C3", lambda: search_case(3)),
+        ("D64", lambda: search_case(3, objective="sum_directed", name="D64_n64_sum_directed_1024")),
         ("C4", lambda: search_case(4)),
         ("C5rd", lambda: batch_case("C5_n1024_rd_65536", 5, "rd", 0, 65536)),
         ("C5", lambda: search_case(5)),

@@ -98,3 +98,58 @@ def test_local_search_replays_in_a_graph():
         torch.cuda.synchronize()
         for g, w in zip(outs, want):
             assert torch.equal(g, w), f"replay {replay}"
+
+
+def test_other_searches_replay_in_a_graph():
+    """The remaining search calls inside one captured step: pair swaps at N = 64 (wavefront kernel) and N = 256
+    (workgroup kernel with its 128 KiB of LDS, folded matrix, skipped general kernel), the directed ring sum at
+    N = 64 (seeded starts, matrix maximum, wavefront kernel, skipped general kernel), and both annealing calls."""
+    say("HIP graph: capture pair-swap searches, a directed-sum search and annealing, replay 3 times")
+    from gen import random_matrix
+    c64_host = make_matrix(2)
+    c3_host = make_matrix(3)
+    c256_host = random_matrix(256, 17, symmetric=False, lo=1, hi=9000)
+    c64, c3, c256 = (torch.from_numpy(x).cuda() for x in (c64_host, c3_host, c256_host))
+    dev = c64.device
+    b_swap64 = cc.SearchBuffers(64, 0, 40, dev)
+    b_swap256 = cc.SearchBuffers(256, 0, 2, dev)
+    b_dsum = cc.SearchBuffers(64, cc.CC_RING_SUM_DIRECTED, 40, dev)
+    b_sa = cc.SearchBuffers(64, 0, 8, dev)
+    b_sard = cc.SearchBuffers(64, 0, 8, dev)
+
+    def step():
+        cc.cc_rd_swap_search_ex(c64, 40, 21, buffers=b_swap64)
+        cc.cc_rd_swap_search_ex(c256, 2, 22, buffers=b_swap256)
+        cc.cc_2opt_search_ex(c3, cc.CC_RING_SUM_DIRECTED, 40, 23, buffers=b_dsum)
+        cc.cc_sa_search_ex(c64, 8, 3000, 300, 0, 24, buffers=b_sa)
+        cc.cc_sa_rd_search_ex(c64, 8, 2000, 300, 0, 25, buffers=b_sard)
+
+    step()
+    torch.cuda.synchronize()
+    bufs = (b_swap64, b_swap256, b_dsum, b_sa, b_sard)
+    outs = [t for b in bufs for t in (b.restart_costs, b.restart_tours, b.restart_moves, b.best_perm, b.best_cost,
+                                       b.best_restart)]
+    want = [t.clone() for t in outs]
+    refs = (oracle.rd_swap_search(c64_host, 40, 21), oracle.rd_swap_search(c256_host, 2, 22),
+            oracle.search(c3_host, oracle.SUM_DIRECTED, 40, 23), oracle.sa_search(c64_host, 8, 3000, 300, 0, 24),
+            oracle.sa_rd_search(c64_host, 8, 2000, 300, 0, 25))
+    for b, ref in zip(bufs, refs):
+        assert np.array_equal(b.restart_tours.cpu().numpy(), ref["tours"])
+        assert int(b.best_cost.item()) == ref["best_cost"]
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for replay in range(3):
+        for t in outs:
+            t.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for g, w in zip(outs, want):
+            assert torch.equal(g, w), f"replay {replay}"

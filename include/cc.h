@@ -108,6 +108,23 @@ int cc_rd_cost_batch(const int32_t* cost_matrix, int32_t N, const int32_t* perms
                      int64_t* out_costs, void* stream);
 
 /*
+ * cc_rd_cost_batch with caller-provided workspace: the same costs, faster for N >= 128.  A link of round k, the two
+ * ranks i and i xor 2^k, contributes max(c[x][y], c[y][x]) of its two nodes to the round's maximum; with every entry
+ * below 2^16 (decided on the device) the call first writes that larger value for every pair of nodes into the
+ * workspace as 16-bit entries, and then scores a link by one look-up instead of one per end.  Other matrices, and
+ * N < 128, are scored as by cc_rd_cost_batch.
+ *   workspace  device memory, 256-byte aligned, at least cc_rd_batch_workspace_bytes(N) bytes (else
+ *              CC_ERR_WORKSPACE); owned by the caller, contents undefined afterwards; calls that overlap in time
+ *              need workspaces of their own.
+ * Enqueues kernels only (no allocation, no memset).
+ */
+int cc_rd_cost_batch_ex(const int32_t* cost_matrix, int32_t N, const int32_t* perms, int64_t B, int64_t* out_costs,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace cc_rd_cost_batch_ex needs (0 on invalid arguments). Host-only computation. */
+size_t cc_rd_batch_workspace_bytes(int32_t N);
+
+/*
  * BCube cost model (Section 4.1, equation C_b; Section 2.2 for the peering pattern): ranks are
  * numbered in base `base`; in round i every rank exchanges with the base-1 ranks whose number differs
  * from its own in digit i only (the printed peer index j + k*base^i is taken modulo `base` within

@@ -21,7 +21,8 @@ CC_MAX_N = 1024
 CC_COST_MAX = (1 << 21) - 1
 
 # every symbol include/cc.h declares
-EXPORTS = ["cc_ring_cost_batch", "cc_ring_cost_batch_u8", "cc_ring_cost_batch_u16", "cc_rd_cost_batch", "cc_bcube_cost_batch",
+EXPORTS = ["cc_ring_cost_batch", "cc_ring_cost_batch_u8", "cc_ring_cost_batch_u16", "cc_rd_cost_batch",
+           "cc_rd_cost_batch_ex", "cc_rd_batch_workspace_bytes", "cc_bcube_cost_batch",
            "cc_bcube_cost_batch_weighted", "cc_dbt_cost_batch", "cc_2opt_search", "cc_2opt_search_ex",
            "cc_2opt_workspace_bytes", "cc_local_search", "cc_local_search_ex", "cc_best_of_restarts", "cc_rd_swap_search", "cc_rd_swap_search_ex",
            "cc_rd_swap_workspace_bytes", "cc_sa_search", "cc_sa_search_ex", "cc_sa_workspace_bytes", "cc_sa_rd_search",
@@ -58,6 +59,10 @@ def lib() -> ctypes.CDLL:
         L.cc_ring_cost_batch_u16.argtypes = [p, i32, i32, p, i64, p, p]
         L.cc_rd_cost_batch.restype = ctypes.c_int
         L.cc_rd_cost_batch.argtypes = [p, i32, p, i64, p, p]
+        L.cc_rd_cost_batch_ex.restype = ctypes.c_int
+        L.cc_rd_cost_batch_ex.argtypes = [p, i32, p, i64, p, p, sz, p]
+        L.cc_rd_batch_workspace_bytes.restype = sz
+        L.cc_rd_batch_workspace_bytes.argtypes = [i32]
         L.cc_bcube_cost_batch.restype = ctypes.c_int
         L.cc_bcube_cost_batch.argtypes = [p, i32, i32, p, i64, p, p]
         L.cc_bcube_cost_batch_weighted.restype = ctypes.c_int
@@ -179,16 +184,30 @@ def cc_ring_cost_batch_u16(cost_matrix: torch.Tensor, perms: torch.Tensor, objec
     return out
 
 
+def cc_rd_batch_workspace_bytes(n: int) -> int:
+    return int(lib().cc_rd_batch_workspace_bytes(n))
+
+
 def cc_rd_cost_batch(cost_matrix: torch.Tensor, perms: torch.Tensor, out: Optional[torch.Tensor] = None,
-                     stream=None) -> torch.Tensor:
+                     stream=None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Calls cc_rd_cost_batch_ex when N >= 128 (with `workspace`, a uint8 device tensor of at least
+    cc_rd_batch_workspace_bytes(N) bytes, or one allocated here), cc_rd_cost_batch otherwise."""
     n = _matrix(cost_matrix)
     if perms.dim() != 2 or perms.shape[1] != n:
         raise ValueError("perms must be [B, N]")
     b = int(perms.shape[0])
     if out is None:
         out = torch.empty(b, dtype=torch.int64, device=cost_matrix.device)
-    _check(lib().cc_rd_cost_batch(_dev(cost_matrix, torch.int32, "cost_matrix"), n, _dev(perms, torch.int32, "perms"),
-                                  b, _dev(out, torch.int64, "out"), _stream(stream)), "cc_rd_cost_batch")
+    if n < 128 and workspace is None:
+        _check(lib().cc_rd_cost_batch(_dev(cost_matrix, torch.int32, "cost_matrix"), n,
+                                      _dev(perms, torch.int32, "perms"), b, _dev(out, torch.int64, "out"),
+                                      _stream(stream)), "cc_rd_cost_batch")
+        return out
+    if workspace is None:
+        workspace = torch.empty(cc_rd_batch_workspace_bytes(n), dtype=torch.uint8, device=cost_matrix.device)
+    _check(lib().cc_rd_cost_batch_ex(_dev(cost_matrix, torch.int32, "cost_matrix"), n, _dev(perms, torch.int32, "perms"),
+                                     b, _dev(out, torch.int64, "out"), _dev(workspace, torch.uint8, "workspace"),
+                                     workspace.numel(), _stream(stream)), "cc_rd_cost_batch_ex")
     return out
 
 

@@ -97,6 +97,27 @@ int cc_rd_cost_batch(const int32_t* cost_matrix, int32_t N, const int32_t* perms
     return CC_OK;
 }
 
+size_t cc_rd_batch_workspace_bytes(int32_t N) {
+    if (N < 2 || N > CC_MAX_N || !is_pow2(N)) return 0;
+    return 256 + align256(sizeof(uint16_t) * (size_t)N * (size_t)N);        // flags, folded 16-bit matrix
+}
+
+int cc_rd_cost_batch_ex(const int32_t* cost_matrix, int32_t N, const int32_t* perms, int64_t B, int64_t* out_costs,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+    if (int rc = check_matrix_args(cost_matrix, N)) return rc;
+    if (!is_pow2(N)) return CC_ERR_UNSUPPORTED_N;
+    if (B < 0) return CC_ERR_INVALID_ARG;
+    if (!workspace || workspace_bytes < cc_rd_batch_workspace_bytes(N) || ((uintptr_t)workspace & 255u))
+        return CC_ERR_WORKSPACE;
+    if (B == 0) return CC_OK;
+    if (!perms || !out_costs) return CC_ERR_INVALID_ARG;
+    if (((uintptr_t)perms & 3u) || ((uintptr_t)out_costs & 7u) || ((uintptr_t)cost_matrix & 3u)) return CC_ERR_INVALID_ARG;
+    char* base = (char*)workspace;
+    CC_HIP(cc::launch_rd_cost_batch(cost_matrix, N, nullptr, perms, B, out_costs, (hipStream_t)stream, (int32_t*)base,
+                                    (uint16_t*)(base + 256)));
+    return CC_OK;
+}
+
 static int bcube_batch(const int32_t* cost_matrix, int32_t N, int32_t base, const int32_t* weights, bool weighted,
                        const int32_t* perms, int64_t B, int64_t* out_costs, void* stream) {
     if (int rc = check_matrix_args(cost_matrix, N)) return rc;
@@ -398,6 +419,6 @@ const char* cc_status_string(int status) {
 
 int cc_last_hip_error(void) { return g_last_hip_error; }
 
-int cc_version(void) { return 500; }
+int cc_version(void) { return 501; }
 
 }  // extern "C"

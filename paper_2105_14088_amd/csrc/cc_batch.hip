@@ -269,7 +269,10 @@ template <int NM, bool LDS_MATRIX>
 __global__ __launch_bounds__(256) void rd_batch_kernel(const int32_t* __restrict__ c, int N,
                                                        const int32_t* __restrict__ weights,
                                                        const int32_t* __restrict__ perms, int64_t B,
-                                                       int64_t* __restrict__ out) {
+                                                       int64_t* __restrict__ out,
+                                                       const int32_t* __restrict__ skip_if_small) {
+    // enqueued beside the folded-matrix kernel: flags[0] = max(c) decides which of the two does the work
+    if (skip_if_small && skip_if_small[0] < (1 << 16)) return;
     extern __shared__ int32_t sm[];
     int32_t* order = sm + (threadIdx.x >> 6) * N;   // this wave's slice
     const int32_t* mat = c;
@@ -413,31 +416,106 @@ static hipError_t rd_small_launch(const int32_t* c, const int32_t* weights, cons
 
 template <int NM>
 static hipError_t rd_launch(const int32_t* c, int N, const int32_t* weights, const int32_t* perms, int64_t B,
-                            int64_t* out, hipStream_t s) {
+                            int64_t* out, const int32_t* skip_if_small, hipStream_t s) {
     const int grid = batch_grid(4, B);
     if (N <= 64) {
         const size_t lds = sizeof(int32_t) * (size_t)(4 * N + N * N);
-        hipLaunchKernelGGL((rd_batch_kernel<NM, true>), dim3(grid), dim3(256), lds, s, c, N, weights, perms, B, out);
+        hipLaunchKernelGGL((rd_batch_kernel<NM, true>), dim3(grid), dim3(256), lds, s, c, N, weights, perms, B, out,
+                           skip_if_small);
     } else {
         const size_t lds = sizeof(int32_t) * (size_t)(4 * N);
-        hipLaunchKernelGGL((rd_batch_kernel<NM, false>), dim3(grid), dim3(256), lds, s, c, N, weights, perms, B, out);
+        hipLaunchKernelGGL((rd_batch_kernel<NM, false>), dim3(grid), dim3(256), lds, s, c, N, weights, perms, B, out,
+                           skip_if_small);
     }
     return hipGetLastError();
 }
 
+// N = 128 .. 1024 on a folded 16-bit copy of the matrix, folded[x][y] = max(c[x][y], c[y][x]) (fold_to_u16_kernel): a
+// link, the two ranks i and i xor 2^k, is one look-up by one lane instead of one per end, so a round is N / 2
+// scattered L2 requests instead of N - and that request rate is what bounds this kernel.  One wave per order, the
+// order parked in LDS; every lane first takes the maximum over its links of every round (all gathers independent),
+// then the rounds' maxima are reduced over the wave three at a time.  Returns at once when the matrix has an entry
+// from 2^16 up (flags[0] = max(c)): the general kernel, enqueued beside it, then does the work.
+template <int LOGN>
+__global__ __launch_bounds__(256) void rd_batch_folded_kernel(const uint16_t* __restrict__ folded,
+                                                              const int32_t* __restrict__ weights,
+                                                              const int32_t* __restrict__ perms, int64_t B,
+                                                              int64_t* __restrict__ out,
+                                                              const int32_t* __restrict__ flags) {
+    constexpr int N = 1 << LOGN, NM = N / 64, LM = NM / 2;      // ranks and links per lane
+    if (flags[0] >= (1 << 16)) return;
+    __shared__ int32_t order_all[4][N];
+    int32_t* order = order_all[threadIdx.x >> 6];
+    const int lane = lane_id();
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    long long w[LOGN];
+#pragma unroll
+    for (int k = 0; k < LOGN; ++k) w[k] = weights ? (long long)clampi(weights[k], 0, kMaxRoundWeight) : 1ll;
+    for (int64_t b = wave; b < B; b += nwaves) {
+        const int32_t* pi = perms + b * N;
+#pragma unroll
+        for (int k = 0; k < NM; ++k) order[lane + 64 * k] = clampi(pi[lane + 64 * k], 0, N - 1);
+        __builtin_amdgcn_wave_barrier();
+        int worst[LOGN + 2];
+        worst[LOGN] = worst[LOGN + 1] = 0;
+#pragma unroll
+        for (int k = 0; k < LOGN; ++k) {
+            const int bit = 1 << k;
+            int v = 0;
+#pragma unroll
+            for (int u = 0; u < LM; ++u) {
+                const int i = lane + 64 * u;                                      // link index
+                const int j = ((i >> k) << (k + 1)) | (i & (bit - 1));            // its lower rank
+                const unsigned at = ((unsigned)order[j] << (LOGN + 1)) | ((unsigned)order[j | bit] << 1);
+                v = max(v, (int)*(const uint16_t*)((const char*)folded + at));
+            }
+            worst[k] = v;
+        }
+        __builtin_amdgcn_wave_barrier();   // all look-ups done before the slice is overwritten
+#pragma unroll
+        for (int k = 0; k < LOGN; k += 3) wave_max3(worst[k], worst[k + 1], worst[k + 2]);
+        long long total = 0;
+#pragma unroll
+        for (int k = 0; k < LOGN; ++k) total += w[k] * worst[k];
+        if (lane == 0) out[b] = total;
+    }
+}
+
+template <int LOGN>
+static hipError_t rd_folded_launch(const uint16_t* folded, const int32_t* weights, const int32_t* perms, int64_t B,
+                                   int64_t* out, const int32_t* flags, hipStream_t s) {
+    hipLaunchKernelGGL(rd_batch_folded_kernel<LOGN>, dim3(batch_grid(4, B)), dim3(256), 0, s, folded, weights, perms, B,
+                       out, flags);
+    return hipGetLastError();
+}
+
 hipError_t launch_rd_cost_batch(const int32_t* c, int N, const int32_t* weights, const int32_t* perms, int64_t B,
-                                int64_t* out, hipStream_t s) {
+                                int64_t* out, hipStream_t s, int32_t* flags, uint16_t* folded) {
     if (B == 0) return hipSuccess;
     if (N == 64) {
         hipLaunchKernelGGL(rd_batch_links64_kernel, dim3(batch_grid(4, B)), dim3(256), 0, s, c, weights, perms, B, out);
         return hipGetLastError();
     }
     if (N == 32) return rd_small_launch<5>(c, weights, perms, B, out, s);
-    if (N <= 64) return rd_launch<1>(c, N, weights, perms, B, out, s);
-    if (N == 128) return rd_launch<2>(c, N, weights, perms, B, out, s);
-    if (N == 256) return rd_launch<4>(c, N, weights, perms, B, out, s);
-    if (N == 512) return rd_launch<8>(c, N, weights, perms, B, out, s);
-    return rd_launch<16>(c, N, weights, perms, B, out, s);
+    if (N <= 64) return rd_launch<1>(c, N, weights, perms, B, out, nullptr, s);
+    const int32_t* skip = nullptr;
+    if (flags && folded) {
+        // both kernels are enqueued; the matrix maximum, computed on the device, decides which of them works
+        hipError_t e = launch_matrix_max(c, N, flags, s);
+        if (e == hipSuccess) e = launch_fold_to_u16(c, N, folded, flags, s);
+        if (e == hipSuccess)
+            e = N == 128   ? rd_folded_launch<7>(folded, weights, perms, B, out, flags, s)
+                : N == 256 ? rd_folded_launch<8>(folded, weights, perms, B, out, flags, s)
+                : N == 512 ? rd_folded_launch<9>(folded, weights, perms, B, out, flags, s)
+                           : rd_folded_launch<10>(folded, weights, perms, B, out, flags, s);
+        if (e != hipSuccess) return e;
+        skip = flags;
+    }
+    if (N == 128) return rd_launch<2>(c, N, weights, perms, B, out, skip, s);
+    if (N == 256) return rd_launch<4>(c, N, weights, perms, B, out, skip, s);
+    if (N == 512) return rd_launch<8>(c, N, weights, perms, B, out, skip, s);
+    return rd_launch<16>(c, N, weights, perms, B, out, skip, s);
 }
 
 // ------------------------------------------------------------------------------- BCube cost model

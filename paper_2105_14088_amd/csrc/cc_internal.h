@@ -14,7 +14,10 @@ hipError_t launch_ring_cost_batch_u16(const int32_t* c, int N, bool is_max, cons
                                       int64_t* out, hipStream_t s);
 // weights: device int32 [rounds] or nullptr (every round weighs 1)
 hipError_t launch_rd_cost_batch(const int32_t* c, int N, const int32_t* weights, const int32_t* perms, int64_t B,
-                                int64_t* out, hipStream_t s);
+                                int64_t* out, hipStream_t s, int32_t* flags = nullptr, uint16_t* folded = nullptr);
+// folded[x][y] = max(c[x][y], c[y][x]) as 16-bit entries, N * N of them; does nothing when flags[0] (the matrix
+// maximum, launch_matrix_max) is 2^16 or more.
+hipError_t launch_fold_to_u16(const int32_t* c, int N, uint16_t* folded, const int32_t* flags, hipStream_t s);
 hipError_t launch_bcube_cost_batch(const int32_t* c, int N, int base, const int32_t* weights, const int32_t* perms,
                                    int64_t B, int64_t* out, hipStream_t s);
 hipError_t launch_dbt_cost_batch(const int32_t* c, int N, const int32_t* perms, int64_t B, int64_t* out,

@@ -492,8 +492,7 @@ static hipError_t rdswap_block_launch(const int32_t* c, uint16_t* folded, int re
     constexpr int N = 1 << LOGN;
     constexpr bool kInLds = LOGN <= 8;
     if (!kInLds) {
-        hipLaunchKernelGGL(fold_to_u16_kernel, dim3(512), dim3(256), 0, s, c, N, folded, flags);
-        hipError_t e = hipGetLastError();
+        hipError_t e = launch_fold_to_u16(c, N, folded, flags, s);
         if (e != hipSuccess) return e;
     }
     // matrix in LDS: a workgroup of 1024 threads whatever N (16 wavefronts on the restart's compute unit); through
@@ -511,6 +510,11 @@ static hipError_t rdswap_block_launch(const int32_t* c, uint16_t* folded, int re
 }
 
 }  // namespace
+
+hipError_t launch_fold_to_u16(const int32_t* c, int N, uint16_t* folded, const int32_t* flags, hipStream_t s) {
+    hipLaunchKernelGGL(fold_to_u16_kernel, dim3(512), dim3(256), 0, s, c, N, folded, flags);
+    return hipGetLastError();
+}
 
 hipError_t launch_rdswap(const int32_t* c, int N, int restarts, uint64_t seed, bool tours_hold_init, int32_t* tours,
                          int64_t* costs, int32_t* moves, int32_t* flags, uint16_t* mat16, hipStream_t s) {

@@ -70,6 +70,17 @@ def test_argument_errors_are_returned_before_any_launch():
     assert L.cc_rd_cost_batch(fake, 48, fake, 1, fake, null) == UNSUPPORTED      # not a power of two
     assert L.cc_rd_cost_batch(fake, 64, fake, -5, fake, null) == INVALID
     assert L.cc_rd_cost_batch(fake, 64, null, 0, null, null) == 0
+    ws256 = ctypes.c_void_p(0x10000)
+    need = L.cc_rd_batch_workspace_bytes(1024)
+    assert need >= 2 * 1024 * 1024 and need % 256 == 0
+    assert L.cc_rd_batch_workspace_bytes(48) == 0 and L.cc_rd_batch_workspace_bytes(2048) == 0
+    assert L.cc_rd_cost_batch_ex(fake, 48, fake, 1, fake, ws256, need, null) == UNSUPPORTED
+    assert L.cc_rd_cost_batch_ex(fake, 1024, fake, 1, fake, null, need, null) == WORKSPACE
+    assert L.cc_rd_cost_batch_ex(fake, 1024, fake, 1, fake, ws256, need - 1, null) == WORKSPACE
+    assert L.cc_rd_cost_batch_ex(fake, 1024, fake, 1, fake, ctypes.c_void_p(0x10010), need, null) == WORKSPACE   # misaligned
+    assert L.cc_rd_cost_batch_ex(fake, 1024, fake, -1, fake, ws256, need, null) == INVALID
+    assert L.cc_rd_cost_batch_ex(fake, 1024, null, 1, fake, ws256, need, null) == INVALID
+    assert L.cc_rd_cost_batch_ex(fake, 1024, null, 0, null, ws256, need, null) == 0
     assert L.cc_bcube_cost_batch(fake, 32, 4, fake, 1, fake, null) == UNSUPPORTED   # not a power of the base
     assert L.cc_bcube_cost_batch(fake, 64, 1, fake, 1, fake, null) == INVALID
     assert L.cc_bcube_cost_batch(fake, 64, 4, fake, -1, fake, null) == INVALID

@@ -150,6 +150,31 @@ def test_rd_batch(n):
         assert np.array_equal(gpu_rd(c, perms), oracle.rd_cost_batch(c, perms))
 
 
+@pytest.mark.parametrize("n", [128, 256, 512, 1024])
+def test_rd_batch_with_workspace_folded_copy_and_its_fallback(n):
+    """cc_rd_cost_batch_ex: symmetric and asymmetric matrices, the largest entry one below 2^16 (folded 16-bit copy, one
+    look-up per link) and at 2^16 (the look-up per rank of cc_rd_cost_batch), a caller's workspace used twice, and
+    the plain call on the same inputs."""
+    ws = torch.empty(cc.cc_rd_batch_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    for top, symmetric in (((1 << 16) - 1, False), ((1 << 16) - 1, True), (1 << 16, False), (40, True)):
+        say(f"rd batch with workspace N={n} largest entry {top} symmetric={symmetric}")
+        c = random_matrix(n, 600 + n + top % 7, symmetric=symmetric, lo=max(0, top - 30000), hi=top)
+        c[1, 2] = top
+        if symmetric:
+            c[2, 1] = top
+        perms = random_perms(n, 131, seed=n + top % 11)
+        want = oracle.rd_cost_batch(c, perms)
+        c_dev, perms_dev = dev(c), dev(perms)
+        got = cc.cc_rd_cost_batch(c_dev, perms_dev, workspace=ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy(), want)
+        plain = torch.empty(131, dtype=torch.int64, device="cuda")
+        rc = cc.lib().cc_rd_cost_batch(c_dev.data_ptr(), n, perms_dev.data_ptr(), 131, plain.data_ptr(),
+                                       torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert rc == 0 and np.array_equal(plain.cpu().numpy(), want)
+
+
 @pytest.mark.parametrize("n,base", [(4, 4), (16, 4), (64, 4), (256, 4), (1024, 4), (9, 3), (27, 3), (243, 3), (729, 3),
                                     (64, 8), (512, 8), (25, 5), (625, 5), (32, 32), (1024, 32), (64, 2), (7, 7)])
 def test_bcube_batch(n, base):

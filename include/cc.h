@@ -121,7 +121,8 @@ int cc_rd_cost_batch(const int32_t* cost_matrix, int32_t N, const int32_t* perms
 int cc_rd_cost_batch_ex(const int32_t* cost_matrix, int32_t N, const int32_t* perms, int64_t B, int64_t* out_costs,
                         void* workspace, size_t workspace_bytes, void* stream);
 
-/* Bytes of workspace cc_rd_cost_batch_ex needs (0 on invalid arguments). Host-only computation. */
+/* Bytes of workspace cc_rd_cost_batch_ex and cc_bcube_cost_batch_ex need for a matrix of N x N, 2 <= N <= CC_MAX_N
+ * (0 for any other N): 256 + 2 N^2, rounded up to a multiple of 256. Host-only computation. */
 size_t cc_rd_batch_workspace_bytes(int32_t N);
 
 /*
@@ -144,6 +145,18 @@ int cc_bcube_cost_batch(const int32_t* cost_matrix, int32_t N, int32_t base, con
  */
 int cc_bcube_cost_batch_weighted(const int32_t* cost_matrix, int32_t N, int32_t base, const int32_t* round_weights,
                                  const int32_t* perms, int64_t B, int64_t* out_costs, void* stream);
+
+/*
+ * cc_bcube_cost_batch / cc_bcube_cost_batch_weighted with caller-provided workspace: the same costs.  round_weights
+ * may be NULL (every round weighs 1).  For base 2 with N >= 128, and for base 4 with N = 256 or 1024, the call
+ * scores on a folded 16-bit copy of the matrix as cc_rd_cost_batch_ex does (an exchange between two ranks costs the
+ * larger of the two directed entries, so each pair of a round needs one look-up); other cases are scored as by
+ * cc_bcube_cost_batch.  workspace: as for cc_rd_cost_batch_ex, at least cc_rd_batch_workspace_bytes(N) bytes.
+ * Enqueues kernels only.
+ */
+int cc_bcube_cost_batch_ex(const int32_t* cost_matrix, int32_t N, int32_t base, const int32_t* round_weights,
+                           const int32_t* perms, int64_t B, int64_t* out_costs, void* workspace, size_t workspace_bytes,
+                           void* stream);
 
 /*
  * Double-binary-tree cost model (Section 4.1, equation C_dbt and its recursion T(i, j)): the ranks i .. j

@@ -22,7 +22,7 @@ CC_COST_MAX = (1 << 21) - 1
 
 # every symbol include/cc.h declares
 EXPORTS = ["cc_ring_cost_batch", "cc_ring_cost_batch_u8", "cc_ring_cost_batch_u16", "cc_rd_cost_batch",
-           "cc_rd_cost_batch_ex", "cc_rd_batch_workspace_bytes", "cc_bcube_cost_batch",
+           "cc_rd_cost_batch_ex", "cc_rd_batch_workspace_bytes", "cc_bcube_cost_batch", "cc_bcube_cost_batch_ex",
            "cc_bcube_cost_batch_weighted", "cc_dbt_cost_batch", "cc_2opt_search", "cc_2opt_search_ex",
            "cc_2opt_workspace_bytes", "cc_local_search", "cc_local_search_ex", "cc_best_of_restarts", "cc_rd_swap_search", "cc_rd_swap_search_ex",
            "cc_rd_swap_workspace_bytes", "cc_sa_search", "cc_sa_search_ex", "cc_sa_workspace_bytes", "cc_sa_rd_search",
@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.cc_rd_cost_batch_ex.argtypes = [p, i32, p, i64, p, p, sz, p]
         L.cc_rd_batch_workspace_bytes.restype = sz
         L.cc_rd_batch_workspace_bytes.argtypes = [i32]
+        L.cc_bcube_cost_batch_ex.restype = ctypes.c_int
+        L.cc_bcube_cost_batch_ex.argtypes = [p, i32, i32, p, p, i64, p, p, sz, p]
         L.cc_bcube_cost_batch.restype = ctypes.c_int
         L.cc_bcube_cost_batch.argtypes = [p, i32, i32, p, i64, p, p]
         L.cc_bcube_cost_batch_weighted.restype = ctypes.c_int
@@ -211,39 +213,47 @@ def cc_rd_cost_batch(cost_matrix: torch.Tensor, perms: torch.Tensor, out: Option
     return out
 
 
-def cc_bcube_cost_batch(cost_matrix: torch.Tensor, base: int, perms: torch.Tensor, out: Optional[torch.Tensor] = None,
-                        stream=None) -> torch.Tensor:
+def _bcube(cost_matrix, base, round_weights, perms, out, stream, workspace, where):
     n = _matrix(cost_matrix)
     if perms.dim() != 2 or perms.shape[1] != n:
         raise ValueError("perms must be [B, N]")
     b = int(perms.shape[0])
     if out is None:
         out = torch.empty(b, dtype=torch.int64, device=cost_matrix.device)
-    _check(lib().cc_bcube_cost_batch(_dev(cost_matrix, torch.int32, "cost_matrix"), n, base,
-                                     _dev(perms, torch.int32, "perms"), b, _dev(out, torch.int64, "out"),
-                                     _stream(stream)), "cc_bcube_cost_batch")
+    folded_form = (base == 2 and n >= 128) or (base == 4 and n in (256, 1024))      # the sizes the workspace serves
+    if workspace is None and folded_form:
+        workspace = torch.empty(cc_rd_batch_workspace_bytes(n), dtype=torch.uint8, device=cost_matrix.device)
+    c, pm, o = _dev(cost_matrix, torch.int32, "cost_matrix"), _dev(perms, torch.int32, "perms"), _dev(out, torch.int64, "out")
+    w = _dev(round_weights, torch.int32, "round_weights")
+    if workspace is not None:
+        _check(lib().cc_bcube_cost_batch_ex(c, n, base, w, pm, b, o, _dev(workspace, torch.uint8, "workspace"),
+                                            workspace.numel(), _stream(stream)), "cc_bcube_cost_batch_ex")
+    elif round_weights is None:
+        _check(lib().cc_bcube_cost_batch(c, n, base, pm, b, o, _stream(stream)), where)
+    else:
+        _check(lib().cc_bcube_cost_batch_weighted(c, n, base, w, pm, b, o, _stream(stream)), where)
     return out
 
 
+def cc_bcube_cost_batch(cost_matrix: torch.Tensor, base: int, perms: torch.Tensor, out: Optional[torch.Tensor] = None,
+                        stream=None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Calls cc_bcube_cost_batch_ex where its workspace pays (base 2 from N = 128, base 4 at N = 256 and 1024; with
+    `workspace`, a uint8 device tensor of cc_rd_batch_workspace_bytes(N) bytes, or one allocated here) and
+    cc_bcube_cost_batch otherwise."""
+    return _bcube(cost_matrix, base, None, perms, out, stream, workspace, "cc_bcube_cost_batch")
+
+
 def cc_bcube_cost_batch_weighted(cost_matrix: torch.Tensor, base: int, round_weights: torch.Tensor, perms: torch.Tensor,
-                                 out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                                 out: Optional[torch.Tensor] = None, stream=None,
+                                 workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     n = _matrix(cost_matrix)
-    if perms.dim() != 2 or perms.shape[1] != n:
-        raise ValueError("perms must be [B, N]")
     rounds, power = 0, 1
     while power < n:
         power *= base
         rounds += 1
     if round_weights.dim() != 1 or round_weights.shape[0] != rounds:
         raise ValueError("round_weights must be [log_base N]")
-    b = int(perms.shape[0])
-    if out is None:
-        out = torch.empty(b, dtype=torch.int64, device=cost_matrix.device)
-    _check(lib().cc_bcube_cost_batch_weighted(_dev(cost_matrix, torch.int32, "cost_matrix"), n, base,
-                                              _dev(round_weights, torch.int32, "round_weights"),
-                                              _dev(perms, torch.int32, "perms"), b, _dev(out, torch.int64, "out"),
-                                              _stream(stream)), "cc_bcube_cost_batch_weighted")
-    return out
+    return _bcube(cost_matrix, base, round_weights, perms, out, stream, workspace, "cc_bcube_cost_batch_weighted")
 
 
 def cc_dbt_cost_batch(cost_matrix: torch.Tensor, perms: torch.Tensor, out: Optional[torch.Tensor] = None,

@@ -98,7 +98,7 @@ int cc_rd_cost_batch(const int32_t* cost_matrix, int32_t N, const int32_t* perms
 }
 
 size_t cc_rd_batch_workspace_bytes(int32_t N) {
-    if (N < 2 || N > CC_MAX_N || !is_pow2(N)) return 0;
+    if (N < 2 || N > CC_MAX_N) return 0;
     return 256 + align256(sizeof(uint16_t) * (size_t)N * (size_t)N);        // flags, folded 16-bit matrix
 }
 
@@ -119,7 +119,7 @@ int cc_rd_cost_batch_ex(const int32_t* cost_matrix, int32_t N, const int32_t* pe
 }
 
 static int bcube_batch(const int32_t* cost_matrix, int32_t N, int32_t base, const int32_t* weights, bool weighted,
-                       const int32_t* perms, int64_t B, int64_t* out_costs, void* stream) {
+                       const int32_t* perms, int64_t B, int64_t* out_costs, void* stream, void* workspace = nullptr) {
     if (int rc = check_matrix_args(cost_matrix, N)) return rc;
     if (base < 2) return CC_ERR_INVALID_ARG;
     int64_t power = 1;
@@ -129,7 +129,9 @@ static int bcube_batch(const int32_t* cost_matrix, int32_t N, int32_t base, cons
     if (B == 0) return CC_OK;
     if (!perms || !out_costs) return CC_ERR_INVALID_ARG;
     if (((uintptr_t)perms & 3u) || ((uintptr_t)out_costs & 7u) || ((uintptr_t)cost_matrix & 3u)) return CC_ERR_INVALID_ARG;
-    CC_HIP(cc::launch_bcube_cost_batch(cost_matrix, N, base, weights, perms, B, out_costs, (hipStream_t)stream));
+    char* ws = (char*)workspace;
+    CC_HIP(cc::launch_bcube_cost_batch(cost_matrix, N, base, weights, perms, B, out_costs, (hipStream_t)stream,
+                                       (int32_t*)ws, ws ? (uint16_t*)(ws + 256) : nullptr));
     return CC_OK;
 }
 
@@ -141,6 +143,16 @@ int cc_bcube_cost_batch(const int32_t* cost_matrix, int32_t N, int32_t base, con
 int cc_bcube_cost_batch_weighted(const int32_t* cost_matrix, int32_t N, int32_t base, const int32_t* round_weights,
                                  const int32_t* perms, int64_t B, int64_t* out_costs, void* stream) {
     return bcube_batch(cost_matrix, N, base, round_weights, true, perms, B, out_costs, stream);
+}
+
+int cc_bcube_cost_batch_ex(const int32_t* cost_matrix, int32_t N, int32_t base, const int32_t* round_weights,
+                           const int32_t* perms, int64_t B, int64_t* out_costs, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+    if (int rc = check_matrix_args(cost_matrix, N)) return rc;
+    if (!workspace || workspace_bytes < cc_rd_batch_workspace_bytes(N) || ((uintptr_t)workspace & 255u))
+        return CC_ERR_WORKSPACE;
+    if (round_weights && ((uintptr_t)round_weights & 3u)) return CC_ERR_INVALID_ARG;
+    return bcube_batch(cost_matrix, N, base, round_weights, false, perms, B, out_costs, stream, workspace);
 }
 
 int cc_dbt_cost_batch(const int32_t* cost_matrix, int32_t N, const int32_t* perms, int64_t B, int64_t* out_costs,

@@ -526,7 +526,10 @@ template <int NM, bool LDS_MATRIX>
 __global__ __launch_bounds__(256) void bcube_batch_kernel(const int32_t* __restrict__ c, int N, int base,
                                                           const int32_t* __restrict__ weights,
                                                           const int32_t* __restrict__ perms, int64_t B,
-                                                          int64_t* __restrict__ out) {
+                                                          int64_t* __restrict__ out,
+                                                          const int32_t* __restrict__ skip_if_small) {
+    // enqueued beside the folded-matrix kernel: flags[0] = max(c) decides which of the two does the work
+    if (skip_if_small && skip_if_small[0] < (1 << 16)) return;
     extern __shared__ int32_t sm[];
     int32_t* order = sm + (threadIdx.x >> 6) * N;
     const int32_t* mat = c;
@@ -576,16 +579,16 @@ __global__ __launch_bounds__(256) void bcube_batch_kernel(const int32_t* __restr
 
 template <int NM>
 static hipError_t bcube_launch(const int32_t* c, int N, int base, const int32_t* weights, const int32_t* perms,
-                               int64_t B, int64_t* out, hipStream_t s) {
+                               int64_t B, int64_t* out, const int32_t* skip_if_small, hipStream_t s) {
     const int grid = batch_grid(4, B);
     if (N <= 64) {
         const size_t lds = sizeof(int32_t) * (size_t)(4 * N + N * N);
         hipLaunchKernelGGL((bcube_batch_kernel<NM, true>), dim3(grid), dim3(256), lds, s, c, N, base, weights, perms, B,
-                           out);
+                           out, skip_if_small);
     } else {
         const size_t lds = sizeof(int32_t) * (size_t)(4 * N);
         hipLaunchKernelGGL((bcube_batch_kernel<NM, false>), dim3(grid), dim3(256), lds, s, c, N, base, weights, perms, B,
-                           out);
+                           out, skip_if_small);
     }
     return hipGetLastError();
 }
@@ -632,19 +635,90 @@ __global__ __launch_bounds__(256) void bcube_batch_b4n64_kernel(const int32_t* _
     }
 }
 
+// Base 4 at N = 256, 1024 on the folded 16-bit copy of the matrix (as rd_batch_folded_kernel): the four ranks that
+// differ in one base-4 digit exchange pairwise, and both directions of a pair are one folded entry, so a round is the
+// maximum over N / 4 groups of six entries - 1.5 N look-ups instead of 3 N.  A lane takes whole groups: four order
+// look-ups in LDS, six gathers.  Returns at once when flags[0] = max(c) is 2^16 or more.
+template <int ROUNDS>
+__global__ __launch_bounds__(256) void bcube_b4_folded_kernel(const uint16_t* __restrict__ folded,
+                                                              const int32_t* __restrict__ weights,
+                                                              const int32_t* __restrict__ perms, int64_t B,
+                                                              int64_t* __restrict__ out,
+                                                              const int32_t* __restrict__ flags) {
+    constexpr int LOGN = 2 * ROUNDS, N = 1 << LOGN, NM = N / 64, GM = N / 256;      // ranks and groups per lane
+    if (flags[0] >= (1 << 16)) return;
+    __shared__ int32_t order_all[4][N];
+    int32_t* order = order_all[threadIdx.x >> 6];
+    const int lane = lane_id();
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    long long w[ROUNDS];
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) w[r] = weights ? (long long)clampi(weights[r], 0, kMaxRoundWeight) : 1ll;
+    for (int64_t b = wave; b < B; b += nwaves) {
+        const int32_t* pi = perms + b * N;
+#pragma unroll
+        for (int k = 0; k < NM; ++k) order[lane + 64 * k] = clampi(pi[lane + 64 * k], 0, N - 1);
+        __builtin_amdgcn_wave_barrier();
+        int worst[ROUNDS + 2];
+        worst[ROUNDS] = worst[ROUNDS + 1] = 0;
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) {
+            int v = 0;
+#pragma unroll
+            for (int u = 0; u < GM; ++u) {
+                const int g = lane + 64 * u;                                       // group: the rank without digit r
+                const int p0 = ((g >> (2 * r)) << (2 * r + 2)) | (g & ((1 << (2 * r)) - 1));
+                unsigned node[4];
+#pragma unroll
+                for (int d = 0; d < 4; ++d) node[d] = (unsigned)order[p0 | (d << (2 * r))];
+#pragma unroll
+                for (int d = 0; d < 3; ++d)
+#pragma unroll
+                    for (int e = d + 1; e < 4; ++e)
+                        v = max(v, (int)*(const uint16_t*)((const char*)folded +
+                                                            ((node[d] << (LOGN + 1)) | (node[e] << 1))));
+            }
+            worst[r] = v;
+        }
+        __builtin_amdgcn_wave_barrier();   // all look-ups done before the slice is overwritten
+#pragma unroll
+        for (int r = 0; r < ROUNDS; r += 3) wave_max3(worst[r], worst[r + 1], worst[r + 2]);
+        long long total = 0;
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) total += w[r] * worst[r];
+        if (lane == 0) out[b] = total;
+    }
+}
+
 hipError_t launch_bcube_cost_batch(const int32_t* c, int N, int base, const int32_t* weights, const int32_t* perms,
-                                   int64_t B, int64_t* out, hipStream_t s) {
+                                   int64_t B, int64_t* out, hipStream_t s, int32_t* flags, uint16_t* folded) {
     if (B == 0) return hipSuccess;
-    if (base == 2) return launch_rd_cost_batch(c, N, weights, perms, B, out, s);
+    if (base == 2) return launch_rd_cost_batch(c, N, weights, perms, B, out, s, flags, folded);
     if (N == 64 && base == 4) {
         hipLaunchKernelGGL(bcube_batch_b4n64_kernel, dim3(batch_grid(4, B)), dim3(256), 0, s, c, weights, perms, B, out);
         return hipGetLastError();
     }
-    if (N <= 64) return bcube_launch<1>(c, N, base, weights, perms, B, out, s);
-    if (N <= 128) return bcube_launch<2>(c, N, base, weights, perms, B, out, s);
-    if (N <= 256) return bcube_launch<4>(c, N, base, weights, perms, B, out, s);
-    if (N <= 512) return bcube_launch<8>(c, N, base, weights, perms, B, out, s);
-    return bcube_launch<16>(c, N, base, weights, perms, B, out, s);
+    const int32_t* skip = nullptr;
+    if (flags && folded && base == 4 && (N == 256 || N == 1024)) {
+        // both kernels are enqueued; the matrix maximum, computed on the device, decides which of them works
+        hipError_t e = launch_matrix_max(c, N, flags, s);
+        if (e == hipSuccess) e = launch_fold_to_u16(c, N, folded, flags, s);
+        if (e != hipSuccess) return e;
+        const int grid = batch_grid(4, B);
+        if (N == 256)
+            hipLaunchKernelGGL(bcube_b4_folded_kernel<4>, dim3(grid), dim3(256), 0, s, folded, weights, perms, B, out, flags);
+        else
+            hipLaunchKernelGGL(bcube_b4_folded_kernel<5>, dim3(grid), dim3(256), 0, s, folded, weights, perms, B, out, flags);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        skip = flags;
+    }
+    if (N <= 64) return bcube_launch<1>(c, N, base, weights, perms, B, out, skip, s);
+    if (N <= 128) return bcube_launch<2>(c, N, base, weights, perms, B, out, skip, s);
+    if (N <= 256) return bcube_launch<4>(c, N, base, weights, perms, B, out, skip, s);
+    if (N <= 512) return bcube_launch<8>(c, N, base, weights, perms, B, out, skip, s);
+    return bcube_launch<16>(c, N, base, weights, perms, B, out, skip, s);
 }
 
 // --------------------------------------------------------------------- double-binary-tree cost model

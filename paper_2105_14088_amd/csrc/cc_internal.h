@@ -19,7 +19,8 @@ hipError_t launch_rd_cost_batch(const int32_t* c, int N, const int32_t* weights,
 // maximum, launch_matrix_max) is 2^16 or more.
 hipError_t launch_fold_to_u16(const int32_t* c, int N, uint16_t* folded, const int32_t* flags, hipStream_t s);
 hipError_t launch_bcube_cost_batch(const int32_t* c, int N, int base, const int32_t* weights, const int32_t* perms,
-                                   int64_t B, int64_t* out, hipStream_t s);
+                                   int64_t B, int64_t* out, hipStream_t s, int32_t* flags = nullptr,
+                                   uint16_t* folded = nullptr);
 hipError_t launch_dbt_cost_batch(const int32_t* c, int N, const int32_t* perms, int64_t B, int64_t* out,
                                  hipStream_t s);
 hipError_t launch_probes_percentile(const int32_t* samples, int N, int K, int rank, bool symmetrize, int32_t* out,

@@ -73,7 +73,8 @@ def test_argument_errors_are_returned_before_any_launch():
     ws256 = ctypes.c_void_p(0x10000)
     need = L.cc_rd_batch_workspace_bytes(1024)
     assert need >= 2 * 1024 * 1024 and need % 256 == 0
-    assert L.cc_rd_batch_workspace_bytes(48) == 0 and L.cc_rd_batch_workspace_bytes(2048) == 0
+    assert L.cc_rd_batch_workspace_bytes(1) == 0 and L.cc_rd_batch_workspace_bytes(2048) == 0
+    assert L.cc_rd_batch_workspace_bytes(27) == 256 + 1536          # 2 * 27 * 27 = 1458 bytes, rounded up
     assert L.cc_rd_cost_batch_ex(fake, 48, fake, 1, fake, ws256, need, null) == UNSUPPORTED
     assert L.cc_rd_cost_batch_ex(fake, 1024, fake, 1, fake, null, need, null) == WORKSPACE
     assert L.cc_rd_cost_batch_ex(fake, 1024, fake, 1, fake, ws256, need - 1, null) == WORKSPACE
@@ -82,6 +83,12 @@ def test_argument_errors_are_returned_before_any_launch():
     assert L.cc_rd_cost_batch_ex(fake, 1024, null, 1, fake, ws256, need, null) == INVALID
     assert L.cc_rd_cost_batch_ex(fake, 1024, null, 0, null, ws256, need, null) == 0
     assert L.cc_bcube_cost_batch(fake, 32, 4, fake, 1, fake, null) == UNSUPPORTED   # not a power of the base
+    assert L.cc_bcube_cost_batch_ex(fake, 32, 4, null, fake, 1, fake, ws256, need, null) == UNSUPPORTED
+    assert L.cc_bcube_cost_batch_ex(fake, 1024, 4, null, fake, 1, fake, ws256, need - 1, null) == WORKSPACE
+    assert L.cc_bcube_cost_batch_ex(fake, 1024, 4, null, fake, 1, fake, null, need, null) == WORKSPACE
+    assert L.cc_bcube_cost_batch_ex(fake, 1024, 4, ctypes.c_void_p(0x1002), fake, 1, fake, ws256, need, null) == INVALID
+    assert L.cc_bcube_cost_batch_ex(fake, 1024, 1, null, fake, 1, fake, ws256, need, null) == INVALID
+    assert L.cc_bcube_cost_batch_ex(fake, 1024, 4, null, null, 0, null, ws256, need, null) == 0
     assert L.cc_bcube_cost_batch(fake, 64, 1, fake, 1, fake, null) == INVALID
     assert L.cc_bcube_cost_batch(fake, 64, 4, fake, -1, fake, null) == INVALID
     assert L.cc_bcube_cost_batch(fake, 64, 4, null, 1, fake, null) == INVALID

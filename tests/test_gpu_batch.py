@@ -203,6 +203,36 @@ def test_bcube_weighted_batch(n, base):
         assert np.array_equal(out.cpu().numpy(), oracle.bcube_cost_weighted_batch(c, base, weights, perms))
 
 
+@pytest.mark.parametrize("n,base", [(256, 4), (1024, 4), (128, 2), (512, 2), (243, 3), (16, 4)])
+def test_bcube_with_workspace_folded_copy_and_its_fallback(n, base):
+    """cc_bcube_cost_batch_ex with and without round weights: the largest entry one below 2^16 (folded copy where
+    the size has one) and at 2^16 (per-rank kernel), symmetric and not; and the call without workspace on the same
+    inputs."""
+    rounds = 0
+    while base ** rounds < n:
+        rounds += 1
+    weights = np.random.default_rng(n).integers(0, 1 << 20, size=rounds).astype(np.int32)
+    ws = torch.empty(cc.cc_rd_batch_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    for top, symmetric in (((1 << 16) - 1, False), ((1 << 16) - 1, True), (1 << 16, False), (3, False)):
+        say(f"bcube with workspace N={n} base={base} largest entry {top} symmetric={symmetric}")
+        c = random_matrix(n, 700 + n + top % 7, symmetric=symmetric, lo=max(0, top - 30000), hi=top)
+        c[0, 1] = top
+        if symmetric:
+            c[1, 0] = top
+        perms = random_perms(n, 131, seed=n + top % 13)
+        c_dev, perms_dev, w_dev = dev(c), dev(perms), dev(weights)
+        got = cc.cc_bcube_cost_batch(c_dev, base, perms_dev, workspace=ws)
+        got_w = cc.cc_bcube_cost_batch_weighted(c_dev, base, w_dev, perms_dev, workspace=ws)
+        plain = torch.empty(131, dtype=torch.int64, device="cuda")
+        rc = cc.lib().cc_bcube_cost_batch(c_dev.data_ptr(), n, base, perms_dev.data_ptr(), 131, plain.data_ptr(),
+                                          torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        want = oracle.bcube_cost_batch(c, base, perms)
+        assert np.array_equal(got.cpu().numpy(), want)
+        assert np.array_equal(got_w.cpu().numpy(), oracle.bcube_cost_weighted_batch(c, base, weights, perms))
+        assert rc == 0 and np.array_equal(plain.cpu().numpy(), want)
+
+
 def test_bcube_base4_n1024_16384_orders():
     """Full-size case: B = 4 (the paper's BCube base) on 16384 seeded orders at N = 1024, sampled against the oracle."""
     say("bcube batch N=1024 base=4 B=16384")

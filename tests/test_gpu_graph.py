@@ -101,7 +101,7 @@ def test_local_search_replays_in_a_graph():
 
 
 def test_other_searches_replay_in_a_graph():
-    """The remaining search calls inside one captured step: pair swaps at N = 64 (wavefront kernel) and N = 256
+    """The remaining search calls and the workspace forms of the batch calls inside one captured step: pair swaps at N = 64 (wavefront kernel) and N = 256
     (workgroup kernel with its 128 KiB of LDS, folded matrix, skipped general kernel), the directed ring sum at
     N = 64 (seeded starts, matrix maximum, wavefront kernel, skipped general kernel), and both annealing calls."""
     say("HIP graph: capture pair-swap searches, a directed-sum search and annealing, replay 3 times")
@@ -117,7 +117,14 @@ def test_other_searches_replay_in_a_graph():
     b_sa = cc.SearchBuffers(64, 0, 8, dev)
     b_sard = cc.SearchBuffers(64, 0, 8, dev)
 
+    orders = cc.cc_init_tours(256, 300, 26)
+    ws_batch = torch.empty(cc.cc_rd_batch_workspace_bytes(256), dtype=torch.uint8, device=dev)
+    out_rd = torch.empty(300, dtype=torch.int64, device=dev)
+    out_bcube = torch.empty(300, dtype=torch.int64, device=dev)
+
     def step():
+        cc.cc_rd_cost_batch(c256, orders, out=out_rd, workspace=ws_batch)          # folded-matrix forms
+        cc.cc_bcube_cost_batch(c256, 4, orders, out=out_bcube, workspace=ws_batch)
         cc.cc_rd_swap_search_ex(c64, 40, 21, buffers=b_swap64)
         cc.cc_rd_swap_search_ex(c256, 2, 22, buffers=b_swap256)
         cc.cc_2opt_search_ex(c3, cc.CC_RING_SUM_DIRECTED, 40, 23, buffers=b_dsum)
@@ -129,7 +136,11 @@ def test_other_searches_replay_in_a_graph():
     bufs = (b_swap64, b_swap256, b_dsum, b_sa, b_sard)
     outs = [t for b in bufs for t in (b.restart_costs, b.restart_tours, b.restart_moves, b.best_perm, b.best_cost,
                                        b.best_restart)]
+    outs += [out_rd, out_bcube]
     want = [t.clone() for t in outs]
+    orders_host = orders.cpu().numpy()
+    assert np.array_equal(out_rd.cpu().numpy(), oracle.rd_cost_batch(c256_host, orders_host))
+    assert np.array_equal(out_bcube.cpu().numpy(), oracle.bcube_cost_batch(c256_host, 4, orders_host))
     refs = (oracle.rd_swap_search(c64_host, 40, 21), oracle.rd_swap_search(c256_host, 2, 22),
             oracle.search(c3_host, oracle.SUM_DIRECTED, 40, 23), oracle.sa_search(c64_host, 8, 3000, 300, 0, 24),
             oracle.sa_rd_search(c64_host, 8, 2000, 300, 0, 25))

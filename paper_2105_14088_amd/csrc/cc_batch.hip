@@ -312,6 +312,170 @@ __global__ __launch_bounds__(256) void rd_batch_kernel(const int32_t* __restrict
     }
 }
 
+// N = 64 with one order per LANE (orders 16-byte aligned): nothing is reduced across lanes.  A wave takes 64 orders:
+// sixteen coalesced 1 KiB loads bring them in (lane l of load i holds four ranks of order 4i + l / 16), every rank
+// is packed as the byte 4 * node, the packed words go through a 4.25 KiB LDS tile (17 words per order: writes two
+// lanes per bank, reads conflict-free) and come back as the lane's own order, 64 bytes in 16 registers.  With all
+// loops unrolled every rank of the order is a register with a constant index, so a matrix entry between the nodes
+// at two ranks is { address = byte[x] << 6 | byte[y]; gather }, and the lane writes its own cost: 64 consecutive
+// results per wave.
+constexpr int kLaneTileStride = 17;                 // words per staged order: 16 of packed ranks, 1 of padding
+
+// node4[p] = 4 * node at rank p of order b0 + lane (the last order again beyond the batch's end)
+__device__ __forceinline__ void load_order_per_lane(const int4* __restrict__ perms4, int64_t b0, int64_t B,
+                                                    uint32_t* tile, int lane, unsigned (&node4)[64]) {
+    constexpr int N = 64;
+    const int quarter = lane >> 4, piece = lane & 15;
+    uint32_t packed[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        int64_t o = b0 + 4 * i + quarter;
+        o = o < B ? o : B - 1;
+        const int4 v = perms4[o * 16 + piece];
+        packed[i] = (uint32_t)(clampi(v.x, 0, N - 1) << 2) | (uint32_t)(clampi(v.y, 0, N - 1) << 10) |
+                    (uint32_t)(clampi(v.z, 0, N - 1) << 18) | (uint32_t)(clampi(v.w, 0, N - 1) << 26);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) tile[(4 * i + quarter) * kLaneTileStride + piece] = packed[i];
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const uint32_t word = tile[lane * kLaneTileStride + q];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) node4[4 * q + j] = (word >> (8 * j)) & 0xffu;
+    }
+    __builtin_amdgcn_wave_barrier();                               // the tile is free for the next 64 orders
+}
+
+// stages the matrix; FOLD: both directed entries of a pair replaced by the larger (an exchange costs the slower way)
+template <bool FOLD>
+__device__ __forceinline__ void stage_matrix_64(const int32_t* __restrict__ c, int32_t* m) {
+    constexpr int N = 64;
+    for (int e = threadIdx.x; e < N * N; e += 256) m[e] = clampi(c[e], 0, (1 << 21) - 1);
+    __syncthreads();
+    if (FOLD) {
+        w64::for_each_pair_64((int)threadIdx.x, [&](int lo, int hi) {
+            const int both = max(m[lo * N + hi], m[hi * N + lo]);
+            m[lo * N + hi] = both;
+            m[hi * N + lo] = both;
+        });
+        __syncthreads();
+    }
+}
+
+// halving-doubling: the 6 x 32 links of an order, one folded entry each
+__global__ __launch_bounds__(256) void rd_batch_lanes64_kernel(const int32_t* __restrict__ c,
+                                                               const int32_t* __restrict__ weights,
+                                                               const int4* __restrict__ perms4, int64_t B,
+                                                               int64_t* __restrict__ out) {
+    constexpr int N = 64;
+    __shared__ int32_t m[N * N];
+    __shared__ uint32_t tile_all[4][N * kLaneTileStride];
+    const int lane = lane_id(), wv = threadIdx.x >> 6;
+    stage_matrix_64<true>(c, m);
+    const char* mbytes = (const char*)m;
+    long long w[6];
+#pragma unroll
+    for (int k = 0; k < 6; ++k) w[k] = weights ? (long long)clampi(weights[k], 0, kMaxRoundWeight) : 1ll;
+    const int64_t tasks = (B + 63) >> 6;
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t task = (int64_t)blockIdx.x * 4 + wv; task < tasks; task += nwaves) {
+        const int64_t b0 = task << 6;
+        unsigned node4[N];
+        load_order_per_lane(perms4, b0, B, tile_all[wv], lane, node4);
+        long long total = 0;
+#pragma unroll
+        for (int k = 0; k < 6; ++k) {
+            int worst = 0;
+#pragma unroll
+            for (int li = 0; li < N / 2; ++li) {
+                const int lo = ((li >> k) << (k + 1)) | (li & ((1 << k) - 1)), hi = lo | (1 << k);
+                worst = max(worst, *(const int32_t*)(mbytes + ((node4[lo] << 6) | node4[hi])));
+            }
+            total += w[k] * worst;
+        }
+        if (b0 + lane < B) out[b0 + lane] = total;
+    }
+}
+
+// BCube, base 4: the four ranks that differ in one base-4 digit exchange pairwise; 3 rounds x 16 groups x 6 pairs,
+// one folded entry each
+__global__ __launch_bounds__(256) void bcube_b4_lanes64_kernel(const int32_t* __restrict__ c,
+                                                               const int32_t* __restrict__ weights,
+                                                               const int4* __restrict__ perms4, int64_t B,
+                                                               int64_t* __restrict__ out) {
+    constexpr int N = 64;
+    __shared__ int32_t m[N * N];
+    __shared__ uint32_t tile_all[4][N * kLaneTileStride];
+    const int lane = lane_id(), wv = threadIdx.x >> 6;
+    stage_matrix_64<true>(c, m);
+    const char* mbytes = (const char*)m;
+    long long w[3];
+#pragma unroll
+    for (int r = 0; r < 3; ++r) w[r] = weights ? (long long)clampi(weights[r], 0, kMaxRoundWeight) : 1ll;
+    const int64_t tasks = (B + 63) >> 6;
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t task = (int64_t)blockIdx.x * 4 + wv; task < tasks; task += nwaves) {
+        const int64_t b0 = task << 6;
+        unsigned node4[N];
+        load_order_per_lane(perms4, b0, B, tile_all[wv], lane, node4);
+        long long total = 0;
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            int worst = 0;
+#pragma unroll
+            for (int g = 0; g < N / 4; ++g) {
+                const int p0 = ((g >> (2 * r)) << (2 * r + 2)) | (g & ((1 << (2 * r)) - 1));
+#pragma unroll
+                for (int d = 0; d < 3; ++d)
+#pragma unroll
+                    for (int e = d + 1; e < 4; ++e)
+                        worst = max(worst, *(const int32_t*)(mbytes + ((node4[p0 | (d << (2 * r))] << 6) |
+                                                                       node4[p0 | (e << (2 * r))])));
+            }
+            total += w[r] * worst;
+        }
+        if (b0 + lane < B) out[b0 + lane] = total;
+    }
+}
+
+// Double binary tree: the tree over positions LO .. HI hangs below a parent whose node and path cost are given; the
+// costliest root-to-leaf path is the largest path cost met.  SHIFT: tree position p holds rank (p + SHIFT) mod 64.
+template <int LO, int HI, int SHIFT>
+__device__ __forceinline__ void dbt_walk_64(const char* mbytes, const unsigned (&node4)[64], unsigned parent4, int cost,
+                                            bool has_parent, int& worst) {
+    if constexpr (LO <= HI) {
+        constexpr int M = (LO + HI) / 2;
+        const unsigned here = node4[(M + SHIFT) & 63];
+        const int mine = has_parent ? cost + *(const int32_t*)(mbytes + ((parent4 << 6) | here)) : 0;
+        worst = max(worst, mine);
+        dbt_walk_64<LO, M - 1, SHIFT>(mbytes, node4, here, mine, true, worst);
+        dbt_walk_64<M + 1, HI, SHIFT>(mbytes, node4, here, mine, true, worst);
+    }
+}
+
+__global__ __launch_bounds__(256) void dbt_lanes64_kernel(const int32_t* __restrict__ c,
+                                                          const int4* __restrict__ perms4, int64_t B,
+                                                          int64_t* __restrict__ out) {
+    constexpr int N = 64;
+    __shared__ int32_t m[N * N];
+    __shared__ uint32_t tile_all[4][N * kLaneTileStride];
+    const int lane = lane_id(), wv = threadIdx.x >> 6;
+    stage_matrix_64<false>(c, m);
+    const char* mbytes = (const char*)m;
+    const int64_t tasks = (B + 63) >> 6;
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t task = (int64_t)blockIdx.x * 4 + wv; task < tasks; task += nwaves) {
+        const int64_t b0 = task << 6;
+        unsigned node4[N];
+        load_order_per_lane(perms4, b0, B, tile_all[wv], lane, node4);
+        int worst = 0;
+        dbt_walk_64<0, N - 1, 0>(mbytes, node4, 0u, 0, false, worst);
+        dbt_walk_64<0, N - 1, 1>(mbytes, node4, 0u, 0, false, worst);
+        if (b0 + lane < B) out[b0 + lane] = worst;
+    }
+}
+
 // N = 32 or 64 with the matrix in LDS: the rounds are unrolled, so the partner look-ups and the gathers of all rounds are
 // in flight together and the rounds' maxima are reduced three at a time; the next order is requested before the
 // current one is scored.
@@ -494,7 +658,11 @@ hipError_t launch_rd_cost_batch(const int32_t* c, int N, const int32_t* weights,
                                 int64_t* out, hipStream_t s, int32_t* flags, uint16_t* folded) {
     if (B == 0) return hipSuccess;
     if (N == 64) {
-        hipLaunchKernelGGL(rd_batch_links64_kernel, dim3(batch_grid(4, B)), dim3(256), 0, s, c, weights, perms, B, out);
+        if (((uintptr_t)perms & 15u) == 0)
+            hipLaunchKernelGGL(rd_batch_lanes64_kernel, dim3(batch_grid(4 * 64, B)), dim3(256), 0, s, c, weights,
+                               (const int4*)perms, B, out);
+        else
+            hipLaunchKernelGGL(rd_batch_links64_kernel, dim3(batch_grid(4, B)), dim3(256), 0, s, c, weights, perms, B, out);
         return hipGetLastError();
     }
     if (N == 32) return rd_small_launch<5>(c, weights, perms, B, out, s);
@@ -696,7 +864,11 @@ hipError_t launch_bcube_cost_batch(const int32_t* c, int N, int base, const int3
     if (B == 0) return hipSuccess;
     if (base == 2) return launch_rd_cost_batch(c, N, weights, perms, B, out, s, flags, folded);
     if (N == 64 && base == 4) {
-        hipLaunchKernelGGL(bcube_batch_b4n64_kernel, dim3(batch_grid(4, B)), dim3(256), 0, s, c, weights, perms, B, out);
+        if (((uintptr_t)perms & 15u) == 0)
+            hipLaunchKernelGGL(bcube_b4_lanes64_kernel, dim3(batch_grid(4 * 64, B)), dim3(256), 0, s, c, weights,
+                               (const int4*)perms, B, out);
+        else
+            hipLaunchKernelGGL(bcube_batch_b4n64_kernel, dim3(batch_grid(4, B)), dim3(256), 0, s, c, weights, perms, B, out);
         return hipGetLastError();
     }
     const int32_t* skip = nullptr;
@@ -834,7 +1006,9 @@ hipError_t launch_dbt_cost_batch(const int32_t* c, int N, const int32_t* perms, 
                                  hipStream_t s) {
     if (B == 0) return hipSuccess;
     const int grid = batch_grid(4, B);
-    if (N == 64) {
+    if (N == 64 && ((uintptr_t)perms & 15u) == 0) {
+        hipLaunchKernelGGL(dbt_lanes64_kernel, dim3(batch_grid(4 * 64, B)), dim3(256), 0, s, c, (const int4*)perms, B, out);
+    } else if (N == 64) {
         hipLaunchKernelGGL(dbt_batch_n64_kernel, dim3(grid), dim3(256), 0, s, c, perms, B, out);
     } else if (N <= 64) {
         const size_t lds = sizeof(int32_t) * (size_t)(4 * N + N * N);

@@ -203,6 +203,31 @@ def test_bcube_weighted_batch(n, base):
         assert np.array_equal(out.cpu().numpy(), oracle.bcube_cost_weighted_batch(c, base, weights, perms))
 
 
+def test_n64_cost_models_on_an_order_stream_that_is_not_16_byte_aligned():
+    """N = 64: the one-order-per-lane kernels need 16-byte aligned orders; a stream that starts one element later
+    takes the one-order-per-wave kernels.  Both against the oracle, on a batch with a ragged last group of 64."""
+    say("N=64 halving-doubling / BCube base 4 / double binary tree: aligned and unaligned order streams, B = 1000")
+    c = random_matrix(64, 321, symmetric=False, lo=0, hi=COST_MAX)
+    perms = random_perms(64, 1000, seed=12)
+    flat = torch.zeros(1 + perms.size, dtype=torch.int32, device="cuda")
+    flat[1:] = torch.from_numpy(perms.reshape(-1)).cuda()
+    shifted = flat[1:].view(1000, 64)
+    assert shifted.data_ptr() % 16 == 4
+    c_dev, aligned = dev(c), dev(perms)
+    for view in (aligned, shifted):
+        rd = torch.empty(1000, dtype=torch.int64, device="cuda")
+        bc = torch.empty(1000, dtype=torch.int64, device="cuda")
+        tr = torch.empty(1000, dtype=torch.int64, device="cuda")
+        L, st = cc.lib(), torch.cuda.current_stream().cuda_stream
+        assert L.cc_rd_cost_batch(c_dev.data_ptr(), 64, view.data_ptr(), 1000, rd.data_ptr(), st) == 0
+        assert L.cc_bcube_cost_batch(c_dev.data_ptr(), 64, 4, view.data_ptr(), 1000, bc.data_ptr(), st) == 0
+        assert L.cc_dbt_cost_batch(c_dev.data_ptr(), 64, view.data_ptr(), 1000, tr.data_ptr(), st) == 0
+        torch.cuda.synchronize()
+        assert np.array_equal(rd.cpu().numpy(), oracle.rd_cost_batch(c, perms))
+        assert np.array_equal(bc.cpu().numpy(), oracle.bcube_cost_batch(c, 4, perms))
+        assert np.array_equal(tr.cpu().numpy(), oracle.dbt_cost_batch(c, perms))
+
+
 @pytest.mark.parametrize("n,base", [(256, 4), (1024, 4), (128, 2), (512, 2), (243, 3), (16, 4)])
 def test_bcube_with_workspace_folded_copy_and_its_fallback(n, base):
     """cc_bcube_cost_batch_ex with and without round weights: the largest entry one below 2^16 (folded copy where

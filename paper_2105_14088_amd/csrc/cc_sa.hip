@@ -15,6 +15,7 @@
 // pair of ranks per lane.
 #include "cc_device.h"
 #include "cc_internal.h"
+#include "cc_wave64.h"
 
 namespace cc {
 using namespace ccd;
@@ -310,6 +311,147 @@ __global__ __launch_bounds__(256) void sa_rd_kernel(const int32_t* __restrict__ 
     }
 }
 
+// N = 64: the chain of sa_rd_kernel with everything a step touches in registers.  The order is one VGPR (lane =
+// rank): the two nodes of a proposal are lane reads by a scalar index, a link's far end one lane permute, the exchange
+// two selects, the best order a register copy.  The matrix is folded in LDS (the larger of the two directed entries
+// in both places), so a link is one gather and a step needs 12 lanes: lane 2r + side scores, for round r, the link of
+// p (side 0) or q (side 1).  What a step draws does not depend on the order: 64 steps are drawn at once, one per lane
+// (ranks p and q, and the acceptance threshold already as E(u)), and read back by step number.
+__global__ __launch_bounds__(256) void sa_rd_n64_kernel(const int32_t* __restrict__ c, int chains, long long steps,
+                                                        int t_start, int t_end, uint64_t seed,
+                                                        int32_t* __restrict__ tours, int64_t* __restrict__ costs,
+                                                        int32_t* __restrict__ accepted) {
+    constexpr int N = 64, LOGN = 6;
+    __shared__ int32_t m[N * N];
+    const int lane = lane_id(), wv = threadIdx.x >> 6;
+    for (int e = threadIdx.x; e < N * N; e += 256) m[e] = clampi(c[e], 0, kCostMax);
+    __syncthreads();
+    w64::for_each_pair_64((int)threadIdx.x, [&](int lo, int hi) {
+        const int both = max(m[lo * N + hi], m[hi * N + lo]);
+        m[lo * N + hi] = both;
+        m[hi * N + lo] = both;
+    });
+    __syncthreads();
+    const int64_t r = (int64_t)blockIdx.x * 4 + wv;
+    if (r >= chains) return;
+    const char* mbytes = (const char*)m;
+    auto link_value = [&](int x, int y) { return *(const int32_t*)(mbytes + ((x << 8) | (y << 2))); };
+
+    int t = clampi(tours[r * N + lane], 0, N - 1);
+    int bt = t;
+    const int my_round = lane >> 1, side = lane & 1;
+    const bool in_play = my_round < LOGN;
+    const int my_bit = 1 << (in_play ? my_round : 0);
+    int k1 = -1, k2 = -1, k3 = -1;                      // this lane's round: its three largest links, value << 10 | lower rank
+
+    // the wave recomputes round kk from the order; the two lanes of that round take the result
+    auto recompute_round = [&](int kk) {
+        const int bit = 1 << kk, i = lane & 31;         // link index (both half-waves compute the same 32 links)
+        const int j = ((i >> kk) << (kk + 1)) | (i & (bit - 1));
+        const int a = __builtin_amdgcn_ds_bpermute(j << 2, t), b = __builtin_amdgcn_ds_bpermute((j | bit) << 2, t);
+        const int key = (link_value(a, b) << 5) | i;
+        int found[3];
+        int taken0 = -2, taken1 = -2;
+#pragma unroll
+        for (int pass = 0; pass < 3; ++pass) {
+            const int best = wave_max((i == taken0 || i == taken1) ? -1 : key);
+            const int bi = best & 31;
+            found[pass] = ((best >> 5) << 10) | ((bi >> kk) << (kk + 1)) | (bi & (bit - 1));
+            if (pass == 0) taken0 = bi;
+            else taken1 = bi;
+        }
+        if (my_round == kk) {
+            k1 = found[0];
+            k2 = found[1];
+            k3 = found[2];
+        }
+    };
+    for (int kk = 0; kk < LOGN; ++kk) recompute_round(kk);
+    int cur = wave_sum((in_play && side == 0) ? (k1 >> 10) : 0);
+    int best = cur;
+    int acc = 0;
+    const uint64_t chain_hi = (uint64_t)(uint32_t)r << 32;
+
+    int draw_pq = 0;                                    // ranks p | q << 8 of step (batch start + lane)
+    int draw_e = 0;                                     // its E(u), 0 .. 22 * 4096
+    for (long long s = 0; s < steps; ++s) {
+        const int slot = (int)(s & 63);
+        if (slot == 0) {
+            const uint64_t w = splitmix64_at(seed, (chain_hi | (uint32_t)(kDrawBase + (uint32_t)s + (uint32_t)lane)) + 1u);
+            const int p = (int)(((uint32_t)(w >> 43) * (uint32_t)N) >> 21);
+            const int d = 1 + (int)((((uint32_t)(w >> 22) & 0x1FFFFFu) * (uint32_t)(N - 1)) >> 21);
+            draw_pq = p | (((p + d) & (N - 1)) << 8);
+            const int u = (int)((uint32_t)w & 0x3FFFFFu) + 1;
+            const int e = 31 - __clz(u);
+            const int mant = u - (1 << e);
+            const int frac = e >= 12 ? (mant >> (e - 12)) : (mant << (12 - e));
+            draw_e = 22 * 4096 - (e * 4096 + frac);
+        }
+        const int pq = __builtin_amdgcn_readlane(draw_pq, slot);
+        const int p = pq & 255, q = pq >> 8;
+        const int node_p = __builtin_amdgcn_readlane(t, p), node_q = __builtin_amdgcn_readlane(t, q);
+        // this lane's link: rank `mine` (p or q) receives the node of the other rank; its partner keeps its node
+        const int mine = side ? q : p;
+        const int x = side ? node_p : node_q;
+        const int y = __builtin_amdgcn_ds_bpermute((mine ^ my_bit) << 2, t);
+        const int link = in_play ? link_value(x, y) : 0;
+        const int link_other = __builtin_amdgcn_update_dpp(link, link, 0xB1, 0xf, 0xf, true);          // the other side
+        const int link_p = side ? link_other : link, link_q = side ? link : link_other;
+        const int lp = p & ~my_bit, lq = q & ~my_bit;
+        const bool same_link = lp == lq;               // q = p xor bit: the link keeps both nodes and its value
+        const int j1 = k1 & 1023, j2 = k2 & 1023;
+        const bool f1 = j1 != lp && j1 != lq, f2 = j2 != lp && j2 != lq;
+        const int others = (f1 ? k1 : (f2 ? k2 : k3)) >> 10;
+        const int stage = same_link ? (k1 >> 10) : max(others, max(link_p, link_q));
+        const int total = wave_sum((in_play && side == 0) ? stage : 0);
+        const int delta = total - cur;
+        bool accept = true;
+        if (delta > 0) {
+            const long long E = __builtin_amdgcn_readlane(draw_e, slot);
+            const long long num = (long long)t_start * (steps - s) + (long long)t_end * s;
+            accept = (long long)delta * 4096 * steps <= num * E;
+        }
+        if (!accept) continue;                          // wave-uniform
+        t = lane == p ? node_q : (lane == q ? node_p : t);
+        cur += delta;
+        ++acc;
+        // the round's three largest links after the exchange
+        bool stale = false;
+        if (in_play && !same_link) {
+            const int f3 = (k3 & 1023) != lp && (k3 & 1023) != lq;
+            int c0 = f1 ? k1 : -1, c1 = f2 ? k2 : -1, c2 = (f3 && k3 >= 0) ? k3 : -1;
+            if (k1 < 0) c0 = -1;
+            if (k2 < 0) c1 = -1;
+            int c3 = (link_p << 10) | lp, c4 = (link_q << 10) | lq;
+            const int bound = k3 >> 10;                // every link outside the candidates is at most this
+            const int n1 = max(max(c0, c1), max(max(c2, c3), c4));
+            c0 = c0 == n1 ? -1 : c0; c1 = c1 == n1 ? -1 : c1; c2 = c2 == n1 ? -1 : c2;
+            c3 = c3 == n1 ? -1 : c3; c4 = c4 == n1 ? -1 : c4;
+            const int n2 = max(max(c0, c1), max(max(c2, c3), c4));
+            c0 = c0 == n2 ? -1 : c0; c1 = c1 == n2 ? -1 : c1; c2 = c2 == n2 ? -1 : c2;
+            c3 = c3 == n2 ? -1 : c3; c4 = c4 == n2 ? -1 : c4;
+            const int n3 = max(max(c0, c1), max(max(c2, c3), c4));
+            stale = (n3 >> 10) < bound;
+            k1 = n1; k2 = n2; k3 = n3;
+        }
+        unsigned long long redo = __ballot(stale);
+        while (redo) {
+            const int kk = (__ffsll((long long)redo) - 1) >> 1;
+            recompute_round(kk);
+            redo &= ~(0x3ull << (2 * kk));
+        }
+        if (cur < best) {
+            best = cur;
+            bt = t;
+        }
+    }
+    tours[r * N + lane] = bt;
+    if (lane == 0) {
+        costs[r] = (int64_t)best;
+        accepted[r] = acc;
+    }
+}
+
 template <int LOGN>
 static hipError_t sa_rd_launch(const int32_t* c, int chains, long long steps, int t_start, int t_end, uint64_t seed,
                                int32_t* tours, int64_t* costs, int32_t* accepted, hipStream_t s) {
@@ -364,7 +506,10 @@ hipError_t launch_sa_rd(const int32_t* c, int N, int chains, long long steps, in
         case 8: return sa_rd_launch<3>(c, chains, steps, t_start, t_end, seed, tours, costs, accepted, s);
         case 16: return sa_rd_launch<4>(c, chains, steps, t_start, t_end, seed, tours, costs, accepted, s);
         case 32: return sa_rd_launch<5>(c, chains, steps, t_start, t_end, seed, tours, costs, accepted, s);
-        case 64: return sa_rd_launch<6>(c, chains, steps, t_start, t_end, seed, tours, costs, accepted, s);
+        case 64:
+            hipLaunchKernelGGL(sa_rd_n64_kernel, dim3((chains + 3) / 4), dim3(256), 0, s, c, chains, steps, t_start,
+                               t_end, seed, tours, costs, accepted);
+            return hipGetLastError();
         case 128: return sa_rd_launch<7>(c, chains, steps, t_start, t_end, seed, tours, costs, accepted, s);
         case 256: return sa_rd_launch<8>(c, chains, steps, t_start, t_end, seed, tours, costs, accepted, s);
         case 512: return sa_rd_launch<9>(c, chains, steps, t_start, t_end, seed, tours, costs, accepted, s);

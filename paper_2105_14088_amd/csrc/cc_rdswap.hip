@@ -352,6 +352,9 @@ __global__ __launch_bounds__(SPLIT << LOGN) void rdswap_block_kernel(const int32
     constexpr int N = 1 << LOGN, THREADS = SPLIT << LOGN, NW = THREADS / 64, LB = LOGN - 1;   // LB: bits of a link index
     constexpr int kIdBits = 2 * LOGN;
     constexpr int kStepUnroll = IN_LDS ? 2 : 1;                // two steps in flight where registers allow
+    // 16 wavefronts: the workgroup-wide reductions finish with a wave reduction over the 16 partial results (read as
+    // a chain into registers they cost spills under the 128-register limit of 1024 threads); 8 wavefronts keep the chain
+    constexpr bool kTwoLevel = NW >= 16;
     if (flags[0] >= (1 << 16)) return;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     int32_t* tl = (int32_t*)smem;                              // [N] the order
@@ -388,9 +391,14 @@ __global__ __launch_bounds__(SPLIT << LOGN) void rdswap_block_kernel(const int32
         v = wave_max(v);
         if (lane == 0) red_i[parity][wv] = v;
         __syncthreads();
-        int o = red_i[parity][0];
+        int o;
+        if (kTwoLevel) {
+            o = wave_max(red_i[parity][lane & (NW - 1)]);      // second level: one value per lane, no long chain
+        } else {
+            o = red_i[parity][0];
 #pragma unroll
-        for (int k = 1; k < NW; ++k) o = max(o, red_i[parity][k]);
+            for (int k = 1; k < NW; ++k) o = max(o, red_i[parity][k]);
+        }
         parity ^= 1;
         return o;
     };
@@ -467,9 +475,14 @@ __global__ __launch_bounds__(SPLIT << LOGN) void rdswap_block_kernel(const int32
         best = wave_min_u64(best);
         if (lane == 0) red_k[wv] = best;
         __syncthreads();
-        unsigned long long win = red_k[0];
+        unsigned long long win;
+        if (kTwoLevel) {
+            win = wave_min_u64(red_k[lane & (NW - 1)]);
+        } else {
+            win = red_k[0];
 #pragma unroll
-        for (int k = 1; k < NW; ++k) win = min(win, red_k[k]);
+            for (int k = 1; k < NW; ++k) win = min(win, red_k[k]);
+        }
         if ((int)(win >> kIdBits) >= cur) break;
         const int id = (int)(win & ((1u << kIdBits) - 1u)), sp = id >> LOGN, sq = id & (N - 1);
         const int a = tl[sp], b = tl[sq];

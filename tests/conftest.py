@@ -15,3 +15,13 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+@pytest.fixture(scope="session", autouse=True)
+def built_library():
+    """The tests load the library that is built in-tree; only when there is none do they build it (hipcc cross-compiles
+    without a GPU).  After a change to a source, build again before running the tests."""
+    from paper_2105_14088_amd.build import LIB_PATH, build
+    if not os.path.exists(LIB_PATH):
+        build(force=True)
+    return LIB_PATH

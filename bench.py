@@ -65,6 +65,9 @@ def main():
     import torch
 
     import paper_2105_14088_amd as cc
+    from paper_2105_14088_amd.build import build as build_library
+    if not os.path.exists(cc.LIB_PATH):           # built in-tree beforehand as a rule; built here only when nothing is
+        build_library(force=True)
     from gen import WORKLOADS, make_matrix
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"

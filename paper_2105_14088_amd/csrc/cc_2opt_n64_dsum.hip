@@ -74,7 +74,7 @@ void twoopt_dsum_n64_kernel(const int32_t* __restrict__ c, int restarts, uint64_
             bwb = from_next_lane(bwb);
             // keeps each rotate an instruction of its own: folded into the subtraction below it would become
             // v_subrev_u32_dpp, which on this chip rotates the other operand
-            asm volatile("" : "+v"(fb), "+v"(bwb));
+            asm("" : "+v"(fb), "+v"(bwb));
             const int G = *(const int32_t*)(mbytes + ((w & 0xfc) | rowofs));        // c[t[a]][t[b]]
             const int GT = *(const int32_t*)(mbytes + ((w & 0x3f00) | col));        // c[t[b]][t[a]]
             const int EG = from_prev_lane(G), EGT = from_prev_lane(GT);

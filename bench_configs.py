@@ -256,6 +256,10 @@ def main():
         ("R64", lambda: batch_case("R64_n64_rd_2^20", 2, "rd", 0, 1 << 20)),
         ("AR64", lambda: sa_case("AR64_n64_sa_rd_1024x20000", 2, 1024, 20000, 300, 0, rd=True)),
         ("AR1024", lambda: sa_case("AR1024_n1024_sa_rd_256x20000", 5, 256, 20000, 300, 0, rd=True)),
+        ("R256", lambda: batch_case("R256_n256_rd_2^18", 4, "rd", 0, 1 << 18)),
+        ("B256", lambda: batch_case("B256_n256_bcube4_2^18", 4, "bcube", 0, 1 << 18)),
+        ("M256", lambda: batch_case("M256_n256_ring_sum_2^18", 4, "ring", 0, 1 << 18)),
+        ("M1024", lambda: batch_case("M1024_n1024_ring_sum_65536", 5, "ring", 0, 65536)),
         ("M64sum", lambda: batch_case("M64_ring_sum_2^20", 2, "ring", 0, 1 << 20)),
         ("M64max", lambda: batch_case("M64_ring_max_2^20", 3, "ring", 1, 1 << 20)),
         ("M64u8", lambda: batch_case("M64_ring_sum_2^20_byte_orders", 2, "ring_u8", 0, 1 << 20)),

@@ -190,6 +190,82 @@ static hipError_t ring_lds(const int32_t* c, bool is_max, const int32_t* perms, 
     return hipGetLastError();
 }
 
+// N = 256 for large batches: the matrix as 16-bit entries in LDS (128 KiB, one 1024-thread workgroup per compute
+// unit), one wave per order: a 1 KiB wave-load is the order, four ranks per lane, the hop into a lane's first rank
+// uses the previous lane's last node (cyclic), four LDS gathers per lane and one wave reduction per order.  Through
+// L2 (generic kernel) the same batch runs at the L2's request rate, 256 scattered requests per order.  The workgroup
+// finds the matrix maximum while staging; with an entry outside 0 .. 2^16 - 1 it scores its orders through L2 instead.
+template <bool IS_MAX>
+__global__ __launch_bounds__(1024) void ring_batch_n256_kernel(const int32_t* __restrict__ c,
+                                                               const int4* __restrict__ perms4, int64_t B,
+                                                               int64_t* __restrict__ out) {
+    constexpr int N = 256, U = 4;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem256[];
+    uint16_t* m16 = (uint16_t*)smem256;
+    __shared__ unsigned wave_top[16];
+    const int lane = lane_id(), wv = threadIdx.x >> 6;
+    unsigned top = 0;
+    for (int e = threadIdx.x; e < N * N; e += 1024) {
+        const unsigned v = (unsigned)c[e];                 // a negative entry counts as too large
+        top = max(top, v);
+        m16[e] = (uint16_t)v;
+    }
+    top = (unsigned)wave_max((int)min(top, 0x7fffffffu));
+    if (lane == 0) wave_top[wv] = top;
+    __syncthreads();
+    unsigned all_top = 0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) all_top = max(all_top, wave_top[k]);
+    const bool in_lds = all_top < (1u << 16);
+    const int64_t wave = (int64_t)blockIdx.x * 16 + wv;
+    const int64_t nwaves = (int64_t)gridDim.x * 16;
+    const char* mbytes = (const char*)m16;
+    for (int64_t base = wave * U; base < B; base += nwaves * U) {
+        int4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t b = base + u < B ? base + u : B - 1;
+            v[u] = perms4[b * 64 + lane];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int x = v[u].x & 255, y = v[u].y & 255, z = v[u].z & 255, w = v[u].w & 255;
+            const int pw = __builtin_amdgcn_update_dpp(w, w, 0x13C, 0xf, 0xf, true);   // lane p <- lane p - 1, cyclic
+            int h0, h1, h2, h3;
+            if (in_lds) {
+                h0 = *(const uint16_t*)(mbytes + ((x << 9) | (pw << 1)));
+                h1 = *(const uint16_t*)(mbytes + ((y << 9) | (x << 1)));
+                h2 = *(const uint16_t*)(mbytes + ((z << 9) | (y << 1)));
+                h3 = *(const uint16_t*)(mbytes + ((w << 9) | (z << 1)));
+            } else {
+                h0 = c[x * N + pw]; h1 = c[y * N + x]; h2 = c[z * N + y]; h3 = c[w * N + z];
+            }
+            long long total;
+            if (IS_MAX) {
+                total = max(wave_max(max(max(h0, h1), max(h2, h3))), 0);
+            } else if (in_lds) {
+                total = wave_sum(h0 + h1 + h2 + h3);       // at most 256 * 65535
+            } else {
+                total = wave_sum64((long long)h0 + h1 + h2 + h3);
+            }
+            if (lane == 0 && base + u < B) out[base + u] = total;
+        }
+    }
+}
+
+template <bool IS_MAX>
+static hipError_t ring_n256_launch(const int32_t* c, const int32_t* perms, int64_t B, int64_t* out, hipStream_t s) {
+    const size_t lds = sizeof(uint16_t) * 256 * 256;
+    hipError_t e = hipFuncSetAttribute((const void*)ring_batch_n256_kernel<IS_MAX>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    int64_t blocks = (B + 16 * 4 - 1) / (16 * 4);
+    if (blocks > 256) blocks = 256;
+    hipLaunchKernelGGL(ring_batch_n256_kernel<IS_MAX>, dim3((int)blocks), dim3(1024), lds, s, c, (const int4*)perms, B,
+                       out);
+    return hipGetLastError();
+}
+
 hipError_t launch_ring_cost_batch(const int32_t* c, int N, bool is_max, const int32_t* perms, int64_t B,
                                   int64_t* out, hipStream_t s) {
     if (B == 0) return hipSuccess;
@@ -203,6 +279,9 @@ hipError_t launch_ring_cost_batch(const int32_t* c, int N, bool is_max, const in
             case 128: return ring_lds<128>(c, is_max, perms, B, out, s);
             default: break;
         }
+        // staging 128 KiB per compute unit pays from a few ten thousand orders on
+        if (N == 256 && B >= 32768)
+            return is_max ? ring_n256_launch<true>(c, perms, B, out, s) : ring_n256_launch<false>(c, perms, B, out, s);
     }
     const int grid = batch_grid(4, B);
     if (is_max)

@@ -101,6 +101,21 @@ def test_ring_batch_u16_orders(n, obj):
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("obj", [0, 1])
+def test_ring_batch_n256_large_batches_lds_kernel_and_its_fallback(obj):
+    """N = 256 from 32768 orders on: the matrix as 16-bit entries in LDS; a matrix with an entry of 2^16 is scored
+    through L2 by the same kernel.  A batch size that is no multiple of the kernel's step, every order compared."""
+    B = 32768 + 4099
+    perms = random_perms(256, B, seed=77 + obj)
+    for top, symmetric in (((1 << 16) - 1, False), (1 << 16, False), (2000, True)):
+        say(f"ring batch N=256 B={B} obj={obj} largest entry {top}")
+        c = random_matrix(256, 4000 + top % 13, symmetric=symmetric, lo=max(0, top - 40000), hi=top)
+        c[7, 9] = top
+        if symmetric:
+            c[9, 7] = top
+        assert np.array_equal(gpu_ring(c, perms, obj), oracle.ring_cost_batch(c, perms, obj))
+
+
 def test_ring_batch_empty_and_unaligned():
     c = random_matrix(64, 1, symmetric=True)
     say("ring batch B=0")

@@ -725,6 +725,119 @@ __global__ __launch_bounds__(256) void rd_batch_folded_kernel(const uint16_t* __
     }
 }
 
+// N = 128, 256 for large batches, matrix in LDS: a 1024-thread workgroup per compute unit stages the matrix as 16-bit
+// entries, folds the two directions of every pair into both places (as rdswap_block_kernel does) and then scores one
+// order per wave as rd_batch_folded_kernel / bcube_b4_folded_kernel do, with LDS gathers instead of L2 requests.
+// The workgroup finds the matrix maximum while staging; with an entry outside 0 .. 2^16 - 1 its links are scored from
+// the caller's matrix through L2 (both directions per link).  BCUBE4: base-4 BCube rounds instead of halving-doubling.
+template <int LOGN, bool BCUBE4>
+__global__ __launch_bounds__(1024) void links_batch_lds16_kernel(const int32_t* __restrict__ c,
+                                                                 const int32_t* __restrict__ weights,
+                                                                 const int32_t* __restrict__ perms, int64_t B,
+                                                                 int64_t* __restrict__ out) {
+    constexpr int N = 1 << LOGN, NM = N / 64, ROUNDS = BCUBE4 ? LOGN / 2 : LOGN;
+    static_assert(!BCUBE4 || LOGN % 2 == 0, "base 4 needs an even log2 N");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_links[];
+    uint16_t* m16 = (uint16_t*)smem_links;                                  // [N * N]
+    int32_t* order_all = (int32_t*)(smem_links + sizeof(uint16_t) * N * N);  // [16][N]
+    __shared__ unsigned wave_top[16];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    unsigned top = 0;
+    for (int e = tid; e < N * N; e += 1024) {
+        const unsigned v = (unsigned)c[e];                 // a negative entry counts as too large
+        top = max(top, v);
+        m16[e] = (uint16_t)v;
+    }
+    top = (unsigned)wave_max((int)min(top, 0x7fffffffu));
+    if (lane == 0) wave_top[wv] = top;
+    __syncthreads();
+    unsigned all_top = 0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) all_top = max(all_top, wave_top[k]);
+    const bool in_lds = all_top < (1u << 16);
+    if (in_lds) {
+        // the threads of rank p take the pairs {p, p + j}, j = 1 .. N/2: every unordered pair exactly once
+        const int p = tid & (N - 1);
+        for (int j = 1 + (tid >> LOGN); j <= N / 2; j += 1024 / N) {
+            const int b = (p + j) & (N - 1);
+            if (j < N / 2 || p < N / 2) {
+                const uint16_t both = max(m16[p * N + b], m16[b * N + p]);
+                m16[p * N + b] = both;
+                m16[b * N + p] = both;
+            }
+        }
+    }
+    __syncthreads();
+    auto pair_value = [&](int x, int y) {
+        if (in_lds) return (int)*(const uint16_t*)((const char*)m16 + ((x << (LOGN + 1)) | (y << 1)));
+        return max(clampi(c[x * N + y], 0, (1 << 21) - 1), clampi(c[y * N + x], 0, (1 << 21) - 1));
+    };
+    int32_t* order = order_all + wv * N;
+    long long w[ROUNDS];
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) w[r] = weights ? (long long)clampi(weights[r], 0, kMaxRoundWeight) : 1ll;
+    const int64_t nwaves = (int64_t)gridDim.x * 16;
+    for (int64_t b = (int64_t)blockIdx.x * 16 + wv; b < B; b += nwaves) {
+        const int32_t* pi = perms + b * N;
+#pragma unroll
+        for (int k = 0; k < NM; ++k) order[lane + 64 * k] = clampi(pi[lane + 64 * k], 0, N - 1);
+        __builtin_amdgcn_wave_barrier();
+        int worst[ROUNDS + 2];
+        worst[ROUNDS] = worst[ROUNDS + 1] = 0;
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) {
+            int v = 0;
+            if (BCUBE4) {
+#pragma unroll
+                for (int u = 0; u < N / 256; ++u) {
+                    const int g = lane + 64 * u;                                   // group: the rank without digit r
+                    const int p0 = ((g >> (2 * r)) << (2 * r + 2)) | (g & ((1 << (2 * r)) - 1));
+                    int node[4];
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) node[d] = order[p0 | (d << (2 * r))];
+#pragma unroll
+                    for (int d = 0; d < 3; ++d)
+#pragma unroll
+                        for (int e = d + 1; e < 4; ++e) v = max(v, pair_value(node[d], node[e]));
+                }
+            } else {
+                const int bit = 1 << r;
+#pragma unroll
+                for (int u = 0; u < NM / 2; ++u) {
+                    const int i = lane + 64 * u;                                   // link index
+                    const int j = ((i >> r) << (r + 1)) | (i & (bit - 1));         // its lower rank
+                    v = max(v, pair_value(order[j], order[j | bit]));
+                }
+            }
+            worst[r] = v;
+        }
+        __builtin_amdgcn_wave_barrier();   // all look-ups done before the slice is overwritten
+#pragma unroll
+        for (int r = 0; r < ROUNDS; r += 3) wave_max3(worst[r], worst[r + 1], worst[r + 2]);
+        long long total = 0;
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) total += w[r] * worst[r];
+        if (lane == 0) out[b] = total;
+    }
+}
+
+constexpr int64_t kLdsBatchMinOrders = 32768;      // staging a matrix per compute unit pays from here on
+
+template <int LOGN, bool BCUBE4>
+static hipError_t links_lds16_launch(const int32_t* c, const int32_t* weights, const int32_t* perms, int64_t B,
+                                     int64_t* out, hipStream_t s) {
+    constexpr int N = 1 << LOGN;
+    const size_t lds = sizeof(uint16_t) * N * N + sizeof(int32_t) * 16 * N;
+    hipError_t e = hipFuncSetAttribute((const void*)links_batch_lds16_kernel<LOGN, BCUBE4>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    int64_t blocks = (B + 15) / 16;
+    if (blocks > 256) blocks = 256;
+    hipLaunchKernelGGL((links_batch_lds16_kernel<LOGN, BCUBE4>), dim3((int)blocks), dim3(1024), lds, s, c, weights, perms,
+                       B, out);
+    return hipGetLastError();
+}
+
 template <int LOGN>
 static hipError_t rd_folded_launch(const uint16_t* folded, const int32_t* weights, const int32_t* perms, int64_t B,
                                    int64_t* out, const int32_t* flags, hipStream_t s) {
@@ -746,6 +859,10 @@ hipError_t launch_rd_cost_batch(const int32_t* c, int N, const int32_t* weights,
     }
     if (N == 32) return rd_small_launch<5>(c, weights, perms, B, out, s);
     if (N <= 64) return rd_launch<1>(c, N, weights, perms, B, out, nullptr, s);
+    if (B >= kLdsBatchMinOrders) {
+        if (N == 128) return links_lds16_launch<7, false>(c, weights, perms, B, out, s);
+        if (N == 256) return links_lds16_launch<8, false>(c, weights, perms, B, out, s);
+    }
     const int32_t* skip = nullptr;
     if (flags && folded) {
         // both kernels are enqueued; the matrix maximum, computed on the device, decides which of them works
@@ -950,6 +1067,7 @@ hipError_t launch_bcube_cost_batch(const int32_t* c, int N, int base, const int3
             hipLaunchKernelGGL(bcube_batch_b4n64_kernel, dim3(batch_grid(4, B)), dim3(256), 0, s, c, weights, perms, B, out);
         return hipGetLastError();
     }
+    if (base == 4 && N == 256 && B >= kLdsBatchMinOrders) return links_lds16_launch<8, true>(c, weights, perms, B, out, s);
     const int32_t* skip = nullptr;
     if (flags && folded && base == 4 && (N == 256 || N == 1024)) {
         // both kernels are enqueued; the matrix maximum, computed on the device, decides which of them works

@@ -116,6 +116,35 @@ def test_ring_batch_n256_large_batches_lds_kernel_and_its_fallback(obj):
         assert np.array_equal(gpu_ring(c, perms, obj), oracle.ring_cost_batch(c, perms, obj))
 
 
+@pytest.mark.parametrize("n,base", [(128, 2), (256, 2), (256, 4)])
+def test_large_batches_n128_n256_matrix_in_lds_and_its_fallback(n, base):
+    """Halving-doubling (base 2) and BCube base 4 from 32768 orders on: folded 16-bit matrix in LDS; with an entry of
+    2^16 the same kernel scores through L2.  With and without round weights, every order compared."""
+    B = 32768 + 1031
+    perms = random_perms(n, B, seed=5 * n + base)
+    rounds = 0
+    while base ** rounds < n:
+        rounds += 1
+    weights = np.random.default_rng(n + base).integers(0, 1 << 20, size=rounds).astype(np.int32)
+    perms_dev, w_dev = dev(perms), dev(weights)
+    for top, symmetric in (((1 << 16) - 1, False), (1 << 16, False), (900, True)):
+        say(f"large batch N={n} base={base} B={B} largest entry {top}")
+        c = random_matrix(n, 6000 + n + top % 17, symmetric=symmetric, lo=max(0, top - 50000), hi=top)
+        c[2, 5] = top
+        if symmetric:
+            c[5, 2] = top
+        c_dev = dev(c)
+        plain = cc.cc_bcube_cost_batch(c_dev, base, perms_dev)
+        weighted = cc.cc_bcube_cost_batch_weighted(c_dev, base, w_dev, perms_dev)
+        torch.cuda.synchronize()
+        assert np.array_equal(plain.cpu().numpy(), oracle.bcube_cost_batch(c, base, perms))
+        assert np.array_equal(weighted.cpu().numpy(), oracle.bcube_cost_weighted_batch(c, base, weights, perms))
+        if base == 2:
+            rd = cc.cc_rd_cost_batch(c_dev, perms_dev)
+            torch.cuda.synchronize()
+            assert np.array_equal(rd.cpu().numpy(), oracle.rd_cost_batch(c, perms))
+
+
 def test_ring_batch_empty_and_unaligned():
     c = random_matrix(64, 1, symmetric=True)
     say("ring batch B=0")

@@ -16,7 +16,7 @@ After the timed steps the same search kernel is also timed on 64 times the resta
 wavefronts per SIMD instead of one; --no-saturated skips it).
 
 Prints ONE JSON line.  --gpus above 1 is refused: the search needs no second GPU (restarts are
-independent) and this build runs on one.
+independent) and this library runs on one.
 """
 import argparse
 import json
@@ -58,7 +58,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py runs on one GPU only: restarts and orders are independent, nothing is exchanged "
-              "between devices, and this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
+              "between devices, and this library has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

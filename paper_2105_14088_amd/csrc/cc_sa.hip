@@ -467,6 +467,96 @@ static hipError_t sa_rd_launch(const int32_t* c, int chains, long long steps, in
     return hipGetLastError();
 }
 
+// N = 64: the chain of sa_ring_kernel with the order in one VGPR (lane = rank).  The four ranks a proposal needs are
+// lane permutes, the committed proposal is read by a scalar lane index, the reversal is one lane permute, the best
+// order a register copy: no order in LDS, so no write-read synchronisation within a round.  Draws as in
+// sa_ring_kernel (a ring of 128 steps in LDS, 64 drawn at a time).
+__global__ __launch_bounds__(256) void sa_ring_n64_kernel(const int32_t* __restrict__ c, int chains, long long steps,
+                                                          int t_start, int t_end, uint64_t seed,
+                                                          int32_t* __restrict__ tours, int64_t* __restrict__ costs,
+                                                          int32_t* __restrict__ accepted) {
+    constexpr int N = 64;
+    __shared__ int32_t m[N * N];
+    __shared__ __attribute__((aligned(16))) int32_t draws_all[4][2 * kDrawRing];
+    const int lane = lane_id(), wv = threadIdx.x >> 6;
+    for (int e = threadIdx.x; e < N * N; e += 256) m[e] = clampi(c[e], 0, kCostMax);
+    __syncthreads();
+    const int64_t r = (int64_t)blockIdx.x * 4 + wv;
+    if (r >= chains) return;
+    int32_t* draws = draws_all[wv];
+    const char* mbytes = (const char*)m;
+    auto M = [&](int x, int y) { return *(const int32_t*)(mbytes + ((x << 8) | (y << 2))); };
+    auto node_at = [&](int rank, int order) { return __builtin_amdgcn_ds_bpermute(rank << 2, order); };
+
+    int t = clampi(tours[r * N + lane], 0, N - 1);
+    int bt = t;
+    long long cur = wave_sum64((long long)M(t, __builtin_amdgcn_update_dpp(t, t, 0x13C, 0xf, 0xf, true)));
+    long long best = cur;
+    int acc = 0;
+    const uint64_t chain_hi = (uint64_t)(uint32_t)r << 32;
+    auto draw_block = [&](long long first) {
+        const long long step = first + lane;
+        const uint64_t w = splitmix64_at(seed, (chain_hi | (uint32_t)(kDrawBase + (uint32_t)step)) + 1u);
+        const int a = (int)(((uint32_t)(w >> 43) * (uint32_t)N) >> 21);
+        const int d = 2 + (int)((((uint32_t)(w >> 22) & 0x1FFFFFu) * (uint32_t)(N - 3)) >> 21);
+        const int b = (a + d) & (N - 1);
+        const int u = (int)((uint32_t)w & 0x3FFFFFu) + 1;
+        const int e = 31 - __clz(u);
+        const int mant = u - (1 << e);
+        const int frac = e >= 12 ? (mant >> (e - 12)) : (mant << (12 - e));
+        const int slot = (int)step & (kDrawRing - 1);
+        *(int2*)(draws + 2 * slot) = make_int2(a | (b << 16), 22 * 4096 - (e * 4096 + frac));
+    };
+    draw_block(0);
+    draw_block(kWave);
+    long long drawn = 2 * kWave;              // steps [drawn - 128, drawn) are in the ring
+    wave_lds_sync();
+    long long s = 0;
+    while (s < steps) {
+        if (s + kWave > drawn) {              // the round reaches past the ring: the older half makes room
+            draw_block(drawn);
+            drawn += kWave;
+            wave_lds_sync();
+        }
+        const long long step = s + lane;
+        const bool active = step < steps;
+        const int2 drawn_step = *(const int2*)(draws + 2 * ((int)step & (kDrawRing - 1)));
+        const int a = drawn_step.x & 0xffff, b = drawn_step.x >> 16;
+        const int ap = (a + N - 1) & (N - 1), bp = (b + N - 1) & (N - 1);
+        const int ta = node_at(a, t), tap = node_at(ap, t), tb = node_at(b, t), tbp = node_at(bp, t);
+        const int delta = M(tap, tbp) + M(ta, tb) - M(ta, tap) - M(tb, tbp);
+        bool accept = active;
+        if (delta > 0) {
+            const long long E = drawn_step.y;
+            const long long num = (long long)t_start * (steps - step) + (long long)t_end * step;
+            accept = active && ((long long)delta * 4096 * steps <= num * E);
+        }
+        const unsigned long long mask = __ballot(accept);
+        if (mask == 0ull) {
+            s += kWave;
+            continue;
+        }
+        const int k = __ffsll((long long)mask) - 1;
+        const int abk = __builtin_amdgcn_readlane(drawn_step.x, k), dk = __builtin_amdgcn_readlane(delta, k);
+        const int ak = abk & 0xffff, bk = abk >> 16;
+        const int lo = min(ak, bk), hi = max(ak, bk);
+        const int i = lo ? lo : hi, j = lo ? hi - 1 : N - 1;
+        t = node_at((lane >= i && lane <= j) ? i + j - lane : lane, t);      // ranks i .. j reversed
+        cur += dk;
+        ++acc;
+        if (cur < best) {
+            best = cur;
+            bt = t;
+        }
+        s += k + 1;
+    }
+    tours[r * N + lane] = bt;
+    if (lane == 0) {
+        costs[r] = best;
+        accepted[r] = acc;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_sa_ring(const int32_t* c, int N, int chains, long long steps, int t_start, int t_end, uint64_t seed,
@@ -476,7 +566,10 @@ hipError_t launch_sa_ring(const int32_t* c, int N, int chains, long long steps, 
         if (e != hipSuccess) return e;
     }
     const int grid = (chains + 3) / 4;
-    if (N <= 128) {
+    if (N == 64) {
+        hipLaunchKernelGGL(sa_ring_n64_kernel, dim3(grid), dim3(256), 0, s, c, chains, steps, t_start, t_end, seed, tours,
+                           costs, accepted);
+    } else if (N <= 128) {
         const size_t lds = sizeof(int32_t) * ((size_t)8 * kDrawRing + (size_t)8 * N + (size_t)N * N);
         if (lds > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute((const void*)sa_ring_kernel<true>,

@@ -34,6 +34,19 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// The acceptance rule of cc.h, "delta * 4096 * steps <= (t_start * (steps - s) + t_end * s) * E(u)", turned into
+// the largest cost increase step s accepts: delta is an integer, so the rule is delta <= floor(right side / (4096 *
+// steps)), and a non-positive delta passes as well (the right side is never negative).  One 64-bit division per step,
+// done where the step's random word is drawn (once per step, 64 steps at a time); the search loop then compares.
+__device__ __forceinline__ int largest_accepted_increase(long long step, long long steps, int t_start, int t_end, int u) {
+    const int e = 31 - __clz(u);
+    const int mant = u - (1 << e);
+    const int frac = e >= 12 ? (mant >> (e - 12)) : (mant << (12 - e));
+    const unsigned long long E = (unsigned long long)(22 * 4096 - (e * 4096 + frac));
+    const unsigned long long num = (unsigned long long)((long long)t_start * (steps - step) + (long long)t_end * step);
+    return (int)((num * E) / (4096ull * (unsigned long long)(steps > 0 ? steps : 1)));       // below 22 * 2^21
+}
+
 template <bool LDS_MATRIX>
 __global__ __launch_bounds__(256) void sa_ring_kernel(const int32_t* __restrict__ c, int N, int chains,
                                                       long long steps, int t_start, int t_end, uint64_t seed,
@@ -78,11 +91,8 @@ __global__ __launch_bounds__(256) void sa_ring_kernel(const int32_t* __restrict_
             int b = a + d;
             b = b >= N ? b - N : b;
             const int u = (int)((uint32_t)w & 0x3FFFFFu) + 1;
-            const int e = 31 - __clz(u);
-            const int mant = u - (1 << e);
-            const int frac = e >= 12 ? (mant >> (e - 12)) : (mant << (12 - e));
             const int slot = (int)step & (kDrawRing - 1);
-            *(int2*)(draws + 2 * slot) = make_int2(a | (b << 16), 22 * 4096 - (e * 4096 + frac));
+            *(int2*)(draws + 2 * slot) = make_int2(a | (b << 16), largest_accepted_increase(step, steps, t_start, t_end, u));
         };
         draw_block(0);
         draw_block(kWave);
@@ -102,12 +112,7 @@ __global__ __launch_bounds__(256) void sa_ring_kernel(const int32_t* __restrict_
             const int ap = a ? a - 1 : N - 1, bp = b ? b - 1 : N - 1;
             const int ta = t[a], tap = t[ap], tb = t[b], tbp = t[bp];
             const int delta = M(tap, tbp) + M(ta, tb) - M(ta, tap) - M(tb, tbp);
-            bool accept = active;
-            if (delta > 0) {
-                const long long E = drawn_step.y;
-                const long long num = (long long)t_start * (steps - step) + (long long)t_end * step;
-                accept = active && ((long long)delta * 4096 * steps <= num * E);
-            }
+            const bool accept = active && delta <= drawn_step.y;
             const unsigned long long mask = __ballot(accept);
             if (mask == 0ull) {
                 s += kWave;
@@ -373,7 +378,7 @@ __global__ __launch_bounds__(256) void sa_rd_n64_kernel(const int32_t* __restric
     const uint64_t chain_hi = (uint64_t)(uint32_t)r << 32;
 
     int draw_pq = 0;                                    // ranks p | q << 8 of step (batch start + lane)
-    int draw_e = 0;                                     // its E(u), 0 .. 22 * 4096
+    int draw_most = 0;                                  // the largest cost increase it accepts
     for (long long s = 0; s < steps; ++s) {
         const int slot = (int)(s & 63);
         if (slot == 0) {
@@ -382,10 +387,7 @@ __global__ __launch_bounds__(256) void sa_rd_n64_kernel(const int32_t* __restric
             const int d = 1 + (int)((((uint32_t)(w >> 22) & 0x1FFFFFu) * (uint32_t)(N - 1)) >> 21);
             draw_pq = p | (((p + d) & (N - 1)) << 8);
             const int u = (int)((uint32_t)w & 0x3FFFFFu) + 1;
-            const int e = 31 - __clz(u);
-            const int mant = u - (1 << e);
-            const int frac = e >= 12 ? (mant >> (e - 12)) : (mant << (12 - e));
-            draw_e = 22 * 4096 - (e * 4096 + frac);
+            draw_most = largest_accepted_increase(s + lane, steps, t_start, t_end, u);
         }
         const int pq = __builtin_amdgcn_readlane(draw_pq, slot);
         const int p = pq & 255, q = pq >> 8;
@@ -405,13 +407,7 @@ __global__ __launch_bounds__(256) void sa_rd_n64_kernel(const int32_t* __restric
         const int stage = same_link ? (k1 >> 10) : max(others, max(link_p, link_q));
         const int total = wave_sum((in_play && side == 0) ? stage : 0);
         const int delta = total - cur;
-        bool accept = true;
-        if (delta > 0) {
-            const long long E = __builtin_amdgcn_readlane(draw_e, slot);
-            const long long num = (long long)t_start * (steps - s) + (long long)t_end * s;
-            accept = (long long)delta * 4096 * steps <= num * E;
-        }
-        if (!accept) continue;                          // wave-uniform
+        if (delta > __builtin_amdgcn_readlane(draw_most, slot)) continue;     // rejected (wave-uniform)
         t = lane == p ? node_q : (lane == q ? node_p : t);
         cur += delta;
         ++acc;
@@ -501,11 +497,8 @@ __global__ __launch_bounds__(256) void sa_ring_n64_kernel(const int32_t* __restr
         const int d = 2 + (int)((((uint32_t)(w >> 22) & 0x1FFFFFu) * (uint32_t)(N - 3)) >> 21);
         const int b = (a + d) & (N - 1);
         const int u = (int)((uint32_t)w & 0x3FFFFFu) + 1;
-        const int e = 31 - __clz(u);
-        const int mant = u - (1 << e);
-        const int frac = e >= 12 ? (mant >> (e - 12)) : (mant << (12 - e));
         const int slot = (int)step & (kDrawRing - 1);
-        *(int2*)(draws + 2 * slot) = make_int2(a | (b << 16), 22 * 4096 - (e * 4096 + frac));
+        *(int2*)(draws + 2 * slot) = make_int2(a | (b << 16), largest_accepted_increase(step, steps, t_start, t_end, u));
     };
     draw_block(0);
     draw_block(kWave);
@@ -525,12 +518,7 @@ __global__ __launch_bounds__(256) void sa_ring_n64_kernel(const int32_t* __restr
         const int ap = (a + N - 1) & (N - 1), bp = (b + N - 1) & (N - 1);
         const int ta = node_at(a, t), tap = node_at(ap, t), tb = node_at(b, t), tbp = node_at(bp, t);
         const int delta = M(tap, tbp) + M(ta, tb) - M(ta, tap) - M(tb, tbp);
-        bool accept = active;
-        if (delta > 0) {
-            const long long E = drawn_step.y;
-            const long long num = (long long)t_start * (steps - step) + (long long)t_end * step;
-            accept = active && ((long long)delta * 4096 * steps <= num * E);
-        }
+        const bool accept = active && delta <= drawn_step.y;
         const unsigned long long mask = __ballot(accept);
         if (mask == 0ull) {
             s += kWave;

@@ -67,3 +67,28 @@ def test_full_size_n64_10000_probes():
     rng = np.random.default_rng(10)
     s = rng.integers(100, 30000, size=(64, 64, 10000), dtype=np.int32)
     check(s, 10, True)
+
+
+def test_whole_pipeline_probes_to_order_stays_on_the_device():
+    """The method end to end (Sections 4.2 and 4.3) without a host round trip: probes -> cost matrix -> annealing ->
+    2-opt from the chains' orders -> the winner scored again by the batch call.  Every stage equals the oracle's, and
+    the reported cost is the ring cost of the reported order."""
+    say("pipeline N=64: probes -> matrix -> annealing -> 2-opt -> batch cost of the winner")
+    samples = probe_samples(make_matrix(2), 300, seed=11)
+    chains, steps, seed = 32, 4000, 2105
+    c_dev = cc.cc_cost_matrix_from_probes(dev(samples), 10, True)
+    annealed = cc.cc_sa_search_ex(c_dev, chains, steps, 300, 0, seed)
+    polished = cc.cc_2opt_search_ex(c_dev, cc.CC_RING_SUM, chains, seed, init_tours=annealed.restart_tours.clone())
+    again = cc.cc_ring_cost_batch(c_dev, polished.best_perm.view(1, 64), cc.CC_RING_SUM)
+    hd = cc.cc_rd_cost_batch(c_dev, polished.best_perm.view(1, 64))
+    torch.cuda.synchronize()
+    c = oracle.cost_matrix_from_probes(samples, 10, True)
+    sa = oracle.sa_search(c, chains, steps, 300, 0, seed)
+    want = oracle.search(c, oracle.SUM, chains, seed, init=sa["tours"])
+    assert np.array_equal(c_dev.cpu().numpy(), c)
+    assert np.array_equal(annealed.restart_tours.cpu().numpy(), sa["tours"])
+    assert np.array_equal(polished.restart_tours.cpu().numpy(), want["tours"])
+    best = polished.best_perm.cpu().numpy()
+    assert np.array_equal(best, want["best_perm"]) and int(polished.best_cost.item()) == want["best_cost"]
+    assert int(again.item()) == want["best_cost"] == oracle.ring_cost(c, best, oracle.SUM)
+    assert int(hd.item()) == int(oracle.rd_cost_batch(c, best.reshape(1, 64))[0])

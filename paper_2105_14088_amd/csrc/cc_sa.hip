@@ -47,7 +47,9 @@ __device__ __forceinline__ int largest_accepted_increase(long long step, long lo
     return (int)((num * E) / (4096ull * (unsigned long long)(steps > 0 ? steps : 1)));       // below 22 * 2^21
 }
 
-template <bool LDS_MATRIX>
+// MAT: where the matrix is read from - 0 through L2, 1 staged in LDS as int32 (N <= 128), 2 staged in LDS as 16-bit
+// entries (N <= 256) when every entry is in 0 .. 2^16 - 1 (found while staging), else through L2.
+template <int MAT>
 __global__ __launch_bounds__(256) void sa_ring_kernel(const int32_t* __restrict__ c, int N, int chains,
                                                       long long steps, int t_start, int t_end, uint64_t seed,
                                                       int32_t* __restrict__ tours, int64_t* __restrict__ costs,
@@ -58,15 +60,36 @@ __global__ __launch_bounds__(256) void sa_ring_kernel(const int32_t* __restrict_
     int32_t* t = sm + 8 * kDrawRing + wv * 2 * N;        // current order
     int32_t* bt = t + N;                                 // best order so far
     const int32_t* mat = c;
-    if (LDS_MATRIX) {
+    const uint16_t* m16 = nullptr;
+    bool narrow = false;                                 // MAT == 2: the 16-bit copy holds the matrix
+    if (MAT == 1) {
         int32_t* m = sm + 8 * kDrawRing + 8 * N;
         for (int e = threadIdx.x; e < N * N; e += 256) m[e] = clampi(c[e], 0, kCostMax);
         __syncthreads();
         mat = m;
     }
+    if (MAT == 2) {
+        uint16_t* m = (uint16_t*)(sm + 8 * kDrawRing + 8 * N);
+        __shared__ unsigned wave_top[4];
+        unsigned top = 0;
+        for (int e = threadIdx.x; e < N * N; e += 256) {
+            const unsigned v = (unsigned)c[e];           // a negative entry counts as too large
+            top = max(top, v);
+            m[e] = (uint16_t)v;
+        }
+        top = (unsigned)wave_max((int)min(top, 0x7fffffffu));
+        if (lane == 0) wave_top[wv] = top;
+        __syncthreads();
+        narrow = max(max(wave_top[0], wave_top[1]), max(wave_top[2], wave_top[3])) < (1u << 16);
+        m16 = m;
+    }
     const int64_t r = (int64_t)blockIdx.x * 4 + wv;
     if (r >= chains) return;
-    auto M = [&](int x, int y) { return LDS_MATRIX ? mat[x * N + y] : clampi(mat[x * N + y], 0, kCostMax); };
+    auto M = [&](int x, int y) {
+        if (MAT == 1) return mat[x * N + y];
+        if (MAT == 2 && narrow) return (int)m16[x * N + y];
+        return clampi(c[x * N + y], 0, kCostMax);
+    };
 
     for (int p = lane; p < N; p += kWave) {
         const int v = clampi(tours[r * N + p], 0, N - 1);
@@ -560,15 +583,22 @@ hipError_t launch_sa_ring(const int32_t* c, int N, int chains, long long steps, 
     } else if (N <= 128) {
         const size_t lds = sizeof(int32_t) * ((size_t)8 * kDrawRing + (size_t)8 * N + (size_t)N * N);
         if (lds > 48 * 1024) {
-            hipError_t e = hipFuncSetAttribute((const void*)sa_ring_kernel<true>,
+            hipError_t e = hipFuncSetAttribute((const void*)sa_ring_kernel<1>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
         }
-        hipLaunchKernelGGL((sa_ring_kernel<true>), dim3(grid), dim3(256), lds, s, c, N, chains, steps, t_start, t_end,
+        hipLaunchKernelGGL((sa_ring_kernel<1>), dim3(grid), dim3(256), lds, s, c, N, chains, steps, t_start, t_end,
                            seed, tours, costs, accepted);
+    } else if (N <= 256) {
+        const size_t lds = sizeof(int32_t) * ((size_t)8 * kDrawRing + (size_t)8 * N) + sizeof(uint16_t) * (size_t)N * N;
+        hipError_t e = hipFuncSetAttribute((const void*)sa_ring_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((sa_ring_kernel<2>), dim3(grid), dim3(256), lds, s, c, N, chains, steps, t_start, t_end, seed,
+                           tours, costs, accepted);
     } else {
         const size_t lds = sizeof(int32_t) * ((size_t)8 * kDrawRing + (size_t)8 * N);
-        hipLaunchKernelGGL((sa_ring_kernel<false>), dim3(grid), dim3(256), lds, s, c, N, chains, steps, t_start, t_end,
+        hipLaunchKernelGGL((sa_ring_kernel<0>), dim3(grid), dim3(256), lds, s, c, N, chains, steps, t_start, t_end,
                            seed, tours, costs, accepted);
     }
     return hipGetLastError();

@@ -55,6 +55,16 @@ def test_extreme_costs_and_temperatures():
     check(c, 4, 3000, 1, 1, SEED)
 
 
+@pytest.mark.parametrize("n", [200, 256])
+def test_ring_chains_at_the_16_bit_boundary_n_up_to_256(n):
+    """128 < N <= 256: the matrix as 16-bit entries in LDS when every entry is below 2^16, through L2 otherwise."""
+    for top in ((1 << 16) - 1, 1 << 16, COST_MAX):
+        say(f"sa N={n} largest entry {top}")
+        c = random_matrix(n, 300 + n + top % 5, symmetric=True, lo=max(1, top - 30000), hi=top)
+        c[1, 4] = c[4, 1] = top
+        check(c, 5, 2000, 20000, 50, SEED + top % 9)
+
+
 def test_given_initial_orders_and_duplicates_in_cost():
     say("sa init tours / ties")
     n = 32

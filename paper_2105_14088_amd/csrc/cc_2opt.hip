@@ -315,7 +315,22 @@ hipError_t launch_2opt(const int32_t* c, int N, int objective, int classes, int 
                        bool tours_hold_init, int32_t* tours, int64_t* costs, int32_t* moves, int32_t* flags,
                        uint16_t* mat16, int32_t* best_perm, int64_t* best_cost, int32_t* best_restart, hipStream_t s) {
     hipError_t e;
-    if (classes != kMoves2opt) {
+    const bool flip = classes == (kMoves2opt | kMovesFlip);      // only defined with the directed objectives
+    if (flip && N == 64 && objective == 3) {
+        e = launch_2opt_max_n64(c, restarts, seed, !tours_hold_init, true, tours, costs, moves, s);
+    } else if ((flip || classes == kMoves2opt) && N == 64 && objective == 2) {
+        // directed sum: wavefront kernel with 32-bit keys when max(c) < 2^16, else the general kernel (both enqueued,
+        // the matrix maximum computed on the device decides)
+        if (!tours_hold_init) {
+            e = launch_init_tours(N, 0, restarts, seed, tours, s);
+            if (e != hipSuccess) return e;
+        }
+        e = launch_matrix_max(c, N, flags, s);
+        if (e != hipSuccess) return e;
+        e = launch_2opt_dsum_n64(c, restarts, seed, false, flip, tours, costs, moves, flags, s);
+        if (e != hipSuccess) return e;
+        e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, flip, s);
+    } else if (classes != kMoves2opt) {
         // wider move sets: the segment-insertion kernel (ring sum) or the general kernel with the orientation flip
         if (!tours_hold_init) {
             e = launch_init_tours(N, 0, restarts, seed, tours, s);
@@ -328,19 +343,7 @@ hipError_t launch_2opt(const int32_t* c, int N, int objective, int classes, int 
     } else if (N == 64 && objective == 0) {
         e = launch_2opt_sum_n64(c, restarts, seed, !tours_hold_init, tours, costs, moves, s);
     } else if (N == 64 && (objective & 1)) {
-        e = launch_2opt_max_n64(c, restarts, seed, !tours_hold_init, tours, costs, moves, s);
-    } else if (N == 64 && objective == 2) {
-        // directed sum: wavefront kernel with 32-bit keys when max(c) < 2^16, else the general kernel (both enqueued,
-        // the matrix maximum computed on the device decides)
-        if (!tours_hold_init) {
-            e = launch_init_tours(N, 0, restarts, seed, tours, s);
-            if (e != hipSuccess) return e;
-        }
-        e = launch_matrix_max(c, N, flags, s);
-        if (e != hipSuccess) return e;
-        e = launch_2opt_dsum_n64(c, restarts, seed, false, tours, costs, moves, flags, s);
-        if (e != hipSuccess) return e;
-        e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, false, s);
+        e = launch_2opt_max_n64(c, restarts, seed, !tours_hold_init, false, tours, costs, moves, s);
     } else {
         if (!tours_hold_init) {
             e = launch_init_tours(N, 0, restarts, seed, tours, s);

@@ -29,7 +29,7 @@ using namespace w64;
 constexpr int kNone = 0x7fffffff;
 
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2)))
-void twoopt_dsum_n64_kernel(const int32_t* __restrict__ c, int restarts, uint64_t seed, int generate,
+void twoopt_dsum_n64_kernel(const int32_t* __restrict__ c, int restarts, uint64_t seed, int generate, int with_flip,
                             int32_t* __restrict__ tours, int64_t* __restrict__ costs, int32_t* __restrict__ moves,
                             const int32_t* __restrict__ flags) {
     if (flags[0] >= (1 << 16)) return;             // keys would not fit: the general kernel does the work
@@ -96,6 +96,10 @@ void twoopt_dsum_n64_kernel(const int32_t* __restrict__ c, int restarts, uint64_
             const int kid = ij * 2 + (which ^ flip);
             if (kv < val || (kv == val && kid < id)) { val = kv; id = kid; }
         }
+        if (with_flip && lane == 0) {                   // the orientation flip: every hop walked the other way
+            const int idf = (kN + kN - 1) * 2;
+            if (turn < val || (turn == val && idf < id)) { val = turn; id = idf; }
+        }
         const int dwin = wave_min_uniform(val);
         if (dwin >= 0) break;
         const int idwin = wave_min_uniform(val == dwin ? id : kNone);
@@ -115,11 +119,11 @@ void twoopt_dsum_n64_kernel(const int32_t* __restrict__ c, int restarts, uint64_
 
 }  // namespace
 
-hipError_t launch_2opt_dsum_n64(const int32_t* c, int restarts, uint64_t seed, bool generate, int32_t* tours,
-                                int64_t* costs, int32_t* moves, const int32_t* flags, hipStream_t s) {
+hipError_t launch_2opt_dsum_n64(const int32_t* c, int restarts, uint64_t seed, bool generate, bool with_flip,
+                                int32_t* tours, int64_t* costs, int32_t* moves, const int32_t* flags, hipStream_t s) {
     const int grid = (restarts + 3) / 4;
-    hipLaunchKernelGGL(twoopt_dsum_n64_kernel, dim3(grid), dim3(256), 0, s, c, restarts, seed, generate ? 1 : 0, tours,
-                       costs, moves, flags);
+    hipLaunchKernelGGL(twoopt_dsum_n64_kernel, dim3(grid), dim3(256), 0, s, c, restarts, seed, generate ? 1 : 0,
+                       with_flip ? 1 : 0, tours, costs, moves, flags);
     return hipGetLastError();
 }
 

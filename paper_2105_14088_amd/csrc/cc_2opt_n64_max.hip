@@ -40,7 +40,8 @@ constexpr int kCostMax = (1 << 21) - 1;
 constexpr int kNone = 0x7fffffff;
 
 // The sweep on a plain int32 matrix (entries up to 2^21 - 1).
-__device__ __forceinline__ void descend_max_wide(const int32_t* m, int lane, int& t, int& cur_out, int& applied_out) {
+__device__ __forceinline__ void descend_max_wide(const int32_t* m, int lane, bool with_flip, int& t, int& cur_out,
+                                                 int& applied_out) {
     const char* mbytes = (const char*)m;
     const int rank_a = (lane + kN - 1) & (kN - 1);
     // byte indices for lane permutes "take the value of lane p + k"
@@ -115,6 +116,10 @@ __device__ __forceinline__ void descend_max_wide(const int32_t* m, int lane, int
             const int kid = ij * 2 + (which ^ flip);
             if (kv < val || (kv == val && kid < id)) { val = kv; id = kid; }
         }
+        if (with_flip && lane == 0) {                   // the orientation flip: every hop walked the other way
+            const int vf = max(m5b, far_b), idf = (kN + kN - 1) * 2;
+            if (vf < val || (vf == val && idf < id)) { val = vf; id = idf; }
+        }
         const int vwin = wave_min_uniform(val);
         if (vwin >= cur) break;
         const int idwin = wave_min_uniform(val == vwin ? id : kNone);
@@ -136,7 +141,7 @@ __device__ __forceinline__ unsigned pk_max(unsigned a, unsigned b) {
 }
 
 // The sweep on the packed matrix m2[x][y] = c[x][y] | c[y][x] << 16 (entries below 2^16).
-__device__ __forceinline__ void descend_max_packed(const int32_t* m2, int lane, int& t, int& cur_out,
+__device__ __forceinline__ void descend_max_packed(const int32_t* m2, int lane, bool with_flip, int& t, int& cur_out,
                                                    int& applied_out) {
     const char* mbytes = (const char*)m2;
     const int rank_a = (lane + kN - 1) & (kN - 1);
@@ -206,6 +211,10 @@ __device__ __forceinline__ void descend_max_packed(const int32_t* m2, int lane, 
             const int kid = ij * 2 + (which ^ flip);
             if (kv < val || (kv == val && kid < id)) { val = kv; id = kid; }
         }
+        if (with_flip && lane == 0) {                   // the orientation flip: every hop walked the other way
+            const int vf = (int)(pk_max(m5, far) & 0xffffu), idf = (kN + kN - 1) * 2;
+            if (vf < val || (vf == val && idf < id)) { val = vf; id = idf; }
+        }
         const int vwin = wave_min_uniform(val);
         if (vwin >= cur) break;
         const int idwin = wave_min_uniform(val == vwin ? id : kNone);
@@ -221,7 +230,7 @@ __device__ __forceinline__ void descend_max_packed(const int32_t* m2, int lane, 
 }
 
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2)))
-void twoopt_max_n64_kernel(const int32_t* __restrict__ c, int restarts, uint64_t seed, int generate,
+void twoopt_max_n64_kernel(const int32_t* __restrict__ c, int restarts, uint64_t seed, int generate, int with_flip,
                            int32_t* __restrict__ tours, int64_t* __restrict__ costs,
                            int32_t* __restrict__ moves) {
     __shared__ __attribute__((aligned(256))) int32_t m[kN * kN];
@@ -262,8 +271,8 @@ void twoopt_max_n64_kernel(const int32_t* __restrict__ c, int restarts, uint64_t
     if (r >= restarts) return;
 
     int cur, applied;
-    if (packed) descend_max_packed(m, lane, t, cur, applied);
-    else descend_max_wide(m, lane, t, cur, applied);
+    if (packed) descend_max_packed(m, lane, with_flip != 0, t, cur, applied);
+    else descend_max_wide(m, lane, with_flip != 0, t, cur, applied);
     tours[r * kN + lane] = t;
     if (lane == 0) {
         costs[r] = (int64_t)cur;
@@ -273,11 +282,11 @@ void twoopt_max_n64_kernel(const int32_t* __restrict__ c, int restarts, uint64_t
 
 }  // namespace
 
-hipError_t launch_2opt_max_n64(const int32_t* c, int restarts, uint64_t seed, bool generate, int32_t* tours,
-                               int64_t* costs, int32_t* moves, hipStream_t s) {
+hipError_t launch_2opt_max_n64(const int32_t* c, int restarts, uint64_t seed, bool generate, bool with_flip,
+                               int32_t* tours, int64_t* costs, int32_t* moves, hipStream_t s) {
     const int grid = (restarts + 3) / 4;
-    hipLaunchKernelGGL(twoopt_max_n64_kernel, dim3(grid), dim3(256), 0, s, c, restarts, seed, generate ? 1 : 0, tours,
-                       costs, moves);
+    hipLaunchKernelGGL(twoopt_max_n64_kernel, dim3(grid), dim3(256), 0, s, c, restarts, seed, generate ? 1 : 0,
+                       with_flip ? 1 : 0, tours, costs, moves);
     return hipGetLastError();
 }
 

@@ -59,12 +59,12 @@ hipError_t launch_2opt_sum_n64(const int32_t* c, int restarts, uint64_t seed, bo
                                int64_t* costs, int32_t* moves, hipStream_t s);
 
 // N = 64, max-hop objective, directed or undirected: one wavefront per restart (cc_2opt_n64_max.hip).
-hipError_t launch_2opt_max_n64(const int32_t* c, int restarts, uint64_t seed, bool generate, int32_t* tours,
+hipError_t launch_2opt_max_n64(const int32_t* c, int restarts, uint64_t seed, bool generate, bool with_flip, int32_t* tours,
                                int64_t* costs, int32_t* moves, hipStream_t s);
 
 // N = 64, directed ring-sum objective, max(c) < 2^16: one wavefront per restart (cc_2opt_n64_dsum.hip); returns at once
 // if flags[0] >= 2^16 (flags[0] = matrix maximum, launch_matrix_max).
-hipError_t launch_2opt_dsum_n64(const int32_t* c, int restarts, uint64_t seed, bool generate, int32_t* tours,
+hipError_t launch_2opt_dsum_n64(const int32_t* c, int restarts, uint64_t seed, bool generate, bool with_flip, int32_t* tours,
                                 int64_t* costs, int32_t* moves, const int32_t* flags, hipStream_t s);
 
 // N = 128 / 192 / 256, ring-sum objective, max(c) < 2^16: one wavefront per restart, 16-bit matrix in LDS

@@ -7,6 +7,7 @@ import re
 import shutil
 import subprocess
 import tempfile
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libcc.so")
@@ -14,7 +15,7 @@ SOURCES = sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")))
 HEADERS = sorted(glob.glob(os.path.join(HERE, "csrc", "*.h"))) + [os.path.join(os.path.dirname(HERE), "include", "cc.h")]
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # packed-FP32 instruction selection off (integer-only code, but applies to every HIP translation unit)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
@@ -52,11 +53,23 @@ def build(force: bool = True, verbose: bool = False) -> str:
         # library is put in place
         with tempfile.TemporaryDirectory(prefix="cc_build_") as tmp:
             out = os.path.join(tmp, "libcc.so")
-            cmd = [hipcc] + HIPCC_FLAGS + ["-save-temps"] + SOURCES + ["-o", out]
-            if verbose:
-                print(" ".join(cmd))
-            subprocess.check_call(cmd, cwd=tmp)
+
+            def compile_one(src: str) -> str:
+                obj = os.path.join(tmp, os.path.basename(src) + ".o")
+                cmd = [hipcc] + HIPCC_FLAGS + ["-save-temps", "-c", src, "-o", obj]
+                if verbose:
+                    print(" ".join(cmd), flush=True)
+                subprocess.check_call(cmd, cwd=tmp)
+                return obj
+
+            # one translation unit per source, a few at a time
+            with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as pool:
+                objects = list(pool.map(compile_one, SOURCES))
             check_device_isa(tmp)
+            link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objects + ["-o", out]
+            if verbose:
+                print(" ".join(link), flush=True)
+            subprocess.check_call(link, cwd=tmp)
             shutil.move(out, LIB_PATH)
     return LIB_PATH
 

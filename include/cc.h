@@ -45,6 +45,7 @@ extern "C" {
 #define CC_COST_MAX ((1 << 21) - 1)
 #define CC_SA_MAX_STEPS (1 << 24)
 #define CC_MAX_PROBES 16384
+#define CC_STATIC_SCRATCH_BYTES (8u << 20)
 
 typedef enum {
     CC_OK = 0,
@@ -53,7 +54,8 @@ typedef enum {
     CC_ERR_WORKSPACE = -3,       /* workspace missing or smaller than cc_2opt_workspace_bytes() */
     CC_ERR_HIP = -4,             /* a HIP runtime call failed; see cc_last_hip_error() */
     CC_ERR_NOT_SYMMETRIC = -5,   /* cc_validate_matrix: matrix is not symmetric */
-    CC_ERR_COST_RANGE = -6       /* cc_validate_matrix: an entry is outside [0, CC_COST_MAX] */
+    CC_ERR_COST_RANGE = -6,      /* cc_validate_matrix: an entry is outside [0, CC_COST_MAX] */
+    CC_ERR_SCRATCH_LIMIT = -7    /* cc_2opt_search_noalloc: the search needs more than CC_STATIC_SCRATCH_BYTES */
 } cc_status;
 
 /* Objectives over the ring (Section 4.1, ring model).  SUM is the paper's sum of hop costs; MAX is
@@ -248,6 +250,23 @@ int cc_best_of_restarts(const int64_t* restart_costs, const int32_t* restart_tou
 
 /* Bytes of workspace cc_2opt_search_ex needs (0 on invalid arguments). Host-only computation. */
 size_t cc_2opt_workspace_bytes(int32_t N, int32_t objective, int32_t restarts);
+
+/*
+ * cc_2opt_search for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): same arguments, same result, but the per-restart costs, move counts
+ * and orders (and the 16-bit matrix copy of N > 256) live in a static device array of CC_STATIC_SCRATCH_BYTES
+ * (8 MiB) that every GPU the library runs on holds until the process ends.  The call allocates and frees nothing;
+ * it only enqueues kernels on `stream`.
+ *   Limit.  cc_2opt_workspace_bytes(N, objective, restarts) must not exceed CC_STATIC_SCRATCH_BYTES (for example
+ *   N = 64 with up to 31,000 restarts, N = 256 with up to 8,000, N = 1024 with up to 1,500); otherwise the call
+ *   returns CC_ERR_SCRATCH_LIMIT and launches nothing.
+ *   Sharing.  All calls on one GPU use that GPU's one array, which keeps the previous call's contents (the search
+ *   overwrites every part it reads, so nothing has to be cleared).  Two calls that overlap in time on one GPU -
+ *   different streams, or different host threads - race on it; the caller serialises them.
+ *   The device that is current when the call is made must be the device of `stream` and of the buffers.
+ */
+int cc_2opt_search_noalloc(const int32_t* cost_matrix, int32_t N, int32_t objective, int32_t restarts, uint64_t seed,
+                           int32_t* best_perm, int64_t* best_cost, void* stream);
 
 /*
  * Multi-start pair-swap search under the halving-doubling model (Section 4.3: neighbours obtained by

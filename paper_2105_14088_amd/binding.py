@@ -23,7 +23,7 @@ CC_COST_MAX = (1 << 21) - 1
 # every symbol include/cc.h declares
 EXPORTS = ["cc_ring_cost_batch", "cc_ring_cost_batch_u8", "cc_ring_cost_batch_u16", "cc_rd_cost_batch",
            "cc_rd_cost_batch_ex", "cc_rd_batch_workspace_bytes", "cc_bcube_cost_batch", "cc_bcube_cost_batch_ex",
-           "cc_bcube_cost_batch_weighted", "cc_dbt_cost_batch", "cc_2opt_search", "cc_2opt_search_ex",
+           "cc_bcube_cost_batch_weighted", "cc_dbt_cost_batch", "cc_2opt_search", "cc_2opt_search_ex", "cc_2opt_search_noalloc",
            "cc_2opt_workspace_bytes", "cc_local_search", "cc_local_search_ex", "cc_best_of_restarts", "cc_rd_swap_search", "cc_rd_swap_search_ex",
            "cc_rd_swap_workspace_bytes", "cc_sa_search", "cc_sa_search_ex", "cc_sa_workspace_bytes", "cc_sa_rd_search",
            "cc_sa_rd_search_ex", "cc_init_tours", "cc_cost_matrix_from_probes", "cc_validate_matrix",
@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.cc_dbt_cost_batch.argtypes = [p, i32, p, i64, p, p]
         L.cc_2opt_search.restype = ctypes.c_int
         L.cc_2opt_search.argtypes = [p, i32, i32, i32, u64, p, p, p]
+        L.cc_2opt_search_noalloc.restype = ctypes.c_int
+        L.cc_2opt_search_noalloc.argtypes = [p, i32, i32, i32, u64, p, p, p]
         L.cc_2opt_search_ex.restype = ctypes.c_int
         L.cc_2opt_search_ex.argtypes = [p, i32, i32, i32, u64, p, p, p, p, p, p, p, p, sz, p]
         L.cc_local_search.restype = ctypes.c_int
@@ -282,6 +284,19 @@ def cc_2opt_search(cost_matrix: torch.Tensor, objective: int, restarts: int, see
                                 seed & (2**64 - 1), _dev(best_perm, torch.int32, "best_perm"),
                                 _dev(best_cost, torch.int64, "best_cost"), _stream(stream)), "cc_2opt_search")
     return best_perm, best_cost
+
+
+def cc_2opt_search_noalloc(cost_matrix: torch.Tensor, objective: int, restarts: int, seed: int,
+                           best_perm: torch.Tensor, best_cost: torch.Tensor, stream=None) -> None:
+    """cc_2opt_search with the library's static device scratch array; writes into the caller's best_perm (int32 [N])
+    and best_cost (int64 [1]).  Nothing is allocated, here or in the library."""
+    n = _matrix(cost_matrix)
+    if best_perm.numel() != n or best_cost.numel() != 1:
+        raise ValueError("best_perm must be [N], best_cost [1]")
+    _check(lib().cc_2opt_search_noalloc(_dev(cost_matrix, torch.int32, "cost_matrix"), n, objective, restarts,
+                                        seed & (2**64 - 1), _dev(best_perm, torch.int32, "best_perm"),
+                                        _dev(best_cost, torch.int64, "best_cost"), _stream(stream)),
+           "cc_2opt_search_noalloc")
 
 
 class SearchBuffers:

@@ -2,6 +2,8 @@
 // Declarations and contracts: include/cc.h.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "../../include/cc.h"
 #include "cc_internal.h"
 
@@ -44,6 +46,31 @@ WsLayout ws_layout(int N, int restarts) {
 int check_matrix_args(const int32_t* c, int N) {
     if (!c) return CC_ERR_INVALID_ARG;
     if (N < 2 || N > CC_MAX_N) return CC_ERR_UNSUPPORTED_N;
+    return CC_OK;
+}
+
+// Device memory of cc_2opt_search_noalloc: one array per GPU, part of the code object, there from the moment the
+// library is loaded on a device until the process ends.  In host code the name `scratch` is only a handle for
+// hipGetSymbolAddress; the array's memory is reached through the per-device pointer that call returns.
+static __device__ __align__(256) unsigned char scratch[CC_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of the current device's scratch array (looked up once per device, with that device current).
+int static_scratch(void** out) {
+    int dev = -1;
+    CC_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return CC_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        CC_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr || ((uintptr_t)ptr & 255u)) return CC_ERR_WORKSPACE;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
     return CC_OK;
 }
 
@@ -256,6 +283,18 @@ int cc_2opt_search(const int32_t* cost_matrix, int32_t N, int32_t objective, int
     return ring_search(cost_matrix, N, objective, CC_MOVES_2OPT, restarts, seed, best_perm, best_cost, stream);
 }
 
+int cc_2opt_search_noalloc(const int32_t* cost_matrix, int32_t N, int32_t objective, int32_t restarts, uint64_t seed,
+                           int32_t* best_perm, int64_t* best_cost, void* stream) {
+    if (int rc = check_matrix_args(cost_matrix, N)) return rc;
+    if (objective < 0 || objective > 3 || restarts < 1 || !best_perm || !best_cost) return CC_ERR_INVALID_ARG;
+    const size_t bytes = cc_2opt_workspace_bytes(N, objective, restarts);
+    if (bytes == 0 || bytes > (size_t)CC_STATIC_SCRATCH_BYTES) return CC_ERR_SCRATCH_LIMIT;
+    void* ws = nullptr;
+    if (int rc = static_scratch(&ws)) return rc;
+    return ring_search_ex(cost_matrix, N, objective, CC_MOVES_2OPT, restarts, seed, nullptr, best_perm, best_cost,
+                          nullptr, nullptr, nullptr, nullptr, ws, bytes, stream);
+}
+
 size_t cc_rd_swap_workspace_bytes(int32_t N, int32_t restarts) {
     if (N < 2 || N > CC_MAX_N || !is_pow2(N) || restarts < 1) return 0;
     return ws_layout(N, restarts).total;       // flags, costs, moves, tours, folded 16-bit matrix (N > 256)
@@ -425,6 +464,7 @@ const char* cc_status_string(int status) {
         case CC_ERR_HIP: return "HIP runtime error";
         case CC_ERR_NOT_SYMMETRIC: return "cost matrix is not symmetric";
         case CC_ERR_COST_RANGE: return "cost matrix entry out of range";
+        case CC_ERR_SCRATCH_LIMIT: return "search too large for the static scratch array (CC_STATIC_SCRATCH_BYTES)";
         default: return "unknown status";
     }
 }

@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 def test_version_and_status_strings():
     assert cc.cc_version() >= 100
     seen = set()
-    for s in range(0, -7, -1):
+    for s in range(0, -8, -1):
         txt = cc.cc_status_string(s)
         assert txt and txt != "unknown status" and txt not in seen
         seen.add(txt)

@@ -132,9 +132,11 @@ def _declare(path: str) -> ctypes.CDLL:
 
 
 def _L():
+    """The oracle library: built from cc_oracle.c on first use, or, when CC_ORACLE_LIB names a file, that build of
+    the same source (the sanitizer test points it at an instrumented one)."""
     global _lib
     if _lib is None:
-        _lib = _declare(build())
+        _lib = _declare(os.environ.get("CC_ORACLE_LIB") or build())
     return _lib
 
 

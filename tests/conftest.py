@@ -17,10 +17,12 @@ def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
 
 
-@pytest.fixture(scope="session", autouse=True)
+@pytest.fixture(scope="session")
 def built_library():
-    """The tests load the library that is built in-tree; only when there is none do they build it (hipcc cross-compiles
-    without a GPU).  After a change to a source, build again before running the tests."""
+    """Requested by the tests that call the HIP library (the GPU parity tests and the ABI checks); the oracle's pins
+    need neither the HIP toolchain nor the product package and do not request it.  The tests load the library that
+    is built in-tree; only when there is none do they build it (hipcc cross-compiles without a GPU).  After a change
+    to a source, build again before running the tests."""
     from paper_2105_14088_amd.build import LIB_PATH, build
     if not os.path.exists(LIB_PATH):
         build(force=True)

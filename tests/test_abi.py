@@ -9,6 +9,7 @@ import pytest
 import paper_2105_14088_amd as cc
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+pytestmark = pytest.mark.usefixtures("built_library")
 
 
 def _declared_symbols():

@@ -18,6 +18,7 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 
 
 @pytest.mark.gpu
+@pytest.mark.usefixtures("built_library")
 def test_one_json_line_with_roofline_and_cpu_baseline():
     p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--steps", "3", "--warmup", "1"],
                        capture_output=True, text=True, timeout=600)

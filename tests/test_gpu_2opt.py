@@ -12,7 +12,7 @@ import paper_2105_14088_amd as cc
 from gen import COST_MAX, WORKLOADS, make_matrix, random_matrix, random_perms
 from gpu_util import assert_search_equal, dev, gpu_search, say
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("built_library")]
 THREADS = min(16, os.cpu_count() or 1)
 
 

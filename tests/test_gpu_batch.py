@@ -9,7 +9,7 @@ import paper_2105_14088_amd as cc
 from gen import COST_MAX, WORKLOADS, make_matrix, random_matrix, random_perms
 from gpu_util import dev, gpu_rd, gpu_ring, say
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("built_library")]
 
 
 def test_workload1_all_2520_rings_and_4096_seeded_orders():

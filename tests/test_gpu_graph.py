@@ -9,7 +9,7 @@ import paper_2105_14088_amd as cc
 from gen import WORKLOADS, make_matrix
 from gpu_util import say
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("built_library")]
 
 
 def test_search_and_batch_calls_replay_in_a_graph():

@@ -10,7 +10,7 @@ import paper_2105_14088_amd as cc
 from gen import COST_MAX, WORKLOADS, make_matrix, random_matrix, random_perms
 from gpu_util import assert_search_equal, dev, say
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("built_library")]
 OROPT, BOTH, FLIP = cc.CC_MOVES_OROPT, cc.CC_MOVES_2OPT | cc.CC_MOVES_OROPT, cc.CC_MOVES_2OPT | cc.CC_MOVES_FLIP
 
 

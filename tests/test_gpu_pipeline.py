@@ -10,7 +10,7 @@ import paper_2105_14088_amd as cc
 from gen import make_matrix, probe_samples
 from gpu_util import dev, say
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("built_library")]
 
 
 def test_probes_to_rank_order_n64():

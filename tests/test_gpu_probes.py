@@ -8,7 +8,7 @@ import paper_2105_14088_amd as cc
 from gen import COST_MAX, make_matrix, probe_samples
 from gpu_util import dev, say
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("built_library")]
 
 
 def check(s, q, sym):

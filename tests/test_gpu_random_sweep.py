@@ -10,7 +10,7 @@ import paper_2105_14088_amd as cc
 from gen import COST_MAX, random_matrix
 from gpu_util import assert_search_equal, dev, gpu_search, say
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("built_library")]
 
 SIZES = [4, 5, 7, 8, 15, 16, 17, 31, 32, 33, 47, 48, 63, 64, 65, 95, 96, 97, 100, 127, 128, 129, 160, 191, 192, 193, 200,
          255, 256]

@@ -9,7 +9,7 @@ import paper_2105_14088_amd as cc
 from gen import COST_MAX, WORKLOADS, make_matrix, random_matrix
 from gpu_util import dev, say
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("built_library")]
 SEED = 0xC0FFEE55
 
 

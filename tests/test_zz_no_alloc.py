@@ -13,7 +13,7 @@ import paper_2105_14088_amd as cc
 from gen import WORKLOADS, make_matrix, random_matrix
 from gpu_util import dev, say
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("built_library")]
 
 
 def _both(c, obj, restarts, seed):

@@ -27,3 +27,13 @@ def built_library():
     if not os.path.exists(LIB_PATH):
         build(force=True)
     return LIB_PATH
+
+
+def pytest_terminal_summary(terminalreporter):
+    """Coverage lines of the full-size GPU parity cases (restarts and orders compared with the oracle)."""
+    util = sys.modules.get("gpu_util")
+    lines = getattr(util, "SUMMARY", []) if util else []
+    if lines:
+        terminalreporter.section("full-size parity coverage")
+        for line in lines:
+            terminalreporter.write_line(line)

@@ -13,6 +13,15 @@ def say(msg: str):
     sys.stdout.flush()
 
 
+SUMMARY = []
+
+
+def report(msg: str):
+    """A line for the end of the test run (how much of a full-size case the oracle replayed), printed now as well."""
+    SUMMARY.append(msg)
+    say(msg)
+
+
 def dev(a: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 

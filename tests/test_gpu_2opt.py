@@ -228,11 +228,12 @@ def _certify(c, obj, tour, cost):
     assert oracle.all_move_values(c, obj, tour).min() >= cost
 
 
-def test_workload4_n256_sum_4096_restarts_full():
+def test_workload4_n256_sum_4096_restarts_full(capfd):
     """Full size on the GPU and in the oracle: every one of the 4096 restarts is replayed by the oracle (the same
     single-threaded routine over disjoint restart ranges on the host's cores) and compared - final order, cost,
     number of applied moves - and so is the winner."""
-    say(f"C4: N=256 sum, 4096 restarts, all replayed by the oracle on {THREADS} threads")
+    with capfd.disabled():
+        say(f"C4: N=256 sum, 4096 restarts, all replayed by the oracle on {THREADS} threads")
     c = make_matrix(4)
     seed = WORKLOADS[4].search_seed
     got = gpu_search(c, 0, 4096, seed)
@@ -255,7 +256,7 @@ C5_MIN_RESTARTS = 64
 C5_ORACLE_BUDGET_S = 420.0
 
 
-def test_workload5_n1024_sum_256_restarts_full():
+def test_workload5_n1024_sum_256_restarts_full(capfd):
     """Full size on the GPU.  The oracle needs several core-seconds per restart at N = 1024, so it replays the
     restarts in rounds of one per host thread, in a fixed order that starts with a spread over the whole range, until
     all 256 are done; on a host too slow for that within the time allowed it stops after at least 64 and says how
@@ -279,7 +280,8 @@ def test_workload5_n1024_sum_256_restarts_full():
                         moves=np.concatenate([p["moves"] for p in parts]))
             assert_search_equal(got, want, rows=rows)
             done += rows
-            say(f"C5: {len(done)} restarts compared after {time.time() - t0:.0f} s")
+            with capfd.disabled():          # a progress line per round, also when output is captured
+                say(f"C5: {len(done)} restarts compared after {time.time() - t0:.0f} s")
             if len(done) >= C5_MIN_RESTARTS and time.time() - t0 > C5_ORACLE_BUDGET_S:
                 break
     report(f"C5 (N=1024 sum): oracle replayed {len(done)} of 256 restarts on {THREADS} threads in {time.time() - t0:.1f} s")

@@ -264,7 +264,7 @@ def test_workload5_n1024_sum_256_restarts_full(capfd):
     c = make_matrix(5)
     seed = WORKLOADS[5].search_seed
     got = gpu_search(c, 0, 256, seed)
-    spread = [0, 131, 255] + list(range(3, 256, 4))
+    spread = list(dict.fromkeys([0, 131, 255] + list(range(3, 256, 4))))
     order = spread + [r for r in range(256) if r not in set(spread)]
     assert sorted(order) == list(range(256))
     say(f"C5: N=1024 sum, 256 restarts, oracle on {THREADS} threads")

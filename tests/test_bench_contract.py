@@ -47,3 +47,15 @@ def test_one_json_line_with_roofline_and_cpu_baseline():
     costs, _, moves = oracle.restarts(make_matrix(2), oracle.SUM, w.search_seed, 0, w.restarts)
     assert d["move_evals_per_step"] == int(((moves.astype(np.int64) + 1) * oracle.neighbourhood_size(w.n, oracle.SUM)).sum())
     assert d["best_cost"] == int(costs.min())
+    # the directed max-hop search of the same step, and the other roofline entries
+    w3 = WORKLOADS[3]
+    costs3, _, moves3 = oracle.restarts(make_matrix(3), oracle.MAX_DIRECTED, w3.search_seed, 0, w3.restarts)
+    assert d["move_evals_per_step_c3"] == int(((moves3.astype(np.int64) + 1)
+                                               * oracle.neighbourhood_size(w3.n, oracle.MAX_DIRECTED)).sum())
+    assert d["best_cost_c3"] == int(costs3.min())
+    r3 = d["roofline_c3"]
+    assert r3["bytes_per_move"] == 16 and abs(r3["frac"] - 2 * r3["frac_at_storage_width"]) < 1e-9
+    rb = d["roofline_batch"]
+    assert rb["bound"] == "hbm" and 0 < rb["frac_cold"] < 1 and rb["cold"]["batch"] == 1 << 22
+    # `value` is the rate of the whole search call, so it cannot exceed the rate of its search kernel alone
+    assert d["value"] <= d["move_evals_per_step"] / (r["kernel_ms"] * 1e-3) * 1.05

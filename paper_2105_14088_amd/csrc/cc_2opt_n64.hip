@@ -27,6 +27,7 @@
 #include "cc_device.h"
 #include "cc_internal.h"
 #include "cc_wave64.h"
+#include "cc_2opt_n64_loop.inc"
 
 namespace cc {
 using namespace ccd;
@@ -103,6 +104,31 @@ __device__ __forceinline__ void descend(const int32_t* m, int lane, int& t, long
     applied_out = applied;
 }
 
+// The same descent for matrices with entries below 2^16, as one hand-scheduled loop (cc_2opt_n64_loop.inc, written by
+// gen_2opt_n64_loop.py).  m holds c << 14.  State across sweeps: the order t and the hop array fm = f << 14 (hop into
+// rank `lane`), both one register per lane.  After a move that reverses ranks mi .. mj the hops of the reversed piece
+// are the old ones read from the other end (the matrix is symmetric), so fm follows the order by the same lane
+// permute, shifted by one rank, and only the two new hops are written: y = c[t[mi]][t[mj+1]] is the matrix entry the
+// winning lane gathered for its best candidate, x = c[t[mi-1]][t[mj]] = delta + f[mi] + f[mj+1] - y.
+__device__ __forceinline__ void descend_narrow(const int32_t* m, int lane, int& t, long long& cost, int& applied_out) {
+    const int rank_a = (lane + kN - 1) & (kN - 1);
+    const int rank_bits = rank_a << 8;
+    const int id_base = lane * kN, id_flip = kN + rank_a;
+    const int mbase = (int)(unsigned)(uintptr_t)(const char*)m;      // LDS byte offset of the matrix (256-byte aligned)
+    const int lane4 = lane << 2;
+    int applied = 0;
+    int fm = m[t * kN + from_prev_lane(t)];
+    int cur = wave_sum(fm >> kSh);
+    // every operand that is written is marked early-clobber: the loop writes them long before it has read the last input
+    asm volatile(CC_N64_DESCENT_LOOP_ASM
+                 : [t] "+&v"(t), [fm] "+&v"(fm), [cur] "+&s"(cur), [applied] "+&s"(applied)
+                 : [rank_bits] "v"(rank_bits), [ra] "v"(rank_a), [id_base] "v"(id_base), [id_flip] "v"(id_flip),
+                   [lane] "v"(lane), [lane4] "v"(lane4), [mbase] "s"(mbase), [mask] "s"(0xff), [himask] "s"(0xfffff000)
+                 : CC_N64_DESCENT_LOOP_CLOBBERS);
+    cost = cur;
+    applied_out = applied;
+}
+
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) void twoopt_sum_n64_kernel(const int32_t* __restrict__ c, int restarts,
                                                              uint64_t seed, int generate,
                                                              int32_t* __restrict__ tours,
@@ -144,7 +170,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
     long long cost;
     int applied;
     if (wide) descend<true>(m, lane, t, cost, applied);
-    else descend<false>(m, lane, t, cost, applied);
+    else descend_narrow(m, lane, t, cost, applied);
     tours[r * kN + lane] = t;
     if (lane == 0) {
         costs[r] = cost;

@@ -7,6 +7,9 @@
 // min-reduced over the workgroup, which makes the lowest-id tie-break independent of the order in
 // which moves are visited.  Handles every objective and every N <= 1024; the matrix sits in LDS for
 // N <= 96 and is gathered through L2 above.
+#include <cstdlib>
+#include <cstring>
+
 #include "cc_device.h"
 #include "cc_internal.h"
 
@@ -304,6 +307,11 @@ hipError_t launch_general_objective(const int32_t* c, int N, int objective, int 
 
 }  // namespace
 
+bool force_general_path() {
+    const char* v = getenv("CC_FORCE_PATH");
+    return v && strcmp(v, "general") == 0;
+}
+
 hipError_t launch_best_restart(const int64_t* costs, const int32_t* tours, int N, int restarts, int32_t* best_perm,
                                int64_t* best_cost, int32_t* best_restart, hipStream_t s) {
     hipLaunchKernelGGL(best_restart_kernel, dim3(1), dim3(restarts > 1024 ? 1024 : 256), 0, s, costs, tours, N, restarts,
@@ -316,7 +324,13 @@ hipError_t launch_2opt(const int32_t* c, int N, int objective, int classes, int 
                        uint16_t* mat16, int32_t* best_perm, int64_t* best_cost, int32_t* best_restart, hipStream_t s) {
     hipError_t e;
     const bool flip = classes == (kMoves2opt | kMovesFlip);      // only defined with the directed objectives
-    if (flip && N == 64 && objective == 3) {
+    if (force_general_path() && !(classes & kMovesOropt)) {
+        if (!tours_hold_init) {
+            e = launch_init_tours(N, 0, restarts, seed, tours, s);
+            if (e != hipSuccess) return e;
+        }
+        e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, nullptr, flip, s);
+    } else if (flip && N == 64 && objective == 3) {
         e = launch_2opt_max_n64(c, restarts, seed, !tours_hold_init, true, tours, costs, moves, s);
     } else if ((flip || classes == kMoves2opt) && N == 64 && objective == 2) {
         // directed sum: wavefront kernel with 32-bit keys when max(c) < 2^16, else the general kernel (both enqueued,

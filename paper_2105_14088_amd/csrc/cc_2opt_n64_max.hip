@@ -198,26 +198,25 @@ __device__ __forceinline__ void descend_max_packed(const int32_t* m2, int lane, 
             bestA = min(bestA, (val & 0xffff0000u) | w);
             bestB = min(bestB, (val << 16) | w);
         }
-        // (value, move id) of the lane's two candidates; keep the lexicographically smaller
-        int val = kNone, id = kNone;
-#pragma unroll
-        for (int which = 0; which < 2; ++which) {
-            const unsigned key = which ? bestB : bestA;
-            const int kv = (int)(key >> 16), rk = (int)(key >> 10) & 63;
-            const int b = (rk + 1) & 63;
-            const int lo = min(lane, b), hi = max(lane, b);
-            const int ij = lo ? lo * kN + hi - 1 : hi * kN + kN - 1;
-            const int flip = rk < rank_a ? 1 : 0;       // the reversed piece is S2, not S1
-            const int kid = ij * 2 + (which ^ flip);
-            if (kv < val || (kv == val && kid < id)) { val = kv; id = kid; }
-        }
-        if (with_flip && lane == 0) {                   // the orientation flip: every hop walked the other way
+        // (value, move id) of the lane's two candidates as one key, value << 13 | id (values are below 2^16, ids below
+        // 2^13), branch-free.  With r = rank(b): the move is (lane, r) when r >= rank(lane) (b lies after the lane, or
+        // b = 0) and A / B are orientations 0 / 1; otherwise it is (r + 1, rank(lane)) and A / B are 1 / 0.
+        auto candidate = [&](unsigned key, int which) {
+            const int rk = (int)(key >> 10) & 63;
+            const bool wrapped = rk < rank_a;
+            const int id = wrapped ? (rk << 7) + ((kN + rank_a) * 2 + (which ^ 1)) : (rk << 1) + (lane * kN * 2 + which);
+            return (int)((key >> 3) & ~0x1fffu) | id;
+        };
+        int key = min(candidate(bestA, 0), candidate(bestB, 1));
+        if (with_flip) {                                // the orientation flip: every hop walked the other way
             const int vf = (int)(pk_max(m5, far) & 0xffffu), idf = (kN + kN - 1) * 2;
-            if (vf < val || (vf == val && idf < id)) { val = vf; id = idf; }
+            const int kf = (vf << 13) | idf;
+            key = lane == 0 ? min(key, kf) : key;
         }
-        const int vwin = wave_min_uniform(val);
+        const int win = wave_min_uniform(key);
+        const int vwin = win >> 13;
         if (vwin >= cur) break;
-        const int idwin = wave_min_uniform(val == vwin ? id : kNone);
+        const int idwin = win & 0x1fff;
         const int o = idwin & 1, ij = idwin >> 1, mi = ij >> 6, mj = ij & 63;
         const int p0 = o ? (lane ? kN - lane : 0) : lane;
         const int src = (p0 >= mi && p0 <= mj) ? mi + mj - p0 : p0;

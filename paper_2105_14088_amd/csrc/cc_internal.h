@@ -6,6 +6,12 @@
 
 namespace cc {
 
+// Environment pin for A/B profiling and for parity tests of the fallback kernels: with CC_FORCE_PATH=general every
+// search call (2-opt, wider move sets, pair swaps) runs its general kernel - one workgroup per restart, every
+// objective, any N - instead of the kernel specialised for its size and value range.  Read at every call; results are
+// the same bit for bit, only the time differs.
+bool force_general_path();
+
 hipError_t launch_ring_cost_batch(const int32_t* c, int N, bool is_max, const int32_t* perms, int64_t B,
                                   int64_t* out, hipStream_t s);
 hipError_t launch_ring_cost_batch_u8(const int32_t* c, int N, bool is_max, const uint8_t* perms, int64_t B,

@@ -170,7 +170,9 @@ hipError_t launch_insertion(const int32_t* c, int N, int restarts, int32_t* tour
 hipError_t launch_insertion_search(const int32_t* c, int N, bool with_2opt, int restarts, int32_t* tours,
                                    int64_t* costs, int32_t* moves, int32_t* flags, hipStream_t s) {
     const int32_t* skip = nullptr;
-    if (N == 64) {
+    if (force_general_path()) {
+        // pinned: the kernel below for every size
+    } else if (N == 64) {
         // one wavefront per restart with 32-bit keys when max(c) < 2^16, else the kernel above: both are enqueued
         // and the matrix maximum, computed on the device, decides which of them does the work
         hipError_t e = launch_matrix_max(c, N, flags, s);

@@ -531,7 +531,8 @@ hipError_t launch_fold_to_u16(const int32_t* c, int N, uint16_t* folded, const i
 
 hipError_t launch_rdswap(const int32_t* c, int N, int restarts, uint64_t seed, bool tours_hold_init, int32_t* tours,
                          int64_t* costs, int32_t* moves, int32_t* flags, uint16_t* mat16, hipStream_t s) {
-    if (N == 64) {
+    const bool pinned = force_general_path();
+    if (N == 64 && !pinned) {
         hipLaunchKernelGGL(rdswap_n64_kernel, dim3((restarts + 3) / 4), dim3(256), 0, s, c, restarts, seed,
                            tours_hold_init ? 0 : 1, tours, costs, moves);
         return hipGetLastError();
@@ -541,7 +542,7 @@ hipError_t launch_rdswap(const int32_t* c, int N, int restarts, uint64_t seed, b
         if (e != hipSuccess) return e;
     }
     const int32_t* skip = nullptr;
-    if (N == 128 || N == 256 || N == 512 || N == 1024) {
+    if (!pinned && (N == 128 || N == 256 || N == 512 || N == 1024)) {
         // 16-bit workgroup kernel when max(c) < 2^16, else the general kernel: both are enqueued and the matrix
         // maximum, computed on the device, decides which one does the work (no host round trip)
         hipError_t e = launch_matrix_max(c, N, flags, s);

@@ -344,6 +344,18 @@ hipError_t launch_2opt(const int32_t* c, int N, int objective, int classes, int 
         e = launch_2opt_dsum_n64(c, restarts, seed, false, flip, tours, costs, moves, flags, s);
         if (e != hipSuccess) return e;
         e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, flip, s);
+    } else if ((flip || classes == kMoves2opt) && (objective & 1) && (N == 128 || N == 192 || N == 256)) {
+        // max-hop at 128 / 192 / 256: several ranks per lane with a 16-bit LDS matrix when max(c) < 2^16, else the
+        // general kernel (both enqueued, the matrix maximum computed on the device decides)
+        if (!tours_hold_init) {
+            e = launch_init_tours(N, 0, restarts, seed, tours, s);
+            if (e != hipSuccess) return e;
+        }
+        e = launch_matrix_max(c, N, flags, s);
+        if (e != hipSuccess) return e;
+        e = launch_2opt_max_multi(c, N, (objective & 2) != 0, restarts, flip, tours, costs, moves, flags, s);
+        if (e != hipSuccess) return e;
+        e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, flip, s);
     } else if (classes != kMoves2opt) {
         // wider move sets: the segment-insertion kernel (ring sum) or the general kernel with the orientation flip
         if (!tours_hold_init) {

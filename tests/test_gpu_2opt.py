@@ -79,6 +79,58 @@ def test_n128_n256_sum_fast_path_and_its_fallback(n, restarts):
     assert_search_equal(gpu_search(c, 0, 19, seed=5, init=init), want)
 
 
+@pytest.mark.parametrize("n,restarts", [(128, 24), (192, 22), (256, 20)])
+@pytest.mark.parametrize("obj", [1, 3])
+def test_n128_n256_max_hop_fast_path_and_its_fallback(n, restarts, obj):
+    """Max-hop objective (undirected on a symmetric matrix, directed on an asymmetric one) with several ranks per lane
+    and a 16-bit LDS matrix: hierarchy-like values, the largest 16-bit entry, the fallback at 2^16, plateaus of ties,
+    caller-provided orders, a single restart, many restarts with a ragged last workgroup, and the orientation flip."""
+    sym = obj == 1
+    for hi, tag in ((6000, "16-bit path"), (65535, "16-bit path, largest entry 65535"), (65536, "fallback at 2^16"),
+                    (3, "ties"), (40, "few distinct values")):
+        say(f"2-opt N={n} objective {obj}, entries up to {hi} ({tag})")
+        c = random_matrix(n, 7100 + n + hi % 97 + obj, symmetric=sym, lo=1, hi=hi)
+        c[3, 5] = hi
+        if sym:
+            c[5, 3] = hi
+        want = oracle.search(c, obj, restarts, seed=12 + n)
+        assert_search_equal(gpu_search(c, obj, restarts, seed=12 + n), want)
+    say(f"2-opt N={n} objective {obj}, caller-provided initial tours; one restart")
+    c = random_matrix(n, 1334 + n + obj, symmetric=sym, lo=1, hi=9000)
+    init = random_perms(n, 19, seed=n)
+    assert_search_equal(gpu_search(c, obj, 19, seed=5, init=init), oracle.search(c, obj, 19, seed=0, init=init))
+    assert_search_equal(gpu_search(c, obj, 1, seed=6), oracle.search(c, obj, 1, seed=6))
+    say(f"2-opt N={n} objective {obj}, 2100 restarts (several wavefronts per workgroup, ragged end), sampled")
+    got = gpu_search(c, obj, 2100, seed=8)
+    rows = np.unique(np.concatenate([np.arange(0, 2100, 150), [2096, 2097, 2098, 2099]]))
+    assert_search_equal(got, _oracle_rows(c, obj, 8, rows), rows=rows)
+    if obj == 3:
+        say(f"2-opt + orientation flip N={n}, directed max-hop")
+        b = cc.cc_local_search_ex(dev(c), 3, cc.CC_MOVES_2OPT | cc.CC_MOVES_FLIP, restarts, 31)
+        torch.cuda.synchronize()
+        want = oracle.local_search(c, 3, cc.CC_MOVES_2OPT | cc.CC_MOVES_FLIP, restarts, 31)
+        assert np.array_equal(b.restart_costs.cpu().numpy(), want["costs"])
+        assert np.array_equal(b.restart_tours.cpu().numpy(), want["tours"])
+        assert np.array_equal(b.restart_moves.cpu().numpy(), want["moves"])
+
+
+def test_workload4_matrix_max_hop_1024_restarts_full(capfd):
+    """The N = 256 hierarchy of workload 4 under the max-hop objective, 1024 restarts, every restart replayed by the
+    oracle."""
+    c = make_matrix(4)
+    seed = WORKLOADS[4].search_seed
+    with capfd.disabled():
+        say(f"matrix 4 (N=256), max-hop, 1024 restarts, all replayed by the oracle on {THREADS} threads")
+    got = gpu_search(c, 1, 1024, seed)
+    t0 = time.time()
+    costs, tours, moves = oracle.restarts_parallel(c, 1, seed, 0, 1024, THREADS)
+    report(f"matrix 4 max-hop (N=256): oracle replayed 1024 of 1024 restarts in {time.time() - t0:.1f} s")
+    assert np.array_equal(got["costs"], costs) and np.array_equal(got["moves"], moves)
+    assert np.array_equal(got["tours"], tours)
+    k = int(np.lexsort((np.arange(1024), costs))[0])
+    assert got["best_restart"] == k and np.array_equal(got["best_perm"], tours[k])
+
+
 def test_n1024_sum_row_streaming_path_and_its_fallback():
     """N = 1024: rows streamed through LDS when max(c) < 2^16, general kernel otherwise; ties."""
     from concurrent.futures import ThreadPoolExecutor

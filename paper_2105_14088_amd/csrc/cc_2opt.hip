@@ -51,9 +51,10 @@ __device__ void block_scan(int32_t* arr, int N) {
 template <int OBJ, bool LDS_MATRIX>
 __global__ void twoopt_general_kernel(const int32_t* __restrict__ c, int N, int32_t* __restrict__ tours,
                                       int64_t* __restrict__ costs, int32_t* __restrict__ moves,
-                                      const int32_t* __restrict__ skip_if_small, int with_flip) {
-    // when a 16-bit fast path is launched beside this kernel, flags[0] = max(c) decides which of the two runs
-    if (skip_if_small && skip_if_small[0] < (1 << 16)) return;
+                                      const int32_t* __restrict__ skip_if_small, int with_flip, int small_limit) {
+    // when a fast path is launched beside this kernel, flags[0] = max(c) decides which of the two runs: the fast one
+    // takes the matrices whose largest entry is below small_limit
+    if (skip_if_small && skip_if_small[0] < small_limit) return;
     constexpr bool IS_MAX = (OBJ & 1) != 0;
     constexpr bool DIRECTED = (OBJ & 2) != 0;
     extern __shared__ int32_t sm[];
@@ -274,7 +275,7 @@ __global__ __launch_bounds__(1024) void best_restart_kernel(const int64_t* __res
 
 template <int OBJ>
 hipError_t launch_general(const int32_t* c, int N, int restarts, int32_t* tours, int64_t* costs, int32_t* moves,
-                          const int32_t* skip_if_small, int with_flip, hipStream_t s) {
+                          const int32_t* skip_if_small, int with_flip, int small_limit, hipStream_t s) {
     const int threads = ((N + 63) / 64) * 64;
     if (N <= kGeneralLdsMatrixMaxN) {
         const size_t lds = sizeof(int32_t) * (7 * (size_t)N + (size_t)N * N);
@@ -284,24 +285,24 @@ hipError_t launch_general(const int32_t* c, int N, int restarts, int32_t* tours,
             if (e != hipSuccess) return e;
         }
         hipLaunchKernelGGL((twoopt_general_kernel<OBJ, true>), dim3(restarts), dim3(threads), lds, s, c, N, tours, costs,
-                           moves, skip_if_small, with_flip);
+                           moves, skip_if_small, with_flip, small_limit);
     } else {
         const size_t lds = sizeof(int32_t) * 7 * (size_t)N;
         hipLaunchKernelGGL((twoopt_general_kernel<OBJ, false>), dim3(restarts), dim3(threads), lds, s, c, N, tours, costs,
-                           moves, skip_if_small, with_flip);
+                           moves, skip_if_small, with_flip, small_limit);
     }
     return hipGetLastError();
 }
 
 hipError_t launch_general_objective(const int32_t* c, int N, int objective, int restarts, int32_t* tours,
                                     int64_t* costs, int32_t* moves, const int32_t* skip_if_small, bool with_flip,
-                                    hipStream_t s) {
+                                    hipStream_t s, int small_limit = 1 << 16) {
     const int flip = with_flip ? 1 : 0;
     switch (objective) {
-        case 0: return launch_general<0>(c, N, restarts, tours, costs, moves, skip_if_small, 0, s);
-        case 1: return launch_general<1>(c, N, restarts, tours, costs, moves, skip_if_small, 0, s);
-        case 2: return launch_general<2>(c, N, restarts, tours, costs, moves, skip_if_small, flip, s);
-        default: return launch_general<3>(c, N, restarts, tours, costs, moves, skip_if_small, flip, s);
+        case 0: return launch_general<0>(c, N, restarts, tours, costs, moves, skip_if_small, 0, small_limit, s);
+        case 1: return launch_general<1>(c, N, restarts, tours, costs, moves, skip_if_small, 0, small_limit, s);
+        case 2: return launch_general<2>(c, N, restarts, tours, costs, moves, skip_if_small, flip, small_limit, s);
+        default: return launch_general<3>(c, N, restarts, tours, costs, moves, skip_if_small, flip, small_limit, s);
     }
 }
 
@@ -356,6 +357,18 @@ hipError_t launch_2opt(const int32_t* c, int N, int objective, int classes, int 
         e = launch_2opt_max_multi(c, N, (objective & 2) != 0, restarts, flip, tours, costs, moves, flags, s);
         if (e != hipSuccess) return e;
         e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, flip, s);
+    } else if ((flip || classes == kMoves2opt) && objective == 2 && (N == 128 || N == 192 || N == 256)) {
+        // directed sum at 128 / 192 / 256: several ranks per lane with a 16-bit LDS matrix when its 32-bit keys hold
+        // every partial delta, else the general kernel (both enqueued, the matrix maximum decides)
+        if (!tours_hold_init) {
+            e = launch_init_tours(N, 0, restarts, seed, tours, s);
+            if (e != hipSuccess) return e;
+        }
+        e = launch_matrix_max(c, N, flags, s);
+        if (e != hipSuccess) return e;
+        e = launch_2opt_dsum_multi(c, N, restarts, flip, tours, costs, moves, flags, s);
+        if (e != hipSuccess) return e;
+        e = launch_general_objective(c, N, objective, restarts, tours, costs, moves, flags, flip, s, dsum_multi_limit(N));
     } else if (classes != kMoves2opt) {
         // wider move sets: the segment-insertion kernel (ring sum) or the general kernel with the orientation flip
         if (!tours_hold_init) {

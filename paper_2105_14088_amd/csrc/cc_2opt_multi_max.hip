@@ -232,6 +232,7 @@ __global__ __launch_bounds__(64 * max_waves(DIRECTED)) void twoopt_max_multi_ker
         slide();
         constexpr int kSwitchQ = kSwitch / K, kSwitchR = kSwitch % K;       // the block of diagonals that holds the switch
         auto blocks = [&](int q0, int q1) {
+            asm("" : "+s"(q1));                // an opaque trip count: unrolled twice, never completely (register pressure)
 #pragma unroll 2
             for (int q = q0; q < q1; ++q) {
 #pragma unroll

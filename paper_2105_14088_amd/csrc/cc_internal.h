@@ -89,6 +89,13 @@ hipError_t launch_2opt_sum_multi(const int32_t* c, int N, int restarts, int32_t*
 hipError_t launch_2opt_max_multi(const int32_t* c, int N, bool directed, int restarts, bool with_flip, int32_t* tours,
                                  int64_t* costs, int32_t* moves, const int32_t* flags, hipStream_t s);
 
+// N = 128 / 192 / 256, directed ring sum: one wavefront per restart, 16-bit matrix in LDS (cc_2opt_multi_dsum.hip).
+// Runs when flags[0] (the matrix maximum) is below dsum_multi_limit(N), so that its 32-bit keys hold every partial
+// delta; otherwise it returns at once and the general kernel, given the same limit, does the work.
+__host__ __device__ constexpr int dsum_multi_limit(int N) { return (1 << 22) / (N + 2); }
+hipError_t launch_2opt_dsum_multi(const int32_t* c, int N, int restarts, bool with_flip, int32_t* tours, int64_t* costs,
+                                  int32_t* moves, const int32_t* flags, hipStream_t s);
+
 // N = 512 or 1024, ring-sum objective, max(c) < 2^16: one workgroup of N/64 waves per restart, matrix rows
 // streamed through LDS (cc_2opt_n1024.hip).  Same flags convention as above.
 hipError_t launch_2opt_sum_n1024(const int32_t* c, int N, uint16_t* c16, int restarts, int32_t* tours, int64_t* costs,

@@ -114,6 +114,35 @@ def test_n128_n256_max_hop_fast_path_and_its_fallback(n, restarts, obj):
         assert np.array_equal(b.restart_moves.cpu().numpy(), want["moves"])
 
 
+@pytest.mark.parametrize("n,restarts", [(128, 24), (192, 22), (256, 20)])
+def test_n128_n256_directed_sum_fast_path_and_its_fallback(n, restarts):
+    """Directed ring sum with several ranks per lane and a 16-bit LDS matrix.  The fast path runs while
+    max(c) * (N + 2) < 2^22 (its 32-bit keys then hold every partial delta); the first value beyond that, and larger
+    ones, take the general kernel.  Also ties, caller-provided orders, one restart, many restarts, the flip."""
+    limit = (1 << 22) // (n + 2)
+    for hi, tag in ((6000, "fast path"), (limit - 1, "fast path, largest entry it takes"), (limit, "fallback at the limit"),
+                    (65535, "fallback"), (COST_MAX, "fallback, COST_MAX"), (3, "ties")):
+        say(f"2-opt N={n} directed sum, entries up to {hi} ({tag})")
+        c = random_matrix(n, 7200 + n + hi % 97, symmetric=False, lo=max(1, hi - 4000), hi=hi)
+        c[3, 5] = hi
+        want = oracle.search(c, 2, restarts, seed=14 + n)
+        assert_search_equal(gpu_search(c, 2, restarts, seed=14 + n), want)
+    c = random_matrix(n, 1434 + n, symmetric=False, lo=1, hi=9000)
+    say(f"2-opt N={n} directed sum, caller-provided initial tours; one restart; 2100 restarts sampled; flip")
+    init = random_perms(n, 19, seed=n)
+    assert_search_equal(gpu_search(c, 2, 19, seed=5, init=init), oracle.search(c, 2, 19, seed=0, init=init))
+    assert_search_equal(gpu_search(c, 2, 1, seed=6), oracle.search(c, 2, 1, seed=6))
+    got = gpu_search(c, 2, 2100, seed=8)
+    rows = np.unique(np.concatenate([np.arange(0, 2100, 300), [2098, 2099]]))
+    assert_search_equal(got, _oracle_rows(c, 2, 8, rows), rows=rows)
+    b = cc.cc_local_search_ex(dev(c), 2, cc.CC_MOVES_2OPT | cc.CC_MOVES_FLIP, restarts, 31)
+    torch.cuda.synchronize()
+    want = oracle.local_search(c, 2, cc.CC_MOVES_2OPT | cc.CC_MOVES_FLIP, restarts, 31)
+    assert np.array_equal(b.restart_costs.cpu().numpy(), want["costs"])
+    assert np.array_equal(b.restart_tours.cpu().numpy(), want["tours"])
+    assert np.array_equal(b.restart_moves.cpu().numpy(), want["moves"])
+
+
 def test_workload4_matrix_max_hop_1024_restarts_full(capfd):
     """The N = 256 hierarchy of workload 4 under the max-hop objective, 1024 restarts, every restart replayed by the
     oracle."""

@@ -499,6 +499,212 @@ __global__ __launch_bounds__(SPLIT << LOGN) void rdswap_block_kernel(const int32
     }
 }
 
+// ------------------------------------------------------------------ N = 512, 1024: tiles of the folded matrix in LDS
+// One workgroup per restart, one thread per rank p.  The folded 16-bit matrix F (512 KiB / 2 MiB, in the workspace)
+// does not fit LDS, and gathered through L2 a sweep is bound by the misses one compute unit keeps in flight.  Here
+// a sweep goes through the partner ranks q in blocks of QB consecutive ranks B; for a block the workgroup stages
+//   CT[x][j]      = F[x][t[B + j]]                 every row x, the QB columns of the block's nodes
+//   RT[h][j][y]   = F[t[(B + j) xor 2^k]][y]       k = log2 QB + h: the rows of the block's mates in the rounds whose
+//                                                  mate lies outside the block, every column y
+// and every link of every pair (p, q in B) is then an LDS gather: rank p holding t[q] costs, in round k,
+// F[t[q]][t[p xor 2^k]] = CT[t[p xor 2^k]][j]; rank q holding t[p] costs F[t[p]][t[q xor 2^k]], which is
+// CT[t[p]][j xor 2^k] when the mate of q lies in the block and RT[h][j][t[p]] otherwise (F is symmetric).
+// Pairs are split so that every thread scores one pair per step: of two neighbouring partners q0, q0 + 1 a thread
+// takes the one with its own parity when it lies below them and the other one when it lies above (every unordered
+// pair is then scored exactly once, by the thread p for which p + q is even and p < q, or odd and p > q).  Pairs of
+// round mates (q = p xor 2^k), whose round k keeps its cost, are scored apart from the folded copy through L2: 9 or
+// 10 per thread.  Round maxima, keys, reduction and the swap as in the kernel above.
+template <int LOGN, int LOGQ>
+__global__ __launch_bounds__(1 << LOGN) void rdswap_tiled_kernel(const uint16_t* __restrict__ folded,
+                                                                 int32_t* __restrict__ tours,
+                                                                 int64_t* __restrict__ costs,
+                                                                 int32_t* __restrict__ moves,
+                                                                 const int32_t* __restrict__ flags) {
+    constexpr int N = 1 << LOGN, QB = 1 << LOGQ, NH = LOGN - LOGQ, NW = N / 64, LB = LOGN - 1;
+    constexpr int kIdBits = 2 * LOGN;
+    constexpr int kInf = 0x7fffffff;
+    // a row of CT takes QB / 2 + 1 words: with QB / 2 the rows of the 64 lanes of a gather would fall into four or
+    // eight LDS banks only
+    constexpr int kCtRowBytes = (QB / 2 + 1) * 4;
+    if (flags[0] >= (1 << 16)) return;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    int32_t* tl = (int32_t*)smem;                                          // [N] the order
+    uint16_t* rt = (uint16_t*)(smem + sizeof(int32_t) * N);                // [NH][QB][N]
+    unsigned char* ct = (unsigned char*)(rt + (size_t)NH * QB * N);        // [N] rows of kCtRowBytes
+    __shared__ int red_i[2][NW];
+    __shared__ unsigned long long red_k[NW];
+    const int tid = threadIdx.x, p = tid, lane = tid & 63, wv = tid >> 6;
+    const int64_t r = blockIdx.x;
+    int t = clampi(tours[r * N + p], 0, N - 1);
+    tl[p] = t;
+    __syncthreads();
+    int parity = 0;
+    auto block_max = [&](int v) {                              // every thread gets the maximum; one barrier per call
+        v = wave_max(v);
+        if (lane == 0) red_i[parity][wv] = v;
+        __syncthreads();
+        int o;
+        if (NW >= 16) {
+            o = wave_max(red_i[parity][lane & (NW - 1)]);
+        } else {
+            o = red_i[parity][0];
+#pragma unroll
+            for (int k = 1; k < NW; ++k) o = max(o, red_i[parity][k]);
+        }
+        parity ^= 1;
+        return o;
+    };
+
+    int applied = 0, cur = 0;
+    for (;;) {
+        // per round: the mate's node, the largest and second largest link that is not this rank's, and the two ranks
+        // (with the round's bit set) of that largest link
+        int pbq[LOGN], x1v[LOGN], x2v[LOGN], a1r[LOGN], round_cost[LOGN];
+        cur = 0;
+#pragma unroll
+        for (int k = 0; k < LOGN; ++k) {
+            const int bit = 1 << k;
+            const int pb = tl[p ^ bit];
+            pbq[k] = pb * kCtRowBytes;                         // the mate's node as a row byte offset of CT
+            const int lv = (int)folded[t * N + pb];
+            const int li = ((p >> (k + 1)) << k) | (p & (bit - 1));
+            const int key = (lv << LB) | li;
+            const int k1 = block_max(key);
+            const int k2 = block_max((li == (k1 & (N / 2 - 1))) ? -1 : key);
+            const int k3 = block_max((li == (k1 & (N / 2 - 1)) || li == (k2 & (N / 2 - 1))) ? -1 : key);
+            const int l1 = k1 & (N / 2 - 1), l2 = k2 & (N / 2 - 1);
+            const int a1 = (li == l1) ? k2 : k1;               // best link that is not this rank's
+            const int a2 = (li == l1 || li == l2) ? k3 : k2;   // second best that is not this rank's
+            x1v[k] = a1 >> LB;
+            x2v[k] = a2 >> LB;
+            const int al = a1 & (N / 2 - 1);
+            a1r[k] = (((al >> k) << (k + 1)) | (al & (bit - 1))) | bit;    // link index -> its rank with bit k set
+            round_cost[k] = __builtin_amdgcn_readfirstlane(k1 >> LB);
+            cur += round_cost[k];
+        }
+        int best_below = kInf, best_above = kInf;              // over partners q < p and q > p: total << LOGN | q
+        // pairs of round mates, scored by the thread whose bit is clear
+#pragma unroll 1
+        for (int km = 0; km < LOGN; ++km) {
+            const int q = p ^ (1 << km);
+            if (q < p) continue;
+            const int tq = tl[q];
+            int total = 0;
+#pragma unroll
+            for (int k = 0; k < LOGN; ++k) {
+                const int bit = 1 << k;
+                const int link_p = (int)folded[tq * N + tl[p ^ bit]];
+                const int link_q = (int)folded[t * N + tl[q ^ bit]];
+                const int others = ((q | bit) == a1r[k]) ? x2v[k] : x1v[k];
+                const int stage = max(others, max(link_p, link_q));
+                total += (k == km) ? round_cost[k] : stage;
+            }
+            best_above = min(best_above, (total << LOGN) | q);
+        }
+        const int tq2 = t * kCtRowBytes, tc2 = t << 1;
+#pragma unroll 1
+        for (int b0 = 0; b0 < N; b0 += QB) {
+            __syncthreads();                                   // the tiles of the previous block are free
+            // all loads of the block first, then the stores: one L2 latency per block
+            // RT: NH * QB rows of N entries, copied 16 bytes at a time; CT: row p, the block's QB columns
+            constexpr int kChunksPerRow = N * 2 / 16, kChunks = NH * QB * kChunksPerRow, kPerThread = kChunks / N;
+            static_assert(kChunks % N == 0, "every thread copies the same number of 16-byte pieces");
+            int4 piece[kPerThread];
+#pragma unroll
+            for (int i = 0; i < kPerThread; ++i) {
+                const int ch = tid + i * N;
+                const int rowi = ch / kChunksPerRow, off = ch % kChunksPerRow;
+                const int h = rowi >> LOGQ, j = rowi & (QB - 1);
+                const int node = tl[(b0 + j) ^ (QB << h)];
+                piece[i] = ((const int4*)(folded + (size_t)node * N))[off];
+            }
+            {
+                const uint16_t* row = folded + (size_t)p * N;
+                uint32_t w[QB / 2];
+#pragma unroll
+                for (int j = 0; j < QB; j += 2)
+                    w[j / 2] = (uint32_t)row[tl[b0 + j]] | ((uint32_t)row[tl[b0 + j + 1]] << 16);
+#pragma unroll
+                for (int j = 0; j < QB / 2; ++j) ((uint32_t*)(ct + p * kCtRowBytes))[j] = w[j];
+            }
+#pragma unroll
+            for (int i = 0; i < kPerThread; ++i) ((int4*)rt)[tid + i * N] = piece[i];
+            __syncthreads();
+#pragma unroll 2
+            for (int i = 0; i < QB / 2; ++i) {
+                const int q0 = b0 + 2 * i;
+                const bool above = p > q0;                     // p = q0 + 1 takes q0; p = q0 sits this step out
+                const int q = q0 + (((p ^ q0) & 1) ^ (above ? 1 : 0));
+                const int j = q - b0, j2 = j << 1;
+                const int x = p ^ q;
+                int total = 0;
+#pragma unroll
+                for (int k = 0; k < LOGN; ++k) {
+                    const int bit = 1 << k;
+                    const int link_p = (int)*(const uint16_t*)((const char*)ct + (pbq[k] + j2));
+                    int link_q;
+                    if (k < LOGQ) link_q = (int)*(const uint16_t*)((const char*)ct + (tq2 + (j2 ^ (bit << 1))));
+                    else link_q = (int)*(const uint16_t*)((const char*)rt + ((((k - LOGQ) << LOGQ) + j) << (LOGN + 1)) + tc2);
+                    const int others = ((q | bit) == a1r[k]) ? x2v[k] : x1v[k];
+                    total += max(others, max(link_p, link_q));
+                }
+                const bool skip = (x & (x - 1)) == 0;          // itself (x = 0) or a round mate (scored above)
+                const int key = skip ? kInf : ((total << LOGN) | q);
+                best_below = min(best_below, above ? key : kInf);
+                best_above = min(best_above, above ? kInf : key);
+            }
+        }
+        unsigned long long best = kNoMove;
+        if (best_below != kInf) {
+            const int q = best_below & (N - 1), total = best_below >> LOGN;
+            best = ((unsigned long long)(unsigned)total << kIdBits) | (unsigned)(q * N + p);
+        }
+        if (best_above != kInf) {
+            const int q = best_above & (N - 1), total = best_above >> LOGN;
+            best = min(best, ((unsigned long long)(unsigned)total << kIdBits) | (unsigned)(p * N + q));
+        }
+        best = wave_min_u64(best);
+        if (lane == 0) red_k[wv] = best;
+        __syncthreads();
+        unsigned long long win;
+        if (NW >= 16) {
+            win = wave_min_u64(red_k[lane & (NW - 1)]);
+        } else {
+            win = red_k[0];
+#pragma unroll
+            for (int k = 1; k < NW; ++k) win = min(win, red_k[k]);
+        }
+        if ((int)(win >> kIdBits) >= cur) break;
+        const int id = (int)(win & ((1u << kIdBits) - 1u)), sp = id >> LOGN, sq = id & (N - 1);
+        const int a = tl[sp], b = tl[sq];
+        __syncthreads();                                       // everyone has read red_k and the two ranks
+        if (p == sp) { t = b; tl[p] = b; }
+        if (p == sq) { t = a; tl[p] = a; }
+        ++applied;
+        __syncthreads();
+    }
+    tours[r * N + p] = t;
+    if (tid == 0) {
+        costs[r] = (int64_t)cur;
+        moves[r] = applied;
+    }
+}
+
+template <int LOGN, int LOGQ>
+static hipError_t rdswap_tiled_launch(const int32_t* c, uint16_t* folded, int restarts, int32_t* tours, int64_t* costs,
+                                      int32_t* moves, const int32_t* flags, hipStream_t s) {
+    constexpr int N = 1 << LOGN, QB = 1 << LOGQ, NH = LOGN - LOGQ;
+    hipError_t e = launch_fold_to_u16(c, N, folded, flags, s);
+    if (e != hipSuccess) return e;
+    const size_t lds = sizeof(int32_t) * N + sizeof(uint16_t) * (size_t)NH * QB * N + (size_t)N * (QB / 2 + 1) * 4;
+    e = hipFuncSetAttribute((const void*)rdswap_tiled_kernel<LOGN, LOGQ>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((rdswap_tiled_kernel<LOGN, LOGQ>), dim3(restarts), dim3(N), lds, s, folded, tours, costs, moves,
+                       flags);
+    return hipGetLastError();
+}
+
 template <int LOGN>
 static hipError_t rdswap_block_launch(const int32_t* c, uint16_t* folded, int restarts, int32_t* tours, int64_t* costs,
                                       int32_t* moves, const int32_t* flags, hipStream_t s) {
@@ -549,8 +755,8 @@ hipError_t launch_rdswap(const int32_t* c, int N, int restarts, uint64_t seed, b
         if (e != hipSuccess) return e;
         e = N == 128   ? rdswap_block_launch<7>(c, mat16, restarts, tours, costs, moves, flags, s)
             : N == 256 ? rdswap_block_launch<8>(c, mat16, restarts, tours, costs, moves, flags, s)
-            : N == 512 ? rdswap_block_launch<9>(c, mat16, restarts, tours, costs, moves, flags, s)
-                       : rdswap_block_launch<10>(c, mat16, restarts, tours, costs, moves, flags, s);
+            : N == 512 ? rdswap_tiled_launch<9, 4>(c, mat16, restarts, tours, costs, moves, flags, s)
+                       : rdswap_tiled_launch<10, 3>(c, mat16, restarts, tours, costs, moves, flags, s);
         if (e != hipSuccess) return e;
         skip = flags;
     }

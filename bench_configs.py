@@ -60,7 +60,7 @@ def main():
         w = WORKLOADS[wid]
         if objective is not None:  # the workload's matrix and restarts under another objective
             import dataclasses
-            w = dataclasses.replace(w, objective=objective, name=name)
+            w = dataclasses.replace(w, objective=objective, name=name, restarts=restarts or w.restarts)
         obj = cc.OBJECTIVES[w.objective]
         c_host = make_matrix(wid)
         if n is not None:         # the workload's hierarchy and value ranges at another size
@@ -123,9 +123,14 @@ def main():
                       "oracle_sample_restarts": sample, "bit_exact_on_sample": ok})
         emit(d)
 
-    def swap_case(name, wid, restarts):
+    def swap_case(name, wid, restarts, n=None):
         w = WORKLOADS[wid]
         c_host = make_matrix(wid)
+        if n is not None:         # the workload's hierarchy and value ranges at another size
+            from gen import hierarchical_matrix
+            import dataclasses
+            c_host = hierarchical_matrix(n, w.group_sizes, w.level_ranges, w.sigma, True, w.matrix_seed + n)
+            w = dataclasses.replace(w, n=n)
         c = torch.from_numpy(c_host).cuda()
         bufs = cc.SearchBuffers(w.n, 0, restarts, c.device)
         ms = timed(lambda: cc.cc_rd_swap_search_ex(c, restarts, w.search_seed, buffers=bufs), args.reps)
@@ -137,7 +142,7 @@ def main():
              "applied_moves_max": int(moves.max()), "best_cost": int(bufs.best_cost.item())}
         if args.oracle:
             import oracle
-            sample = min(restarts, 64 if w.n <= 64 else 2)
+            sample = min(restarts, 64 if w.n <= 64 else 2 if w.n <= 256 else 1)
             t0 = time.perf_counter()
             oc, ot, om = oracle.rd_swap_restarts(c_host, w.search_seed, 0, sample)
             dt = time.perf_counter() - t0
@@ -234,6 +239,11 @@ def main():
         ("C3", lambda: search_case(3)),
         ("D64", lambda: search_case(3, objective="sum_directed", name="D64_n64_sum_directed_1024")),
         ("C4", lambda: search_case(4)),
+        ("X256", lambda: search_case(4, objective="max", name="X256_n256_max_1024", restarts=1024)),
+        ("X256big", lambda: search_case(4, objective="max", name="X256_n256_max_4096")),
+        ("X256d", lambda: search_case(4, objective="max_directed", name="X256_n256_max_directed_1024", restarts=1024)),
+        ("D256", lambda: search_case(4, objective="sum_directed", name="D256_n256_sum_directed_1024", restarts=1024)),
+        ("X128", lambda: search_case(4, n=128, restarts=1024, name="X128_n128_max_1024", objective="max")),
         ("C5rd", lambda: batch_case("C5_n1024_rd_65536", 5, "rd", 0, 65536)),
         ("C5", lambda: search_case(5)),
         ("C512", lambda: search_case(5, n=512, restarts=768, name="C512_n512_sum_768_restarts")),
@@ -243,6 +253,8 @@ def main():
         ("L256", lambda: local_case("L256_n256_2opt+insertion_4096", 4, 3)),
         ("S64", lambda: swap_case("S64_n64_rd_swap_1024", 2, 1024)),
         ("S256", lambda: swap_case("S256_n256_rd_swap_256", 4, 256)),
+        ("S512", lambda: swap_case("S512_n512_rd_swap_64", 5, 64, n=512)),
+        ("S1024", lambda: swap_case("S1024_n1024_rd_swap_32", 5, 32)),
         ("A64", lambda: sa_case("A64_n64_sa_1024x100000", 2, 1024, 100000, 300, 0)),
         ("A64big", lambda: sa_case("A64_n64_sa_8192x100000", 2, 8192, 100000, 300, 0)),
         ("A256", lambda: sa_case("A256_n256_sa_1024x200000", 4, 1024, 200000, 300, 0)),

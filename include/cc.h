@@ -30,6 +30,10 @@
  *     of the orders they produce; the annealing calls run a fixed number of steps.
  *     cc_validate_matrix checks the matrix contract.
  *   - All arithmetic is exact integer; costs are returned as int64.
+ *   - Kernel choice never changes a result.  Each search call picks, from N, the objective and the size of
+ *     the matrix entries, either a kernel specialised for that case or a general kernel that serves every
+ *     case.  The environment variable CC_FORCE_PATH=general (read at every call) pins the general kernels:
+ *     for comparing the two on the same input, nothing else.
  */
 #ifndef CC_H_
 #define CC_H_
@@ -241,9 +245,11 @@ int cc_local_search_ex(const int32_t* cost_matrix, int32_t N, int32_t objective,
                        int32_t* restart_moves, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * The last step of every search call on its own: the lexicographically smallest (restart_costs[r], r) over
- * r in [0, restarts); best_perm (int32 [N]) receives restart_tours[r], best_cost (int64 [1]) the cost,
- * best_restart (int32 [1] or NULL) r.  restart_costs int64 [restarts], restart_tours int32 [restarts, N].
+ * Section 4.3 keeps the cheapest order its search has seen; with many independent descents that is the cheapest
+ * final order, and this call is that selection, the last step of every search call, on its own (so that a caller can
+ * time or capture the descents apart from it, or merge restarts from several calls): the lexicographically
+ * smallest (restart_costs[r], r) over r in [0, restarts); best_perm (int32 [N]) receives restart_tours[r],
+ * best_cost (int64 [1]) the cost, best_restart (int32 [1] or NULL) r.  restart_costs int64 [restarts], restart_tours int32 [restarts, N].
  */
 int cc_best_of_restarts(const int64_t* restart_costs, const int32_t* restart_tours, int32_t N, int32_t restarts,
                         int32_t* best_perm, int64_t* best_cost, int32_t* best_restart, void* stream);
@@ -344,9 +350,11 @@ int cc_sa_rd_search_ex(const int32_t* cost_matrix, int32_t N, int32_t chains, in
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Initial orders of restarts first .. first+count-1 for `seed` (the shuffle described above);
- * tours: int32 [count, N].  Also the generator of the seeded random orders used to exercise the
- * batch calls.
+ * The random initial orders of Section 4.3's search (the provider's list arrives in random order, Section 1):
+ * initial orders of restarts first .. first+count-1 for `seed` (the shuffle described above);
+ * tours: int32 [count, N].  `first` lets a caller draw any slice of the restart sequence (one shard of a search
+ * split over several calls draws its own restarts with their global ids).  Also the generator of the seeded
+ * random orders used to exercise the batch calls.
  */
 int cc_init_tours(int32_t N, int64_t first, int64_t count, uint64_t seed, int32_t* tours, void* stream);
 
@@ -363,7 +371,10 @@ int cc_cost_matrix_from_probes(const int32_t* samples, int32_t N, int32_t K, int
                                int32_t* cost_matrix, void* stream);
 
 /*
- * Checks the matrix contract: every entry in [0, CC_COST_MAX], and, if require_symmetric != 0,
+ * Checks the matrix contract that the other calls take on trust.  Section 4.2 makes the matrix symmetric
+ * (c_ij <- MAX(c_ij, c_ji)) before the undirected models of Section 4.1 are applied to it, and this library
+ * keeps costs in integer units with a fixed ceiling so that every sum over N <= CC_MAX_N hops fits 32 bits:
+ * every entry in [0, CC_COST_MAX] (else CC_ERR_COST_RANGE), and, if require_symmetric != 0,
  * c[a][b] == c[b][a].  Synchronises `stream` and returns CC_OK, CC_ERR_COST_RANGE or
  * CC_ERR_NOT_SYMMETRIC.  Allocates and frees four bytes of device memory.
  */

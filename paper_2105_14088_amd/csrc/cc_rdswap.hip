@@ -619,11 +619,12 @@ __global__ __launch_bounds__(1 << LOGN) void rdswap_tiled_kernel(const uint16_t*
                 piece[i] = ((const int4*)(folded + (size_t)node * N))[off];
             }
             {
-                const uint16_t* row = folded + (size_t)p * N;
+                // F is symmetric: column t[B + j] is read as row t[B + j], which the threads of a wave read side by side
+                const uint16_t* col = folded + p;
                 uint32_t w[QB / 2];
 #pragma unroll
                 for (int j = 0; j < QB; j += 2)
-                    w[j / 2] = (uint32_t)row[tl[b0 + j]] | ((uint32_t)row[tl[b0 + j + 1]] << 16);
+                    w[j / 2] = (uint32_t)col[(size_t)tl[b0 + j] * N] | ((uint32_t)col[(size_t)tl[b0 + j + 1] * N] << 16);
 #pragma unroll
                 for (int j = 0; j < QB / 2; ++j) ((uint32_t*)(ct + p * kCtRowBytes))[j] = w[j];
             }

@@ -51,11 +51,12 @@ VALU_OPS_PER_MOVE = 3                   # combine two gathers with the removed h
 #   LDS: SQ_INSTS_LDS wave instructions per launch x 256 B (64 lanes x 4 B) = bytes the kernel moved through LDS
 #   HBM: FETCH_SIZE (x 2.000) + WRITE_SIZE (x 1.000) KiB, scale factors from a plain 256 MiB device copy
 COUNTERS = {
-    "search_sum_lds_insts": None,
-    "search_sum_hbm_bytes": None,
-    "search_max_lds_insts": None,
-    "ring_batch_hbm_bytes": (262317.6 + 8196.2) * 1024,
-    "ring_batch_cold_hbm_bytes": None,
+    "search_sum_lds_insts": 2263348,                       # twoopt_sum_n64_kernel, 1024 restarts of workload 2
+    "search_sum_hbm_bytes": (120.0 * 2 + 272.0) * 1024,
+    "search_max_lds_insts": 840968,                        # twoopt_max_n64_kernel, 1024 restarts of workload 3
+    "search_max_hbm_bytes": (150.0 * 2 + 272.0) * 1024,
+    "ring_batch_hbm_bytes": (131158.5 * 2 + 8195.9) * 1024,        # 2^20 orders
+    "ring_batch_cold_hbm_bytes": (524374.5 * 2 + 32779.3) * 1024,  # 2^22 orders
 }
 
 
@@ -240,6 +241,9 @@ def main():
                         "frac_at_storage_width": lds_gbs3_packed / LDS_PEAK_GBS,
                         "bytes_per_move_at_storage_width": LDS_BYTES_PER_DIRECTED_MOVE_PACKED,
                         "traffic": lds_traffic("search_max_lds_insts"),
+                        "traffic_kind": "bytes moved through LDS per launch: SQ_INSTS_LDS x 256 B (one packed gather "
+                                        "per move delivers both directions of a pair)",
+                        "hbm_traffic": COUNTERS["search_max_hbm_bytes"],
                         "sweeps_per_launch": sweeps3,
                         "sweeps_per_restart": {"mean": float((moves3 + 1).mean()), "max": int((moves3 + 1).max())},
                         "ns_per_sweep_longest_restart": t_kernel3 * 1e6 / int((moves3 + 1).max())},

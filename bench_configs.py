@@ -80,7 +80,7 @@ def main():
              "best_cost": int(bufs.best_cost.item())}
         if args.oracle:
             import oracle
-            sample = min(w.restarts, {64: 256, 256: 16, 512: 4, 1024: 1}[w.n])
+            sample = min(w.restarts, 256 if w.n <= 64 else 16 if w.n <= 256 else 4 if w.n <= 512 else 1)
             t0 = time.perf_counter()
             oc, ot, om = oracle.restarts(c_host, obj, w.search_seed, 0, sample)
             dt = time.perf_counter() - t0
@@ -114,7 +114,7 @@ def main():
              "best_cost": int(bufs.best_cost.item()), "mean_cost": float(bufs.restart_costs.double().mean().item())}
         if args.oracle:
             import oracle
-            sample = min(restarts, {64: 64, 256: 4, 1024: 1}[n])
+            sample = min(restarts, 64 if n <= 64 else 4 if n <= 256 else 1)
             t0 = time.perf_counter()
             oc, ot, om = oracle.local_restarts(c_host, obj, classes, w.search_seed, 0, sample)
             dt = time.perf_counter() - t0

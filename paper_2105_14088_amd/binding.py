@@ -132,6 +132,17 @@ def _stream(stream) -> ctypes.c_void_p:
     return ctypes.c_void_p(s.cuda_stream)
 
 
+def _new(shape, dtype, device, stream=None) -> torch.Tensor:
+    """A tensor this binding allocates for a call.  The call only enqueues kernels, so with an explicit stream that
+    is not torch's current one the caching allocator must learn that the block is in use on that stream: otherwise
+    a tensor dropped by the caller (or a workspace dropped here on return) could be handed to other work while the
+    kernels still read or write it."""
+    t = torch.empty(shape, dtype=dtype, device=device)
+    if stream is not None:
+        t.record_stream(stream)
+    return t
+
+
 def _matrix(c: torch.Tensor) -> int:
     if c.dim() != 2 or c.shape[0] != c.shape[1]:
         raise ValueError("cost_matrix must be square")
@@ -150,7 +161,7 @@ def cc_ring_cost_batch(cost_matrix: torch.Tensor, perms: torch.Tensor, objective
         raise ValueError("perms must be [B, N]")
     b = int(perms.shape[0])
     if out is None:
-        out = torch.empty(b, dtype=torch.int64, device=cost_matrix.device)
+        out = _new(b, torch.int64, cost_matrix.device, stream)
     _check(lib().cc_ring_cost_batch(_dev(cost_matrix, torch.int32, "cost_matrix"), n, objective,
                                     _dev(perms, torch.int32, "perms"), b, _dev(out, torch.int64, "out"),
                                     _stream(stream)), "cc_ring_cost_batch")
@@ -164,7 +175,7 @@ def cc_ring_cost_batch_u8(cost_matrix: torch.Tensor, perms: torch.Tensor, object
         raise ValueError("perms must be [B, N]")
     b = int(perms.shape[0])
     if out is None:
-        out = torch.empty(b, dtype=torch.int64, device=cost_matrix.device)
+        out = _new(b, torch.int64, cost_matrix.device, stream)
     _check(lib().cc_ring_cost_batch_u8(_dev(cost_matrix, torch.int32, "cost_matrix"), n, objective,
                                        _dev(perms, torch.uint8, "perms"), b, _dev(out, torch.int64, "out"),
                                        _stream(stream)), "cc_ring_cost_batch_u8")
@@ -181,7 +192,7 @@ def cc_ring_cost_batch_u16(cost_matrix: torch.Tensor, perms: torch.Tensor, objec
         raise ValueError("perms must be a 16-bit integer tensor")
     b = int(perms.shape[0])
     if out is None:
-        out = torch.empty(b, dtype=torch.int64, device=cost_matrix.device)
+        out = _new(b, torch.int64, cost_matrix.device, stream)
     _check(lib().cc_ring_cost_batch_u16(_dev(cost_matrix, torch.int32, "cost_matrix"), n, objective,
                                         _dev(perms, perms.dtype, "perms"), b, _dev(out, torch.int64, "out"),
                                         _stream(stream)), "cc_ring_cost_batch_u16")
@@ -201,14 +212,14 @@ def cc_rd_cost_batch(cost_matrix: torch.Tensor, perms: torch.Tensor, out: Option
         raise ValueError("perms must be [B, N]")
     b = int(perms.shape[0])
     if out is None:
-        out = torch.empty(b, dtype=torch.int64, device=cost_matrix.device)
+        out = _new(b, torch.int64, cost_matrix.device, stream)
     if n < 128 and workspace is None:
         _check(lib().cc_rd_cost_batch(_dev(cost_matrix, torch.int32, "cost_matrix"), n,
                                       _dev(perms, torch.int32, "perms"), b, _dev(out, torch.int64, "out"),
                                       _stream(stream)), "cc_rd_cost_batch")
         return out
     if workspace is None:
-        workspace = torch.empty(cc_rd_batch_workspace_bytes(n), dtype=torch.uint8, device=cost_matrix.device)
+        workspace = _new(cc_rd_batch_workspace_bytes(n), torch.uint8, cost_matrix.device, stream)
     _check(lib().cc_rd_cost_batch_ex(_dev(cost_matrix, torch.int32, "cost_matrix"), n, _dev(perms, torch.int32, "perms"),
                                      b, _dev(out, torch.int64, "out"), _dev(workspace, torch.uint8, "workspace"),
                                      workspace.numel(), _stream(stream)), "cc_rd_cost_batch_ex")
@@ -221,10 +232,10 @@ def _bcube(cost_matrix, base, round_weights, perms, out, stream, workspace, wher
         raise ValueError("perms must be [B, N]")
     b = int(perms.shape[0])
     if out is None:
-        out = torch.empty(b, dtype=torch.int64, device=cost_matrix.device)
+        out = _new(b, torch.int64, cost_matrix.device, stream)
     folded_form = (base == 2 and n >= 128) or (base == 4 and n in (256, 1024))      # the sizes the workspace serves
     if workspace is None and folded_form:
-        workspace = torch.empty(cc_rd_batch_workspace_bytes(n), dtype=torch.uint8, device=cost_matrix.device)
+        workspace = _new(cc_rd_batch_workspace_bytes(n), torch.uint8, cost_matrix.device, stream)
     c, pm, o = _dev(cost_matrix, torch.int32, "cost_matrix"), _dev(perms, torch.int32, "perms"), _dev(out, torch.int64, "out")
     w = _dev(round_weights, torch.int32, "round_weights")
     if workspace is not None:
@@ -265,7 +276,7 @@ def cc_dbt_cost_batch(cost_matrix: torch.Tensor, perms: torch.Tensor, out: Optio
         raise ValueError("perms must be [B, N]")
     b = int(perms.shape[0])
     if out is None:
-        out = torch.empty(b, dtype=torch.int64, device=cost_matrix.device)
+        out = _new(b, torch.int64, cost_matrix.device, stream)
     _check(lib().cc_dbt_cost_batch(_dev(cost_matrix, torch.int32, "cost_matrix"), n, _dev(perms, torch.int32, "perms"),
                                    b, _dev(out, torch.int64, "out"), _stream(stream)), "cc_dbt_cost_batch")
     return out
@@ -278,8 +289,8 @@ def cc_2opt_workspace_bytes(n: int, objective: int, restarts: int) -> int:
 def cc_2opt_search(cost_matrix: torch.Tensor, objective: int, restarts: int, seed: int, stream=None):
     """Returns (best_perm int32[N], best_cost int64[1]) device tensors (valid after stream sync)."""
     n = _matrix(cost_matrix)
-    best_perm = torch.empty(n, dtype=torch.int32, device=cost_matrix.device)
-    best_cost = torch.empty(1, dtype=torch.int64, device=cost_matrix.device)
+    best_perm = _new(n, torch.int32, cost_matrix.device, stream)
+    best_cost = _new(1, torch.int64, cost_matrix.device, stream)
     _check(lib().cc_2opt_search(_dev(cost_matrix, torch.int32, "cost_matrix"), n, objective, restarts,
                                 seed & (2**64 - 1), _dev(best_perm, torch.int32, "best_perm"),
                                 _dev(best_cost, torch.int64, "best_cost"), _stream(stream)), "cc_2opt_search")
@@ -302,18 +313,18 @@ def cc_2opt_search_noalloc(cost_matrix: torch.Tensor, objective: int, restarts: 
 class SearchBuffers:
     """Device buffers for cc_2opt_search_ex, allocated once and reusable across calls."""
 
-    def __init__(self, n: int, objective: int, restarts: int, device, per_restart: bool = True):
+    def __init__(self, n: int, objective: int, restarts: int, device, per_restart: bool = True, stream=None):
         self.n, self.objective, self.restarts = n, objective, restarts
-        self.best_perm = torch.empty(n, dtype=torch.int32, device=device)
-        self.best_cost = torch.empty(1, dtype=torch.int64, device=device)
-        self.best_restart = torch.empty(1, dtype=torch.int32, device=device)
-        self.restart_costs = torch.empty(restarts, dtype=torch.int64, device=device) if per_restart else None
-        self.restart_tours = torch.empty((restarts, n), dtype=torch.int32, device=device) if per_restart else None
-        self.restart_moves = torch.empty(restarts, dtype=torch.int32, device=device) if per_restart else None
+        self.best_perm = _new(n, torch.int32, device, stream)
+        self.best_cost = _new(1, torch.int64, device, stream)
+        self.best_restart = _new(1, torch.int32, device, stream)
+        self.restart_costs = _new(restarts, torch.int64, device, stream) if per_restart else None
+        self.restart_tours = _new((restarts, n), torch.int32, device, stream) if per_restart else None
+        self.restart_moves = _new(restarts, torch.int32, device, stream) if per_restart else None
         nbytes = cc_2opt_workspace_bytes(n, objective, restarts)
         if nbytes == 0:
             raise ValueError("invalid (N, objective, restarts)")
-        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+        self.workspace = _new(nbytes + 256, torch.uint8, device, stream)
         off = (-self.workspace.data_ptr()) % 256
         self.ws_ptr = self.workspace.data_ptr() + off
         self.ws_bytes = nbytes
@@ -325,7 +336,7 @@ def cc_2opt_search_ex(cost_matrix: torch.Tensor, objective: int, restarts: int, 
     """pick_best=False stops after the per-restart results (cc_best_of_restarts picks the winner later)."""
     n = _matrix(cost_matrix)
     if buffers is None:
-        buffers = SearchBuffers(n, objective, restarts, cost_matrix.device)
+        buffers = SearchBuffers(n, objective, restarts, cost_matrix.device, stream=stream)
     if (buffers.n, buffers.restarts) != (n, restarts):
         raise ValueError("buffers were sized for a different search")
     if init_tours is not None and tuple(init_tours.shape) != (restarts, n):
@@ -347,8 +358,8 @@ def cc_local_search(cost_matrix: torch.Tensor, objective: int, move_classes: int
                     stream=None):
     """Returns (best_perm int32[N], best_cost int64[1]) device tensors (valid after stream sync)."""
     n = _matrix(cost_matrix)
-    best_perm = torch.empty(n, dtype=torch.int32, device=cost_matrix.device)
-    best_cost = torch.empty(1, dtype=torch.int64, device=cost_matrix.device)
+    best_perm = _new(n, torch.int32, cost_matrix.device, stream)
+    best_cost = _new(1, torch.int64, cost_matrix.device, stream)
     _check(lib().cc_local_search(_dev(cost_matrix, torch.int32, "cost_matrix"), n, objective, move_classes, restarts,
                                  seed & (2**64 - 1), _dev(best_perm, torch.int32, "best_perm"),
                                  _dev(best_cost, torch.int64, "best_cost"), _stream(stream)), "cc_local_search")
@@ -361,7 +372,7 @@ def cc_local_search_ex(cost_matrix: torch.Tensor, objective: int, move_classes: 
     """cc_2opt_search_ex over the move classes `move_classes` (CC_MOVES_*)."""
     n = _matrix(cost_matrix)
     if buffers is None:
-        buffers = SearchBuffers(n, objective, restarts, cost_matrix.device)
+        buffers = SearchBuffers(n, objective, restarts, cost_matrix.device, stream=stream)
     if (buffers.n, buffers.restarts) != (n, restarts):
         raise ValueError("buffers were sized for a different search")
     if init_tours is not None and tuple(init_tours.shape) != (restarts, n):
@@ -394,8 +405,8 @@ def cc_best_of_restarts(buffers: SearchBuffers, stream=None) -> SearchBuffers:
 def cc_rd_swap_search(cost_matrix: torch.Tensor, restarts: int, seed: int, stream=None):
     """Returns (best_perm int32[N], best_cost int64[1]) device tensors (valid after stream sync)."""
     n = _matrix(cost_matrix)
-    best_perm = torch.empty(n, dtype=torch.int32, device=cost_matrix.device)
-    best_cost = torch.empty(1, dtype=torch.int64, device=cost_matrix.device)
+    best_perm = _new(n, torch.int32, cost_matrix.device, stream)
+    best_cost = _new(1, torch.int64, cost_matrix.device, stream)
     _check(lib().cc_rd_swap_search(_dev(cost_matrix, torch.int32, "cost_matrix"), n, restarts, seed & (2**64 - 1),
                                    _dev(best_perm, torch.int32, "best_perm"),
                                    _dev(best_cost, torch.int64, "best_cost"), _stream(stream)), "cc_rd_swap_search")
@@ -407,7 +418,7 @@ def cc_rd_swap_search_ex(cost_matrix: torch.Tensor, restarts: int, seed: int,
                          stream=None) -> SearchBuffers:
     n = _matrix(cost_matrix)
     if buffers is None:
-        buffers = SearchBuffers(n, 0, restarts, cost_matrix.device)
+        buffers = SearchBuffers(n, 0, restarts, cost_matrix.device, stream=stream)
     if (buffers.n, buffers.restarts) != (n, restarts):
         raise ValueError("buffers were sized for a different search")
     if init_tours is not None and tuple(init_tours.shape) != (restarts, n):
@@ -429,8 +440,8 @@ def _sa_search(fn_name: str, cost_matrix: torch.Tensor, chains: int, steps: int,
                stream=None):
     """Returns (best_perm int32[N], best_cost int64[1]) device tensors (valid after stream sync)."""
     n = _matrix(cost_matrix)
-    best_perm = torch.empty(n, dtype=torch.int32, device=cost_matrix.device)
-    best_cost = torch.empty(1, dtype=torch.int64, device=cost_matrix.device)
+    best_perm = _new(n, torch.int32, cost_matrix.device, stream)
+    best_cost = _new(1, torch.int64, cost_matrix.device, stream)
     _check(getattr(lib(), fn_name)(_dev(cost_matrix, torch.int32, "cost_matrix"), n, chains, steps, t_start, t_end,
                                    seed & (2**64 - 1), _dev(best_perm, torch.int32, "best_perm"),
                                    _dev(best_cost, torch.int64, "best_cost"), _stream(stream)), fn_name)
@@ -444,7 +455,7 @@ def _sa_search_ex(fn_name: str, cost_matrix: torch.Tensor, chains: int, steps: i
     and restart_moves (accepted proposals); best_restart is the winning chain."""
     n = _matrix(cost_matrix)
     if buffers is None:
-        buffers = SearchBuffers(n, 0, chains, cost_matrix.device)
+        buffers = SearchBuffers(n, 0, chains, cost_matrix.device, stream=stream)
     if (buffers.n, buffers.restarts) != (n, chains):
         raise ValueError("buffers were sized for a different search")
     if init_tours is not None and tuple(init_tours.shape) != (chains, n):
@@ -484,7 +495,7 @@ def cc_sa_rd_search_ex(cost_matrix, chains, steps, t_start, t_end, seed, init_to
 def cc_init_tours(n: int, count: int, seed: int, first: int = 0, device="cuda", out: Optional[torch.Tensor] = None,
                   stream=None) -> torch.Tensor:
     if out is None:
-        out = torch.empty((count, n), dtype=torch.int32, device=device)
+        out = _new((count, n), torch.int32, device, stream)
     _check(lib().cc_init_tours(n, first, count, seed & (2**64 - 1), _dev(out, torch.int32, "tours"), _stream(stream)),
            "cc_init_tours")
     return out
@@ -496,7 +507,7 @@ def cc_cost_matrix_from_probes(samples: torch.Tensor, percentile: int = 10, symm
         raise ValueError("samples must be [N, N, K]")
     n, k = int(samples.shape[0]), int(samples.shape[2])
     if out is None:
-        out = torch.empty((n, n), dtype=torch.int32, device=samples.device)
+        out = _new((n, n), torch.int32, samples.device, stream)
     _check(lib().cc_cost_matrix_from_probes(_dev(samples, torch.int32, "samples"), n, k, percentile,
                                             1 if symmetrize else 0, _dev(out, torch.int32, "cost_matrix"),
                                             _stream(stream)), "cc_cost_matrix_from_probes")

@@ -34,6 +34,9 @@
  *     the matrix entries, either a kernel specialised for that case or a general kernel that serves every
  *     case.  The environment variable CC_FORCE_PATH=general (read at every call) pins the general kernels:
  *     for comparing the two on the same input, nothing else.
+ *   - CC_LDS_POISON=1 in the environment (a debugging aid, read at every call) makes every call first fill the
+ *     on-chip shared memory of all compute units with 0x7f bytes, so that a kernel reading shared memory it has
+ *     not written cannot pass a test on what an earlier launch left there.  Costs one extra launch per call.
  */
 #ifndef CC_H_
 #define CC_H_

@@ -2,6 +2,7 @@
 // Declarations and contracts: include/cc.h.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
 #include <mutex>
 
 #include "../../include/cc.h"
@@ -49,6 +50,28 @@ int check_matrix_args(const int32_t* c, int N) {
     return CC_OK;
 }
 
+// Debug aid.  With CC_LDS_POISON=1 in the environment (read at every call) each call first fills the LDS of every
+// compute unit with 0x7f bytes, so that a kernel that reads LDS it has not written gets large garbage instead of
+// whatever an earlier kernel left there (often the very data it expects), and a parity test fails.  LDS keeps its
+// contents between workgroups; a workgroup that asks for all of a compute unit's LDS has the unit to itself, and far
+// more such workgroups than compute units are launched, so every unit is reached.
+constexpr int kLdsBytesPerCu = 160 * 1024;
+__global__ __launch_bounds__(1024) void lds_poison_kernel() {
+    extern __shared__ uint32_t lds_words[];
+    volatile uint32_t* p = lds_words;
+    for (int i = threadIdx.x; i < kLdsBytesPerCu / 4; i += 1024) p[i] = 0x7f7f7f7fu;
+}
+
+hipError_t poison_lds_if_asked(hipStream_t s) {
+    const char* v = getenv("CC_LDS_POISON");
+    if (!v || v[0] != '1') return hipSuccess;
+    hipError_t e = hipFuncSetAttribute((const void*)lds_poison_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       kLdsBytesPerCu);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(lds_poison_kernel, dim3(2048), dim3(1024), kLdsBytesPerCu, s);
+    return hipGetLastError();
+}
+
 // Device memory of cc_2opt_search_noalloc: one array per GPU, part of the code object, there from the moment the
 // library is loaded on a device until the process ends.  In host code the name `scratch` is only a handle for
 // hipGetSymbolAddress; the array's memory is reached through the per-device pointer that call returns.
@@ -85,6 +108,7 @@ int cc_ring_cost_batch(const int32_t* cost_matrix, int32_t N, int32_t objective,
     if (B == 0) return CC_OK;
     if (!perms || !out_costs) return CC_ERR_INVALID_ARG;
     if (((uintptr_t)perms & 3u) || ((uintptr_t)out_costs & 7u) || ((uintptr_t)cost_matrix & 3u)) return CC_ERR_INVALID_ARG;
+    CC_HIP(poison_lds_if_asked((hipStream_t)stream));
     CC_HIP(cc::launch_ring_cost_batch(cost_matrix, N, (objective & 1) != 0, perms, B, out_costs, (hipStream_t)stream));
     return CC_OK;
 }
@@ -97,6 +121,7 @@ int cc_ring_cost_batch_u8(const int32_t* cost_matrix, int32_t N, int32_t objecti
     if (B == 0) return CC_OK;
     if (!perms || !out_costs) return CC_ERR_INVALID_ARG;
     if (((uintptr_t)out_costs & 7u) || ((uintptr_t)cost_matrix & 3u)) return CC_ERR_INVALID_ARG;
+    CC_HIP(poison_lds_if_asked((hipStream_t)stream));
     CC_HIP(cc::launch_ring_cost_batch_u8(cost_matrix, N, (objective & 1) != 0, perms, B, out_costs, (hipStream_t)stream));
     return CC_OK;
 }
@@ -108,6 +133,7 @@ int cc_ring_cost_batch_u16(const int32_t* cost_matrix, int32_t N, int32_t object
     if (B == 0) return CC_OK;
     if (!perms || !out_costs) return CC_ERR_INVALID_ARG;
     if (((uintptr_t)perms & 1u) || ((uintptr_t)out_costs & 7u) || ((uintptr_t)cost_matrix & 3u)) return CC_ERR_INVALID_ARG;
+    CC_HIP(poison_lds_if_asked((hipStream_t)stream));
     CC_HIP(cc::launch_ring_cost_batch_u16(cost_matrix, N, (objective & 1) != 0, perms, B, out_costs, (hipStream_t)stream));
     return CC_OK;
 }
@@ -120,6 +146,7 @@ int cc_rd_cost_batch(const int32_t* cost_matrix, int32_t N, const int32_t* perms
     if (B == 0) return CC_OK;
     if (!perms || !out_costs) return CC_ERR_INVALID_ARG;
     if (((uintptr_t)perms & 3u) || ((uintptr_t)out_costs & 7u) || ((uintptr_t)cost_matrix & 3u)) return CC_ERR_INVALID_ARG;
+    CC_HIP(poison_lds_if_asked((hipStream_t)stream));
     CC_HIP(cc::launch_rd_cost_batch(cost_matrix, N, nullptr, perms, B, out_costs, (hipStream_t)stream));
     return CC_OK;
 }
@@ -140,6 +167,7 @@ int cc_rd_cost_batch_ex(const int32_t* cost_matrix, int32_t N, const int32_t* pe
     if (!perms || !out_costs) return CC_ERR_INVALID_ARG;
     if (((uintptr_t)perms & 3u) || ((uintptr_t)out_costs & 7u) || ((uintptr_t)cost_matrix & 3u)) return CC_ERR_INVALID_ARG;
     char* base = (char*)workspace;
+    CC_HIP(poison_lds_if_asked((hipStream_t)stream));
     CC_HIP(cc::launch_rd_cost_batch(cost_matrix, N, nullptr, perms, B, out_costs, (hipStream_t)stream, (int32_t*)base,
                                     (uint16_t*)(base + 256)));
     return CC_OK;
@@ -157,6 +185,7 @@ static int bcube_batch(const int32_t* cost_matrix, int32_t N, int32_t base, cons
     if (!perms || !out_costs) return CC_ERR_INVALID_ARG;
     if (((uintptr_t)perms & 3u) || ((uintptr_t)out_costs & 7u) || ((uintptr_t)cost_matrix & 3u)) return CC_ERR_INVALID_ARG;
     char* ws = (char*)workspace;
+    CC_HIP(poison_lds_if_asked((hipStream_t)stream));
     CC_HIP(cc::launch_bcube_cost_batch(cost_matrix, N, base, weights, perms, B, out_costs, (hipStream_t)stream,
                                        (int32_t*)ws, ws ? (uint16_t*)(ws + 256) : nullptr));
     return CC_OK;
@@ -189,6 +218,7 @@ int cc_dbt_cost_batch(const int32_t* cost_matrix, int32_t N, const int32_t* perm
     if (B == 0) return CC_OK;
     if (!perms || !out_costs) return CC_ERR_INVALID_ARG;
     if (((uintptr_t)perms & 3u) || ((uintptr_t)out_costs & 7u) || ((uintptr_t)cost_matrix & 3u)) return CC_ERR_INVALID_ARG;
+    CC_HIP(poison_lds_if_asked((hipStream_t)stream));
     CC_HIP(cc::launch_dbt_cost_batch(cost_matrix, N, perms, B, out_costs, (hipStream_t)stream));
     return CC_OK;
 }
@@ -226,6 +256,7 @@ static int ring_search_ex(const int32_t* cost_matrix, int32_t N, int32_t objecti
     if (init_tours && init_tours != tours)
         CC_HIP(hipMemcpyAsync(tours, init_tours, sizeof(int32_t) * (size_t)restarts * (size_t)N,
                               hipMemcpyDeviceToDevice, s));
+    CC_HIP(poison_lds_if_asked((hipStream_t)stream));
     CC_HIP(cc::launch_2opt(cost_matrix, N, objective, classes, restarts, seed, init_tours != nullptr, tours, costs,
                            moves, flags, (uint16_t*)(base + w.mat16), best_perm, best_cost, best_restart, s));
     return CC_OK;
@@ -273,6 +304,7 @@ int cc_best_of_restarts(const int64_t* restart_costs, const int32_t* restart_tou
                         int32_t* best_perm, int64_t* best_cost, int32_t* best_restart, void* stream) {
     if (N < 2 || N > CC_MAX_N) return CC_ERR_UNSUPPORTED_N;
     if (!restart_costs || !restart_tours || restarts < 1 || !best_perm || !best_cost) return CC_ERR_INVALID_ARG;
+    CC_HIP(poison_lds_if_asked((hipStream_t)stream));
     CC_HIP(cc::launch_best_restart(restart_costs, restart_tours, N, restarts, best_perm, best_cost, best_restart,
                                    (hipStream_t)stream));
     return CC_OK;
@@ -317,6 +349,7 @@ int cc_rd_swap_search_ex(const int32_t* cost_matrix, int32_t N, int32_t restarts
     if (init_tours && init_tours != tours)
         CC_HIP(hipMemcpyAsync(tours, init_tours, sizeof(int32_t) * (size_t)restarts * (size_t)N,
                               hipMemcpyDeviceToDevice, s));
+    CC_HIP(poison_lds_if_asked((hipStream_t)stream));
     CC_HIP(cc::launch_rdswap(cost_matrix, N, restarts, seed, init_tours != nullptr, tours, costs, moves,
                              (int32_t*)(base + w.flags), (uint16_t*)(base + w.mat16), s));
     CC_HIP(cc::launch_best_restart(costs, tours, N, restarts, best_perm, best_cost, best_restart, s));
@@ -364,6 +397,7 @@ static int sa_search_ex(bool halving_doubling, const int32_t* cost_matrix, int32
     int32_t* tours = chain_tours ? chain_tours : (int32_t*)(base + w.tours);
     if (init_tours && init_tours != tours)
         CC_HIP(hipMemcpyAsync(tours, init_tours, sizeof(int32_t) * (size_t)chains * (size_t)N, hipMemcpyDeviceToDevice, s));
+    CC_HIP(poison_lds_if_asked(s));
     if (halving_doubling)
         CC_HIP(cc::launch_sa_rd(cost_matrix, N, chains, steps, t_start, t_end, seed, init_tours == nullptr, tours, costs,
                                 acc, s));
@@ -423,6 +457,7 @@ int cc_init_tours(int32_t N, int64_t first, int64_t count, uint64_t seed, int32_
     if (first < 0 || count < 0 || first + count > (int64_t)1 << 32) return CC_ERR_INVALID_ARG;
     if (count == 0) return CC_OK;
     if (!tours || ((uintptr_t)tours & 3u)) return CC_ERR_INVALID_ARG;
+    CC_HIP(poison_lds_if_asked((hipStream_t)stream));
     CC_HIP(cc::launch_init_tours(N, first, count, seed, tours, (hipStream_t)stream));
     return CC_OK;
 }
@@ -434,6 +469,7 @@ int cc_cost_matrix_from_probes(const int32_t* samples, int32_t N, int32_t K, int
     if (K < 1 || K > CC_MAX_PROBES || percentile < 0 || percentile > 100) return CC_ERR_INVALID_ARG;
     int64_t rank = ((int64_t)percentile * K + 99) / 100;
     if (rank < 1) rank = 1;
+    CC_HIP(poison_lds_if_asked((hipStream_t)stream));
     CC_HIP(cc::launch_probes_percentile(samples, N, K, (int)rank, symmetrize != 0, cost_matrix, (hipStream_t)stream));
     return CC_OK;
 }

@@ -210,6 +210,13 @@ def loop():
     return out
 
 
+def operands(lane, rank_a, mbase):
+    """The read-only operands of the asm statement as cc_2opt_n64.hip computes them (lane = 0 .. 63,
+    rank_a = (lane - 1) mod 64, mbase = LDS byte offset of the matrix): for the CPU model of the loop in the tests."""
+    return {"rank_bits": rank_a << 8, "ra": rank_a, "id_base": lane * 64, "id_flip": 64 + rank_a, "lane": lane,
+            "lane4": lane << 2, "mbase": mbase, "mask": 0xff, "himask": 0xfffff000}
+
+
 def text():
     lines = loop()
     out = ["// Generated by gen_2opt_n64_loop.py - do not edit by hand.  The descent loop of twoopt_sum_n64_kernel for matrices",

@@ -132,3 +132,43 @@ def test_the_loop_is_bounded_and_has_one_back_edge():
     assert sum(i.startswith("s_branch LOOP_TOP") for i in ins) == 1
     assert "s_bitcmp1_b32 %[applied], 22" in ins and ins.count("s_cbranch_scc1 LOOP_DONE%=") == 1
     assert ins.count("s_cbranch_scc0 LOOP_DONE%=") == 1
+
+
+def _emulated_descent(c, tour):
+    """Runs the committed loop text in the wave64 interpreter: matrix c (64 x 64, symmetric, entries below 2^16),
+    start order `tour`; returns (final order, final cost, applied moves)."""
+    import numpy as np
+    from wave64_emulator import Wave
+    gen = _generator()
+    lines = gen.loop()
+    n, mbase = 64, 0x2000
+    lds = np.zeros(mbase // 4 + n * n, dtype="<u4")
+    lds[mbase // 4:] = (c.astype(np.int64) << 14).reshape(-1)
+    lane = np.arange(n)
+    t = np.asarray(tour, dtype=np.int64)
+    fm = (c[t, np.roll(t, 1)].astype(np.int64)) << 14
+    rank_a = (lane + n - 1) & (n - 1)
+    w = Wave(lds.tobytes(), dict(gen.operands(lane, rank_a, mbase), t=t, fm=fm, cur=int(fm.sum() >> 14), applied=0))
+    w.run(lines)
+    return w.named["t"].astype(np.int64), w.named["cur"], w.named["applied"]
+
+
+def test_emulated_loop_takes_the_oracles_descent():
+    """What the loop computes, checked on the CPU: the committed text, run instruction by instruction in a wave64
+    interpreter, ends every descent with the oracle's order, cost and move count (random matrices with few distinct
+    values, so that many moves tie and the lowest-id rule decides; the 16-bit edge of the value range)."""
+    import sys
+    import numpy as np
+    sys.path.insert(0, ROOT)
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import oracle
+    for case, hi in enumerate((3, 40, 65535, 1000)):
+        rng = np.random.default_rng(100 + case)
+        c = rng.integers(0 if hi > 3 else 1, hi + 1, size=(64, 64))
+        c = np.triu(c, 1)
+        c = (c + c.T).astype(np.int32)
+        tours = np.stack([np.concatenate(([0], 1 + rng.permutation(63))) for _ in range(3)]).astype(np.int32)
+        want_c, want_t, want_m = oracle.restarts(c, oracle.SUM, 0, 0, len(tours), init=tours)
+        for r, tour in enumerate(tours):
+            t, cost, applied = _emulated_descent(c, tour)
+            assert np.array_equal(t, want_t[r]) and cost == want_c[r] and applied == want_m[r], (case, r)

@@ -158,6 +158,8 @@ class Wave:
             self.put(a[0], g(a[2]) - g(a[1]))
         elif op == "v_lshl_add_u32":
             self.put(a[0], (g(a[1]) << (sc(a[2]) & 31)) + g(a[3]))
+        elif op == "v_lshl_or_b32":
+            self.put(a[0], (g(a[1]) << (sc(a[2]) & 31)) | g(a[3]))
         elif op == "v_lshlrev_b32":
             self.put(a[0], g(a[2]) << (sc(a[1]) & 31))
         elif op == "v_and_or_b32":

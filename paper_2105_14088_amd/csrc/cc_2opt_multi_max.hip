@@ -167,15 +167,20 @@ __global__ __launch_bounds__(64 * max_waves(DIRECTED)) void twoopt_max_multi_ker
             kw[K + m] = from_next_lane(kw[m]);
             wl[K + m] = from_next_lane(wl[m]);
         }
+        // N = 128, 256: the windows keep their length up to the last diagonal (kSwitch == H), and a move's value is the
+        // maximum over both pieces anyway, so the fixed window that ends at a-1 starts the running maximum of S1 and
+        // costs nothing per diagonal; the last diagonal, with its shorter windows, takes S1's inner hops from the table.
+        constexpr bool kFold = kSwitch == H;
         unsigned s1[K], bestA[K], bestB[K], far[K];
 #pragma unroll
         for (int m = 0; m < K; ++m) {
             s1[m] = hw[m + 1];                  // hop a+1: S1's only inner hop at d = 2
             bestA[m] = bestB[m] = 0xffffffffu;
             far[m] = far1[m];
+            if (kFold) s1[m] = wmax(s1[m], far1[m]);
         }
 
-        auto diagonal = [&](int rr) {                    // partner of slot m sits at window index m + rr
+        auto diagonal = [&](int rr, bool folded) {       // partner of slot m sits at window index m + rr
             unsigned P[K];
 #pragma unroll
             for (int m = 0; m < K; ++m) {
@@ -186,7 +191,7 @@ __global__ __launch_bounds__(64 * max_waves(DIRECTED)) void twoopt_max_multi_ker
 #pragma unroll
             for (int m = 0; m < K; ++m) {
                 const unsigned EP = m ? P[m - 1] : Plast;
-                const unsigned s2 = wmax(wl[m + rr], far[m]);
+                const unsigned s2 = folded ? wl[m + rr] : wmax(wl[m + rr], far[m]);
                 const unsigned val = wmax(wmax(P[m], EP), wmax(s1[m], s2));
                 if (DIRECTED) {
                     bestA[m] = min(bestA[m], (val & 0xffff0000u) | kw[m + rr]);
@@ -228,7 +233,7 @@ __global__ __launch_bounds__(64 * max_waves(DIRECTED)) void twoopt_max_multi_ker
         };
         // d = K*q + rr.  q = 0: only rr >= 2 (K = 2: nothing); q = 1 .. H/K - 1: all rr; q = H/K: rr = 0 (d = N/2)
 #pragma unroll
-        for (int rr = 2; rr < K; ++rr) diagonal(rr);
+        for (int rr = 2; rr < K; ++rr) diagonal(rr, kFold);
         slide();
         constexpr int kSwitchQ = kSwitch / K, kSwitchR = kSwitch % K;       // the block of diagonals that holds the switch
         auto blocks = [&](int q0, int q1) {
@@ -236,7 +241,7 @@ __global__ __launch_bounds__(64 * max_waves(DIRECTED)) void twoopt_max_multi_ker
 #pragma unroll 2
             for (int q = q0; q < q1; ++q) {
 #pragma unroll
-                for (int rr = 0; rr < K; ++rr) diagonal(rr);
+                for (int rr = 0; rr < K; ++rr) diagonal(rr, kFold);
                 slide();
             }
         };
@@ -245,15 +250,25 @@ __global__ __launch_bounds__(64 * max_waves(DIRECTED)) void twoopt_max_multi_ker
 #pragma unroll
             for (int rr = 0; rr < K; ++rr) {
                 if (rr == kSwitchR) shorter_windows(kSwitchQ);
-                diagonal(rr);
+                diagonal(rr, false);
             }
             slide();
             blocks(kSwitchQ + 1, H / K);
         } else {
             blocks(1, H / K);
         }
-        if (kSwitch == H) shorter_windows(H / K);
-        diagonal(0);
+        if (kSwitch == H) {
+            shorter_windows(H / K);
+            // S1's inner hops a+1 .. a+H-1 without the fixed window: two windows of L0 = H / 2 hops from the table one level
+            // down, whose words carry the two directions the other way round
+#pragma unroll
+            for (int m = 0; m < K; ++m) {
+                const int a = K * lane + m;
+                const unsigned x = wmax(keep[wrap(a + 1)], keep[wrap(a + H - L0)]);
+                s1[m] = DIRECTED ? __builtin_amdgcn_alignbit(x, x, 16) : x;
+            }
+        }
+        diagonal(0, false);
 
         // per rank and direction: best partner -> move id; then the lexicographic minimum of (value, id) over the wave
         int bv = 0x7fffffff, bid = 0x7fffffff;

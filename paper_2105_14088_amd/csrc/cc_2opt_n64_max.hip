@@ -179,7 +179,10 @@ __device__ __forceinline__ void descend_max_packed(const int32_t* m2, int lane, 
         unsigned w = rol((unsigned)((rank_a << 10) | (t << 2)));
         unsigned fbr = rol(fb);
         unsigned r5 = rol(rol(m5));
-        unsigned s1 = 0, bestA = kNoKey, bestB = kNoKey;
+        // S2's inner hops b+1 .. a-1 are hops b+1 .. b+32 together with hops a+33 .. a+63 for every d < 32 (the first
+        // window ends at a+d+32 >= a+34), and hops a+33 .. a+63 alone at d = 32.  A move's value is the maximum over both
+        // pieces anyway, so the fixed window starts the running maximum of S1 and costs nothing per diagonal.
+        unsigned s1 = far32, bestA = kNoKey, bestB = kNoKey;
 #pragma unroll
         for (int d = 2; d <= kN / 2; ++d) {
             s1 = pk_max(s1, fbr);        // edge b-1 (the previous diagonal's partner) joins S1's inner edges
@@ -192,9 +195,9 @@ __device__ __forceinline__ void descend_max_packed(const int32_t* m2, int lane, 
             asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(off) : "v"(w), "s"(0xfc), "v"(rowofs));
             const unsigned P = *(const uint32_t*)(mbytes + off);                                 // G | GT << 16
             const unsigned EP = (unsigned)from_prev_lane((int)P);
-            const unsigned s2 = d < kN / 2 ? pk_max(r5, far) : far32;                // S2: b | f << 16
             // lower half: max(G, EG, S2's b, S1's f) = value B; upper half: max(GT, EGT, S2's f, S1's b) = value A
-            const unsigned val = pk_max(pk_max(P, EP), pk_max(s1, s2));
+            const unsigned PE = pk_max(P, EP);
+            const unsigned val = d < kN / 2 ? pk_max(PE, pk_max(s1, r5)) : pk_max(PE, s1);
             bestA = min(bestA, (val & 0xffff0000u) | w);
             bestB = min(bestB, (val << 16) | w);
         }

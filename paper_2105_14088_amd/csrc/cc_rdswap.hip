@@ -500,7 +500,8 @@ __global__ __launch_bounds__(SPLIT << LOGN) void rdswap_block_kernel(const int32
 }
 
 // ------------------------------------------------------------------ N = 512, 1024: tiles of the folded matrix in LDS
-// One workgroup per restart, one thread per rank p.  The folded 16-bit matrix F (512 KiB / 2 MiB, in the workspace)
+// One workgroup per restart, one or two threads per rank p (two at N = 512: 1024 threads either way).  The folded
+// 16-bit matrix F (512 KiB / 2 MiB, in the workspace)
 // does not fit LDS, and gathered through L2 a sweep is bound by the misses one compute unit keeps in flight.  Here
 // a sweep goes through the partner ranks q in blocks of QB consecutive ranks B; for a block the workgroup stages
 //   CT[x][j]      = F[x][t[B + j]]                 every row x, the QB columns of the block's nodes
@@ -514,13 +515,14 @@ __global__ __launch_bounds__(SPLIT << LOGN) void rdswap_block_kernel(const int32
 // pair is then scored exactly once, by the thread p for which p + q is even and p < q, or odd and p > q).  Pairs of
 // round mates (q = p xor 2^k), whose round k keeps its cost, are scored apart from the folded copy through L2: 9 or
 // 10 per thread.  Round maxima, keys, reduction and the swap as in the kernel above.
-template <int LOGN, int LOGQ>
-__global__ __launch_bounds__(1 << LOGN) void rdswap_tiled_kernel(const uint16_t* __restrict__ folded,
+template <int LOGN, int LOGQ, int SPLIT>
+__global__ __launch_bounds__(SPLIT << LOGN) void rdswap_tiled_kernel(const uint16_t* __restrict__ folded,
                                                                  int32_t* __restrict__ tours,
                                                                  int64_t* __restrict__ costs,
                                                                  int32_t* __restrict__ moves,
                                                                  const int32_t* __restrict__ flags) {
-    constexpr int N = 1 << LOGN, QB = 1 << LOGQ, NH = LOGN - LOGQ, NW = N / 64, LB = LOGN - 1;
+    constexpr int N = 1 << LOGN, QB = 1 << LOGQ, NH = LOGN - LOGQ, NT = SPLIT * N, NW = NT / 64, LB = LOGN - 1;
+    static_assert(SPLIT == 1 || SPLIT == 2, "one or two threads per rank");
     constexpr int kIdBits = 2 * LOGN;
     constexpr int kInf = 0x7fffffff;
     // a row of CT takes QB / 2 + 1 words: with QB / 2 the rows of the 64 lanes of a gather would fall into four or
@@ -533,10 +535,13 @@ __global__ __launch_bounds__(1 << LOGN) void rdswap_tiled_kernel(const uint16_t*
     unsigned char* ct = (unsigned char*)(rt + (size_t)NH * QB * N);        // [N] rows of kCtRowBytes
     __shared__ int red_i[2][NW];
     __shared__ unsigned long long red_k[NW];
-    const int tid = threadIdx.x, p = tid, lane = tid & 63, wv = tid >> 6;
+    // SPLIT threads per rank p share the rank's steps (part 0 takes the first half of every block of partners): with one
+    // thread per rank at N = 512 a SIMD holds two wavefronts, too few to overlap one's LDS gathers with the other's
+    // arithmetic
+    const int tid = threadIdx.x, p = tid & (N - 1), part = tid >> LOGN, lane = tid & 63, wv = tid >> 6;
     const int64_t r = blockIdx.x;
     int t = clampi(tours[r * N + p], 0, N - 1);
-    tl[p] = t;
+    if (part == 0) tl[p] = t;
     __syncthreads();
     int parity = 0;
     auto block_max = [&](int v) {                              // every thread gets the maximum; one barrier per call
@@ -587,7 +592,7 @@ __global__ __launch_bounds__(1 << LOGN) void rdswap_tiled_kernel(const uint16_t*
 #pragma unroll 1
         for (int km = 0; km < LOGN; ++km) {
             const int q = p ^ (1 << km);
-            if (q < p) continue;
+            if (q < p || (km & (SPLIT - 1)) != part) continue;
             const int tq = tl[q];
             int total = 0;
 #pragma unroll
@@ -607,12 +612,12 @@ __global__ __launch_bounds__(1 << LOGN) void rdswap_tiled_kernel(const uint16_t*
             __syncthreads();                                   // the tiles of the previous block are free
             // all loads of the block first, then the stores: one L2 latency per block
             // RT: NH * QB rows of N entries, copied 16 bytes at a time; CT: row p, the block's QB columns
-            constexpr int kChunksPerRow = N * 2 / 16, kChunks = NH * QB * kChunksPerRow, kPerThread = kChunks / N;
-            static_assert(kChunks % N == 0, "every thread copies the same number of 16-byte pieces");
+            constexpr int kChunksPerRow = N * 2 / 16, kChunks = NH * QB * kChunksPerRow, kPerThread = kChunks / NT;
+            static_assert(kChunks % NT == 0, "every thread copies the same number of 16-byte pieces");
             int4 piece[kPerThread];
 #pragma unroll
             for (int i = 0; i < kPerThread; ++i) {
-                const int ch = tid + i * N;
+                const int ch = tid + i * NT;
                 const int rowi = ch / kChunksPerRow, off = ch % kChunksPerRow;
                 const int h = rowi >> LOGQ, j = rowi & (QB - 1);
                 const int node = tl[(b0 + j) ^ (QB << h)];
@@ -621,18 +626,23 @@ __global__ __launch_bounds__(1 << LOGN) void rdswap_tiled_kernel(const uint16_t*
             {
                 // F is symmetric: column t[B + j] is read as row t[B + j], which the threads of a wave read side by side
                 const uint16_t* col = folded + p;
-                uint32_t w[QB / 2];
+                constexpr int kWords = QB / 2 / SPLIT;             // words of row p that this thread stages
+                const int j0 = part * kWords;
+                uint32_t w[kWords];
 #pragma unroll
-                for (int j = 0; j < QB; j += 2)
-                    w[j / 2] = (uint32_t)col[(size_t)tl[b0 + j] * N] | ((uint32_t)col[(size_t)tl[b0 + j + 1] * N] << 16);
+                for (int j = 0; j < kWords; ++j)
+                    w[j] = (uint32_t)col[(size_t)tl[b0 + 2 * (j0 + j)] * N] |
+                           ((uint32_t)col[(size_t)tl[b0 + 2 * (j0 + j) + 1] * N] << 16);
 #pragma unroll
-                for (int j = 0; j < QB / 2; ++j) ((uint32_t*)(ct + p * kCtRowBytes))[j] = w[j];
+                for (int j = 0; j < kWords; ++j) ((uint32_t*)(ct + p * kCtRowBytes))[j0 + j] = w[j];
             }
 #pragma unroll
-            for (int i = 0; i < kPerThread; ++i) ((int4*)rt)[tid + i * N] = piece[i];
+            for (int i = 0; i < kPerThread; ++i) ((int4*)rt)[tid + i * NT] = piece[i];
             __syncthreads();
+            constexpr int kSteps = QB / 2 / SPLIT;
 #pragma unroll 2
-            for (int i = 0; i < QB / 2; ++i) {
+            for (int ii = 0; ii < kSteps; ++ii) {
+                const int i = part * kSteps + ii;
                 const int q0 = b0 + 2 * i;
                 const bool above = p > q0;                     // p = q0 + 1 takes q0; p = q0 sits this step out
                 const int q = q0 + (((p ^ q0) & 1) ^ (above ? 1 : 0));
@@ -679,29 +689,29 @@ __global__ __launch_bounds__(1 << LOGN) void rdswap_tiled_kernel(const uint16_t*
         const int id = (int)(win & ((1u << kIdBits) - 1u)), sp = id >> LOGN, sq = id & (N - 1);
         const int a = tl[sp], b = tl[sq];
         __syncthreads();                                       // everyone has read red_k and the two ranks
-        if (p == sp) { t = b; tl[p] = b; }
-        if (p == sq) { t = a; tl[p] = a; }
+        if (p == sp) { t = b; if (part == 0) tl[p] = b; }
+        if (p == sq) { t = a; if (part == 0) tl[p] = a; }
         ++applied;
         __syncthreads();
     }
-    tours[r * N + p] = t;
+    if (part == 0) tours[r * N + p] = t;
     if (tid == 0) {
         costs[r] = (int64_t)cur;
         moves[r] = applied;
     }
 }
 
-template <int LOGN, int LOGQ>
+template <int LOGN, int LOGQ, int SPLIT>
 static hipError_t rdswap_tiled_launch(const int32_t* c, uint16_t* folded, int restarts, int32_t* tours, int64_t* costs,
                                       int32_t* moves, const int32_t* flags, hipStream_t s) {
     constexpr int N = 1 << LOGN, QB = 1 << LOGQ, NH = LOGN - LOGQ;
     hipError_t e = launch_fold_to_u16(c, N, folded, flags, s);
     if (e != hipSuccess) return e;
     const size_t lds = sizeof(int32_t) * N + sizeof(uint16_t) * (size_t)NH * QB * N + (size_t)N * (QB / 2 + 1) * 4;
-    e = hipFuncSetAttribute((const void*)rdswap_tiled_kernel<LOGN, LOGQ>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    e = hipFuncSetAttribute((const void*)rdswap_tiled_kernel<LOGN, LOGQ, SPLIT>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((rdswap_tiled_kernel<LOGN, LOGQ>), dim3(restarts), dim3(N), lds, s, folded, tours, costs, moves,
+    hipLaunchKernelGGL((rdswap_tiled_kernel<LOGN, LOGQ, SPLIT>), dim3(restarts), dim3(SPLIT * N), lds, s, folded, tours, costs, moves,
                        flags);
     return hipGetLastError();
 }
@@ -756,8 +766,8 @@ hipError_t launch_rdswap(const int32_t* c, int N, int restarts, uint64_t seed, b
         if (e != hipSuccess) return e;
         e = N == 128   ? rdswap_block_launch<7>(c, mat16, restarts, tours, costs, moves, flags, s)
             : N == 256 ? rdswap_block_launch<8>(c, mat16, restarts, tours, costs, moves, flags, s)
-            : N == 512 ? rdswap_tiled_launch<9, 4>(c, mat16, restarts, tours, costs, moves, flags, s)
-                       : rdswap_tiled_launch<10, 3>(c, mat16, restarts, tours, costs, moves, flags, s);
+            : N == 512 ? rdswap_tiled_launch<9, 4, 2>(c, mat16, restarts, tours, costs, moves, flags, s)
+                       : rdswap_tiled_launch<10, 3, 1>(c, mat16, restarts, tours, costs, moves, flags, s);
         if (e != hipSuccess) return e;
         skip = flags;
     }

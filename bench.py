@@ -54,7 +54,7 @@ COUNTERS = {
     "search_sum_lds_insts": 2263348,                       # twoopt_sum_n64_kernel, 1024 restarts of workload 2
     "search_sum_hbm_bytes": (120.0 * 2 + 272.0) * 1024,
     "search_max_lds_insts": 840968,                        # twoopt_max_n64_kernel, 1024 restarts of workload 3
-    "search_max_hbm_bytes": (150.0 * 2 + 272.0) * 1024,
+    "search_max_hbm_bytes": (148.5 * 2 + 272.0) * 1024,
     "ring_batch_hbm_bytes": (131158.5 * 2 + 8195.9) * 1024,        # 2^20 orders
     "ring_batch_cold_hbm_bytes": (524374.5 * 2 + 32779.3) * 1024,  # 2^22 orders
 }

@@ -414,3 +414,28 @@ def test_init_tours_every_generation_path(n):
     tours = cc.cc_init_tours(n, count, seed, first=first)
     torch.cuda.synchronize()
     assert np.array_equal(tours.cpu().numpy(), oracle.init_tours(seed, n, count, first=first))
+
+
+def test_calls_on_an_explicit_stream_own_their_allocations():
+    """The binding allocates outputs and workspaces for calls that only enqueue kernels; given a stream that is not
+    torch's current one it must tell the allocator so (a dropped workspace may not be reused while the kernels still
+    run).  Batches and a search on a side stream, with allocator churn on the current stream in between."""
+    n = 256
+    c = random_matrix(n, 41, symmetric=False, lo=0, hi=50000)
+    perms = random_perms(n, 40000, 42)
+    side = torch.cuda.Stream()
+    cd, pd = dev(c), dev(perms)
+    torch.cuda.synchronize()
+    say("explicit stream: halving-doubling and BCube batches with binding-owned workspace, 2-opt search")
+    rd = cc.cc_rd_cost_batch(cd, pd, stream=side)
+    junk = [torch.full((1 << 18,), 7, dtype=torch.int32, device="cuda") for _ in range(8)]     # churn on the current stream
+    bc = cc.cc_bcube_cost_batch(cd, 4, pd, stream=side)
+    res = cc.cc_2opt_search_ex(dev(random_matrix(64, 43, True, 1, 9000)), 0, 64, 5, stream=side)
+    junk += [torch.full((1 << 18,), 9, dtype=torch.int32, device="cuda") for _ in range(8)]
+    side.synchronize()
+    torch.cuda.synchronize()
+    assert np.array_equal(rd.cpu().numpy(), oracle.rd_cost_batch(c, perms))
+    assert np.array_equal(bc.cpu().numpy(), oracle.bcube_cost_batch(c, 4, perms))
+    want = oracle.search(random_matrix(64, 43, True, 1, 9000), 0, 64, seed=5)
+    assert np.array_equal(res.restart_costs.cpu().numpy(), want["costs"]) and int(res.best_cost.item()) == want["best_cost"]
+    del junk

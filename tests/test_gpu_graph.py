@@ -164,3 +164,63 @@ def test_other_searches_replay_in_a_graph():
         torch.cuda.synchronize()
         for g, w in zip(outs, want):
             assert torch.equal(g, w), f"replay {replay}"
+
+
+def test_searches_at_128_to_512_replay_in_a_graph():
+    """The kernels for the larger sizes inside one captured step: max-hop (directed and not) at N = 256, the directed
+    ring sum at N = 128 (each with its matrix maximum, the multi-rank kernel and the skipped general kernel), pair swaps at
+    N = 512 (folded copy, LDS tiles), and the 2-opt search on the library's static scratch array."""
+    say("HIP graph: capture max-hop and directed-sum searches at N = 128 / 256, pair swaps at N = 512, the no-allocation search")
+    from gen import random_matrix
+    c256_host = random_matrix(256, 61, symmetric=True, lo=1, hi=9000)
+    a256_host = random_matrix(256, 62, symmetric=False, lo=1, hi=9000)
+    a128_host = random_matrix(128, 63, symmetric=False, lo=1, hi=9000)
+    c512_host = random_matrix(512, 64, symmetric=True, lo=1, hi=9000)
+    c64_host = make_matrix(2)
+    c256, a256, a128, c512, c64 = (torch.from_numpy(x).cuda() for x in (c256_host, a256_host, a128_host, c512_host, c64_host))
+    dev = c256.device
+    b_max = cc.SearchBuffers(256, cc.CC_RING_MAX, 6, dev)
+    b_maxd = cc.SearchBuffers(256, cc.CC_RING_MAX_DIRECTED, 5, dev)
+    b_dsum = cc.SearchBuffers(128, cc.CC_RING_SUM_DIRECTED, 7, dev)
+    b_swap = cc.SearchBuffers(512, 0, 1, dev)
+    na_perm = torch.empty(64, dtype=torch.int32, device=dev)
+    na_cost = torch.empty(1, dtype=torch.int64, device=dev)
+
+    def step():
+        cc.cc_2opt_search_ex(c256, cc.CC_RING_MAX, 6, 31, buffers=b_max)
+        cc.cc_2opt_search_ex(a256, cc.CC_RING_MAX_DIRECTED, 5, 32, buffers=b_maxd)
+        cc.cc_2opt_search_ex(a128, cc.CC_RING_SUM_DIRECTED, 7, 33, buffers=b_dsum)
+        cc.cc_rd_swap_search_ex(c512, 1, 34, buffers=b_swap)
+        cc.cc_2opt_search_noalloc(c64, cc.CC_RING_SUM, 50, 35, na_perm, na_cost)
+
+    step()                                   # also the first call of the no-allocation entry on this device
+    torch.cuda.synchronize()
+    bufs = (b_max, b_maxd, b_dsum, b_swap)
+    outs = [t for b in bufs for t in (b.restart_costs, b.restart_tours, b.restart_moves, b.best_perm, b.best_cost,
+                                       b.best_restart)]
+    outs += [na_perm, na_cost]
+    want = [t.clone() for t in outs]
+    refs = (oracle.search(c256_host, oracle.MAX, 6, 31), oracle.search(a256_host, oracle.MAX_DIRECTED, 5, 32),
+            oracle.search(a128_host, oracle.SUM_DIRECTED, 7, 33), oracle.rd_swap_search(c512_host, 1, 34))
+    for b, ref in zip(bufs, refs):
+        assert np.array_equal(b.restart_tours.cpu().numpy(), ref["tours"])
+        assert int(b.best_cost.item()) == ref["best_cost"]
+    ref = oracle.search(c64_host, oracle.SUM, 50, 35)
+    assert np.array_equal(na_perm.cpu().numpy(), ref["best_perm"]) and int(na_cost.item()) == ref["best_cost"]
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for replay in range(3):
+        for t in outs:
+            t.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for g, w in zip(outs, want):
+            assert torch.equal(g, w), f"replay {replay}"

@@ -14,7 +14,10 @@ directed max-hop rate (`move_evals_per_s_c3`) and the batch rate (`perm_evals_pe
 it.  Segment times come from HIP events recorded on the launch stream inside the timed region.
 
 After the timed steps, each of its own and evented launch by launch on the same stream:
-  - the two search kernels alone (the search calls without winner selection): `roofline`, `roofline_c3`;
+  - the two search kernels alone (the search calls without winner selection), the launches back to back between one
+    pair of events (`kernel_ms` = the average launch duration that `frac` is computed from; it is the figure the
+    profiler reports for the kernel) and every launch between a pair of its own (`kernel_ms_with_own_events`, 2 us
+    more: the events' own cost): `roofline`, `roofline_c3`;
   - the ring-sum search kernel on 64 times the restarts (`roofline_saturated`; --no-saturated skips it);
   - the ring batch on 2^22 orders, a 1 GiB stream that cannot sit in the 256 MB last-level cache
     (`roofline_batch.cold`; --no-cold skips it);
@@ -141,6 +144,19 @@ def main():
         torch.cuda.synchronize()
         return float(np.mean([e0.elapsed_time(e1) for e0, e1 in pairs]))
 
+    def back_to_back(fn, reps):
+        """Mean duration in ms of `reps` calls of fn issued back to back between ONE pair of HIP events: without the
+        few microseconds that an event of its own adds to every launch."""
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
     if args.pmc_calibration:
         cal_src = torch.zeros(64 << 20, dtype=torch.int32, device="cuda")
         cal_dst = torch.empty_like(cal_src)
@@ -172,10 +188,14 @@ def main():
 
     # the search kernels alone: the same calls without winner selection, one kernel launch each
     reps = max(args.steps, 10)
-    t_kernel = evented(lambda: cc.cc_2opt_search_ex(c, cc.CC_RING_SUM, restarts, seed, buffers=bufs, pick_best=False),
-                       reps)
-    t_kernel3 = evented(lambda: cc.cc_2opt_search_ex(c3, cc.CC_RING_MAX_DIRECTED, restarts, seed3, buffers=bufs3,
-                                                     pick_best=False), reps)
+    t_kernel_own = evented(lambda: cc.cc_2opt_search_ex(c, cc.CC_RING_SUM, restarts, seed, buffers=bufs,
+                                                        pick_best=False), reps)
+    t_kernel3_own = evented(lambda: cc.cc_2opt_search_ex(c3, cc.CC_RING_MAX_DIRECTED, restarts, seed3, buffers=bufs3,
+                                                         pick_best=False), reps)
+    t_kernel = back_to_back(lambda: cc.cc_2opt_search_ex(c, cc.CC_RING_SUM, restarts, seed, buffers=bufs,
+                                                             pick_best=False), reps)
+    t_kernel3 = back_to_back(lambda: cc.cc_2opt_search_ex(c3, cc.CC_RING_MAX_DIRECTED, restarts, seed3,
+                                                              buffers=bufs3, pick_best=False), reps)
     kernel_move_rate = move_evals / (t_kernel * 1e-3)
     kernel_move_rate3 = move_evals3 / (t_kernel3 * 1e-3)
     lds_gbs = kernel_move_rate * LDS_BYTES_PER_MOVE / 1e9
@@ -217,7 +237,10 @@ def main():
         "perm_evals_per_s": perm_rate,
         "rd_perm_evals_per_s": rd_batch / (t_rd * 1e-3),
         "roofline": {"kernel": "twoopt_sum_n64_kernel (2-opt search: neighbourhood sweep, argmin, apply)",
-                     "kernel_ms": t_kernel, "launches": reps, "bound": "lds", "achieved": lds_gbs,
+                     "kernel_ms": t_kernel, "launches": reps,
+                     "kernel_ms_with_own_events": t_kernel_own,
+                     "frac_with_own_events": move_evals / (t_kernel_own * 1e-3) * LDS_BYTES_PER_MOVE / 1e9 / LDS_PEAK_GBS,
+                     "bound": "lds", "achieved": lds_gbs,
                      "peak": LDS_PEAK_GBS, "unit": "GB/s", "frac": lds_gbs / LDS_PEAK_GBS,
                      "bytes_per_move": LDS_BYTES_PER_MOVE,
                      "traffic": lds_traffic("search_sum_lds_insts"),
@@ -235,7 +258,8 @@ def main():
                               "frac": kernel_move_rate * VALU_OPS_PER_MOVE / 1e9 / VALU_PEAK_GOPS,
                               "ops_per_move": VALU_OPS_PER_MOVE}},
         "roofline_c3": {"kernel": "twoopt_max_n64_kernel (directed max-hop 2-opt search, packed 16-bit entries)",
-                        "kernel_ms": t_kernel3, "launches": reps, "move_evals_per_s": kernel_move_rate3,
+                        "kernel_ms": t_kernel3, "launches": reps, "kernel_ms_with_own_events": t_kernel3_own,
+                        "move_evals_per_s": kernel_move_rate3,
                         "bound": "lds", "achieved": lds_gbs3, "peak": LDS_PEAK_GBS, "unit": "GB/s",
                         "frac": lds_gbs3 / LDS_PEAK_GBS, "bytes_per_move": LDS_BYTES_PER_DIRECTED_MOVE,
                         "frac_at_storage_width": lds_gbs3_packed / LDS_PEAK_GBS,
